@@ -1,0 +1,432 @@
+/*
+ * CPU oracle for adaptive-block sparse decode attention (AB-Sparse).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, obviously-correct statement
+ * of what the decode path computes.  It shares no code, header, table or helper with
+ * the HIP library, is never linked into it, and may be used only by the tests, by the
+ * smoke check and by the benchmark's CPU-baseline leg.
+ *
+ * What it follows, step by step, in the paper's order and notation:
+ *   - block-sparse workflow (Sec. 2.2): partition each head's keys into blocks of size
+ *     B_h, one centroid c_j per block, importance r_j = q . c_j^T, Top-K blocks, attention
+ *     over the selected blocks only;
+ *   - centroid = mean pooling of the block's keys (Sec. 2.2, footnote on pooling);
+ *   - INT4 asymmetric per-channel centroid quantization: one scale and one zero-point
+ *     offset per head-dim channel, shared by all blocks of a head (Sec. 3.3);
+ *   - flattened 1-D centroid layout, offset[s+1] = offset[s] + N_s (Sec. 3.4, kernel 1);
+ *   - per-head K_h = ceil(T / B_h) under a token budget T (Sec. 3.4, kernel 2);
+ *   - a selected logical block maps onto fixed-size physical pages through the page
+ *     table with no data movement (Sec. 3.4, kernel 3);
+ *   - softmax attention, Eq. (1), restricted to the selected tokens; GQA: G = Hq/Hkv
+ *     query heads share one KV head.
+ *
+ * Where the paper is silent the reading is fixed here once (and listed in the design
+ * notes): one segment per (request, KV head), request-major; the G query heads of a
+ * group are folded by summation before scoring (the score is linear in q); the last
+ * block may be partial and its centroid is the mean of its valid keys only; ties in
+ * Top-K go to the lowest block index and the index list is emitted ascending; scoring
+ * is carried out in exact integers on a 16-bit fixed-point image of (q * scale) so that
+ * the ranking has exactly one correct answer on any machine.
+ *
+ * Arithmetic: steps that decide integers (codes, scores, selected indices) use IEEE
+ * binary32 single operations in the stated order (compile with -ffp-contract=off, no
+ * fast-math); attention is evaluated in binary64 from the exactly widened inputs.
+ *
+ * Parity pins (tests/test_oracle_*.py): every function here is pinned to something
+ * other than itself - fp64 means, quantization error bound/idempotence/extremes,
+ * an independent fp64 dot-product bound for the scores, numpy lexsort and exhaustive
+ * tiny cases for Top-K, an independent numpy dense softmax (Eq. 1) for attention with
+ * K = all blocks, page-permutation invariance, and single-token / equal-key closed forms.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_F16 = 0, ORC_BF16 = 1 };
+
+/* ---- exact widening of the 16-bit storage formats -------------------------------- */
+static float widen_f16(uint16_t h) {
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    uint32_t ex = (h >> 10) & 0x1Fu;
+    uint32_t man = h & 0x3FFu;
+    uint32_t out;
+    if (ex == 0) {
+        if (man == 0) {
+            out = sign;
+        } else { /* subnormal: value = man * 2^-24, exact in binary32 */
+            float v = (float)man * 0x1p-24f;
+            memcpy(&out, &v, 4);
+            out |= sign;
+        }
+    } else if (ex == 31) {
+        out = sign | 0x7F800000u | (man << 13);
+    } else {
+        out = sign | ((ex + 112u) << 23) | (man << 13);
+    }
+    float f;
+    memcpy(&f, &out, 4);
+    return f;
+}
+
+static float widen_bf16(uint16_t h) {
+    uint32_t out = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &out, 4);
+    return f;
+}
+
+static float widen(uint16_t bits, int dtype) { return dtype == ORC_F16 ? widen_f16(bits) : widen_bf16(bits); }
+
+/* row of logical token t of (request b, KV head h) in a paged cache */
+typedef struct {
+    const uint16_t *base;
+    const int32_t *page_table; /* [Bt][pt_stride] */
+    int32_t pt_stride, P;
+    int64_t s_page, s_head, s_tok; /* element strides; channels contiguous */
+} paged_t;
+
+static const uint16_t *row_of(const paged_t *c, int b, int h, int64_t t) {
+    int64_t page = c->page_table[(int64_t)b * c->pt_stride + t / c->P];
+    return c->base + page * c->s_page + (int64_t)h * c->s_head + (t % c->P) * c->s_tok;
+}
+
+static int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ---- segment layout: offset[s+1] = offset[s] + N_s, N_s = ceil(L_b / B_h) ----------
+ * (Sec. 3.4, kernel 1; one segment per (request, KV head), s = b*Hkv + h).
+ * Returns the total number of centroids. */
+int64_t orc_offsets(int Bt, int Hkv, const int32_t *seq_lens, const int32_t *block_size, int64_t *off) {
+    off[0] = 0;
+    for (int b = 0; b < Bt; ++b)
+        for (int h = 0; h < Hkv; ++h) {
+            int s = b * Hkv + h;
+            off[s + 1] = off[s] + ceil_div64(seq_lens[b], block_size[h]);
+        }
+    return off[Bt * Hkv];
+}
+
+/* ---- O1: block centroid = mean of the block's keys (binary32, tokens in order) ------ */
+void orc_centroids(int dtype, int Bt, int Hkv, int d, int P, int64_t s_page, int64_t s_head, int64_t s_tok,
+                   const uint16_t *k_cache, const int32_t *page_table, int pt_stride, const int32_t *seq_lens,
+                   const int32_t *block_size, const int64_t *off, float *cent /* [total][d] */) {
+    paged_t kc = {k_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        int64_t L = seq_lens[b], B = block_size[h];
+        int64_t N = off[s + 1] - off[s];
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t t0 = j * B;
+            int64_t n = (L - t0 < B) ? (L - t0) : B; /* the last block may be partial */
+            float *c = cent + (off[s] + j) * d;
+            for (int ch = 0; ch < d; ++ch) c[ch] = 0.0f;
+            for (int64_t t = t0; t < t0 + n; ++t) {
+                const uint16_t *row = row_of(&kc, b, h, t);
+                for (int ch = 0; ch < d; ++ch) c[ch] = c[ch] + widen(row[ch], dtype);
+            }
+            float fn = (float)n;
+            for (int ch = 0; ch < d; ++ch) c[ch] = c[ch] / fn;
+        }
+    }
+}
+
+/* ---- O2: per-(segment, channel) range: scale = (max-min)/15, zero-point offset = min */
+void orc_quant_params(int nseg, int d, const int64_t *off, const float *cent, float *qscale, float *qmin,
+                      float *qinv /* [nseg][d] each */) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < nseg; ++s) {
+        for (int ch = 0; ch < d; ++ch) {
+            float mn = INFINITY, mx = -INFINITY;
+            for (int64_t j = off[s]; j < off[s + 1]; ++j) {
+                float v = cent[j * d + ch];
+                if (v < mn) mn = v;
+                if (v > mx) mx = v;
+            }
+            float rng = mx - mn;
+            float sc = 0.0f, inv = 0.0f;
+            if (rng > 0.0f) {
+                sc = rng / 15.0f;
+                inv = 15.0f / rng;
+            }
+            if (off[s + 1] == off[s]) mn = 0.0f;
+            qscale[(int64_t)s * d + ch] = sc;
+            qinv[(int64_t)s * d + ch] = inv;
+            qmin[(int64_t)s * d + ch] = mn;
+        }
+    }
+}
+
+/* ---- O3: 4-bit codes, round-half-to-even, two channels per byte (even = low nibble) - */
+void orc_quantize(int nseg, int d, const int64_t *off, const float *cent, const float *qmin, const float *qinv,
+                  uint8_t *codes /* [total][d/2] */) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < nseg; ++s) {
+        const float *mn = qmin + (int64_t)s * d, *inv = qinv + (int64_t)s * d;
+        for (int64_t j = off[s]; j < off[s + 1]; ++j) {
+            for (int ch = 0; ch < d; ++ch) {
+                float x = cent[j * d + ch] - mn[ch];
+                float y = x * inv[ch];
+                float r = rintf(y); /* default rounding mode: to nearest, ties to even */
+                if (r < 0.0f) r = 0.0f;
+                if (r > 15.0f) r = 15.0f;
+                uint8_t code = (uint8_t)r;
+                uint8_t *byte = codes + j * (d / 2) + ch / 2;
+                if (ch % 2 == 0)
+                    *byte = code;
+                else
+                    *byte = (uint8_t)(*byte | (code << 4));
+            }
+        }
+    }
+}
+
+/* dequantized centroid (diagnostics): c^ = code * scale + min */
+void orc_dequantize(int nseg, int d, const int64_t *off, const uint8_t *codes, const float *qscale,
+                    const float *qmin, float *out /* [total][d] */) {
+    for (int s = 0; s < nseg; ++s)
+        for (int64_t j = off[s]; j < off[s + 1]; ++j)
+            for (int ch = 0; ch < d; ++ch) {
+                uint8_t byte = codes[j * (d / 2) + ch / 2];
+                int code = (ch % 2 == 0) ? (byte & 15) : (byte >> 4);
+                out[j * d + ch] = fmaf((float)code, qscale[(int64_t)s * d + ch], qmin[(int64_t)s * d + ch]);
+            }
+}
+
+/* ---- O4: fixed-point importance score --------------------------------------------
+ * r_j = sum_g q_g . c^_j (Sec. 2.2) = sum_c u_c * (code_jc * scale_c + min_c), u = sum_g q_g.
+ * The min term is the same for every block of the segment, so the ranking is that of
+ * sum_c (u_c * scale_c) * code_jc.  w_c = u_c*scale_c is imaged on integers wq_c with the
+ * largest |w_c| placed in [2^14, 2^15]; S_j = sum_c wq_c * code_jc is exact in int32. */
+void orc_score(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t *q /* [Bt][Hq][d] */,
+               const uint8_t *codes, const float *qscale, const int64_t *off, int32_t *scores /* [total] */,
+               int32_t *score_exp /* [Bt*Hkv] */, int32_t *wq_out /* [Bt*Hkv][d] or NULL */) {
+    int G = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        float w[1024];
+        int32_t wq[1024];
+        float A = 0.0f;
+        for (int ch = 0; ch < d; ++ch) {
+            float u = widen(q[((int64_t)b * Hq + h * G) * d + ch], dtype);
+            for (int g = 1; g < G; ++g) u = u + widen(q[((int64_t)b * Hq + h * G + g) * d + ch], dtype);
+            w[ch] = u * qscale[(int64_t)s * d + ch];
+            float a = fabsf(w[ch]);
+            if (a > A) A = a;
+        }
+        int ex = 0;
+        if (!(A >= 0x1p-100f) || isinf(A)) {
+            for (int ch = 0; ch < d; ++ch) wq[ch] = 0;
+        } else {
+            ex = ilogbf(A) - 14;
+            for (int ch = 0; ch < d; ++ch) wq[ch] = (int32_t)rintf(ldexpf(w[ch], -ex));
+        }
+        score_exp[s] = ex;
+        if (wq_out)
+            for (int ch = 0; ch < d; ++ch) wq_out[(int64_t)s * d + ch] = wq[ch];
+        for (int64_t j = off[s]; j < off[s + 1]; ++j) {
+            int32_t acc = 0;
+            for (int ch = 0; ch < d; ++ch) {
+                uint8_t byte = codes[j * (d / 2) + ch / 2];
+                int32_t code = (ch % 2 == 0) ? (byte & 15) : (byte >> 4);
+                acc += wq[ch] * code;
+            }
+            scores[j] = acc;
+        }
+    }
+}
+
+/* ---- O5: Top-K_s per segment, K_s = min(N_s, ceil(T_b / B_h)) ----------------------- */
+typedef struct {
+    int32_t score;
+    int32_t idx;
+} pair_t;
+
+static int by_score_desc_then_index(const void *a, const void *b) {
+    const pair_t *x = (const pair_t *)a, *y = (const pair_t *)b;
+    if (x->score != y->score) return x->score > y->score ? -1 : 1;
+    if (x->idx != y->idx) return x->idx < y->idx ? -1 : 1;
+    return 0;
+}
+
+static int by_index(const void *a, const void *b) {
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+void orc_topk(int Bt, int Hkv, const int64_t *off, const int32_t *block_size, const int32_t *budget,
+              const int32_t *scores, int32_t *sel_idx /* [Bt*Hkv][sel_stride] */, int32_t *sel_cnt,
+              int sel_stride) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        int64_t N = off[s + 1] - off[s];
+        int64_t K = ceil_div64(budget[b], block_size[h]);
+        if (K > N) K = N;
+        if (K > sel_stride) K = sel_stride;
+        pair_t *p = (pair_t *)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
+        for (int64_t j = 0; j < N; ++j) {
+            p[j].score = scores[off[s] + j];
+            p[j].idx = (int32_t)j;
+        }
+        qsort(p, (size_t)N, sizeof(pair_t), by_score_desc_then_index);
+        int32_t *out = sel_idx + (int64_t)s * sel_stride;
+        for (int64_t i = 0; i < K; ++i) out[i] = p[i].idx;
+        qsort(out, (size_t)K, sizeof(int32_t), by_index);
+        for (int64_t i = K; i < sel_stride; ++i) out[i] = -1;
+        sel_cnt[s] = (int32_t)K;
+        free(p);
+    }
+}
+
+/* ---- O6: attention over the selected tokens, Eq. (1) restricted to the selection ----
+ * For query head hq of KV head h: z_t = sm_scale * q . k_t, a = softmax(z), o = sum a_t v_t,
+ * all in binary64; lse = max z + ln sum exp(z - max z).  A selected last block contributes
+ * only its valid tokens.  An empty selection gives o = 0, lse = -inf. */
+static void attend_tokens(int dtype, int d, const paged_t *kc, const paged_t *vc, int b, int h,
+                          const uint16_t *qrow, const int64_t *tok, int64_t ntok, double sm_scale,
+                          double *z /* scratch [ntok] */, double *o /* [d] */, double *lse) {
+    double m = -INFINITY;
+    for (int64_t i = 0; i < ntok; ++i) {
+        const uint16_t *kr = row_of(kc, b, h, tok[i]);
+        double dot = 0.0;
+        for (int ch = 0; ch < d; ++ch) dot += (double)widen(qrow[ch], dtype) * (double)widen(kr[ch], dtype);
+        z[i] = sm_scale * dot;
+        if (z[i] > m) m = z[i];
+    }
+    for (int ch = 0; ch < d; ++ch) o[ch] = 0.0;
+    if (ntok == 0) {
+        *lse = -INFINITY;
+        return;
+    }
+    double l = 0.0;
+    for (int64_t i = 0; i < ntok; ++i) {
+        double p = exp(z[i] - m);
+        const uint16_t *vr = row_of(vc, b, h, tok[i]);
+        l += p;
+        for (int ch = 0; ch < d; ++ch) o[ch] += p * (double)widen(vr[ch], dtype);
+    }
+    for (int ch = 0; ch < d; ++ch) o[ch] /= l;
+    *lse = m + log(l);
+}
+
+void orc_sparse_attention(int dtype, int Bt, int Hq, int Hkv, int d, int P, int64_t s_page, int64_t s_head,
+                          int64_t s_tok, const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
+                          const int32_t *page_table, int pt_stride, const int32_t *seq_lens,
+                          const int32_t *block_size, const int32_t *sel_idx, const int32_t *sel_cnt,
+                          int sel_stride, double sm_scale, double *out /* [Bt][Hq][d] */,
+                          double *lse /* [Bt][Hq] */) {
+    paged_t kc = {k_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+    paged_t vc = {v_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+    int G = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        int64_t L = seq_lens[b], B = block_size[h];
+        int64_t cnt = sel_cnt[s];
+        int64_t *tok = (int64_t *)malloc(sizeof(int64_t) * (size_t)(cnt * B + 1));
+        int64_t ntok = 0;
+        for (int64_t i = 0; i < cnt; ++i) {
+            int64_t j = sel_idx[(int64_t)s * sel_stride + i];
+            if (j < 0) continue;
+            for (int64_t t = j * B; t < (j + 1) * B && t < L; ++t) tok[ntok++] = t;
+        }
+        double *z = (double *)malloc(sizeof(double) * (size_t)(ntok + 1));
+        for (int g = 0; g < G; ++g) {
+            int hq = h * G + g;
+            attend_tokens(dtype, d, &kc, &vc, b, h, q + ((int64_t)b * Hq + hq) * d, tok, ntok, sm_scale, z,
+                          out + ((int64_t)b * Hq + hq) * d, lse + (int64_t)b * Hq + hq);
+        }
+        free(z);
+        free(tok);
+    }
+}
+
+/* ---- dense reference: Eq. (1) over every token of the context ---------------------- */
+void orc_dense_attention(int dtype, int Bt, int Hq, int Hkv, int d, int P, int64_t s_page, int64_t s_head,
+                         int64_t s_tok, const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
+                         const int32_t *page_table, int pt_stride, const int32_t *seq_lens, double sm_scale,
+                         double *out, double *lse) {
+    paged_t kc = {k_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+    paged_t vc = {v_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+    int G = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        int64_t L = seq_lens[b];
+        int64_t *tok = (int64_t *)malloc(sizeof(int64_t) * (size_t)(L + 1));
+        for (int64_t t = 0; t < L; ++t) tok[t] = t;
+        double *z = (double *)malloc(sizeof(double) * (size_t)(L + 1));
+        for (int g = 0; g < G; ++g) {
+            int hq = h * G + g;
+            attend_tokens(dtype, d, &kc, &vc, b, h, q + ((int64_t)b * Hq + hq) * d, tok, L, sm_scale, z,
+                          out + ((int64_t)b * Hq + hq) * d, lse + (int64_t)b * Hq + hq);
+        }
+        free(z);
+        free(tok);
+    }
+}
+
+/* ---- attention recall (Sec. 2.3): share of the dense softmax mass that falls on the
+ * selected tokens, per query head.  Diagnostic only. */
+void orc_attention_recall(int dtype, int Bt, int Hq, int Hkv, int d, int P, int64_t s_page, int64_t s_head,
+                          int64_t s_tok, const uint16_t *q, const uint16_t *k_cache, const int32_t *page_table,
+                          int pt_stride, const int32_t *seq_lens, const int32_t *block_size,
+                          const int32_t *sel_idx, const int32_t *sel_cnt, int sel_stride, double sm_scale,
+                          double *recall /* [Bt][Hq] */) {
+    paged_t kc = {k_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+    int G = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        int64_t L = seq_lens[b], B = block_size[h];
+        int64_t N = ceil_div64(L, B);
+        uint8_t *picked = (uint8_t *)calloc((size_t)(N + 1), 1);
+        for (int64_t i = 0; i < sel_cnt[s]; ++i) {
+            int64_t j = sel_idx[(int64_t)s * sel_stride + i];
+            if (j >= 0 && j < N) picked[j] = 1;
+        }
+        double *z = (double *)malloc(sizeof(double) * (size_t)(L + 1));
+        for (int g = 0; g < G; ++g) {
+            const uint16_t *qrow = q + ((int64_t)b * Hq + h * G + g) * d;
+            double m = -INFINITY;
+            for (int64_t t = 0; t < L; ++t) {
+                const uint16_t *kr = row_of(&kc, b, h, t);
+                double dot = 0.0;
+                for (int ch = 0; ch < d; ++ch) dot += (double)widen(qrow[ch], dtype) * (double)widen(kr[ch], dtype);
+                z[t] = sm_scale * dot;
+                if (z[t] > m) m = z[t];
+            }
+            double all = 0.0, in = 0.0;
+            for (int64_t t = 0; t < L; ++t) {
+                double p = exp(z[t] - m);
+                all += p;
+                if (picked[t / B]) in += p;
+            }
+            recall[(int64_t)b * Hq + h * G + g] = in / all;
+        }
+        free(z);
+        free(picked);
+    }
+}

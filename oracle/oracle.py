@@ -1,0 +1,221 @@
+"""ctypes front end of the CPU oracle (absb_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: importable from tests/, from the smoke check and from the
+benchmark's CPU-baseline leg, never from the product package.  It takes plain numpy
+arrays (the ones the seeded generators produce) and returns numpy arrays.  No function
+here contains arithmetic of the method: everything numeric happens in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "absb_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+# -ffp-contract=off / no fast-math: every binary32 step is a single IEEE operation.
+_CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+           "-fno-unsafe-math-optimizations", "-Wall", "-Wextra"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (a checker being built is not the checker being used)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", *_CFLAGS, _SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_offsets.restype = C.c_int64
+        _lib.orc_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    assert a.flags["C_CONTIGUOUS"], "oracle arrays must be C-contiguous"
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().orc_set_threads(C.c_int(n))
+
+
+@dataclass
+class CentroidStore:
+    off: np.ndarray        # int64 [nseg+1]
+    cent: np.ndarray       # float32 [total, d]   (unquantized block means)
+    qscale: np.ndarray     # float32 [nseg, d]
+    qmin: np.ndarray       # float32 [nseg, d]
+    qinv: np.ndarray       # float32 [nseg, d]
+    codes: np.ndarray      # uint8 [total, d/2]
+
+
+def _geom(wl):
+    sp, sh, st = wl.strides
+    return (C.c_int(wl.dtype), C.c_int(wl.batch), C.c_int(wl.num_q_heads), C.c_int(wl.num_kv_heads),
+            C.c_int(wl.head_dim), C.c_int(wl.page_size), C.c_int64(sp), C.c_int64(sh), C.c_int64(st))
+
+
+def offsets(wl) -> np.ndarray:
+    nseg = wl.batch * wl.num_kv_heads
+    off = np.zeros(nseg + 1, dtype=np.int64)
+    lib().orc_offsets(C.c_int(wl.batch), C.c_int(wl.num_kv_heads), _p(_i32(wl.seq_lens)),
+                      _p(_i32(wl.block_size)), _p(off))
+    return off
+
+
+def centroids(wl, off: np.ndarray) -> np.ndarray:
+    dt, Bt, _, Hkv, d, P, sp, sh, st = _geom(wl)
+    cent = np.empty((int(off[-1]), wl.head_dim), dtype=np.float32)
+    pt = _i32(wl.page_table)
+    lib().orc_centroids(dt, Bt, Hkv, d, P, sp, sh, st, _p(wl.k_cache), _p(pt), C.c_int(pt.shape[1]),
+                        _p(_i32(wl.seq_lens)), _p(_i32(wl.block_size)), _p(off), _p(cent))
+    return cent
+
+
+def quant_params(off, cent):
+    nseg, d = len(off) - 1, cent.shape[1]
+    qscale = np.empty((nseg, d), np.float32)
+    qmin = np.empty((nseg, d), np.float32)
+    qinv = np.empty((nseg, d), np.float32)
+    lib().orc_quant_params(C.c_int(nseg), C.c_int(d), _p(off), _p(cent), _p(qscale), _p(qmin), _p(qinv))
+    return qscale, qmin, qinv
+
+
+def quantize(off, cent, qmin, qinv) -> np.ndarray:
+    nseg, d = len(off) - 1, cent.shape[1]
+    cent = np.ascontiguousarray(cent, dtype=np.float32)
+    codes = np.zeros((cent.shape[0], d // 2), np.uint8)
+    lib().orc_quantize(C.c_int(nseg), C.c_int(d), _p(off), _p(cent), _p(qmin), _p(qinv), _p(codes))
+    return codes
+
+
+def dequantize(off, codes, qscale, qmin) -> np.ndarray:
+    nseg, d = len(off) - 1, qscale.shape[1]
+    out = np.empty((codes.shape[0], d), np.float32)
+    lib().orc_dequantize(C.c_int(nseg), C.c_int(d), _p(off), _p(codes), _p(qscale), _p(qmin), _p(out))
+    return out
+
+
+def build_centroids(wl) -> CentroidStore:
+    """O1-O3: means, per-channel ranges, INT4 codes."""
+    off = offsets(wl)
+    cent = centroids(wl, off)
+    qscale, qmin, qinv = quant_params(off, cent)
+    codes = quantize(off, cent, qmin, qinv)
+    return CentroidStore(off, cent, qscale, qmin, qinv, codes)
+
+
+def score(wl, store: CentroidStore, q: Optional[np.ndarray] = None, want_weights: bool = False):
+    """O4: int32 fixed-point scores for every centroid, per-segment exponent."""
+    q = wl.q if q is None else q
+    nseg = wl.batch * wl.num_kv_heads
+    scores = np.empty(int(store.off[-1]), np.int32)
+    ex = np.empty(nseg, np.int32)
+    wq = np.empty((nseg, wl.head_dim), np.int32) if want_weights else None
+    lib().orc_score(C.c_int(wl.dtype), C.c_int(wl.batch), C.c_int(wl.num_q_heads), C.c_int(wl.num_kv_heads),
+                    C.c_int(wl.head_dim), _p(np.ascontiguousarray(q)), _p(store.codes), _p(store.qscale),
+                    _p(store.off), _p(scores), _p(ex), _p(wq))
+    return (scores, ex, wq) if want_weights else (scores, ex)
+
+
+def topk_raw(Bt, Hkv, off, block_size, budget, scores, sel_stride):
+    nseg = Bt * Hkv
+    sel_idx = np.empty((nseg, sel_stride), np.int32)
+    sel_cnt = np.empty(nseg, np.int32)
+    lib().orc_topk(C.c_int(Bt), C.c_int(Hkv), _p(np.ascontiguousarray(off, dtype=np.int64)), _p(_i32(block_size)),
+                   _p(_i32(budget)), _p(_i32(scores)), _p(sel_idx), _p(sel_cnt), C.c_int(sel_stride))
+    return sel_idx, sel_cnt
+
+
+def topk(wl, off, scores, sel_stride: Optional[int] = None, budget=None):
+    """O5: per segment the K_s best blocks (score desc, index asc), emitted ascending, -1 padded."""
+    budget = wl.budget if budget is None else budget
+    if sel_stride is None:
+        # widest possible list: every block of the longest segment (always enough)
+        sel_stride = int(np.max(np.diff(off))) if len(off) > 1 else 1
+        sel_stride = max(sel_stride, 1)
+    return topk_raw(wl.batch, wl.num_kv_heads, off, wl.block_size, budget, scores, sel_stride)
+
+
+def sparse_attention(wl, sel_idx, sel_cnt, sm_scale: Optional[float] = None, q=None):
+    """O6: fp64 attention over the selected blocks.  Returns (out [Bt,Hq,d], lse [Bt,Hq])."""
+    q = wl.q if q is None else q
+    sm = float(1.0 / np.sqrt(wl.head_dim)) if sm_scale is None else float(sm_scale)
+    out = np.empty((wl.batch, wl.num_q_heads, wl.head_dim), np.float64)
+    lse = np.empty((wl.batch, wl.num_q_heads), np.float64)
+    sel_idx = _i32(sel_idx)
+    pt = _i32(wl.page_table)
+    lib().orc_sparse_attention(*_geom(wl), _p(np.ascontiguousarray(q)), _p(wl.k_cache), _p(wl.v_cache), _p(pt),
+                               C.c_int(pt.shape[1]), _p(_i32(wl.seq_lens)), _p(_i32(wl.block_size)),
+                               _p(sel_idx), _p(_i32(sel_cnt)), C.c_int(sel_idx.shape[1]), C.c_double(sm),
+                               _p(out), _p(lse))
+    return out, lse
+
+
+def dense_attention(wl, sm_scale: Optional[float] = None, q=None):
+    """Eq. (1) over the whole context, fp64."""
+    q = wl.q if q is None else q
+    sm = float(1.0 / np.sqrt(wl.head_dim)) if sm_scale is None else float(sm_scale)
+    out = np.empty((wl.batch, wl.num_q_heads, wl.head_dim), np.float64)
+    lse = np.empty((wl.batch, wl.num_q_heads), np.float64)
+    pt = _i32(wl.page_table)
+    lib().orc_dense_attention(*_geom(wl), _p(np.ascontiguousarray(q)), _p(wl.k_cache), _p(wl.v_cache), _p(pt),
+                              C.c_int(pt.shape[1]), _p(_i32(wl.seq_lens)), C.c_double(sm), _p(out), _p(lse))
+    return out, lse
+
+
+def attention_recall(wl, sel_idx, sel_cnt, sm_scale: Optional[float] = None):
+    """Share of the dense softmax mass on the selected tokens (Sec. 2.3), per query head."""
+    sm = float(1.0 / np.sqrt(wl.head_dim)) if sm_scale is None else float(sm_scale)
+    rec = np.empty((wl.batch, wl.num_q_heads), np.float64)
+    sel_idx = _i32(sel_idx)
+    pt = _i32(wl.page_table)
+    lib().orc_attention_recall(*_geom(wl), _p(wl.q), _p(wl.k_cache), _p(pt), C.c_int(pt.shape[1]),
+                               _p(_i32(wl.seq_lens)), _p(_i32(wl.block_size)), _p(sel_idx), _p(_i32(sel_cnt)),
+                               C.c_int(sel_idx.shape[1]), C.c_double(sm), _p(rec))
+    return rec
+
+
+def planted_recall(wl, sel_idx, sel_cnt) -> float:
+    """Fraction of the generator's planted heavy tokens whose block was selected (diagnostic)."""
+    hit = tot = 0
+    for (b, h), pos in wl.planted.items():
+        s = b * wl.num_kv_heads + h
+        chosen = set(int(x) for x in sel_idx[s, :sel_cnt[s]])
+        blocks = pos // int(wl.block_size[h])
+        hit += sum(1 for j in blocks if int(j) in chosen)
+        tot += len(blocks)
+    return hit / max(tot, 1)
+
+
+def decode_step(wl, store: CentroidStore, sel_stride: Optional[int] = None):
+    """O4 -> O5 -> O6 given a prebuilt centroid store: the per-step hot path."""
+    scores, ex = score(wl, store)
+    sel_idx, sel_cnt = topk(wl, store.off, scores, sel_stride)
+    out, lse = sparse_attention(wl, sel_idx, sel_cnt)
+    return dict(scores=scores, score_exp=ex, sel_idx=sel_idx, sel_cnt=sel_cnt, out=out, lse=lse)
