@@ -1,0 +1,174 @@
+/*
+ * absb - adaptive-block sparse decode attention for AMD MI355X (gfx950).
+ *
+ * C ABI of libabsb.so.  The library implements the decode-step hot path of AB-Sparse:
+ * block-sparse attention in which every KV head has its own block size B_h.
+ *
+ *   build  : block centroids (mean pooling, Sec. 2.2) quantized to INT4, asymmetric,
+ *            one scale and one zero-point offset per head-dim channel (Sec. 3.3),
+ *            stored in a flattened 1-D array delimited by prefix sums (Sec. 3.4, kernel 1)
+ *   score  : importance of every block, r_j = q . c_j^T (Sec. 2.2), dequantization fused,
+ *            all heads of all requests in one launch (Sec. 3.4, kernel 1)
+ *   topk   : per head the K_h = ceil(T / B_h) best blocks under a token budget T
+ *            (Sec. 3.4, kernel 2)
+ *   decode : softmax attention, Eq. (1), over the selected blocks only, read in place
+ *            from a paged KV cache through the page table (Sec. 3.4, kernel 3), as
+ *            split-K partials merged by log-sum-exp
+ *
+ * Conventions
+ *   - Every function returns ABSB_OK (0) or a negative absb_status.  No exceptions, no exit.
+ *   - Host-visible arguments are validated before anything is launched; on error nothing
+ *     has been enqueued.
+ *   - All device work is enqueued on the caller's stream (`stream` is a hipStream_t passed
+ *     as void*; NULL = the default stream).  No call synchronises, allocates or frees.
+ *   - The caller owns every buffer.  Pointers are DEVICE pointers unless the comment says
+ *     "host".  Host arrays are read during the call only.  Device buffers must stay valid
+ *     until the enqueued work has finished.
+ *   - Contents of device arrays (page indices, lengths, selected indices) are trusted:
+ *     out-of-range values are undefined behaviour.  The device copies `seq_lens`/`budget`
+ *     must hold the same values as their host twins.
+ *   - One segment per (request b, KV head h): s = b*num_kv_heads + h, request-major.  The
+ *     G = num_q_heads/num_kv_heads query heads of a KV head share its blocks and its
+ *     selection; their scores are summed (the score is linear in q).
+ *   - Workspace: `absb_plan` reports the size that suffices for every entry point on that
+ *     (layer, batch); 256-byte aligned; contents need not be preserved between calls and
+ *     need no initialisation.  Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef ABSB_H
+#define ABSB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define ABSB_API __attribute__((visibility("default")))
+#else
+#define ABSB_API
+#endif
+
+typedef enum absb_dtype { ABSB_F16 = 0, ABSB_BF16 = 1 } absb_dtype;
+
+typedef enum absb_status {
+  ABSB_OK = 0,
+  ABSB_ERR_NULL = -1,           /* a required pointer is NULL                                   */
+  ABSB_ERR_BAD_SHAPE = -2,      /* head counts, lengths, strides, budgets or list width invalid */
+  ABSB_ERR_BAD_BLOCK_SIZE = -3, /* block size not a power of two in [8,128], or not nesting with
+                                   the page size                                                */
+  ABSB_ERR_UNSUPPORTED = -4,    /* head_dim != 128, group size > 8, more than 64 KV heads, dtype */
+  ABSB_ERR_WORKSPACE = -5,      /* workspace NULL, misaligned or smaller than absb_plan reports  */
+  ABSB_ERR_HIP = -6             /* a HIP launch failed (see hipGetLastError)                     */
+} absb_status;
+
+/* Static description of one attention layer.  Host memory. */
+typedef struct absb_layer {
+  int32_t num_q_heads;       /* Hq                                                              */
+  int32_t num_kv_heads;      /* Hkv; Hq % Hkv == 0; G = Hq/Hkv <= 8; Hkv <= 64                   */
+  int32_t head_dim;          /* d; 128                                                          */
+  int32_t page_size;         /* P tokens per physical page; power of two, >= 8                  */
+  int32_t dtype;             /* absb_dtype of q, K, V and out                                   */
+  int32_t reserved0;
+  const int32_t* block_size; /* host [Hkv]: B_h, power of two in [8,128]; B_h | P or P | B_h    */
+  /* K/V cache addressing, in elements: element (page, head, slot, c) of either cache is at
+     page*kv_stride_page + head*kv_stride_head + slot*kv_stride_tok + c (channels contiguous).
+     Every stride must be a multiple of 8 elements (16-byte rows).  "HND" pages
+     [page][Hkv][P][d] are {Hkv*P*d, P*d, d}. */
+  int64_t kv_stride_page, kv_stride_head, kv_stride_tok;
+  float sm_scale;            /* softmax scale; 0 selects 1/sqrt(head_dim) as in Eq. (1)         */
+  int32_t reserved1;
+} absb_layer;
+
+/* One decode step's batch. */
+typedef struct absb_batch {
+  int32_t batch;                /* Bt >= 1                                                      */
+  int32_t pt_stride;            /* row pitch of page_table, >= ceil(max L_b / P)                */
+  const int32_t* seq_lens_host; /* host [Bt]: context length L_b >= 1 (includes the new token)  */
+  const int32_t* seq_lens;      /* device [Bt], same values                                     */
+  const int32_t* page_table;    /* device [Bt][pt_stride]: logical page -> physical page        */
+  const int32_t* cent_off;      /* device [Bt*Hkv+1]: off[s+1] = off[s] + ceil(L_b/B_h)
+                                   (Sec. 3.4 kernel 1); absb_plan computes the host copy        */
+  const int32_t* budget_host;   /* host [Bt]: token budget T_b >= 1 per KV head                 */
+  const int32_t* budget;        /* device [Bt], same values                                     */
+} absb_batch;
+
+/* Sizes derived on the host from a (layer, batch) pair.  Only the host fields of `batch`
+ * are read (seq_lens_host, budget_host); device pointers may be NULL here.
+ *   cent_off_host [Bt*Hkv+1] : prefix sums of N_s = ceil(L_b/B_h)           (may be NULL)
+ *   total_centroids          : off[Bt*Hkv]
+ *   sel_stride               : max_s K_s, K_s = min(N_s, ceil(T_b/B_h)) (Sec. 3.4 kernel 2)
+ *   workspace_bytes          : enough for any entry point below on this (layer, batch) */
+ABSB_API int absb_plan(const absb_layer* layer, const absb_batch* batch, int32_t* cent_off_host,
+                       int64_t* total_centroids, int32_t* sel_stride, size_t* workspace_bytes);
+
+/* Centroid store build (Sec. 2.2 mean pooling; Sec. 3.3 INT4 asymmetric per-channel; Sec. 3.4
+ * flattened layout).  Reads every key of every request once.
+ *   k_cache          : paged K cache (layout above)
+ *   codes [total][d/2] u8 : centroid j of segment s at byte (off[s]+j)*(d/2); byte i holds
+ *                      channel 2i in its low nibble and channel 2i+1 in its high nibble
+ *   qscale [Bt*Hkv][d] f32: per (segment, channel) step (max-min)/15 over that segment's centroids
+ *   qmin   [Bt*Hkv][d] f32: per (segment, channel) minimum (the asymmetric zero-point offset)
+ * A last block shorter than B_h is the mean of its valid keys.  Arithmetic is binary32 in a
+ * fixed order (keys summed in token order, one division, round-half-even codes), so the codes
+ * are reproducible bit for bit. */
+ABSB_API int absb_build_centroids(const absb_layer* layer, const absb_batch* batch, const void* k_cache,
+                                  uint8_t* codes, float* qscale, float* qmin, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/* Estimation (Sec. 2.2 r = q . c^T; Sec. 3.4 kernel 1): one launch over the flattened code array.
+ *   q [Bt][Hq][d]     : queries of this step
+ *   scores [total] i32: S_j = sum_c wq_c * code_jc, where wq is the 16-bit fixed-point image
+ *                       (largest magnitude in [2^14, 2^15]) of w_c = (sum_g q_g[c]) * qscale[s][c].
+ *                       Within a segment S_j ranks the blocks exactly as the dequantized
+ *                       score does (the zero-point term is constant per segment).
+ *   score_exp [Bt*Hkv] i32, optional (NULL ok): e with w ~= wq * 2^e */
+ABSB_API int absb_score(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
+                        const float* qscale, int32_t* scores, int32_t* score_exp, void* stream);
+
+/* Selection (Sec. 3.4 kernel 2): per segment the K_s = min(N_s, ceil(T_b/B_h)) blocks with the
+ * highest score; equal scores go to the lower block index.
+ *   sel_idx [Bt*Hkv][sel_stride] i32: chosen block indices in ascending order, padded with -1
+ *   sel_cnt [Bt*Hkv] i32            : K_s
+ *   sel_stride >= the value absb_plan reports, else ABSB_ERR_BAD_SHAPE */
+ABSB_API int absb_topk(const absb_layer* layer, const absb_batch* batch, const int32_t* scores,
+                       int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/* Attention over selected blocks (Eq. (1) restricted to the selection; Sec. 3.4 kernel 3).
+ * Block j of segment (b,h) covers tokens [j*B_h, min((j+1)*B_h, L_b)); token t lives in
+ * physical page page_table[b][t / P], slot t % P.  K and V rows are read in place.
+ *   sel_idx/sel_cnt : any block list per segment (order free, no duplicates), sel_cnt[s] <=
+ *                     sel_stride; when batch->budget_host is non-NULL also sel_cnt[s] <= K_s
+ *   out [Bt][Hq][d] : attention output in the K/V dtype
+ *   lse [Bt][Hq] f32, optional (NULL ok): natural-log sum of exp of the scaled logits
+ * An empty selection yields out = 0 and lse = -inf.  Accumulation is binary32. */
+ABSB_API int absb_sparse_decode(const absb_layer* layer, const absb_batch* batch, const void* q,
+                                const void* k_cache, const void* v_cache, const int32_t* sel_idx,
+                                const int32_t* sel_cnt, int32_t sel_stride, void* out, float* lse,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* The whole step: score -> topk -> sparse decode, enqueued back to back.  Produces exactly the
+ * selection of absb_score + absb_topk and the output of absb_sparse_decode on it.
+ *   sel_idx_out [Bt*Hkv][plan's sel_stride], sel_cnt_out [Bt*Hkv]: optional copies of the
+ *   selection (NULL ok: kept in the workspace). */
+ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const void* q,
+                               const uint8_t* codes, const float* qscale, const void* k_cache,
+                               const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
+                               int32_t* sel_cnt_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static string for a status code. */
+ABSB_API const char* absb_strerror(int status);
+
+/* Launch-shape knobs for benchmarking sweeps (process-wide; not needed for correct use).
+ *   ABSB_TUNE_SPLIT_TOKENS : tokens per split-K work-group in decode (multiple of 64; 0 = auto)
+ *   ABSB_TUNE_SCORE_CHUNK  : centroids per work-group in score (multiple of 64; 0 = auto)
+ * Returns ABSB_ERR_BAD_SHAPE for an unknown key or an invalid value. */
+enum { ABSB_TUNE_SPLIT_TOKENS = 0, ABSB_TUNE_SCORE_CHUNK = 1, ABSB_TUNE_COUNT_ = 2 };
+ABSB_API int absb_set_tuning(int key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABSB_H */

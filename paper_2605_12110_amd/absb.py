@@ -1,0 +1,206 @@
+"""Thin Python binding of libabsb.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; this module converts torch
+tensors to device pointers, keeps the host-side arrays alive and turns status codes into
+exceptions.  There is no fallback: a missing library or a missing GPU raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libabsb.so")
+
+F16, BF16 = 0, 1
+TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK = 0, 1
+
+OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = ("absb_plan", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
+           "absb_decode_fused", "absb_strerror", "absb_set_tuning")
+
+
+class AbsbError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class _Layer(C.Structure):
+    _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("page_size", C.c_int32), ("dtype", C.c_int32), ("reserved0", C.c_int32),
+                ("block_size", C.POINTER(C.c_int32)),
+                ("kv_stride_page", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64),
+                ("sm_scale", C.c_float), ("reserved1", C.c_int32)]
+
+
+class _Batch(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("pt_stride", C.c_int32),
+                ("seq_lens_host", C.POINTER(C.c_int32)), ("seq_lens", C.c_void_p),
+                ("page_table", C.c_void_p), ("cent_off", C.c_void_p),
+                ("budget_host", C.POINTER(C.c_int32)), ("budget", C.c_void_p)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libabsb.so (built in-tree by paper_2605_12110_amd.build).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                               "(there is no CPU fallback)")
+        lib = C.CDLL(LIB_PATH)
+        lib.absb_strerror.restype = C.c_char_p
+        lib.absb_strerror.argtypes = [C.c_int]
+        for name in EXPORTS:
+            getattr(lib, name)            # fail loudly on a stale library
+        _lib = lib
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return load().absb_strerror(int(status)).decode()
+
+
+def set_tuning(key: int, value: int) -> None:
+    _check(load().absb_set_tuning(C.c_int(key), C.c_int(value)), "absb_set_tuning")
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise AbsbError(status, where)
+
+
+def _ptr(t) -> Optional[C.c_void_p]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _i32_host(a: Optional[Sequence[int]]):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+    return arr, arr.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+@dataclass
+class Layer:
+    """Host description of a layer (mirrors absb_layer)."""
+    num_q_heads: int
+    num_kv_heads: int
+    head_dim: int
+    page_size: int
+    dtype: int
+    block_size: Sequence[int]
+    kv_strides: Sequence[int]          # (page, head, token) in elements
+    sm_scale: float = 0.0
+
+    def c(self) -> _Layer:
+        self._bs, bs_p = _i32_host(self.block_size)
+        sp, sh, st = (int(x) for x in self.kv_strides)
+        return _Layer(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size, self.dtype, 0,
+                      bs_p, sp, sh, st, float(self.sm_scale), 0)
+
+
+@dataclass
+class Batch:
+    """One decode step's batch (mirrors absb_batch).  Host arrays are numpy/sequences, device
+    arrays are int32 torch tensors on the GPU (or None where an entry point does not need them)."""
+    seq_lens_host: Sequence[int]
+    budget_host: Optional[Sequence[int]] = None
+    seq_lens: object = None
+    page_table: object = None
+    cent_off: object = None
+    budget: object = None
+    pt_stride: Optional[int] = None
+
+    def c(self) -> _Batch:
+        self._sl, sl_p = _i32_host(self.seq_lens_host)
+        self._bg, bg_p = _i32_host(self.budget_host)
+        pts = self.pt_stride
+        if pts is None:
+            pts = int(self.page_table.shape[1]) if self.page_table is not None else 0
+        return _Batch(len(self._sl), int(pts), sl_p, _ptr(self.seq_lens), _ptr(self.page_table),
+                      _ptr(self.cent_off), bg_p, _ptr(self.budget))
+
+
+@dataclass
+class PlanResult:
+    cent_off: np.ndarray       # int32 [Bt*Hkv+1]
+    total_centroids: int
+    sel_stride: int
+    workspace_bytes: int
+
+
+def absb_plan(layer: Layer, batch: Batch) -> PlanResult:
+    cl, cb = layer.c(), batch.c()
+    nseg = cb.batch * layer.num_kv_heads
+    off = np.zeros(max(nseg, 0) + 1, dtype=np.int32)
+    total, stride, ws = C.c_int64(0), C.c_int32(0), C.c_size_t(0)
+    _check(load().absb_plan(C.byref(cl), C.byref(cb), off.ctypes.data_as(C.POINTER(C.c_int32)),
+                            C.byref(total), C.byref(stride), C.byref(ws)), "absb_plan")
+    return PlanResult(off, int(total.value), int(stride.value), int(ws.value))
+
+
+def absb_build_centroids(layer: Layer, batch: Batch, k_cache, codes, qscale, qmin, workspace, stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_build_centroids(C.byref(cl), C.byref(cb), _ptr(k_cache), _ptr(codes), _ptr(qscale),
+                                       _ptr(qmin), _ptr(workspace), C.c_size_t(_nbytes(workspace)),
+                                       _stream(stream)), "absb_build_centroids")
+
+
+def absb_score(layer: Layer, batch: Batch, q, codes, qscale, scores, score_exp=None, stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_score(C.byref(cl), C.byref(cb), _ptr(q), _ptr(codes), _ptr(qscale), _ptr(scores),
+                             _ptr(score_exp), _stream(stream)), "absb_score")
+
+
+def absb_topk(layer: Layer, batch: Batch, scores, sel_idx, sel_cnt, sel_stride: int, workspace=None,
+              stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_topk(C.byref(cl), C.byref(cb), _ptr(scores), _ptr(sel_idx), _ptr(sel_cnt),
+                            C.c_int32(sel_stride), _ptr(workspace), C.c_size_t(_nbytes(workspace)),
+                            _stream(stream)), "absb_topk")
+
+
+def absb_sparse_decode(layer: Layer, batch: Batch, q, k_cache, v_cache, sel_idx, sel_cnt, sel_stride: int,
+                       out, lse, workspace, stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_sparse_decode(C.byref(cl), C.byref(cb), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                     _ptr(sel_idx), _ptr(sel_cnt), C.c_int32(sel_stride), _ptr(out), _ptr(lse),
+                                     _ptr(workspace), C.c_size_t(_nbytes(workspace)), _stream(stream)),
+           "absb_sparse_decode")
+
+
+def absb_decode_fused(layer: Layer, batch: Batch, q, codes, qscale, k_cache, v_cache, out, lse=None,
+                      sel_idx_out=None, sel_cnt_out=None, workspace=None, stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_decode_fused(C.byref(cl), C.byref(cb), _ptr(q), _ptr(codes), _ptr(qscale), _ptr(k_cache),
+                                    _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(sel_idx_out), _ptr(sel_cnt_out),
+                                    _ptr(workspace), C.c_size_t(_nbytes(workspace)), _stream(stream)),
+           "absb_decode_fused")
+
+
+def _nbytes(t) -> int:
+    if t is None:
+        return 0
+    return int(t.numel() * t.element_size())

@@ -1,0 +1,276 @@
+// Host side of libabsb.so: argument validation, size planning, workspace carving and the
+// extern "C" entry points.  Nothing here touches the device except through the launchers.
+#include <atomic>
+#include <cmath>
+
+#include "common.h"
+
+namespace absb {
+
+static std::atomic<int> g_tuning[ABSB_TUNE_COUNT_] = {};
+
+int tuning(int key) { return g_tuning[key].load(std::memory_order_relaxed); }
+
+static inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+static inline int ilog2(int64_t v) {
+  int r = 0;
+  while ((int64_t(1) << (r + 1)) <= v) ++r;
+  return r;
+}
+static inline size_t align256(size_t v) { return (v + 255) & ~size_t(255); }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget, int32_t sel_stride_in,
+              Geometry* geo, Plan* pl) {
+  if (!layer || !batch) return ABSB_ERR_NULL;
+  if (!layer->block_size || !batch->seq_lens_host) return ABSB_ERR_NULL;
+  if (need_budget && !batch->budget_host) return ABSB_ERR_NULL;
+  if (layer->head_dim != ABSB_HEAD_DIM) return ABSB_ERR_UNSUPPORTED;
+  if (layer->dtype != ABSB_F16 && layer->dtype != ABSB_BF16) return ABSB_ERR_UNSUPPORTED;
+  const int Hq = layer->num_q_heads, Hkv = layer->num_kv_heads;
+  if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0) return ABSB_ERR_BAD_SHAPE;
+  if (Hq / Hkv > ABSB_MAX_GROUP || Hkv > ABSB_MAX_KV_HEADS) return ABSB_ERR_UNSUPPORTED;
+  const int P = layer->page_size;
+  if (!is_pow2(P) || P < 8 || P > 65536) return ABSB_ERR_BAD_SHAPE;
+  const int64_t sp = layer->kv_stride_page, sh = layer->kv_stride_head, st = layer->kv_stride_tok;
+  if (sp <= 0 || sh <= 0 || st < ABSB_HEAD_DIM || (sp % 8) || (sh % 8) || (st % 8)) return ABSB_ERR_BAD_SHAPE;
+  if (!(layer->sm_scale >= 0.0f) || std::isinf(layer->sm_scale)) return ABSB_ERR_BAD_SHAPE;
+  const int Bt = batch->batch;
+  if (Bt < 1 || (int64_t)Bt * Hkv > 65535) return ABSB_ERR_BAD_SHAPE;  // segments index grid.y
+
+  Geometry g = {};
+  g.Bt = Bt;
+  g.Hq = Hq;
+  g.Hkv = Hkv;
+  g.G = Hq / Hkv;
+  g.log2_page = ilog2(P);
+  g.pt_stride = batch->pt_stride;
+  g.s_page = sp;
+  g.s_head = sh;
+  g.s_tok = st;
+  for (int h = 0; h < Hkv; ++h) {
+    const int B = layer->block_size[h];
+    if (!is_pow2(B) || B < 8 || B > 128) return ABSB_ERR_BAD_BLOCK_SIZE;
+    // both are powers of two, so B | P or P | B holds: blocks never straddle a page partially
+    g.heads.log2_block[h] = (uint8_t)ilog2(B);
+  }
+
+  Plan p = {};
+  p.nseg = Bt * Hkv;
+  int64_t max_len = 0;
+  for (int b = 0; b < Bt; ++b) {
+    const int64_t L = batch->seq_lens_host[b];
+    if (L < 1) return ABSB_ERR_BAD_SHAPE;
+    if (L > max_len) max_len = L;
+    if (batch->budget_host && batch->budget_host[b] < 1) return ABSB_ERR_BAD_SHAPE;
+    for (int h = 0; h < Hkv; ++h) {
+      const int64_t B = layer->block_size[h];
+      const int64_t N = ceil_div(L, B);
+      int64_t K = N;
+      if (batch->budget_host) {
+        const int64_t kb = ceil_div(batch->budget_host[b], B);
+        if (kb < K) K = kb;
+        if (K > p.sel_stride) p.sel_stride = (int32_t)K;
+      }
+      if (sel_stride_in > 0 && sel_stride_in < K) K = sel_stride_in;
+      p.total += N;
+      if (N > p.max_blocks) p.max_blocks = (int32_t)N;
+      const int64_t tok = K * B;
+      if (tok > p.max_tokens) p.max_tokens = tok;
+      p.sum_tokens += tok;
+    }
+  }
+  if (!batch->budget_host) p.sel_stride = p.max_blocks;
+  if (p.total >= (int64_t(1) << 31) - 1) return ABSB_ERR_BAD_SHAPE;
+  if ((int64_t)batch->pt_stride < ceil_div(max_len, P)) return ABSB_ERR_BAD_SHAPE;
+
+  // split-K shape: enough work-groups to cover the chip a few times over, 64-token granules
+  int st_tok = tuning(ABSB_TUNE_SPLIT_TOKENS);
+  if (st_tok <= 0) {
+    const int64_t target_wgs = 1024;
+    st_tok = (int)(ceil_div(ceil_div(p.sum_tokens, target_wgs), 64) * 64);
+    if (st_tok < 64) st_tok = 64;
+    if (st_tok > 1024) st_tok = 1024;
+  }
+  p.split_tokens = st_tok;
+  p.max_splits = (int32_t)ceil_div(p.max_tokens, st_tok);
+  if (p.max_splits < 1) p.max_splits = 1;
+  if (p.max_splits > 65535) return ABSB_ERR_BAD_SHAPE;
+
+  int sc = tuning(ABSB_TUNE_SCORE_CHUNK);
+  p.score_chunk = sc > 0 ? sc : 256;
+  p.build_chunk = 64;
+  p.build_max_chunks = (int32_t)ceil_div(p.max_blocks, p.build_chunk);
+
+  // workspace: the three users never run concurrently on one workspace, so they overlap
+  size_t o = 0;
+  p.ws_scores = o;
+  o += align256((size_t)p.total * 4);
+  p.ws_sel_idx = o;
+  o += align256((size_t)p.nseg * (size_t)(p.sel_stride > 0 ? p.sel_stride : 1) * 4);
+  p.ws_sel_cnt = o;
+  o += align256((size_t)p.nseg * 4);
+  const size_t fused_head = o;
+  p.ws_part_o = o;
+  o += align256((size_t)p.nseg * p.max_splits * g.G * ABSB_HEAD_DIM * 4);
+  p.ws_part_ml = o;
+  o += align256((size_t)p.nseg * p.max_splits * g.G * 2 * 4);
+  p.ws_fused_bytes = o;
+  p.ws_decode_bytes = o;  // the stand-alone decode uses the same offsets (the head is left unused)
+  (void)fused_head;
+  size_t bo = 0;
+  p.ws_cent = bo;
+  bo += align256((size_t)p.total * ABSB_HEAD_DIM * 4);
+  p.ws_minmax = bo;
+  bo += align256((size_t)p.nseg * p.build_max_chunks * 2 * ABSB_HEAD_DIM * 4);
+  p.ws_qinv = bo;
+  bo += align256((size_t)p.nseg * ABSB_HEAD_DIM * 4);
+  p.ws_build_bytes = bo;
+  p.ws_bytes = p.ws_fused_bytes > p.ws_build_bytes ? p.ws_fused_bytes : p.ws_build_bytes;
+
+  if (geo) *geo = g;
+  if (pl) *pl = p;
+  return ABSB_OK;
+}
+
+static int check_ws(const void* ws, size_t have, size_t need) {
+  if (need == 0) return ABSB_OK;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || have < need) return ABSB_ERR_WORKSPACE;
+  return ABSB_OK;
+}
+
+static float resolve_scale(const absb_layer* layer) {
+  return layer->sm_scale > 0.0f ? layer->sm_scale : 1.0f / std::sqrt((float)layer->head_dim);
+}
+
+}  // namespace absb
+
+using namespace absb;
+
+extern "C" {
+
+int absb_plan(const absb_layer* layer, const absb_batch* batch, int32_t* cent_off_host,
+              int64_t* total_centroids, int32_t* sel_stride, size_t* workspace_bytes) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (cent_off_host) {
+    int32_t acc = 0;
+    cent_off_host[0] = 0;
+    for (int b = 0; b < g.Bt; ++b)
+      for (int h = 0; h < g.Hkv; ++h) {
+        const int64_t B = layer->block_size[h];
+        acc += (int32_t)((batch->seq_lens_host[b] + B - 1) / B);
+        cent_off_host[b * g.Hkv + h + 1] = acc;
+      }
+  }
+  if (total_centroids) *total_centroids = p.total;
+  if (sel_stride) *sel_stride = p.sel_stride;
+  if (workspace_bytes) *workspace_bytes = p.ws_bytes;
+  return ABSB_OK;
+}
+
+int absb_build_centroids(const absb_layer* layer, const absb_batch* batch, const void* k_cache, uint8_t* codes,
+                         float* qscale, float* qmin, void* workspace, size_t workspace_bytes, void* stream) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!k_cache || !codes || !qscale || !qmin || !batch->seq_lens || !batch->page_table || !batch->cent_off)
+    return ABSB_ERR_NULL;
+  rc = check_ws(workspace, workspace_bytes, p.ws_build_bytes);
+  if (rc != ABSB_OK) return rc;
+  return launch_build(g, p, layer->dtype, k_cache, batch->page_table, batch->seq_lens, batch->cent_off, codes,
+                      qscale, qmin, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+int absb_score(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
+               const float* qscale, int32_t* scores, int32_t* score_exp, void* stream) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!q || !codes || !qscale || !scores || !batch->cent_off) return ABSB_ERR_NULL;
+  return launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, scores, score_exp,
+                      static_cast<hipStream_t>(stream));
+}
+
+int absb_topk(const absb_layer* layer, const absb_batch* batch, const int32_t* scores, int32_t* sel_idx,
+              int32_t* sel_cnt, int32_t sel_stride, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;  // the selection needs no scratch memory
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, true, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!scores || !sel_idx || !sel_cnt || !batch->cent_off || !batch->budget) return ABSB_ERR_NULL;
+  if (sel_stride < p.sel_stride) return ABSB_ERR_BAD_SHAPE;
+  return launch_topk(g, p, scores, batch->cent_off, batch->budget, sel_idx, sel_cnt, sel_stride,
+                     static_cast<hipStream_t>(stream));
+}
+
+int absb_sparse_decode(const absb_layer* layer, const absb_batch* batch, const void* q, const void* k_cache,
+                       const void* v_cache, const int32_t* sel_idx, const int32_t* sel_cnt, int32_t sel_stride,
+                       void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  if (sel_stride < 1) return layer && batch ? ABSB_ERR_BAD_SHAPE : ABSB_ERR_NULL;
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, sel_stride, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!q || !k_cache || !v_cache || !sel_idx || !sel_cnt || !out || !batch->seq_lens || !batch->page_table)
+    return ABSB_ERR_NULL;
+  rc = check_ws(workspace, workspace_bytes, p.ws_decode_bytes);
+  if (rc != ABSB_OK) return rc;
+  return launch_decode(g, p, layer->dtype, resolve_scale(layer), q, k_cache, v_cache, batch->page_table,
+                       batch->seq_lens, sel_idx, sel_cnt, sel_stride, out, lse, static_cast<char*>(workspace),
+                       static_cast<hipStream_t>(stream));
+}
+
+int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
+                      const float* qscale, const void* k_cache, const void* v_cache, void* out, float* lse,
+                      int32_t* sel_idx_out, int32_t* sel_cnt_out, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, true, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!q || !codes || !qscale || !k_cache || !v_cache || !out || !batch->seq_lens || !batch->page_table ||
+      !batch->cent_off || !batch->budget)
+    return ABSB_ERR_NULL;
+  rc = check_ws(workspace, workspace_bytes, p.ws_fused_bytes);
+  if (rc != ABSB_OK) return rc;
+  char* ws = static_cast<char*>(workspace);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int32_t* scores = reinterpret_cast<int32_t*>(ws + p.ws_scores);
+  int32_t* sel_idx = sel_idx_out ? sel_idx_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_idx);
+  int32_t* sel_cnt = sel_cnt_out ? sel_cnt_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_cnt);
+  rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, scores, nullptr, st);
+  if (rc != ABSB_OK) return rc;
+  rc = launch_topk(g, p, scores, batch->cent_off, batch->budget, sel_idx, sel_cnt, p.sel_stride, st);
+  if (rc != ABSB_OK) return rc;
+  return launch_decode(g, p, layer->dtype, resolve_scale(layer), q, k_cache, v_cache, batch->page_table,
+                       batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, st);
+}
+
+const char* absb_strerror(int status) {
+  switch (status) {
+    case ABSB_OK: return "ok";
+    case ABSB_ERR_NULL: return "a required pointer is NULL";
+    case ABSB_ERR_BAD_SHAPE: return "invalid shape, length, stride, budget or list width";
+    case ABSB_ERR_BAD_BLOCK_SIZE: return "block size must be a power of two in [8,128]";
+    case ABSB_ERR_UNSUPPORTED: return "unsupported configuration (head_dim, group size, head count or dtype)";
+    case ABSB_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case ABSB_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int absb_set_tuning(int key, int value) {
+  if (key < 0 || key >= ABSB_TUNE_COUNT_ || value < 0) return ABSB_ERR_BAD_SHAPE;
+  if (value % 64 != 0) return ABSB_ERR_BAD_SHAPE;
+  g_tuning[key].store(value, std::memory_order_relaxed);
+  return ABSB_OK;
+}
+
+}  // extern "C"

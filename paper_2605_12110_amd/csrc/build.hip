@@ -1,0 +1,207 @@
+// Centroid store build: block means (mean pooling, Sec. 2.2), per-channel asymmetric INT4
+// quantization (Sec. 3.3) and the flattened, prefix-sum-delimited code array (Sec. 3.4, kernel 1).
+// Runs once per context (prefill side), reads every key once.
+//
+// Arithmetic is fixed so that the 4-bit codes are reproducible bit for bit: binary32 running sum
+// of a block's keys in token order, one IEEE division by the number of valid tokens, exact
+// min/max per (segment, channel), scale = (max-min)/15 and 15/(max-min) as two IEEE divisions,
+// code = clamp(round-half-even((c - min) * (15/(max-min)))).  Compiled with -ffp-contract=off.
+//
+// Three launches:
+//   1. means: a 16-lane row-group owns a block (each lane 8 channels = one 128-bit load per key),
+//      walks its tokens in order, writes the binary32 centroid to the workspace and folds it into
+//      per-work-group channel minima/maxima;
+//   2. params: reduces the partial extrema per segment and writes qscale, qmin (and 15/range);
+//   3. codes: quantizes the centroids, eight channels per lane packed into one 32-bit store.
+#include "common.h"
+
+namespace absb {
+
+struct BuildParams {
+  const uint16_t* k;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  const int32_t* cent_off;
+  float* cent;     // [total][128]
+  float* minmax;   // [nseg][max_chunks][2][128]
+  float* qinv;     // [nseg][128]
+  float* qscale;   // [nseg][128]
+  float* qmin;     // [nseg][128]
+  uint8_t* codes;  // [total][64]
+  int32_t chunk, max_chunks;
+  Geometry g;
+};
+
+constexpr int BUILD_THREADS = 256;
+constexpr int BUILD_GROUPS = BUILD_THREADS / 16;
+
+template <int DT>
+__global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams p) {
+  const int s = blockIdx.y, chunk = blockIdx.x;
+  const int off = p.cent_off[s];
+  const int N = p.cent_off[s + 1] - off;
+  const int j0 = chunk * p.chunk;
+  if (j0 >= N) return;
+  const int jend = min(N, j0 + p.chunk);
+  const int b = s / p.g.Hkv, h = s % p.g.Hkv;
+  const int lb = p.g.heads.log2_block[h], lP = p.g.log2_page;
+  const int B = 1 << lb;
+  const int L = p.seq_lens[b];
+  const int tid = threadIdx.x, grp = tid >> 4, li = tid & 15;
+  const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
+  const size_t lane_off = (size_t)h * p.g.s_head + (size_t)li * 8;
+
+  float mn[8], mx[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    mn[c] = __builtin_inff();
+    mx[c] = -__builtin_inff();
+  }
+
+  for (int j = j0 + grp; j < jend; j += BUILD_GROUPS) {
+    const int t0 = j << lb;
+    const int n = min(B, L - t0);
+    float sum[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) sum[c] = 0.0f;
+    for (int i = 0; i < n; i += 4) {
+      uint4 row[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int t = min(t0 + i + r, L - 1);
+        const int page = pt[t >> lP];
+        row[r] = *reinterpret_cast<const uint4*>(p.k + (size_t)page * p.g.s_page + lane_off +
+                                                 (size_t)(t & ((1 << lP) - 1)) * p.g.s_tok);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (i + r < n) {
+          const uint32_t w[4] = {row[r].x, row[r].y, row[r].z, row[r].w};
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            sum[2 * c] = sum[2 * c] + Elem<DT>::lo(w[c]);
+            sum[2 * c + 1] = sum[2 * c + 1] + Elem<DT>::hi(w[c]);
+          }
+        }
+      }
+    }
+    const float fn = (float)n;
+    float cen[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      cen[c] = sum[c] / fn;
+      mn[c] = fminf(mn[c], cen[c]);
+      mx[c] = fmaxf(mx[c], cen[c]);
+    }
+    float4* dst = reinterpret_cast<float4*>(p.cent + ((size_t)off + j) * ABSB_HEAD_DIM + li * 8);
+    dst[0] = make_float4(cen[0], cen[1], cen[2], cen[3]);
+    dst[1] = make_float4(cen[4], cen[5], cen[6], cen[7]);
+  }
+
+  // fold the 16 row-groups: channel ch = li*8 + c
+  __shared__ float s_mn[BUILD_GROUPS][ABSB_HEAD_DIM], s_mx[BUILD_GROUPS][ABSB_HEAD_DIM];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    s_mn[grp][li * 8 + c] = mn[c];
+    s_mx[grp][li * 8 + c] = mx[c];
+  }
+  __syncthreads();
+  if (tid < ABSB_HEAD_DIM) {
+    float a = s_mn[0][tid], z = s_mx[0][tid];
+    for (int g2 = 1; g2 < BUILD_GROUPS; ++g2) {
+      a = fminf(a, s_mn[g2][tid]);
+      z = fmaxf(z, s_mx[g2][tid]);
+    }
+    float* dst = p.minmax + ((size_t)s * p.max_chunks + chunk) * 2 * ABSB_HEAD_DIM;
+    dst[tid] = a;
+    dst[ABSB_HEAD_DIM + tid] = z;
+  }
+}
+
+__global__ __launch_bounds__(ABSB_HEAD_DIM) void build_params_kernel(BuildParams p) {
+  const int s = blockIdx.x, ch = threadIdx.x;
+  const int N = p.cent_off[s + 1] - p.cent_off[s];
+  const int nchunks = (N + p.chunk - 1) / p.chunk;
+  float mn = __builtin_inff(), mx = -__builtin_inff();
+  for (int i = 0; i < nchunks; ++i) {
+    const float* src = p.minmax + ((size_t)s * p.max_chunks + i) * 2 * ABSB_HEAD_DIM;
+    mn = fminf(mn, src[ch]);
+    mx = fmaxf(mx, src[ABSB_HEAD_DIM + ch]);
+  }
+  const float rng = mx - mn;
+  float sc = 0.0f, inv = 0.0f;
+  if (rng > 0.0f) {
+    sc = rng / 15.0f;
+    inv = 15.0f / rng;
+  }
+  if (N == 0) mn = 0.0f;
+  p.qscale[(size_t)s * ABSB_HEAD_DIM + ch] = sc;
+  p.qmin[(size_t)s * ABSB_HEAD_DIM + ch] = mn;
+  p.qinv[(size_t)s * ABSB_HEAD_DIM + ch] = inv;
+}
+
+__global__ __launch_bounds__(BUILD_THREADS) void build_codes_kernel(BuildParams p) {
+  const int s = blockIdx.y;
+  const int off = p.cent_off[s];
+  const int N = p.cent_off[s + 1] - off;
+  const int j0 = blockIdx.x * p.chunk;
+  if (j0 >= N) return;
+  const int jend = min(N, j0 + p.chunk);
+  const int tid = threadIdx.x, grp = tid >> 4, li = tid & 15;
+  float mn[8], inv[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    mn[c] = p.qmin[(size_t)s * ABSB_HEAD_DIM + li * 8 + c];
+    inv[c] = p.qinv[(size_t)s * ABSB_HEAD_DIM + li * 8 + c];
+  }
+  for (int j = j0 + grp; j < jend; j += BUILD_GROUPS) {
+    const float4* src = reinterpret_cast<const float4*>(p.cent + ((size_t)off + j) * ABSB_HEAD_DIM + li * 8);
+    const float4 a = src[0], z = src[1];
+    const float cen[8] = {a.x, a.y, a.z, a.w, z.x, z.y, z.z, z.w};
+    uint32_t packed = 0;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const float x = cen[c] - mn[c];
+      const float y = x * inv[c];
+      float r = __builtin_rintf(y);
+      r = fminf(fmaxf(r, 0.0f), 15.0f);
+      packed |= (uint32_t)r << (4 * c);
+    }
+    // byte i of a centroid holds channel 2i (low nibble) and 2i+1 (high nibble): little-endian
+    // nibble n of this word is channel li*8 + n
+    *reinterpret_cast<uint32_t*>(p.codes + ((size_t)off + j) * 64 + li * 4) = packed;
+  }
+}
+
+int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cache, const int32_t* page_table,
+                 const int32_t* seq_lens, const int32_t* cent_off, uint8_t* codes, float* qscale, float* qmin,
+                 char* ws, hipStream_t stream) {
+  BuildParams p;
+  p.k = static_cast<const uint16_t*>(k_cache);
+  p.page_table = page_table;
+  p.seq_lens = seq_lens;
+  p.cent_off = cent_off;
+  p.cent = reinterpret_cast<float*>(ws + pl.ws_cent);
+  p.minmax = reinterpret_cast<float*>(ws + pl.ws_minmax);
+  p.qinv = reinterpret_cast<float*>(ws + pl.ws_qinv);
+  p.qscale = qscale;
+  p.qmin = qmin;
+  p.codes = codes;
+  p.chunk = pl.build_chunk;
+  p.max_chunks = pl.build_max_chunks;
+  p.g = g;
+  dim3 grid((unsigned)pl.build_max_chunks, (unsigned)pl.nseg);
+  if (dtype == ABSB_F16)
+    hipLaunchKernelGGL(build_means_kernel<ABSB_F16>, grid, dim3(BUILD_THREADS), 0, stream, p);
+  else
+    hipLaunchKernelGGL(build_means_kernel<ABSB_BF16>, grid, dim3(BUILD_THREADS), 0, stream, p);
+  int rc = check_launch();
+  if (rc != ABSB_OK) return rc;
+  hipLaunchKernelGGL(build_params_kernel, dim3((unsigned)pl.nseg), dim3(ABSB_HEAD_DIM), 0, stream, p);
+  rc = check_launch();
+  if (rc != ABSB_OK) return rc;
+  hipLaunchKernelGGL(build_codes_kernel, grid, dim3(BUILD_THREADS), 0, stream, p);
+  return check_launch();
+}
+
+}  // namespace absb

@@ -1,0 +1,148 @@
+// Internal declarations shared by the translation units of libabsb.so (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "absb.h"
+
+#define ABSB_HEAD_DIM 128
+#define ABSB_MAX_KV_HEADS 64
+#define ABSB_MAX_GROUP 8
+#define ABSB_HIDDEN __attribute__((visibility("hidden")))
+
+namespace absb {
+
+// Per-KV-head block sizes as log2, passed to kernels by value.
+struct HeadTable {
+  uint8_t log2_block[ABSB_MAX_KV_HEADS];
+};
+
+// Shape of the layer and of the paged cache, passed to kernels by value.
+struct Geometry {
+  int32_t Bt, Hq, Hkv, G;
+  int32_t log2_page;  // P = 1 << log2_page
+  int32_t pt_stride;
+  int64_t s_page, s_head, s_tok;  // element strides of the K/V caches
+  HeadTable heads;
+};
+
+// Host-side sizes derived from (layer, batch).
+struct Plan {
+  int32_t nseg;
+  int64_t total;            // total centroids
+  int32_t max_blocks;       // max_s N_s
+  int32_t sel_stride;       // max_s K_s (0 when no budget was given)
+  int64_t max_tokens;       // max_s (upper bound of selected tokens of a segment)
+  int64_t sum_tokens;       // sum_s of the same bound
+  int32_t split_tokens;     // tokens per split-K work-group
+  int32_t max_splits;       // grid.x of the decode kernels
+  int32_t score_chunk;      // centroids per work-group in score
+  int32_t build_chunk;      // blocks per work-group in build
+  int32_t build_max_chunks; // max_s ceil(N_s / build_chunk)
+  // workspace carving (byte offsets, 256-aligned)
+  size_t ws_part_o, ws_part_ml;                   // decode partials
+  size_t ws_scores, ws_sel_idx, ws_sel_cnt;       // fused step intermediates
+  size_t ws_cent, ws_minmax, ws_qinv;             // build intermediates
+  size_t ws_decode_bytes, ws_fused_bytes, ws_build_bytes, ws_bytes;
+};
+
+// Validates the host-visible arguments and fills geometry + plan.  `need_budget`: budget_host
+// must be present (topk, fused); otherwise it is used when present.  `sel_stride_in` > 0 bounds
+// the selected-token estimate for the stand-alone decode.
+ABSB_HIDDEN int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget,
+                          int32_t sel_stride_in, Geometry* geo, Plan* plan);
+ABSB_HIDDEN int tuning(int key);
+
+// Launchers (one per stage); all enqueue on `stream` and return an absb_status.
+ABSB_HIDDEN int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cache,
+                             const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
+                             uint8_t* codes, float* qscale, float* qmin, char* ws, hipStream_t stream);
+ABSB_HIDDEN int launch_score(const Geometry& g, const Plan& pl, int dtype, const void* q, const uint8_t* codes,
+                             const float* qscale, const int32_t* cent_off, int32_t* scores, int32_t* score_exp,
+                             hipStream_t stream);
+ABSB_HIDDEN int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const int32_t* cent_off,
+                            const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride,
+                            hipStream_t stream);
+ABSB_HIDDEN int launch_decode(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
+                              const void* k_cache, const void* v_cache, const int32_t* page_table,
+                              const int32_t* seq_lens, const int32_t* sel_idx, const int32_t* sel_cnt,
+                              int32_t sel_stride, void* out, float* lse, char* ws, hipStream_t stream);
+
+inline int check_launch() { return hipGetLastError() == hipSuccess ? ABSB_OK : ABSB_ERR_HIP; }
+
+// ------------------------------------------------------------------ device helpers
+#ifdef __HIPCC__
+template <typename To, typename From>
+__device__ __forceinline__ To bitcast(From v) {
+  return __builtin_bit_cast(To, v);
+}
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// Element traits of the two storage formats.  A 32-bit word holds two consecutive channels
+// (low half = even channel).
+template <int DT>
+struct Elem;
+
+template <>
+struct Elem<ABSB_F16> {
+  static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2(bitcast<half2_t>(a), bitcast<half2_t>(b), c, false);
+  }
+  static __device__ __forceinline__ float lo(uint32_t v) { return (float)bitcast<half2_t>(v).x; }
+  static __device__ __forceinline__ float hi(uint32_t v) { return (float)bitcast<half2_t>(v).y; }
+  static __device__ __forceinline__ float widen(uint16_t v) { return (float)bitcast<_Float16>(v); }
+  static __device__ __forceinline__ uint16_t narrow(float f) { return bitcast<uint16_t>((_Float16)f); }
+};
+
+template <>
+struct Elem<ABSB_BF16> {
+  static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(bitcast<bf16x2_t>(a), bitcast<bf16x2_t>(b), c, false);
+  }
+  static __device__ __forceinline__ float lo(uint32_t v) { return bitcast<float>(v << 16); }
+  static __device__ __forceinline__ float hi(uint32_t v) { return bitcast<float>(v & 0xffff0000u); }
+  static __device__ __forceinline__ float widen(uint16_t v) { return bitcast<float>((uint32_t)v << 16); }
+  static __device__ __forceinline__ uint16_t narrow(float f) {  // round to nearest, ties to even
+    uint32_t u = bitcast<uint32_t>(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+  }
+};
+
+// DPP controls (GFX9 encoding).
+enum : int {
+  DPP_QUAD_XOR1 = 0xB1,        // quad_perm:[1,0,3,2]
+  DPP_QUAD_XOR2 = 0x4E,        // quad_perm:[2,3,0,1]
+  DPP_ROW_MIRROR = 0x140,      // lane i <- lane 15-i within a row of 16
+  DPP_ROW_HALF_MIRROR = 0x141  // lane i <- lane 7-i within a half row of 8
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return bitcast<float>(__builtin_amdgcn_update_dpp(0, bitcast<int>(v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the same bits.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f<DPP_QUAD_XOR1>(v);
+  v += dpp_f<DPP_QUAD_XOR2>(v);
+  v += dpp_f<DPP_ROW_HALF_MIRROR>(v);
+  v += dpp_f<DPP_ROW_MIRROR>(v);
+  return v;
+}
+__device__ __forceinline__ int quad_sum(int v) {
+  v += dpp_i<DPP_QUAD_XOR1>(v);
+  v += dpp_i<DPP_QUAD_XOR2>(v);
+  return v;
+}
+#endif  // __HIPCC__
+
+}  // namespace absb

@@ -1,0 +1,271 @@
+// Attention over the selected blocks (Sec. 3.4, kernel 3; Eq. (1) restricted to the selection).
+//
+// A selected logical block j of KV head h covers tokens [j*B_h, (j+1)*B_h); token t sits in
+// physical page page_table[b][t / P] at slot t % P.  The kernel walks the selection as a virtual
+// token sequence (position -> block list entry -> token -> page/slot) and reads K and V rows in
+// place: no gather, no per-head page list, any mix of block sizes in one launch.
+//
+// Split-K flash decoding: work-group (split, segment) handles `split_tokens` consecutive positions
+// of its segment's selection and emits an unnormalised partial (m, l, o~) for the G query heads
+// of the group; a second kernel merges the partials with the log-sum-exp rule.
+//
+// Thread mapping: a K/V row is 256 bytes = 16 lanes x 16 bytes, so one wave load instruction
+// covers four whole rows with 128-bit loads.  Each 16-lane row-group owns one row per step, keeps
+// its own online-softmax state for the G heads (no cross-lane traffic in the main loop except the
+// 16-lane DPP reduction of q.k), and each lane accumulates the 8 output channels it loaded.
+#include "common.h"
+
+namespace absb {
+
+struct DecodeParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  const int32_t* sel_idx;
+  const int32_t* sel_cnt;
+  float* part_o;   // [nseg][max_splits][G][128]
+  float* part_ml;  // [nseg][max_splits][G][2]  (running max in log2 units, sum)
+  void* out;       // [Bt][Hq][128]
+  float* lse;      // [Bt][Hq] or null
+  int32_t sel_stride, split_tokens, max_splits;
+  float scale_log2;  // sm_scale * log2(e)
+  Geometry g;
+};
+
+constexpr float M_INIT = -1.0e30f;  // finite stand-in for "no token seen yet"
+constexpr int DEC_THREADS = 256;
+constexpr int DEC_WAVES = DEC_THREADS / 64;
+constexpr int ROWS_PER_WAVE_STEP = 16;  // 4 row-groups x 4 rows
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <int DT, int G>
+__global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParams p) {
+  const int s = blockIdx.y, split = blockIdx.x;
+  const int b = s / p.g.Hkv, h = s % p.g.Hkv;
+  const int lb = p.g.heads.log2_block[h];
+  // never beyond what the launch covers (a list longer than promised is cut, not overrun)
+  const int ntok = min(p.sel_cnt[s] << lb, p.max_splits * p.split_tokens);
+  const int pos_begin = split * p.split_tokens;
+  if (pos_begin >= ntok) return;
+  const int pos_end = min(ntok, pos_begin + p.split_tokens);
+  const int L = p.seq_lens[b];
+  const int lP = p.g.log2_page;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, grp = lane >> 4, li = lane & 15;
+
+  const int32_t* sel = p.sel_idx + (size_t)s * p.sel_stride;
+  const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
+  const size_t lane_off = (size_t)h * p.g.s_head + (size_t)li * 8;
+
+  // the lane's 8 channels of the G queries, as packed pairs
+  uint32_t qr[G][4];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const uint4 t = *reinterpret_cast<const uint4*>(p.q + ((size_t)b * p.g.Hq + (size_t)h * G + g) * ABSB_HEAD_DIM +
+                                                    li * 8);
+    qr[g][0] = t.x;
+    qr[g][1] = t.y;
+    qr[g][2] = t.z;
+    qr[g][3] = t.w;
+  }
+
+  float m[G], l[G], o[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = M_INIT;
+    l[g] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[g][c] = 0.0f;
+  }
+
+  for (int base = pos_begin + wave * ROWS_PER_WAVE_STEP; base < pos_end; base += DEC_WAVES * ROWS_PER_WAVE_STEP) {
+    // ---- block -> page mapping for this group's four rows
+    size_t off[4];
+    bool valid[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int pos = base + r * 4 + grp;
+      const bool in = pos < pos_end;
+      const int pc = in ? pos : pos_begin;  // always a position of the list
+      const int t = (sel[pc >> lb] << lb) + (pc & ((1 << lb) - 1));
+      valid[r] = in && t < L;               // a selected last block may be partial
+      const int tc = min(t, L - 1);         // addresses stay inside the request's pages
+      const int page = pt[tc >> lP];
+      off[r] = (size_t)page * p.g.s_page + lane_off + (size_t)(tc & ((1 << lP) - 1)) * p.g.s_tok;
+    }
+    uint4 kk[4], vv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) kk[r] = *reinterpret_cast<const uint4*>(p.k + off[r]);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) vv[r] = *reinterpret_cast<const uint4*>(p.v + off[r]);
+
+    // ---- logits (log2 units) of the four rows for the G heads
+    float sc[G][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float a = Elem<DT>::dot2(qr[g][0], kk[r].x, 0.0f);
+        a = Elem<DT>::dot2(qr[g][1], kk[r].y, a);
+        a = Elem<DT>::dot2(qr[g][2], kk[r].z, a);
+        a = Elem<DT>::dot2(qr[g][3], kk[r].w, a);
+        a = row16_sum(a);
+        sc[g][r] = valid[r] ? a * p.scale_log2 : -__builtin_inff();
+      }
+    }
+
+    // ---- online softmax over the tile and P.V
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float mn = fmaxf(fmaxf(m[g], fmaxf(sc[g][0], sc[g][1])), fmaxf(sc[g][2], sc[g][3]));
+      const float alpha = fast_exp2(m[g] - mn);
+      float pr[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pr[r] = fast_exp2(sc[g][r] - mn);
+      l[g] = __builtin_fmaf(l[g], alpha, (pr[0] + pr[1]) + (pr[2] + pr[3]));
+      m[g] = mn;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[g][c] *= alpha;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint32_t vw[4] = {vv[r].x, vv[r].y, vv[r].z, vv[r].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          o[g][2 * c] = __builtin_fmaf(pr[r], Elem<DT>::lo(vw[c]), o[g][2 * c]);
+          o[g][2 * c + 1] = __builtin_fmaf(pr[r], Elem<DT>::hi(vw[c]), o[g][2 * c + 1]);
+        }
+      }
+    }
+  }
+
+  // ---- merge the four row-groups of the wave (xor-shuffles over lanes 16 and 32 apart)
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int d = 16; d <= 32; d <<= 1) {
+      const float m_o = __shfl_xor(m[g], d);
+      const float mn = fmaxf(m[g], m_o);
+      const float a_me = fast_exp2(m[g] - mn), a_ot = fast_exp2(m_o - mn);
+      l[g] = l[g] * a_me + __shfl_xor(l[g], d) * a_ot;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[g][c] = o[g][c] * a_me + __shfl_xor(o[g][c], d) * a_ot;
+      m[g] = mn;
+    }
+  }
+
+  // ---- merge the waves through LDS, write the split's partial
+  __shared__ float s_o[DEC_WAVES][G][ABSB_HEAD_DIM];
+  __shared__ float s_m[DEC_WAVES][G], s_l[DEC_WAVES][G];
+  if (grp == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) s_o[wave][g][li * 8 + c] = o[g][c];
+      if (li == 0) {
+        s_m[wave][g] = m[g];
+        s_l[wave][g] = l[g];
+      }
+    }
+  }
+  __syncthreads();
+  const size_t slot = (size_t)s * p.max_splits + split;
+  for (int i = tid; i < G * ABSB_HEAD_DIM; i += DEC_THREADS) {
+    const int g = i >> 7, c = i & 127;
+    float M = s_m[0][g];
+#pragma unroll
+    for (int w = 1; w < DEC_WAVES; ++w) M = fmaxf(M, s_m[w][g]);
+    float Lsum = 0.0f, O = 0.0f;
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) {
+      const float a = fast_exp2(s_m[w][g] - M);
+      Lsum = __builtin_fmaf(s_l[w][g], a, Lsum);
+      O = __builtin_fmaf(s_o[w][g][c], a, O);
+    }
+    p.part_o[(slot * G + g) * ABSB_HEAD_DIM + c] = O;
+    if (c == 0) {
+      p.part_ml[(slot * G + g) * 2 + 0] = M;
+      p.part_ml[(slot * G + g) * 2 + 1] = Lsum;
+    }
+  }
+}
+
+// Log-sum-exp merge of a segment's split partials; one work-group per segment, one thread per
+// (query head of the group, channel).
+template <int DT>
+__global__ __launch_bounds__(ABSB_MAX_GROUP* ABSB_HEAD_DIM) void decode_merge_kernel(DecodeParams p) {
+  const int s = blockIdx.x;
+  const int G = p.g.G;
+  const int b = s / p.g.Hkv, h = s % p.g.Hkv;
+  const int lb = p.g.heads.log2_block[h];
+  const int ntok = min(p.sel_cnt[s] << lb, p.max_splits * p.split_tokens);
+  const int nsplit = (ntok + p.split_tokens - 1) / p.split_tokens;
+  const int g = threadIdx.x >> 7, c = threadIdx.x & 127;
+  const size_t slot0 = (size_t)s * p.max_splits;
+  float M = M_INIT;
+  for (int i = 0; i < nsplit; ++i) M = fmaxf(M, p.part_ml[((slot0 + i) * G + g) * 2]);
+  float Lsum = 0.0f, O = 0.0f;
+  for (int i = 0; i < nsplit; ++i) {
+    const float a = fast_exp2(p.part_ml[((slot0 + i) * G + g) * 2] - M);
+    Lsum = __builtin_fmaf(p.part_ml[((slot0 + i) * G + g) * 2 + 1], a, Lsum);
+    O = __builtin_fmaf(p.part_o[((slot0 + i) * G + g) * ABSB_HEAD_DIM + c], a, O);
+  }
+  const bool any = Lsum > 0.0f;
+  const float res = any ? O / Lsum : 0.0f;
+  const size_t row = (size_t)b * p.g.Hq + (size_t)h * G + g;
+  static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + c] = Elem<DT>::narrow(res);
+  if (p.lse && c == 0)
+    p.lse[row] = any ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
+}
+
+template <int DT>
+static void launch_partial(const DecodeParams& p, dim3 grid, hipStream_t stream) {
+  switch (p.g.G) {
+    case 1: hipLaunchKernelGGL((decode_partial_kernel<DT, 1>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((decode_partial_kernel<DT, 2>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 3: hipLaunchKernelGGL((decode_partial_kernel<DT, 3>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((decode_partial_kernel<DT, 4>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 5: hipLaunchKernelGGL((decode_partial_kernel<DT, 5>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 6: hipLaunchKernelGGL((decode_partial_kernel<DT, 6>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 7: hipLaunchKernelGGL((decode_partial_kernel<DT, 7>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    default: hipLaunchKernelGGL((decode_partial_kernel<DT, 8>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+  }
+}
+
+int launch_decode(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
+                  const void* k_cache, const void* v_cache, const int32_t* page_table, const int32_t* seq_lens,
+                  const int32_t* sel_idx, const int32_t* sel_cnt, int32_t sel_stride, void* out, float* lse,
+                  char* ws, hipStream_t stream) {
+  DecodeParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = static_cast<const uint16_t*>(k_cache);
+  p.v = static_cast<const uint16_t*>(v_cache);
+  p.page_table = page_table;
+  p.seq_lens = seq_lens;
+  p.sel_idx = sel_idx;
+  p.sel_cnt = sel_cnt;
+  p.part_o = reinterpret_cast<float*>(ws + pl.ws_part_o);
+  p.part_ml = reinterpret_cast<float*>(ws + pl.ws_part_ml);
+  p.out = out;
+  p.lse = lse;
+  p.sel_stride = sel_stride;
+  p.split_tokens = pl.split_tokens;
+  p.max_splits = pl.max_splits;
+  p.scale_log2 = sm_scale * 1.4426950408889634f;
+  p.g = g;
+  dim3 grid((unsigned)pl.max_splits, (unsigned)pl.nseg);
+  if (dtype == ABSB_F16)
+    launch_partial<ABSB_F16>(p, grid, stream);
+  else
+    launch_partial<ABSB_BF16>(p, grid, stream);
+  int rc = check_launch();
+  if (rc != ABSB_OK) return rc;
+  if (dtype == ABSB_F16)
+    hipLaunchKernelGGL(decode_merge_kernel<ABSB_F16>, dim3((unsigned)pl.nseg), dim3(g.G * ABSB_HEAD_DIM), 0, stream, p);
+  else
+    hipLaunchKernelGGL(decode_merge_kernel<ABSB_BF16>, dim3((unsigned)pl.nseg), dim3(g.G * ABSB_HEAD_DIM), 0, stream, p);
+  return check_launch();
+}
+
+}  // namespace absb

@@ -1,0 +1,87 @@
+"""Device-side holder for a synthetic workload: uploads the generator's arrays to HBM with
+torch (memory and streams only) and wires them into the binding's Layer/Batch records."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import absb
+
+
+def _up(a: np.ndarray, dtype=None, device="cuda:0"):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.view(dtype)
+    return t.to(device)
+
+
+class DeviceWorkload:
+    """Everything one layer's decode step needs, resident on the GPU."""
+
+    def __init__(self, wl, device: str = "cuda:0", budget: Optional[np.ndarray] = None):
+        self.wl = wl
+        self.device = device
+        tdt = torch.float16 if wl.dtype == absb.F16 else torch.bfloat16
+        self.torch_dtype = tdt
+        budget = wl.budget if budget is None else np.asarray(budget, dtype=np.int32)
+        self.layer = absb.Layer(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.dtype,
+                                wl.block_size, wl.strides)
+        self.k_cache = _up(wl.k_cache.view(np.int16), tdt, device)
+        self.v_cache = _up(wl.v_cache.view(np.int16), tdt, device)
+        self.q = _up(wl.q.view(np.int16), tdt, device)
+        self.seq_lens = _up(wl.seq_lens.astype(np.int32), None, device)
+        self.page_table = _up(wl.page_table.astype(np.int32), None, device)
+        self.budget = _up(budget.astype(np.int32), None, device)
+        self.batch = absb.Batch(seq_lens_host=wl.seq_lens, budget_host=budget, seq_lens=self.seq_lens,
+                                page_table=self.page_table, budget=self.budget)
+        self.plan = absb.absb_plan(self.layer, self.batch)
+        self.cent_off = _up(self.plan.cent_off, None, device)
+        self.batch.cent_off = self.cent_off
+        nseg = wl.batch * wl.num_kv_heads
+        self.nseg = nseg
+        total = self.plan.total_centroids
+        self.codes = torch.empty((total, wl.head_dim // 2), dtype=torch.uint8, device=device)
+        self.qscale = torch.empty((nseg, wl.head_dim), dtype=torch.float32, device=device)
+        self.qmin = torch.empty((nseg, wl.head_dim), dtype=torch.float32, device=device)
+        self.scores = torch.empty((total,), dtype=torch.int32, device=device)
+        self.score_exp = torch.empty((nseg,), dtype=torch.int32, device=device)
+        self.sel_stride = max(self.plan.sel_stride, 1)
+        self.sel_idx = torch.empty((nseg, self.sel_stride), dtype=torch.int32, device=device)
+        self.sel_cnt = torch.empty((nseg,), dtype=torch.int32, device=device)
+        self.out = torch.empty((wl.batch, wl.num_q_heads, wl.head_dim), dtype=tdt, device=device)
+        self.lse = torch.empty((wl.batch, wl.num_q_heads), dtype=torch.float32, device=device)
+        # poison the workspace: no entry point may depend on its previous contents
+        self.workspace = torch.full((self.plan.workspace_bytes + 256,), 0xA5, dtype=torch.uint8, device=device)
+
+    # -- entry points, in path order
+    def build(self, stream=None):
+        absb.absb_build_centroids(self.layer, self.batch, self.k_cache, self.codes, self.qscale, self.qmin,
+                                  self.workspace, stream)
+
+    def load_store(self, codes: np.ndarray, qscale: np.ndarray, qmin: np.ndarray):
+        """Install a centroid store computed elsewhere (e.g. by the oracle, for stage-isolated tests)."""
+        self.codes.copy_(torch.from_numpy(np.ascontiguousarray(codes)))
+        self.qscale.copy_(torch.from_numpy(np.ascontiguousarray(qscale)))
+        self.qmin.copy_(torch.from_numpy(np.ascontiguousarray(qmin)))
+
+    def score(self, stream=None):
+        absb.absb_score(self.layer, self.batch, self.q, self.codes, self.qscale, self.scores, self.score_exp, stream)
+
+    def topk(self, stream=None):
+        absb.absb_topk(self.layer, self.batch, self.scores, self.sel_idx, self.sel_cnt, self.sel_stride,
+                       None, stream)
+
+    def sparse_decode(self, stream=None):
+        absb.absb_sparse_decode(self.layer, self.batch, self.q, self.k_cache, self.v_cache, self.sel_idx,
+                                self.sel_cnt, self.sel_stride, self.out, self.lse, self.workspace, stream)
+
+    def decode_fused(self, stream=None, want_sel: bool = True):
+        absb.absb_decode_fused(self.layer, self.batch, self.q, self.codes, self.qscale, self.k_cache,
+                               self.v_cache, self.out, self.lse, self.sel_idx if want_sel else None,
+                               self.sel_cnt if want_sel else None, self.workspace, stream)
+
+    # -- results back on the host
+    def out_f32(self) -> np.ndarray:
+        return self.out.float().cpu().numpy()

@@ -15,6 +15,8 @@ can be handed to a C program and to the GPU without any dtype support on the way
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import Dict, Optional, Sequence
 
@@ -117,15 +119,29 @@ def _scatter_rows(cache, pt_row, h, P, positions, rows_bits):
     cache[pt_row[positions // P], h, positions % P] = rows_bits
 
 
-def _fill_normal(rng, cache, dtype, scale=1.0, chunk_pages=2048):
+def _parallel_chunks(rng, n_items, chunk, work):
+    """Run work(child_generator, lo, hi) over [0, n_items) in chunks on a thread pool.  Each chunk
+    draws from its own spawned child stream, so the result does not depend on the thread count."""
+    starts = list(range(0, n_items, chunk))
+    kids = rng.bit_generator.seed_seq.spawn(len(starts))
+
+    def run(i):
+        g = np.random.Generator(np.random.PCG64(kids[i]))
+        work(g, starts[i], min(n_items, starts[i] + chunk))
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+        list(ex.map(run, range(len(starts))))
+
+
+def _fill_normal(rng, cache, dtype, scale=1.0, chunk_pages=128):
     """cache[...] <- N(0, scale^2) rounded to the storage format, generated in bounded chunks."""
-    n = cache.shape[0]
-    for p0 in range(0, n, chunk_pages):
-        p1 = min(n, p0 + chunk_pages)
-        x = rng.standard_normal(size=(p1 - p0,) + cache.shape[1:], dtype=np.float32)
+    def work(g, p0, p1):
+        x = g.standard_normal(size=(p1 - p0,) + cache.shape[1:], dtype=np.float32)
         if scale != 1.0:
             x *= np.float32(scale)
         cache[p0:p1] = f32_to_bits(x, dtype)
+
+    _parallel_chunks(rng, cache.shape[0], chunk_pages, work)
 
 
 def _unit_rms_direction(rng, d, unit):
@@ -253,13 +269,14 @@ def make_workload(config: int, *, seed: Optional[int] = None, context: Optional[
     if config == 2:
         # keys = coefficients x per-head rank-8 basis + 0.1 * noise
         W = (r_data.standard_normal(size=(Hkv, 8, d)) / np.sqrt(8.0)).astype(np.float32)
-        chunk = 1024
-        for p0 in range(0, total_pages, chunk):
-            p1 = min(total_pages, p0 + chunk)
-            C = r_data.standard_normal(size=(p1 - p0, Hkv, P, 8), dtype=np.float32)
+
+        def work(g, p0, p1):
+            C = g.standard_normal(size=(p1 - p0, Hkv, P, 8), dtype=np.float32)
             x = np.einsum("phtr,hrd->phtd", C, W, optimize=True)
-            x += np.float32(0.1) * r_data.standard_normal(size=x.shape, dtype=np.float32)
+            x += np.float32(0.1) * g.standard_normal(size=x.shape, dtype=np.float32)
             wl.k_cache[p0:p1] = f32_to_bits(x.astype(np.float32), dtype)
+
+        _parallel_chunks(r_data, total_pages, 128, work)
         wl.knobs.update(key_rank=8, key_noise=0.1)
     else:
         _fill_normal(r_data, wl.k_cache, dtype)

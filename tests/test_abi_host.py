@@ -1,0 +1,170 @@
+"""Host-side checks of the C ABI (no GPU, no compute calls): the library loads, exports every
+symbol the header declares, plans sizes correctly and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_12110_amd import absb, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(absb.LIB_PATH):
+        from paper_2605_12110_amd.build import build_library
+        build_library(force=False)
+
+
+def _layer(**kw):
+    d = dict(num_q_heads=32, num_kv_heads=8, head_dim=128, page_size=64, dtype=absb.F16,
+             block_size=[8, 16, 32, 64, 128, 8, 16, 32], kv_strides=(8 * 64 * 128, 64 * 128, 128))
+    d.update(kw)
+    return absb.Layer(**d)
+
+
+def _batch(lens=(4096,), budget=(512,), **kw):
+    return absb.Batch(seq_lens_host=list(lens), budget_host=None if budget is None else list(budget),
+                      pt_stride=kw.pop("pt_stride", (max(lens) + 63) // 64), **kw)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "absb.h")).read()
+    declared = re.findall(r"ABSB_API\s+[\w\s\*]+?\b(absb_\w+)\s*\(", header)
+    assert set(declared) == set(absb.EXPORTS)
+    lib = absb.load()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert absb.strerror(0) == "ok" and "workspace" in absb.strerror(absb.ERR_WORKSPACE)
+
+
+def test_plan_matches_the_papers_layout_rules():
+    # off[s+1] = off[s] + ceil(L/B_h) (Sec. 3.4 kernel 1); K_s = min(N_s, ceil(T/B_h)) (kernel 2)
+    lens, T = (4096, 1000, 77), (512, 100, 4000)
+    layer = _layer()
+    plan = absb.absb_plan(layer, _batch(lens, T))
+    n = np.diff(plan.cent_off).reshape(3, 8)
+    ks = []
+    for b, L in enumerate(lens):
+        for h, B in enumerate(layer.block_size):
+            assert n[b, h] == -(-L // B)
+            ks.append(min(-(-L // B), -(-T[b] // B)))
+    assert plan.total_centroids == n.sum() and plan.cent_off[0] == 0
+    assert plan.sel_stride == max(ks)
+    assert plan.workspace_bytes > 0 and plan.workspace_bytes % 256 == 0
+    # the same offsets as the (independent) generator-side arithmetic of the oracle
+    from oracle import oracle as O
+    wl = synth.tiny_workload(Bt=3, Hq=8, Hkv=8, P=64, seq_lens=lens, block_size=layer.block_size, budget=T)
+    assert np.array_equal(O.offsets(wl), plan.cent_off.astype(np.int64))
+
+
+def test_plan_without_budget_sizes_for_every_block():
+    plan = absb.absb_plan(_layer(), _batch((4096,), None))
+    assert plan.sel_stride == 4096 // 8
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(head_dim=64), absb.ERR_UNSUPPORTED),
+    (dict(dtype=7), absb.ERR_UNSUPPORTED),
+    (dict(num_q_heads=30), absb.ERR_BAD_SHAPE),
+    (dict(num_q_heads=128), absb.ERR_UNSUPPORTED),            # group of 16
+    (dict(num_q_heads=0), absb.ERR_BAD_SHAPE),
+    (dict(page_size=48), absb.ERR_BAD_SHAPE),
+    (dict(page_size=4), absb.ERR_BAD_SHAPE),
+    (dict(block_size=[8, 16, 32, 64, 128, 8, 16, 24]), absb.ERR_BAD_BLOCK_SIZE),
+    (dict(block_size=[4] * 8), absb.ERR_BAD_BLOCK_SIZE),
+    (dict(block_size=[256] * 8), absb.ERR_BAD_BLOCK_SIZE),
+    (dict(kv_strides=(8 * 64 * 128, 64 * 128, 100)), absb.ERR_BAD_SHAPE),
+    (dict(kv_strides=(8 * 64 * 128 + 4, 64 * 128, 128)), absb.ERR_BAD_SHAPE),
+    (dict(sm_scale=-1.0), absb.ERR_BAD_SHAPE),
+    (dict(sm_scale=float("nan")), absb.ERR_BAD_SHAPE),
+])
+def test_plan_rejects_bad_layers(kw, status):
+    with pytest.raises(absb.AbsbError) as e:
+        absb.absb_plan(_layer(**kw), _batch())
+    assert e.value.status == status
+
+
+@pytest.mark.parametrize("lens,budget,pts,status", [
+    ((0,), (512,), 64, absb.ERR_BAD_SHAPE),
+    ((4096,), (0,), 64, absb.ERR_BAD_SHAPE),
+    ((4096,), (-5,), 64, absb.ERR_BAD_SHAPE),
+    ((4096,), (512,), 63, absb.ERR_BAD_SHAPE),                # page-table pitch too small
+])
+def test_plan_rejects_bad_batches(lens, budget, pts, status):
+    with pytest.raises(absb.AbsbError) as e:
+        absb.absb_plan(_layer(), _batch(lens, budget, pt_stride=pts))
+    assert e.value.status == status
+
+
+def test_null_structs_and_pointers_are_reported_not_dereferenced():
+    lib = absb.load()
+    assert lib.absb_plan(None, None, None, None, None, None) == absb.ERR_NULL
+    layer, batch = _layer(), _batch()
+    cl, cb = layer.c(), batch.c()
+    assert lib.absb_plan(C.byref(cl), None, None, None, None, None) == absb.ERR_NULL
+    # every compute entry point validates host-visible arguments before launching anything:
+    # with all device pointers NULL they must return ERR_NULL (and never touch a device)
+    null = C.c_void_p(None)
+    assert lib.absb_build_centroids(C.byref(cl), C.byref(cb), null, null, null, null, null, C.c_size_t(0), null) \
+        == absb.ERR_NULL
+    assert lib.absb_score(C.byref(cl), C.byref(cb), null, null, null, null, null, null) == absb.ERR_NULL
+    assert lib.absb_topk(C.byref(cl), C.byref(cb), null, null, null, C.c_int32(64), null, C.c_size_t(0), null) \
+        == absb.ERR_NULL
+    assert lib.absb_sparse_decode(C.byref(cl), C.byref(cb), null, null, null, null, null, C.c_int32(64), null,
+                                  null, null, C.c_size_t(0), null) == absb.ERR_NULL
+    assert lib.absb_decode_fused(C.byref(cl), C.byref(cb), null, null, null, null, null, null, null, null, null,
+                                 null, C.c_size_t(0), null) == absb.ERR_NULL
+    # a budget is mandatory for selection
+    nb = _batch(budget=None).c()
+    assert lib.absb_topk(C.byref(cl), C.byref(nb), null, null, null, C.c_int32(64), null, C.c_size_t(0), null) \
+        == absb.ERR_NULL
+
+
+def test_workspace_and_list_width_checks_come_before_any_launch():
+    lib = absb.load()
+    layer = _layer()
+    fake = C.c_void_p(0x1000)             # never dereferenced: the calls below must fail validation first
+    batch = _batch()
+    batch_c = batch.c()
+    for f in ("seq_lens", "page_table", "cent_off", "budget"):
+        setattr(batch_c, f, 0x1000)
+    cl = layer.c()
+    plan = absb.absb_plan(layer, batch)
+    # too small / missing / misaligned workspace
+    for ws, nbytes in ((C.c_void_p(None), 0), (C.c_void_p(0x100000), 16), (C.c_void_p(0x100010), plan.workspace_bytes)):
+        rc = lib.absb_decode_fused(C.byref(cl), C.byref(batch_c), fake, fake, fake, fake, fake, fake, None, None,
+                                   None, ws, C.c_size_t(nbytes), None)
+        assert rc == absb.ERR_WORKSPACE
+        rc = lib.absb_build_centroids(C.byref(cl), C.byref(batch_c), fake, fake, fake, fake, ws, C.c_size_t(nbytes),
+                                      None)
+        assert rc == absb.ERR_WORKSPACE
+    # selection list narrower than the plan's K
+    rc = lib.absb_topk(C.byref(cl), C.byref(batch_c), fake, fake, fake, C.c_int32(plan.sel_stride - 1), None,
+                       C.c_size_t(0), None)
+    assert rc == absb.ERR_BAD_SHAPE
+    rc = lib.absb_sparse_decode(C.byref(cl), C.byref(batch_c), fake, fake, fake, fake, fake, C.c_int32(0), fake,
+                                None, fake, C.c_size_t(0), None)
+    assert rc == absb.ERR_BAD_SHAPE
+
+
+def test_tuning_knobs_validate():
+    absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 128)
+    absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 0)
+    with pytest.raises(absb.AbsbError):
+        absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 100)
+    with pytest.raises(absb.AbsbError):
+        absb.set_tuning(99, 64)
+
+
+def test_product_package_does_not_reach_the_oracle():
+    # the product path must not import, link, load or execute anything under oracle/
+    pkg = os.path.join(ROOT, "paper_2605_12110_amd")
+    bad = re.compile(r"^\s*(from|import)\s+oracle\b|liboracle|absb_oracle|oracle[/.]oracle", re.M)
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                assert not bad.search(open(os.path.join(dirpath, f)).read()), f

@@ -1,0 +1,274 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Integer results (codes, scores, selected block indices) must be
+bit-exact; attention outputs must be within max-abs 2e-3 (fp16) / 1e-2 (bf16) of the fp64 oracle.
+"""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2605_12110_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.F16: 2e-3, synth.BF16: 1e-2}
+LSE_TOL = 2e-3
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _dev(wl, **kw):
+    import torch
+    from paper_2605_12110_amd.device import DeviceWorkload
+    assert torch.cuda.is_available()
+    return DeviceWorkload(wl, **kw)
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _check_out(dw, want_out, want_lse, what):
+    _sync()
+    got = dw.out_f32().astype(np.float64)
+    err = np.abs(got - want_out).max()
+    lse = dw.lse.cpu().numpy().astype(np.float64)
+    fin = np.isfinite(want_lse)
+    lerr = np.abs(lse[fin] - want_lse[fin]).max() if fin.any() else 0.0
+    _say(f"    {what}: max|out-oracle| = {err:.3e} (tol {TOL[dw.wl.dtype]:.0e}), max|lse-oracle| = {lerr:.3e}")
+    assert np.isfinite(got).all()
+    assert err <= TOL[dw.wl.dtype], what
+    assert lerr <= LSE_TOL, what
+    assert np.array_equal(np.isneginf(lse), np.isneginf(want_lse))
+
+
+def run_all_stages(wl, name):
+    """Stage by stage (each GPU stage fed the oracle's inputs), then the fused call end to end."""
+    _say(f"[case {name}] Bt={wl.batch} Hq={wl.num_q_heads} Hkv={wl.num_kv_heads} P={wl.page_size} "
+         f"L={wl.seq_lens.tolist()[:4]}.. B={wl.block_size.tolist()} T={wl.budget.tolist()[:4]}.. dtype={wl.dtype}")
+    t0 = time.time()
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st, sel_stride=None)
+    _say(f"    oracle: build+step {time.time() - t0:.2f}s, centroids={int(st.off[-1])}")
+    dw = _dev(wl)
+    assert np.array_equal(dw.plan.cent_off.astype(np.int64), st.off)
+    K = dw.sel_stride
+    assert K == int(ref["sel_cnt"].max())
+
+    # a0 build: bit-exact codes and parameters
+    dw.build(); _sync()
+    codes = dw.codes.cpu().numpy()
+    assert np.array_equal(dw.qscale.cpu().numpy(), st.qscale), "qscale"
+    assert np.array_equal(dw.qmin.cpu().numpy(), st.qmin), "qmin"
+    nbad = int((codes != st.codes).sum())
+    assert nbad == 0, f"{nbad} code bytes differ"
+    _say("    build: codes/qscale/qmin bit-exact")
+
+    # a1 score on the oracle's store
+    dw.load_store(st.codes, st.qscale, st.qmin)
+    dw.score(); _sync()
+    assert np.array_equal(dw.score_exp.cpu().numpy(), ref["score_exp"]), "score exponent"
+    assert np.array_equal(dw.scores.cpu().numpy(), ref["scores"]), "scores"
+    _say("    score: int32 scores bit-exact")
+
+    # a2 top-k on the oracle's scores
+    import torch
+    dw.scores.copy_(torch.from_numpy(ref["scores"]))
+    dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7)
+    dw.topk(); _sync()
+    assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"]), "sel_cnt"
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K]), "sel_idx"
+    _say("    topk: indices bit-exact")
+
+    # a3-a5 sparse decode on the oracle's selection
+    dw.sel_idx.copy_(torch.from_numpy(np.ascontiguousarray(ref["sel_idx"][:, :K])))
+    dw.sel_cnt.copy_(torch.from_numpy(ref["sel_cnt"]))
+    dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+    dw.sparse_decode()
+    _check_out(dw, ref["out"], ref["lse"], "sparse_decode")
+
+    # the whole step from the GPU-built store
+    dw.build()
+    dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+    dw.workspace.fill_(0x5A)
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "decode_fused")
+    assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
+    # and again without asking for the selection, different workspace poison: same bits out
+    first = dw.out.cpu().numpy().copy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy().copy()
+    dw.workspace.fill_(0xC3)
+    dw.decode_fused(want_sel=False); _sync()
+    second = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
+    assert np.array_equal(first, second), "fused output depends on workspace contents or is not deterministic"
+    _say("    fused: selection bit-exact, output within tolerance, deterministic")
+    return dw, st, ref
+
+
+# ------------------------------------------------------------------ small cases: several tiles, ragged tails
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_ragged_small_batch(dtype):
+    wl = synth.tiny_workload(seed=21, dtype=dtype, Bt=3, Hq=8, Hkv=2, P=16, seq_lens=(37, 64, 1301),
+                             block_size=(8, 32), budget=(16, 24, 400))
+    run_all_stages(wl, f"ragged dtype={dtype}")
+
+
+def test_group_of_five_and_blocks_larger_than_a_page():
+    wl = synth.tiny_workload(seed=22, dtype=synth.BF16, Bt=2, Hq=20, Hkv=4, P=16, seq_lens=(999, 2500),
+                             block_size=(128, 8, 64, 16), budget=(300, 520))
+    run_all_stages(wl, "G=5, B>P")
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 6, 7, 8])
+def test_other_group_sizes(G):
+    wl = synth.tiny_workload(seed=23 + G, dtype=synth.F16, Bt=1, Hq=2 * G, Hkv=2, P=64, seq_lens=(777,),
+                             block_size=(16, 128), budget=(200,))
+    run_all_stages(wl, f"G={G}")
+
+
+def test_config1_full():
+    run_all_stages(synth.make_workload(1), "config1")
+
+
+def test_config2_scaled():
+    run_all_stages(synth.make_workload(2, context=8192, batch=3, budget=1024), "config2 (8K ctx, batch 3)")
+
+
+def test_config4_scaled_mixed_lengths():
+    run_all_stages(synth.make_workload(4, context=16384, batch=5), "config4 (<=16K ctx, batch 5)")
+
+
+def test_config5_uniform16_scaled():
+    run_all_stages(synth.make_workload(5, context=16384, batch=2, uniform_block=16, budget=2048), "config5-U")
+
+
+# ------------------------------------------------------------------ full-size cases
+def test_config3_full_headline():
+    """128K context, batch 1: the configuration the benchmark times."""
+    dw, st, ref = run_all_stages(synth.make_workload(3), "config3 full (128K)")
+    # every selected block holds the budget: K_s * B_h = 4096
+    assert np.all(ref["sel_cnt"] * dw.wl.block_size == 4096)
+
+
+def test_config2_full():
+    run_all_stages(synth.make_workload(2), "config2 full (8 x 32K)")
+
+
+# ------------------------------------------------------------------ edge cases
+def test_budget_covering_the_context_is_dense_attention():
+    wl = synth.tiny_workload(seed=31, dtype=synth.F16, Bt=2, Hq=8, Hkv=2, P=16, seq_lens=(300, 129),
+                             block_size=(8, 64), budget=(10 ** 6, 129))
+    dw, st, ref = run_all_stages(wl, "dense")
+    dense, dense_lse = O.dense_attention(wl)
+    dw.decode_fused()
+    _check_out(dw, dense, dense_lse, "fused vs dense oracle")
+
+
+def test_single_token_context_and_single_block_budget():
+    wl = synth.tiny_workload(seed=32, dtype=synth.BF16, Bt=2, Hq=4, Hkv=2, P=16, seq_lens=(1, 50),
+                             block_size=(8, 16), budget=(1, 1))
+    dw, st, ref = run_all_stages(wl, "L=1 / K=1")
+    assert list(ref["sel_cnt"]) == [1, 1, 1, 1]
+    # L = 1: the output is exactly that token's value
+    v = wl.value_rows(0, 0)[0]
+    assert np.array_equal(dw.out_f32()[0, 0], v)
+
+
+def test_all_equal_scores_pick_lowest_indices():
+    import torch
+    wl = synth.tiny_workload(seed=33, Bt=1, Hq=4, Hkv=2, P=16, seq_lens=(4096,), block_size=(8, 16), budget=(800,))
+    dw = _dev(wl)
+    dw.scores.fill_(12345)
+    dw.topk(); _sync()
+    cnt = dw.sel_cnt.cpu().numpy()
+    idx = dw.sel_idx.cpu().numpy()
+    assert list(cnt) == [100, 50]
+    assert np.array_equal(idx[0, :100], np.arange(100)) and np.array_equal(idx[1, :50], np.arange(50))
+    assert np.all(idx[1, 50:] == -1)
+    # extreme values and heavy ties against the oracle
+    rng = np.random.default_rng(0)
+    sc = rng.choice(np.array([-2 ** 31, -1, 0, 1, 2 ** 31 - 1], dtype=np.int64), size=dw.plan.total_centroids)
+    sc = sc.astype(np.int32)
+    dw.scores.copy_(torch.from_numpy(sc))
+    dw.topk(); _sync()
+    want_idx, want_cnt = O.topk(wl, dw.plan.cent_off.astype(np.int64), sc, sel_stride=dw.sel_stride)
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), want_idx) and np.array_equal(dw.sel_cnt.cpu().numpy(), want_cnt)
+
+
+def test_decode_accepts_any_list_order_partial_last_block_and_empty_lists():
+    import torch
+    wl = synth.tiny_workload(seed=34, dtype=synth.F16, Bt=2, Hq=8, Hkv=2, P=16, seq_lens=(203, 77),
+                             block_size=(8, 32), budget=(64, 64))
+    dw = _dev(wl)
+    K = dw.sel_stride
+    rng = np.random.default_rng(1)
+    sel = np.full((4, K), -1, np.int32)
+    cnt = np.zeros(4, np.int32)
+    for s in range(4):
+        b, h = divmod(s, 2)
+        N = -(-int(wl.seq_lens[b]) // int(wl.block_size[h]))
+        k = min(K, N, 1 + s)
+        pick = rng.choice(N - 1, size=k - 1, replace=False).tolist() + [N - 1]   # always the partial last block
+        rng.shuffle(pick)
+        sel[s, :k] = pick
+        cnt[s] = k
+    cnt[2] = 0                                                                   # an empty selection
+    sel[2, :] = -1
+    want, want_lse = O.sparse_attention(wl, sel, cnt)
+    dw.sel_idx.copy_(torch.from_numpy(sel)); dw.sel_cnt.copy_(torch.from_numpy(cnt))
+    dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+    dw.sparse_decode()
+    _check_out(dw, want, want_lse, "arbitrary lists")
+    G = wl.group
+    assert not dw.out_f32()[1, 0:G].any() and np.all(np.isneginf(dw.lse.cpu().numpy()[1, 0:G]))
+
+
+def test_split_shapes_do_not_change_the_selection_and_stay_within_tolerance():
+    from paper_2605_12110_amd import absb
+    wl = synth.make_workload(1, context=8192, budget=2048)
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    try:
+        for split in (64, 128, 512, 1024):
+            absb.set_tuning(absb.TUNE_SPLIT_TOKENS, split)
+            dw = _dev(wl)
+            dw.build()
+            dw.decode_fused()
+            _check_out(dw, ref["out"], ref["lse"], f"split_tokens={split}")
+            assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+        for chunk in (64, 1024):
+            absb.set_tuning(absb.TUNE_SCORE_CHUNK, chunk)
+            dw = _dev(wl)
+            dw.load_store(st.codes, st.qscale, st.qmin)
+            dw.score(); _sync()
+            assert np.array_equal(dw.scores.cpu().numpy(), ref["scores"])
+    finally:
+        absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 0)
+        absb.set_tuning(absb.TUNE_SCORE_CHUNK, 0)
+
+
+def test_nonstandard_cache_strides_nhd_layout():
+    """Token-major pages ([page][slot][head][d]) through the stride fields."""
+    import torch
+    from paper_2605_12110_amd import absb
+    wl = synth.tiny_workload(seed=35, dtype=synth.F16, Bt=2, Hq=8, Hkv=2, P=16, seq_lens=(150, 90),
+                             block_size=(8, 32), budget=(48, 48))
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    dw = _dev(wl)
+    # re-lay the caches as NHD on the device and point the layer's strides at that layout
+    H, P, d = wl.num_kv_heads, wl.page_size, wl.head_dim
+    dw.k_cache = dw.k_cache.permute(0, 2, 1, 3).contiguous()
+    dw.v_cache = dw.v_cache.permute(0, 2, 1, 3).contiguous()
+    dw.layer = absb.Layer(wl.num_q_heads, H, d, P, wl.dtype, wl.block_size, (P * H * d, d, H * d))
+    dw.build(); _sync()
+    assert np.array_equal(dw.codes.cpu().numpy(), st.codes)
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "NHD strides")
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
