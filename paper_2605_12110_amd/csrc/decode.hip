@@ -46,16 +46,26 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
   const int s = blockIdx.y, split = blockIdx.x;
   const int b = s / p.g.Hkv, h = s % p.g.Hkv;
   const int lb = p.g.heads.log2_block[h];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, grp = lane >> 4, li = lane & 15;
+  const int32_t* sel = p.sel_idx + (size_t)s * p.sel_stride;
+  const int pos_begin = split * p.split_tokens;
+
+  // The first step's list entries are fetched before the list length is known (the address is
+  // clamped to the list's storage, so the read is always legal); this takes one memory round
+  // trip off the dependent chain count -> entry -> page -> row.
+  const int maxpos = (p.sel_stride << lb) - 1;
+  int selj[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+    selj[r] = sel[min(pos_begin + wave * ROWS_PER_WAVE_STEP + r * 4 + grp, maxpos) >> lb];
+
   // never beyond what the launch covers (a list longer than promised is cut, not overrun)
   const int ntok = min(p.sel_cnt[s] << lb, p.max_splits * p.split_tokens);
-  const int pos_begin = split * p.split_tokens;
   if (pos_begin >= ntok) return;
   const int pos_end = min(ntok, pos_begin + p.split_tokens);
   const int L = p.seq_lens[b];
   const int lP = p.g.log2_page;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, grp = lane >> 4, li = lane & 15;
 
-  const int32_t* sel = p.sel_idx + (size_t)s * p.sel_stride;
   const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
   const size_t lane_off = (size_t)h * p.g.s_head + (size_t)li * 8;
 
@@ -88,10 +98,9 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
     for (int r = 0; r < 4; ++r) {
       const int pos = base + r * 4 + grp;
       const bool in = pos < pos_end;
-      const int pc = in ? pos : pos_begin;  // always a position of the list
-      const int t = (sel[pc >> lb] << lb) + (pc & ((1 << lb) - 1));
-      valid[r] = in && t < L;               // a selected last block may be partial
-      const int tc = min(t, L - 1);         // addresses stay inside the request's pages
+      const int t = (selj[r] << lb) + (pos & ((1 << lb) - 1));
+      valid[r] = in && t < L;                // a selected last block may be partial
+      const int tc = max(0, min(t, L - 1));  // addresses stay inside the request's pages
       const int page = pt[tc >> lP];
       off[r] = (size_t)page * p.g.s_page + lane_off + (size_t)(tc & ((1 << lP) - 1)) * p.g.s_tok;
     }
@@ -100,6 +109,10 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
     for (int r = 0; r < 4; ++r) kk[r] = *reinterpret_cast<const uint4*>(p.k + off[r]);
 #pragma unroll
     for (int r = 0; r < 4; ++r) vv[r] = *reinterpret_cast<const uint4*>(p.v + off[r]);
+    // list entries of the next step, in flight behind the rows
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      selj[r] = sel[min(base + DEC_WAVES * ROWS_PER_WAVE_STEP + r * 4 + grp, maxpos) >> lb];
 
     // ---- logits (log2 units) of the four rows for the G heads
     float sc[G][4];
@@ -191,32 +204,94 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
   }
 }
 
-// Log-sum-exp merge of a segment's split partials; one work-group per segment, one thread per
-// (query head of the group, channel).
+// Log-sum-exp merge of a segment's split partials.  One work-group per (query head, segment):
+// 128 channels x 4 split lanes; a thread takes every 4th split, with up to MRG_UNROLL independent
+// loads in flight, so the whole merge costs about one memory round trip.
+constexpr int MRG_THREADS = 512;
+constexpr int MRG_LANES = MRG_THREADS / ABSB_HEAD_DIM;
+constexpr int MRG_UNROLL = 16;
+
 template <int DT>
-__global__ __launch_bounds__(ABSB_MAX_GROUP* ABSB_HEAD_DIM) void decode_merge_kernel(DecodeParams p) {
-  const int s = blockIdx.x;
+__global__ __launch_bounds__(MRG_THREADS) void decode_merge_kernel(DecodeParams p) {
+  const int s = blockIdx.y, g = blockIdx.x;
   const int G = p.g.G;
   const int b = s / p.g.Hkv, h = s % p.g.Hkv;
   const int lb = p.g.heads.log2_block[h];
+  const int tid = threadIdx.x, c = tid & 127, sl = tid >> 7, lane = tid & 63, wave = tid >> 6;
+  const size_t slot0 = (size_t)s * p.max_splits;
+  const float2* ml = reinterpret_cast<const float2*>(p.part_ml);
+
+  // first batch of partials: issued before the split count is known (slots up to max_splits
+  // exist for every segment; unused ones hold stale bytes and are masked out below)
+  float2 mlv[MRG_UNROLL];
+  float ov[MRG_UNROLL];
+#pragma unroll
+  for (int u = 0; u < MRG_UNROLL; ++u) {
+    const int i = min(sl + u * MRG_LANES, p.max_splits - 1);
+    mlv[u] = ml[(slot0 + i) * G + g];
+    ov[u] = p.part_o[((slot0 + i) * G + g) * ABSB_HEAD_DIM + c];
+  }
   const int ntok = min(p.sel_cnt[s] << lb, p.max_splits * p.split_tokens);
   const int nsplit = (ntok + p.split_tokens - 1) / p.split_tokens;
-  const int g = threadIdx.x >> 7, c = threadIdx.x & 127;
-  const size_t slot0 = (size_t)s * p.max_splits;
-  float M = M_INIT;
-  for (int i = 0; i < nsplit; ++i) M = fmaxf(M, p.part_ml[((slot0 + i) * G + g) * 2]);
-  float Lsum = 0.0f, O = 0.0f;
-  for (int i = 0; i < nsplit; ++i) {
-    const float a = fast_exp2(p.part_ml[((slot0 + i) * G + g) * 2] - M);
-    Lsum = __builtin_fmaf(p.part_ml[((slot0 + i) * G + g) * 2 + 1], a, Lsum);
-    O = __builtin_fmaf(p.part_o[((slot0 + i) * G + g) * ABSB_HEAD_DIM + c], a, O);
+#pragma unroll
+  for (int u = 0; u < MRG_UNROLL; ++u) {
+    const bool in = sl + u * MRG_LANES < nsplit;
+    mlv[u] = in ? mlv[u] : make_float2(M_INIT, 0.0f);
+    ov[u] = in ? ov[u] : 0.0f;
   }
-  const bool any = Lsum > 0.0f;
-  const float res = any ? O / Lsum : 0.0f;
-  const size_t row = (size_t)b * p.g.Hq + (size_t)h * G + g;
-  static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + c] = Elem<DT>::narrow(res);
-  if (p.lse && c == 0)
-    p.lse[row] = any ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
+
+  // global maximum over the splits
+  float M = M_INIT;
+#pragma unroll
+  for (int u = 0; u < MRG_UNROLL; ++u) M = fmaxf(M, mlv[u].x);  // the work-group's lanes cover splits 0..63
+  for (int i = MRG_UNROLL * MRG_LANES + tid; i < nsplit; i += MRG_THREADS) M = fmaxf(M, ml[(slot0 + i) * G + g].x);
+  for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+  __shared__ float s_max[MRG_THREADS / 64];
+  __shared__ float s_acc[MRG_LANES][ABSB_HEAD_DIM], s_l[MRG_LANES];
+  if (lane == 0) s_max[wave] = M;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < MRG_THREADS / 64; ++w) M = fmaxf(M, s_max[w]);
+
+  float acc = 0.0f, lacc = 0.0f;
+#pragma unroll
+  for (int u = 0; u < MRG_UNROLL; ++u) {
+    const float w = fast_exp2(mlv[u].x - M);
+    acc = __builtin_fmaf(ov[u], w, acc);
+    lacc = __builtin_fmaf(mlv[u].y, w, lacc);
+  }
+  for (int i0 = sl + MRG_UNROLL * MRG_LANES; i0 < nsplit; i0 += MRG_UNROLL * MRG_LANES) {
+#pragma unroll
+    for (int u = 0; u < MRG_UNROLL; ++u) {
+      const int i = i0 + u * MRG_LANES;
+      const bool in = i < nsplit;
+      mlv[u] = in ? ml[(slot0 + i) * G + g] : make_float2(M_INIT, 0.0f);
+      ov[u] = in ? p.part_o[((slot0 + i) * G + g) * ABSB_HEAD_DIM + c] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < MRG_UNROLL; ++u) {
+      const float w = fast_exp2(mlv[u].x - M);
+      acc = __builtin_fmaf(ov[u], w, acc);
+      lacc = __builtin_fmaf(mlv[u].y, w, lacc);
+    }
+  }
+  s_acc[sl][c] = acc;
+  if (c == 0) s_l[sl] = lacc;
+  __syncthreads();
+  if (sl == 0) {
+    float O = s_acc[0][c], Lsum = s_l[0];
+#pragma unroll
+    for (int k = 1; k < MRG_LANES; ++k) {
+      O += s_acc[k][c];
+      Lsum += s_l[k];
+    }
+    const bool any = Lsum > 0.0f;
+    const float res = any ? O / Lsum : 0.0f;
+    const size_t row = (size_t)b * p.g.Hq + (size_t)h * G + g;
+    static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + c] = Elem<DT>::narrow(res);
+    if (p.lse && c == 0)
+      p.lse[row] = any ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
+  }
 }
 
 template <int DT>
@@ -262,9 +337,9 @@ int launch_decode(const Geometry& g, const Plan& pl, int dtype, float sm_scale, 
   int rc = check_launch();
   if (rc != ABSB_OK) return rc;
   if (dtype == ABSB_F16)
-    hipLaunchKernelGGL(decode_merge_kernel<ABSB_F16>, dim3((unsigned)pl.nseg), dim3(g.G * ABSB_HEAD_DIM), 0, stream, p);
+    hipLaunchKernelGGL(decode_merge_kernel<ABSB_F16>, dim3((unsigned)g.G, (unsigned)pl.nseg), dim3(MRG_THREADS), 0, stream, p);
   else
-    hipLaunchKernelGGL(decode_merge_kernel<ABSB_BF16>, dim3((unsigned)pl.nseg), dim3(g.G * ABSB_HEAD_DIM), 0, stream, p);
+    hipLaunchKernelGGL(decode_merge_kernel<ABSB_BF16>, dim3((unsigned)g.G, (unsigned)pl.nseg), dim3(MRG_THREADS), 0, stream, p);
   return check_launch();
 }
 

@@ -40,6 +40,19 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
   __shared__ float s_absmax[2];
   __shared__ int32_t s_wq[ABSB_HEAD_DIM];
 
+  // ---- the work-group's first batch of codes goes in flight before anything else: the loads do
+  // not depend on the query, so their latency overlaps the prologue below
+  constexpr int PF = 4;  // 64 centroids per work-group step, PF steps per batch
+  const int quarter = tid & 3;
+  const int jend = min(N, j0 + p.chunk);
+  const uint8_t* base = p.codes + (size_t)off * 64 + quarter * 16;
+  uint4 pre[PF];
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    const int j = j0 + u * 64 + (tid >> 2);
+    pre[u] = j < jend ? *reinterpret_cast<const uint4*>(base + (size_t)j * 64) : make_uint4(0, 0, 0, 0);
+  }
+
   // ---- prologue: fixed-point image of w = (sum_g q_g) * scale, by threads 0..127
   float w = 0.0f;
   if (tid < ABSB_HEAD_DIM) {
@@ -67,29 +80,37 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
   __syncthreads();
 
   // ---- each lane: the 32 weights of its quarter of the channels
-  const int quarter = tid & 3;
   int32_t wq[32];
 #pragma unroll
   for (int i = 0; i < 32; ++i) wq[i] = s_wq[quarter * 32 + i];
 
-  // ---- main loop: 64 centroids per work-group step (16 per wave)
-  const int jend = min(N, j0 + p.chunk);
-  const uint8_t* base = p.codes + (size_t)off * 64 + quarter * 16;
-  for (int j = j0 + (tid >> 2); j < jend; j += 64) {
-    const uint4 c = *reinterpret_cast<const uint4*>(base + (size_t)j * 64);
+  auto dot = [&](const uint4& c) -> int32_t {
     const uint32_t dw[4] = {c.x, c.y, c.z, c.w};
     int32_t acc = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
 #pragma unroll
-      for (int n = 0; n < 8; ++n) {
-        const int32_t code = (int32_t)((dw[k] >> (4 * n)) & 15u);
-        acc += wq[k * 8 + n] * code;
-      }
+      for (int n = 0; n < 8; ++n) acc += wq[k * 8 + n] * (int32_t)((dw[k] >> (4 * n)) & 15u);
     }
-    // NOTE: every lane of a quad takes the same trip count (j depends on tid>>2 only)
-    acc = quad_sum(acc);
-    if (quarter == 0) p.scores[off + j] = acc;
+    return quad_sum(acc);  // the four lanes of a quad hold the four quarters of one centroid
+  };
+
+  // ---- main loop: 64 centroids per work-group step (16 per wave), PF steps per batch.
+  // Every lane of a quad shares j, so the quad reduction always sees four live lanes.
+  for (int jb = j0;;) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int j = jb + u * 64 + (tid >> 2);
+      const int32_t sc = dot(pre[u]);
+      if (j < jend && quarter == 0) p.scores[off + j] = sc;
+    }
+    jb += PF * 64;
+    if (jb >= jend) break;
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int j = jb + u * 64 + (tid >> 2);
+      pre[u] = j < jend ? *reinterpret_cast<const uint4*>(base + (size_t)j * 64) : make_uint4(0, 0, 0, 0);
+    }
   }
 }
 

@@ -3,14 +3,18 @@
 // stage delimit the segments.  Equal scores go to the lower block index and the index list is
 // written in ascending order, so there is exactly one correct output.
 //
-// One work-group of 1024 threads per segment runs an exact radix select in LDS:
-//   1. min / max of the segment's scores -> keys relative to the minimum, so that the digits of
-//      the first pass are spread over the histogram bins instead of piling up in a few;
-//   2. most-significant-digit-first 8-bit histogram passes narrow down the threshold key tau and
-//      the number `need` of tau-valued blocks that still fit;
-//   3. one ordered compaction: block j is selected iff key_j > tau, or key_j == tau and fewer than
-//      `need` tau-valued blocks precede it; its output slot is the count of selected blocks before it.
-// Scores are re-read from L2 in each pass (a segment is at most a few hundred KiB).
+// One work-group of 1024 threads per segment.  Selection is an exact threshold search:
+//   1. the segment's scores are loaded once (coalesced, all loads in flight together) and kept in
+//      registers as order-preserving unsigned keys relative to the segment minimum;
+//   2. one 256-bin LDS histogram over the top 8 significant bits of the key range finds the bin
+//      that holds the K-th largest key;
+//   3. the few candidates of that bin are appended to an LDS list and ranked exactly by
+//      (key desc, index asc); the candidate of rank `need`-1 fixes the threshold key tau and how
+//      many tau-valued blocks are taken (a crowded bin falls back to further radix digits);
+//   4. one ordered compaction: block j is selected iff key_j > tau, or key_j == tau and fewer than
+//      `need_eq` tau-valued blocks precede it; its output slot is the number of selected blocks
+//      before it (ballots + one scan of per-(tile, wave) counts).
+// Segments with more than 16384 blocks use the same algorithm with keys re-read from L2.
 #include "common.h"
 
 namespace absb {
@@ -27,9 +31,48 @@ struct TopkParams {
 
 constexpr int TOPK_THREADS = 1024;
 constexpr int TOPK_WAVES = TOPK_THREADS / 64;
+constexpr int TOPK_MAX_CAND = 1024;  // candidates ranked by brute force
+constexpr int TOPK_MAX_KPT = 16;     // keys per thread held in registers
 
 __device__ __forceinline__ uint32_t ordered_key(int32_t score) { return (uint32_t)score ^ 0x80000000u; }
 
+struct TopkShared {
+  uint32_t red[2 * TOPK_WAVES];
+  uint32_t hist[256];
+  uint32_t bcast[4];
+  uint32_t cand_key[TOPK_MAX_CAND];
+  uint32_t cand_idx[TOPK_MAX_CAND];
+  uint32_t cand_n;
+  uint32_t cnt_gt[TOPK_MAX_KPT * TOPK_WAVES];
+  uint32_t cnt_eq[TOPK_MAX_KPT * TOPK_WAVES];
+};
+
+// Finds, from a 256-bin histogram of the candidates' current digit, the bin holding the
+// `need`-th largest candidate; run by wave 0.  bcast[0] = bin, bcast[1] = candidates above it.
+__device__ __forceinline__ void pick_bin(TopkShared& sh, int lane, uint32_t need) {
+  const uint32_t c0 = sh.hist[4 * lane], c1 = sh.hist[4 * lane + 1], c2 = sh.hist[4 * lane + 2],
+                 c3 = sh.hist[4 * lane + 3];
+  const uint32_t mine = c0 + c1 + c2 + c3;
+  uint32_t incl = mine;  // inclusive suffix sum over lanes (lane 63 owns the highest bins)
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t v = (uint32_t)__shfl_down((int)incl, d);
+    if (lane + d < 64) incl += v;
+  }
+  uint32_t above = incl - mine;
+  const uint32_t c[4] = {c0, c1, c2, c3};
+#pragma unroll
+  for (int i = 3; i >= 0; --i) {
+    if (above < need && need <= above + c[i]) {
+      sh.bcast[0] = (uint32_t)(4 * lane + i);
+      sh.bcast[1] = above;
+      sh.bcast[2] = c[i];
+    }
+    above += c[i];
+  }
+}
+
+// KPT > 0: keys of the segment live in registers (N <= KPT*1024).  KPT == 0: keys are re-read.
+template <int KPT>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
   const int s = blockIdx.x;
   const int b = s / p.Hkv, h = s % p.Hkv;
@@ -42,6 +85,22 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t* sc = p.scores + off;
   int32_t* out = p.sel_idx + (size_t)s * p.sel_stride;
+  constexpr int R = KPT > 0 ? KPT : 1;
+  const int ntiles = KPT > 0 ? KPT : (N + TOPK_THREADS - 1) / TOPK_THREADS;
+
+  // keys first: everything else waits on them
+  uint32_t key[R];
+  if (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int j = i * TOPK_THREADS + tid;
+      key[i] = j < N ? ordered_key(sc[j]) : 0u;
+    }
+  }
+  auto key_at = [&](int i) -> uint32_t {  // valid only for i*1024+tid < N
+    if (KPT > 0) return key[i];
+    return ordered_key(sc[i * TOPK_THREADS + tid]);
+  };
 
   if (tid == 0) p.sel_cnt[s] = K;
   for (int i = K + tid; i < p.sel_stride; i += TOPK_THREADS) out[i] = -1;
@@ -50,112 +109,212 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
     return;
   }
 
-  __shared__ uint32_t s_red[2 * TOPK_WAVES];
-  __shared__ uint32_t s_hist[256];
-  __shared__ uint32_t s_bcast[2];
-  __shared__ uint32_t s_cnt_gt[TOPK_WAVES], s_cnt_eq[TOPK_WAVES];
+  __shared__ TopkShared sh;
+  if (tid < 256) sh.hist[tid] = 0;
+  if (tid == 0) sh.cand_n = 0;
 
   // ---- 1. range of the keys
   uint32_t kmin = 0xffffffffu, kmax = 0u;
-  for (int j = tid; j < N; j += TOPK_THREADS) {
-    const uint32_t k = ordered_key(sc[j]);
-    kmin = min(kmin, k);
-    kmax = max(kmax, k);
+#pragma unroll
+  for (int i = 0; i < (KPT > 0 ? KPT : 1); ++i) {
+    if (KPT > 0) {
+      if (i * TOPK_THREADS + tid < N) {
+        kmin = min(kmin, key[i]);
+        kmax = max(kmax, key[i]);
+      }
+    }
+  }
+  if (KPT == 0) {
+    for (int i = 0; i < ntiles; ++i)
+      if (i * TOPK_THREADS + tid < N) {
+        const uint32_t k = key_at(i);
+        kmin = min(kmin, k);
+        kmax = max(kmax, k);
+      }
   }
   for (int d = 32; d >= 1; d >>= 1) {
     kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, d));
     kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, d));
   }
   if (lane == 0) {
-    s_red[wave] = kmin;
-    s_red[TOPK_WAVES + wave] = kmax;
+    sh.red[wave] = kmin;
+    sh.red[TOPK_WAVES + wave] = kmax;
   }
   __syncthreads();
-  kmin = s_red[0];
-  kmax = s_red[TOPK_WAVES];
+  kmin = sh.red[0];
+  kmax = sh.red[TOPK_WAVES];
+#pragma unroll
   for (int w = 1; w < TOPK_WAVES; ++w) {
-    kmin = min(kmin, s_red[w]);
-    kmax = max(kmax, s_red[TOPK_WAVES + w]);
+    kmin = min(kmin, sh.red[w]);
+    kmax = max(kmax, sh.red[TOPK_WAVES + w]);
   }
   const uint32_t range = kmax - kmin;  // relative keys live in [0, range]
   const int bits = 32 - __builtin_clz(range | 1u);
-  const int passes = (bits + 7) / 8;
+  int shift = bits > 8 ? bits - 8 : 0;  // first digit = the top 8 significant bits
 
-  // ---- 2. radix select on rel = key - kmin, most significant digit first
-  uint32_t prefix = 0, mask = 0;
-  int need = K;
-  for (int pass = passes - 1; pass >= 0; --pass) {
-    const int shift = pass * 8;
-    if (tid < 256) s_hist[tid] = 0;
-    __syncthreads();
-    for (int j = tid; j < N; j += TOPK_THREADS) {
-      const uint32_t rel = ordered_key(sc[j]) - kmin;
-      if ((rel & mask) == prefix) atomicAdd(&s_hist[(rel >> shift) & 255u], 1u);
-    }
-    __syncthreads();
-    if (wave == 0) {
-      // lane owns bins 4*lane .. 4*lane+3; above = number of candidates in strictly higher bins
-      const uint32_t c0 = s_hist[4 * lane], c1 = s_hist[4 * lane + 1], c2 = s_hist[4 * lane + 2],
-                     c3 = s_hist[4 * lane + 3];
-      const uint32_t mine = c0 + c1 + c2 + c3;
-      uint32_t incl = mine;  // inclusive suffix sum over lanes (lane 63 = highest bins)
-      for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t v = (uint32_t)__shfl_down((int)incl, d);
-        if (lane + d < 64) incl += v;
-      }
-      uint32_t above = incl - mine;
-      // walk the four bins from the top
-      const uint32_t c[4] = {c0, c1, c2, c3};
+  // ---- 2. histogram of the first digit, threshold bin
+  uint32_t prefix = 0, mask = 0;  // candidates: (rel & mask) == prefix
+  uint32_t need = (uint32_t)K;
 #pragma unroll
-      for (int i = 3; i >= 0; --i) {
-        if (above < (uint32_t)need && (uint32_t)need <= above + c[i]) {
-          s_bcast[0] = (uint32_t)(4 * lane + i);
-          s_bcast[1] = above;
-        }
-        above += c[i];
-      }
-    }
-    __syncthreads();
-    prefix |= s_bcast[0] << shift;
-    mask |= 255u << shift;
-    need -= (int)s_bcast[1];
+  for (int i = 0; i < ntiles; ++i) {
+    if (i * TOPK_THREADS + tid < N) atomicAdd(&sh.hist[((key_at(i) - kmin) >> shift) & 255u], 1u);
   }
-  // tau = prefix (relative key); `need` >= 1 blocks with key == tau are taken, lowest index first
+  __syncthreads();
+  if (wave == 0) pick_bin(sh, lane, need);
+  __syncthreads();
+  prefix = sh.bcast[0] << shift;
+  mask = 255u << shift;
+  need -= sh.bcast[1];
+  uint32_t ncand = sh.bcast[2];
 
-  // ---- 3. ordered compaction in tiles of 1024 consecutive indices
-  int base_gt = 0, base_eq = 0;  // selected-by-gt / eq-valued blocks before the tile
-  for (int t0 = 0; t0 < N; t0 += TOPK_THREADS) {
-    const int j = t0 + tid;
-    uint32_t rel = 0;
-    bool gt = false, eq = false;
-    if (j < N) {
-      rel = ordered_key(sc[j]) - kmin;
-      gt = rel > prefix;
-      eq = rel == prefix;
-    }
-    const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
-    if (lane == 0) {
-      s_cnt_gt[wave] = (uint32_t)__popcll(bgt);
-      s_cnt_eq[wave] = (uint32_t)__popcll(beq);
-    }
-    __syncthreads();
-    int gt_before = base_gt, eq_before = base_eq, gt_tile = 0, eq_tile = 0;
-    for (int w = 0; w < TOPK_WAVES; ++w) {
-      const int cg = (int)s_cnt_gt[w], ce = (int)s_cnt_eq[w];
-      if (w < wave) {
-        gt_before += cg;
-        eq_before += ce;
+  // ---- 3. exact threshold inside the bin
+  uint32_t tau = prefix, need_eq = need;  // valid as is when no bits are left (shift == 0)
+  while (shift > 0) {
+    if (ncand <= (uint32_t)TOPK_MAX_CAND) {
+      // few candidates: list them, rank them by (key desc, index asc)
+#pragma unroll
+      for (int i = 0; i < ntiles; ++i) {
+        const int j = i * TOPK_THREADS + tid;
+        if (j < N) {
+          const uint32_t rel = key_at(i) - kmin;
+          if ((rel & mask) == prefix) {
+            const uint32_t slot = atomicAdd(&sh.cand_n, 1u);
+            sh.cand_key[slot] = rel;
+            sh.cand_idx[slot] = (uint32_t)j;
+          }
+        }
       }
-      gt_tile += cg;
-      eq_tile += ce;
+      __syncthreads();
+      if ((uint32_t)tid < ncand) {
+        const uint32_t mk = sh.cand_key[tid], mi = sh.cand_idx[tid];
+        uint32_t rank = 0, gtk = 0;
+        for (uint32_t u = 0; u < ncand; ++u) {
+          const uint32_t ok = sh.cand_key[u], oi = sh.cand_idx[u];
+          gtk += ok > mk;
+          rank += (ok > mk) || (ok == mk && oi < mi);
+        }
+        if (rank == need - 1) {
+          sh.bcast[0] = mk;
+          sh.bcast[1] = need - gtk;  // how many blocks with key == tau are taken
+        }
+      }
+      __syncthreads();
+      tau = sh.bcast[0];
+      need_eq = sh.bcast[1];
+      break;
     }
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-    gt_before += __popcll(bgt & lt_mask);
-    eq_before += __popcll(beq & lt_mask);
-    if (gt || (eq && eq_before < need)) out[gt_before + min(eq_before, need)] = j;
-    base_gt += gt_tile;
-    base_eq += eq_tile;
+    // crowded bin: next 8-bit digit
+    shift = shift > 8 ? shift - 8 : 0;
+    if (tid < 256) sh.hist[tid] = 0;
     __syncthreads();
+#pragma unroll
+    for (int i = 0; i < ntiles; ++i) {
+      if (i * TOPK_THREADS + tid < N) {
+        const uint32_t rel = key_at(i) - kmin;
+        if ((rel & mask) == prefix) atomicAdd(&sh.hist[(rel >> shift) & 255u], 1u);
+      }
+    }
+    __syncthreads();
+    if (wave == 0) pick_bin(sh, lane, need);
+    __syncthreads();
+    prefix |= sh.bcast[0] << shift;
+    mask |= 255u << shift;
+    need -= sh.bcast[1];
+    ncand = sh.bcast[2];
+    tau = prefix;
+    need_eq = need;
+    __syncthreads();  // bcast is rewritten by the next round
+  }
+
+  // ---- 4. ordered compaction
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  if (KPT > 0) {
+    // per-(tile, wave) counts -> one exclusive scan in index order -> slots
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int j = i * TOPK_THREADS + tid;
+      const uint32_t rel = key[i] - kmin;
+      const bool v = j < N;
+      const uint64_t bgt = __ballot(v && rel > tau), beq = __ballot(v && rel == tau);
+      if (lane == 0) {
+        sh.cnt_gt[i * TOPK_WAVES + wave] = (uint32_t)__popcll(bgt);
+        sh.cnt_eq[i * TOPK_WAVES + wave] = (uint32_t)__popcll(beq);
+      }
+    }
+    __syncthreads();
+    if (wave < 2) {  // wave 0 scans cnt_gt, wave 1 scans cnt_eq; lane owns R*16/64 consecutive entries
+      uint32_t* arr = wave == 0 ? sh.cnt_gt : sh.cnt_eq;
+      constexpr int PER = (R * TOPK_WAVES + 63) / 64;
+      uint32_t v[PER], tot = 0;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) {
+        const int idx = lane * PER + e;
+        v[e] = idx < R * TOPK_WAVES ? arr[idx] : 0u;
+        tot += v[e];
+      }
+      uint32_t incl = tot;
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, d);
+        if (lane >= d) incl += o;
+      }
+      uint32_t run = incl - tot;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) {
+        const int idx = lane * PER + e;
+        if (idx < R * TOPK_WAVES) arr[idx] = run;
+        run += v[e];
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < R; ++i) {
+      const int j = i * TOPK_THREADS + tid;
+      const uint32_t rel = key[i] - kmin;
+      const bool v = j < N;
+      const bool gt = v && rel > tau, eq = v && rel == tau;
+      const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
+      const uint32_t gt_before = sh.cnt_gt[i * TOPK_WAVES + wave] + (uint32_t)__popcll(bgt & lt_mask);
+      const uint32_t eq_before = sh.cnt_eq[i * TOPK_WAVES + wave] + (uint32_t)__popcll(beq & lt_mask);
+      if (gt || (eq && eq_before < need_eq)) {
+        const uint32_t slot = gt_before + min(eq_before, need_eq);
+        if (slot < (uint32_t)K) out[slot] = j;  // always true for consistent counts; keeps stores in bounds
+      }
+    }
+  } else {
+    // long segments: tile by tile with running bases
+    uint32_t base_gt = 0, base_eq = 0;
+    for (int i = 0; i < ntiles; ++i) {
+      const int j = i * TOPK_THREADS + tid;
+      const bool v = j < N;
+      const uint32_t rel = v ? key_at(i) - kmin : 0u;
+      const bool gt = v && rel > tau, eq = v && rel == tau;
+      const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
+      if (lane == 0) {
+        sh.cnt_gt[wave] = (uint32_t)__popcll(bgt);
+        sh.cnt_eq[wave] = (uint32_t)__popcll(beq);
+      }
+      __syncthreads();
+      uint32_t gt_before = base_gt, eq_before = base_eq, gt_tile = 0, eq_tile = 0;
+#pragma unroll
+      for (int w = 0; w < TOPK_WAVES; ++w) {
+        const uint32_t cg = sh.cnt_gt[w], ce = sh.cnt_eq[w];
+        if (w < wave) {
+          gt_before += cg;
+          eq_before += ce;
+        }
+        gt_tile += cg;
+        eq_tile += ce;
+      }
+      gt_before += (uint32_t)__popcll(bgt & lt_mask);
+      eq_before += (uint32_t)__popcll(beq & lt_mask);
+      if (gt || (eq && eq_before < need_eq)) {
+        const uint32_t slot = gt_before + min(eq_before, need_eq);
+        if (slot < (uint32_t)K) out[slot] = j;
+      }
+      base_gt += gt_tile;
+      base_eq += eq_tile;
+      __syncthreads();
+    }
   }
 }
 
@@ -171,7 +330,20 @@ int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const 
   p.sel_stride = sel_stride;
   p.Hkv = g.Hkv;
   p.heads = g.heads;
-  hipLaunchKernelGGL(topk_kernel, dim3((unsigned)pl.nseg), dim3(TOPK_THREADS), 0, stream, p);
+  const dim3 grid((unsigned)pl.nseg), block(TOPK_THREADS);
+  const int tiles = (pl.max_blocks + TOPK_THREADS - 1) / TOPK_THREADS;
+  if (tiles <= 1)
+    hipLaunchKernelGGL(topk_kernel<1>, grid, block, 0, stream, p);
+  else if (tiles <= 2)
+    hipLaunchKernelGGL(topk_kernel<2>, grid, block, 0, stream, p);
+  else if (tiles <= 4)
+    hipLaunchKernelGGL(topk_kernel<4>, grid, block, 0, stream, p);
+  else if (tiles <= 8)
+    hipLaunchKernelGGL(topk_kernel<8>, grid, block, 0, stream, p);
+  else if (tiles <= 16)
+    hipLaunchKernelGGL(topk_kernel<16>, grid, block, 0, stream, p);
+  else
+    hipLaunchKernelGGL(topk_kernel<0>, grid, block, 0, stream, p);
   return check_launch();
 }
 

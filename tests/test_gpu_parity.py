@@ -204,7 +204,7 @@ def test_all_equal_scores_pick_lowest_indices():
 def test_decode_accepts_any_list_order_partial_last_block_and_empty_lists():
     import torch
     wl = synth.tiny_workload(seed=34, dtype=synth.F16, Bt=2, Hq=8, Hkv=2, P=16, seq_lens=(203, 77),
-                             block_size=(8, 32), budget=(64, 64))
+                             block_size=(8, 32), budget=(256, 256))      # lists below stay within K_s
     dw = _dev(wl)
     K = dw.sel_stride
     rng = np.random.default_rng(1)
