@@ -143,6 +143,49 @@ __device__ __forceinline__ int quad_sum(int v) {
   v += dpp_i<DPP_QUAD_XOR2>(v);
   return v;
 }
+
+// Reductions and scans over a wave built from DPP row operations and four lane reads.  They
+// replace ds_bpermute shuffle chains (each shuffle is an LDS-crossbar round trip of >100 cycles).
+// All 64 lanes must be active.
+template <typename Op>
+__device__ __forceinline__ uint32_t row16_reduce_u32(uint32_t v, Op op) {  // every lane of a row gets the row's result
+  v = op(v, (uint32_t)dpp_i<DPP_QUAD_XOR1>((int)v));
+  v = op(v, (uint32_t)dpp_i<DPP_QUAD_XOR2>((int)v));
+  v = op(v, (uint32_t)dpp_i<DPP_ROW_HALF_MIRROR>((int)v));
+  v = op(v, (uint32_t)dpp_i<DPP_ROW_MIRROR>((int)v));
+  return v;
+}
+template <typename Op>
+__device__ __forceinline__ uint32_t wave_reduce_u32(uint32_t v, Op op) {  // wave-uniform result
+  v = row16_reduce_u32(v, op);
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16),
+                 c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return op(op(a, b), op(c, d));
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+  v = fmaxf(v, dpp_f<DPP_QUAD_XOR1>(v));
+  v = fmaxf(v, dpp_f<DPP_QUAD_XOR2>(v));
+  v = fmaxf(v, dpp_f<DPP_ROW_HALF_MIRROR>(v));
+  v = fmaxf(v, dpp_f<DPP_ROW_MIRROR>(v));
+  const float a = bitcast<float>(__builtin_amdgcn_readlane(bitcast<int>(v), 0)),
+              b = bitcast<float>(__builtin_amdgcn_readlane(bitcast<int>(v), 16)),
+              c = bitcast<float>(__builtin_amdgcn_readlane(bitcast<int>(v), 32)),
+              d = bitcast<float>(__builtin_amdgcn_readlane(bitcast<int>(v), 48));
+  return fmaxf(fmaxf(a, b), fmaxf(c, d));
+}
+// Inclusive prefix sum over the wave in lane order; *total receives the wave's sum.
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, uint32_t* total) {
+  v += (uint32_t)dpp_i<0x111>((int)v);  // row_shr:1 (lanes shifted in from outside the row read 0)
+  v += (uint32_t)dpp_i<0x112>((int)v);  // row_shr:2
+  v += (uint32_t)dpp_i<0x114>((int)v);  // row_shr:4
+  v += (uint32_t)dpp_i<0x118>((int)v);  // row_shr:8
+  const uint32_t t0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15), t1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 31),
+                 t2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 47), t3 = (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+  const int row = (int)(__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)) >> 4);
+  v += (row >= 1 ? t0 : 0u) + (row >= 2 ? t1 : 0u) + (row >= 3 ? t2 : 0u);
+  *total = t0 + t1 + t2 + t3;
+  return v;
+}
 #endif  // __HIPCC__
 
 }  // namespace absb

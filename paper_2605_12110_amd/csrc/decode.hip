@@ -153,63 +153,63 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
     }
   }
 
-  // ---- merge the four row-groups of the wave (xor-shuffles over lanes 16 and 32 apart)
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-#pragma unroll
-    for (int d = 16; d <= 32; d <<= 1) {
-      const float m_o = __shfl_xor(m[g], d);
-      const float mn = fmaxf(m[g], m_o);
-      const float a_me = fast_exp2(m[g] - mn), a_ot = fast_exp2(m_o - mn);
-      l[g] = l[g] * a_me + __shfl_xor(l[g], d) * a_ot;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) o[g][c] = o[g][c] * a_me + __shfl_xor(o[g][c], d) * a_ot;
-      m[g] = mn;
-    }
-  }
-
-  // ---- merge the waves through LDS, write the split's partial
-  __shared__ float s_o[DEC_WAVES][G][ABSB_HEAD_DIM];
-  __shared__ float s_m[DEC_WAVES][G], s_l[DEC_WAVES][G];
-  if (grp == 0) {
+  // ---- merge the work-group's 16 row-group states through LDS and write the split's partial.
+  // Rolled loops on purpose: this code runs once per work-group, and straight-line code that runs
+  // once costs more in instruction fetch than it saves in issue slots.
+  constexpr int PARTS = DEC_WAVES * 4;
+  constexpr int GC = G < 4 ? G : 4;  // heads staged per pass (bounds LDS at 32 KiB)
+  __shared__ float s_o[PARTS][GC][ABSB_HEAD_DIM];
+  __shared__ float s_m[PARTS][G], s_l[PARTS][G];
+  const int part = wave * 4 + grp;
+  if (li == 0) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-#pragma unroll
-      for (int c = 0; c < 8; ++c) s_o[wave][g][li * 8 + c] = o[g][c];
-      if (li == 0) {
-        s_m[wave][g] = m[g];
-        s_l[wave][g] = l[g];
-      }
+      s_m[part][g] = m[g];
+      s_l[part][g] = l[g];
     }
   }
-  __syncthreads();
   const size_t slot = (size_t)s * p.max_splits + split;
-  for (int i = tid; i < G * ABSB_HEAD_DIM; i += DEC_THREADS) {
-    const int g = i >> 7, c = i & 127;
-    float M = s_m[0][g];
 #pragma unroll
-    for (int w = 1; w < DEC_WAVES; ++w) M = fmaxf(M, s_m[w][g]);
-    float Lsum = 0.0f, O = 0.0f;
+  for (int g0 = 0; g0 < G; g0 += GC) {
+    if (g0 > 0) __syncthreads();
 #pragma unroll
-    for (int w = 0; w < DEC_WAVES; ++w) {
-      const float a = fast_exp2(s_m[w][g] - M);
-      Lsum = __builtin_fmaf(s_l[w][g], a, Lsum);
-      O = __builtin_fmaf(s_o[w][g][c], a, O);
+    for (int k = 0; k < GC; ++k) {
+      if (g0 + k < G) {
+        float4* dst = reinterpret_cast<float4*>(&s_o[part][k][li * 8]);
+        dst[0] = make_float4(o[g0 + k][0], o[g0 + k][1], o[g0 + k][2], o[g0 + k][3]);
+        dst[1] = make_float4(o[g0 + k][4], o[g0 + k][5], o[g0 + k][6], o[g0 + k][7]);
+      }
     }
-    p.part_o[(slot * G + g) * ABSB_HEAD_DIM + c] = O;
-    if (c == 0) {
-      p.part_ml[(slot * G + g) * 2 + 0] = M;
-      p.part_ml[(slot * G + g) * 2 + 1] = Lsum;
+    __syncthreads();
+    const int nout = (G - g0 < GC ? G - g0 : GC) * ABSB_HEAD_DIM;
+#pragma unroll 1
+    for (int i = tid; i < nout; i += DEC_THREADS) {
+      const int k = i >> 7, c = i & 127, g = g0 + k;
+      float M = M_INIT;
+#pragma unroll 1
+      for (int q = 0; q < PARTS; ++q) M = fmaxf(M, s_m[q][g]);
+      float Lsum = 0.0f, O = 0.0f;
+#pragma unroll 1
+      for (int q = 0; q < PARTS; ++q) {
+        const float a = fast_exp2(s_m[q][g] - M);
+        Lsum = __builtin_fmaf(s_l[q][g], a, Lsum);
+        O = __builtin_fmaf(s_o[q][k][c], a, O);
+      }
+      p.part_o[(slot * G + g) * ABSB_HEAD_DIM + c] = O;
+      if (c == 0) {
+        p.part_ml[(slot * G + g) * 2 + 0] = M;
+        p.part_ml[(slot * G + g) * 2 + 1] = Lsum;
+      }
     }
   }
 }
 
 // Log-sum-exp merge of a segment's split partials.  One work-group per (query head, segment):
-// 128 channels x 4 split lanes; a thread takes every 4th split, with up to MRG_UNROLL independent
+// 128 channels x 8 split lanes; a thread takes every 8th split, with up to MRG_UNROLL independent
 // loads in flight, so the whole merge costs about one memory round trip.
-constexpr int MRG_THREADS = 512;
+constexpr int MRG_THREADS = 1024;
 constexpr int MRG_LANES = MRG_THREADS / ABSB_HEAD_DIM;
-constexpr int MRG_UNROLL = 16;
+constexpr int MRG_UNROLL = 8;
 
 template <int DT>
 __global__ __launch_bounds__(MRG_THREADS) void decode_merge_kernel(DecodeParams p) {

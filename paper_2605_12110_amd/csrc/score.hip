@@ -11,8 +11,13 @@
 // with -ffp-contract=off.
 //
 // Memory: a centroid is 64 bytes of codes.  Four lanes share one centroid (16 bytes = 32 channels
-// each), so one wave load instruction reads 1 KiB of consecutive codes; each lane keeps its 32
-// integer weights in registers for the whole work-group.
+// each), so one wave load instruction reads 1 KiB of consecutive codes.
+//
+// Arithmetic: the codes are unsigned 4-bit, so the dot product runs on the packed 4-bit dot
+// instruction (8 multiply-adds per lane and instruction).  The biased weight wq + 2^15 (17 bits,
+// unsigned) is cut into five 4-bit planes; S = sum_k 16^k * dot(plane_k, codes) - 2^15 * sum(codes).
+// Six packed dots per 8 channels replace 16 unpack-and-multiply steps, and the kernel stays short:
+// it is launched with one batch of work per lane, so instruction count is what bounds it.
 #include "common.h"
 
 namespace absb {
@@ -27,6 +32,15 @@ struct ScoreParams {
   int32_t Hq, Hkv, G, chunk;
 };
 
+constexpr int SCORE_PLANES = 5;
+
+__device__ __forceinline__ uint32_t or8(uint32_t v) {  // OR over aligned groups of 8 lanes
+  v |= (uint32_t)dpp_i<DPP_QUAD_XOR1>((int)v);
+  v |= (uint32_t)dpp_i<DPP_QUAD_XOR2>((int)v);
+  v |= (uint32_t)dpp_i<DPP_ROW_HALF_MIRROR>((int)v);
+  return v;
+}
+
 template <int DT>
 __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
   const int s = blockIdx.y;
@@ -38,7 +52,7 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
   const int tid = threadIdx.x;
 
   __shared__ float s_absmax[2];
-  __shared__ int32_t s_wq[ABSB_HEAD_DIM];
+  __shared__ uint32_t s_plane[SCORE_PLANES][ABSB_HEAD_DIM / 8];
 
   // ---- the work-group's first batch of codes goes in flight before anything else: the loads do
   // not depend on the query, so their latency overlaps the prologue below
@@ -49,21 +63,21 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
   uint4 pre[PF];
 #pragma unroll
   for (int u = 0; u < PF; ++u) {
-    const int j = j0 + u * 64 + (tid >> 2);
-    pre[u] = j < jend ? *reinterpret_cast<const uint4*>(base + (size_t)j * 64) : make_uint4(0, 0, 0, 0);
+    const int j = min(j0 + u * 64 + (tid >> 2), jend - 1);  // clamped, not predicated: loads issue back to back
+    pre[u] = *reinterpret_cast<const uint4*>(base + (size_t)j * 64);
   }
 
-  // ---- prologue: fixed-point image of w = (sum_g q_g) * scale, by threads 0..127
+  // ---- prologue: fixed-point image of w = (sum_g q_g) * scale, by threads 0..127 (channel = tid)
   float w = 0.0f;
   if (tid < ABSB_HEAD_DIM) {
     const uint16_t* qrow = p.q + ((size_t)b * p.Hq + (size_t)h * p.G) * ABSB_HEAD_DIM + tid;
     float u = Elem<DT>::widen(qrow[0]);
+#pragma unroll 1
     for (int g = 1; g < p.G; ++g) u = u + Elem<DT>::widen(qrow[(size_t)g * ABSB_HEAD_DIM]);
     w = u * p.qscale[(size_t)s * ABSB_HEAD_DIM + tid];
     float a = __builtin_fabsf(w);
     a = (a != a) ? 0.0f : a;  // a NaN never wins the maximum
-    // wave-wide maximum (exact, order-free)
-    for (int d = 32; d >= 1; d >>= 1) a = fmaxf(a, __shfl_xor(a, d));
+    a = wave_max_f32(a);  // exact, order-free
     if ((tid & 63) == 0) s_absmax[tid >> 6] = a;
   }
   __syncthreads();
@@ -74,29 +88,44 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
   if (tid < ABSB_HEAD_DIM) {
     int32_t wq = 0;
     if (live) wq = (int32_t)__builtin_rintf(__builtin_ldexpf(w, -ex));
-    s_wq[tid] = wq;
+    // biased weight in [0, 2^16]; its five 4-bit digits, packed over 8 consecutive channels
+    const uint32_t wo = (uint32_t)(wq + 32768);
+    const int sh = 4 * (tid & 7);
+#pragma unroll
+    for (int k = 0; k < SCORE_PLANES; ++k) {
+      const uint32_t packed = or8(((wo >> (4 * k)) & 15u) << sh);
+      if ((tid & 7) == 0) s_plane[k][tid >> 3] = packed;
+    }
   }
   if (tid == 0 && blockIdx.x == 0 && p.score_exp) p.score_exp[s] = ex;
   __syncthreads();
 
-  // ---- each lane: the 32 weights of its quarter of the channels
-  int32_t wq[32];
+  // ---- each lane: the digit planes of its quarter of the channels (4 words of 8 channels)
+  uint4 wp[SCORE_PLANES];
 #pragma unroll
-  for (int i = 0; i < 32; ++i) wq[i] = s_wq[quarter * 32 + i];
+  for (int k = 0; k < SCORE_PLANES; ++k) wp[k] = *reinterpret_cast<const uint4*>(&s_plane[k][quarter * 4]);
 
   auto dot = [&](const uint4& c) -> int32_t {
-    const uint32_t dw[4] = {c.x, c.y, c.z, c.w};
-    int32_t acc = 0;
+    uint32_t acc = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-#pragma unroll
-      for (int n = 0; n < 8; ++n) acc += wq[k * 8 + n] * (int32_t)((dw[k] >> (4 * n)) & 15u);
+    for (int k = 0; k < SCORE_PLANES; ++k) {
+      uint32_t d = __builtin_amdgcn_udot8(c.x, wp[k].x, 0u, false);
+      d = __builtin_amdgcn_udot8(c.y, wp[k].y, d, false);
+      d = __builtin_amdgcn_udot8(c.z, wp[k].z, d, false);
+      d = __builtin_amdgcn_udot8(c.w, wp[k].w, d, false);
+      acc += d << (4 * k);
     }
-    return quad_sum(acc);  // the four lanes of a quad hold the four quarters of one centroid
+    uint32_t ones = __builtin_amdgcn_udot8(c.x, 0x11111111u, 0u, false);
+    ones = __builtin_amdgcn_udot8(c.y, 0x11111111u, ones, false);
+    ones = __builtin_amdgcn_udot8(c.z, 0x11111111u, ones, false);
+    ones = __builtin_amdgcn_udot8(c.w, 0x11111111u, ones, false);
+    acc -= ones << 15;                 // two's complement: exact sum_c wq_c * code_c of this quarter
+    return quad_sum((int32_t)acc);     // the four lanes of a quad hold the four quarters of one centroid
   };
 
   // ---- main loop: 64 centroids per work-group step (16 per wave), PF steps per batch.
   // Every lane of a quad shares j, so the quad reduction always sees four live lanes.
+#pragma unroll 1
   for (int jb = j0;;) {
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
@@ -108,8 +137,8 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
     if (jb >= jend) break;
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
-      const int j = jb + u * 64 + (tid >> 2);
-      pre[u] = j < jend ? *reinterpret_cast<const uint4*>(base + (size_t)j * 64) : make_uint4(0, 0, 0, 0);
+      const int j = min(jb + u * 64 + (tid >> 2), jend - 1);
+      pre[u] = *reinterpret_cast<const uint4*>(base + (size_t)j * 64);
     }
   }
 }

@@ -3,18 +3,21 @@
 // stage delimit the segments.  Equal scores go to the lower block index and the index list is
 // written in ascending order, so there is exactly one correct output.
 //
-// One work-group of 1024 threads per segment.  Selection is an exact threshold search:
-//   1. the segment's scores are loaded once (coalesced, all loads in flight together) and kept in
-//      registers as order-preserving unsigned keys relative to the segment minimum;
-//   2. one 256-bin LDS histogram over the top 8 significant bits of the key range finds the bin
-//      that holds the K-th largest key;
-//   3. the few candidates of that bin are appended to an LDS list and ranked exactly by
-//      (key desc, index asc); the candidate of rank `need`-1 fixes the threshold key tau and how
-//      many tau-valued blocks are taken (a crowded bin falls back to further radix digits);
-//   4. one ordered compaction: block j is selected iff key_j > tau, or key_j == tau and fewer than
-//      `need_eq` tau-valued blocks precede it; its output slot is the number of selected blocks
-//      before it (ballots + one scan of per-(tile, wave) counts).
-// Segments with more than 16384 blocks use the same algorithm with keys re-read from L2.
+// One work-group of 1024 threads per segment.  Selection is an exact threshold search that touches
+// every key three times with a handful of instructions each (the kernel runs on one CU per
+// segment, so instructions per key and dependent latencies, not bytes, bound it):
+//   1. the segment's scores are loaded once (coalesced, unconditional, all loads in flight
+//      together) and kept in registers as order-preserving unsigned keys; min/max give the range;
+//   2. a 2048-bin LDS histogram over the top 11 significant bits of (key - min) and a work-group
+//      scan find the bin d1 that holds the K-th largest key;
+//   3. keys above bin d1 set their bit in an LDS bitmap of selected blocks; the few keys inside
+//      d1 are appended to a candidate list, ranked exactly by (key desc, index asc), and the best
+//      `need` of them set their bits too;
+//   4. the bitmap is scanned in index order (popcount prefix sums) and the indices written out.
+// A crowded bin (more than 1024 candidates, e.g. all scores equal) takes a slow path: further radix
+// digits give the exact threshold tau, and blocks equal to tau are admitted in index order through
+// a second bitmap.  Segments longer than 16384 blocks run the same code with keys re-read from L2.
+// Wave-level reductions and scans use DPP row operations, not LDS-crossbar shuffles.
 #include "common.h"
 
 namespace absb {
@@ -31,49 +34,77 @@ struct TopkParams {
 
 constexpr int TOPK_THREADS = 1024;
 constexpr int TOPK_WAVES = TOPK_THREADS / 64;
-constexpr int TOPK_MAX_CAND = 1024;  // candidates ranked by brute force
-constexpr int TOPK_MAX_KPT = 16;     // keys per thread held in registers
+constexpr int TOPK_MAX_CAND = 1024;       // candidates ranked by brute force
+constexpr int TOPK_MAX_BLOCKS = 1 << 17;  // bitmap capacity (2 x 16 KiB of LDS)
+constexpr int TOPK_DIGIT_BITS = 11;
+constexpr int TOPK_BINS = 1 << TOPK_DIGIT_BITS;  // two bins per thread
 
 __device__ __forceinline__ uint32_t ordered_key(int32_t score) { return (uint32_t)score ^ 0x80000000u; }
 
 struct TopkShared {
   uint32_t red[2 * TOPK_WAVES];
-  uint32_t hist[256];
+  uint32_t hist[TOPK_BINS];
   uint32_t bcast[4];
   uint32_t cand_key[TOPK_MAX_CAND];
   uint32_t cand_idx[TOPK_MAX_CAND];
   uint32_t cand_n;
-  uint32_t cnt_gt[TOPK_MAX_KPT * TOPK_WAVES];
-  uint32_t cnt_eq[TOPK_MAX_KPT * TOPK_WAVES];
+  uint32_t wave_a[TOPK_WAVES], wave_b[TOPK_WAVES];
 };
 
-// Finds, from a 256-bin histogram of the candidates' current digit, the bin holding the
-// `need`-th largest candidate; run by wave 0.  bcast[0] = bin, bcast[1] = candidates above it.
-__device__ __forceinline__ void pick_bin(TopkShared& sh, int lane, uint32_t need) {
-  const uint32_t c0 = sh.hist[4 * lane], c1 = sh.hist[4 * lane + 1], c2 = sh.hist[4 * lane + 2],
-                 c3 = sh.hist[4 * lane + 3];
-  const uint32_t mine = c0 + c1 + c2 + c3;
-  uint32_t incl = mine;  // inclusive suffix sum over lanes (lane 63 owns the highest bins)
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t v = (uint32_t)__shfl_down((int)incl, d);
-    if (lane + d < 64) incl += v;
+struct UMin {
+  __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a < b ? a : b; }
+};
+struct UMax {
+  __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; }
+};
+
+// Exclusive prefix sum of one value per thread over the work-group (thread order); *total = sum.
+// `slot` is 16 words of LDS scratch.  Contains one barrier: call from uniform control flow.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* slot, int lane, int wave, uint32_t* total) {
+  uint32_t wave_total;
+  const uint32_t incl = wave_incl_scan_u32(v, &wave_total);
+  if (lane == 0) slot[wave] = wave_total;
+  __syncthreads();
+  // 16 wave totals: every 16-lane row scans them again (cheaper than a second barrier)
+  const uint32_t mine = slot[lane & (TOPK_WAVES - 1)];
+  uint32_t s = mine;
+  s += (uint32_t)dpp_i<0x111>((int)s);
+  s += (uint32_t)dpp_i<0x112>((int)s);
+  s += (uint32_t)dpp_i<0x114>((int)s);
+  s += (uint32_t)dpp_i<0x118>((int)s);  // inclusive over the row = over waves 0..(lane&15)
+  *total = (uint32_t)__builtin_amdgcn_readlane((int)s, 15);
+  // exclusive prefix of this thread's wave: lane `wave` holds the sum over waves 0..wave; drop own total
+  const uint32_t upto = (uint32_t)__builtin_amdgcn_readlane((int)s, __builtin_amdgcn_readfirstlane(wave));
+  return upto - wave_total + incl - v;
+}
+
+// From the histogram of the current digit among the candidates: the bin holding the `need`-th
+// largest candidate.  All threads take part (two bins each, highest bins first).
+// bcast = {bin, candidates above it, candidates in it}.  Two barriers inside.
+__device__ __forceinline__ void pick_bin(TopkShared& sh, int tid, int lane, int wave, uint32_t need) {
+  const int hi = TOPK_BINS - 1 - 2 * tid;  // descending: thread 0 owns the two highest bins
+  const uint32_t c0 = sh.hist[hi], c1 = sh.hist[hi - 1];
+  uint32_t total;
+  uint32_t above = block_excl_scan(c0 + c1, sh.wave_a, lane, wave, &total);
+  if (above < need && need <= above + c0) {
+    sh.bcast[0] = (uint32_t)hi;
+    sh.bcast[1] = above;
+    sh.bcast[2] = c0;
   }
-  uint32_t above = incl - mine;
-  const uint32_t c[4] = {c0, c1, c2, c3};
-#pragma unroll
-  for (int i = 3; i >= 0; --i) {
-    if (above < need && need <= above + c[i]) {
-      sh.bcast[0] = (uint32_t)(4 * lane + i);
-      sh.bcast[1] = above;
-      sh.bcast[2] = c[i];
-    }
-    above += c[i];
+  above += c0;
+  if (above < need && need <= above + c1) {
+    sh.bcast[0] = (uint32_t)(hi - 1);
+    sh.bcast[1] = above;
+    sh.bcast[2] = c1;
   }
+  __syncthreads();
 }
 
 // KPT > 0: keys of the segment live in registers (N <= KPT*1024).  KPT == 0: keys are re-read.
 template <int KPT>
 __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
+  extern __shared__ uint32_t s_bitmap[];  // [2][words]: selected-by-key bits, then equal-to-tau bits
+  __shared__ TopkShared sh;
   const int s = blockIdx.x;
   const int b = s / p.Hkv, h = s % p.Hkv;
   const int off = p.cent_off[s];
@@ -87,240 +118,179 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
   int32_t* out = p.sel_idx + (size_t)s * p.sel_stride;
   constexpr int R = KPT > 0 ? KPT : 1;
   const int ntiles = KPT > 0 ? KPT : (N + TOPK_THREADS - 1) / TOPK_THREADS;
+  const int nwords = (N + 31) >> 5;
+  uint32_t* bm_gt = s_bitmap;
+  uint32_t* bm_eq = s_bitmap + nwords;
 
-  // keys first: everything else waits on them
+  // keys first: everything else waits on them.  The index is clamped instead of the load being
+  // predicated, so the loads issue back to back (N >= 1 always).
   uint32_t key[R];
   if (KPT > 0) {
 #pragma unroll
-    for (int i = 0; i < R; ++i) {
-      const int j = i * TOPK_THREADS + tid;
-      key[i] = j < N ? ordered_key(sc[j]) : 0u;
-    }
+    for (int i = 0; i < R; ++i) key[i] = ordered_key(sc[min(i * TOPK_THREADS + tid, N - 1)]);
   }
-  auto key_at = [&](int i) -> uint32_t {  // valid only for i*1024+tid < N
+  auto key_at = [&](int i) -> uint32_t {  // meaningful only for i*1024+tid < N
     if (KPT > 0) return key[i];
-    return ordered_key(sc[i * TOPK_THREADS + tid]);
+    return ordered_key(sc[min(i * TOPK_THREADS + tid, N - 1)]);
   };
 
   if (tid == 0) p.sel_cnt[s] = K;
+#pragma unroll 1
   for (int i = K + tid; i < p.sel_stride; i += TOPK_THREADS) out[i] = -1;
   if (K >= N) {  // everything is selected
+#pragma unroll 1
     for (int i = tid; i < N; i += TOPK_THREADS) out[i] = i;
     return;
   }
 
-  __shared__ TopkShared sh;
-  if (tid < 256) sh.hist[tid] = 0;
+  sh.hist[tid] = 0;
+  sh.hist[tid + TOPK_THREADS] = 0;
   if (tid == 0) sh.cand_n = 0;
+#pragma unroll 1
+  for (int w = tid; w < 2 * nwords; w += TOPK_THREADS) s_bitmap[w] = 0;
 
-  // ---- 1. range of the keys
+  // ---- 1. range of the keys (clamped duplicates of the last key do not change min/max)
   uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
-  for (int i = 0; i < (KPT > 0 ? KPT : 1); ++i) {
-    if (KPT > 0) {
-      if (i * TOPK_THREADS + tid < N) {
-        kmin = min(kmin, key[i]);
-        kmax = max(kmax, key[i]);
-      }
-    }
+  for (int i = 0; i < ntiles; ++i) {
+    const uint32_t k = key_at(i);
+    kmin = min(kmin, k);
+    kmax = max(kmax, k);
   }
-  if (KPT == 0) {
-    for (int i = 0; i < ntiles; ++i)
-      if (i * TOPK_THREADS + tid < N) {
-        const uint32_t k = key_at(i);
-        kmin = min(kmin, k);
-        kmax = max(kmax, k);
-      }
-  }
-  for (int d = 32; d >= 1; d >>= 1) {
-    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, d));
-    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, d));
-  }
+  kmin = wave_reduce_u32(kmin, UMin());
+  kmax = wave_reduce_u32(kmax, UMax());
   if (lane == 0) {
     sh.red[wave] = kmin;
     sh.red[TOPK_WAVES + wave] = kmax;
   }
   __syncthreads();
-  kmin = sh.red[0];
-  kmax = sh.red[TOPK_WAVES];
-#pragma unroll
-  for (int w = 1; w < TOPK_WAVES; ++w) {
-    kmin = min(kmin, sh.red[w]);
-    kmax = max(kmax, sh.red[TOPK_WAVES + w]);
-  }
+  kmin = row16_reduce_u32(sh.red[lane & (TOPK_WAVES - 1)], UMin());
+  kmax = row16_reduce_u32(sh.red[TOPK_WAVES + (lane & (TOPK_WAVES - 1))], UMax());
   const uint32_t range = kmax - kmin;  // relative keys live in [0, range]
   const int bits = 32 - __builtin_clz(range | 1u);
-  int shift = bits > 8 ? bits - 8 : 0;  // first digit = the top 8 significant bits
+  int shift = bits > TOPK_DIGIT_BITS ? bits - TOPK_DIGIT_BITS : 0;  // first digit = the top significant bits
 
   // ---- 2. histogram of the first digit, threshold bin
-  uint32_t prefix = 0, mask = 0;  // candidates: (rel & mask) == prefix
-  uint32_t need = (uint32_t)K;
 #pragma unroll
   for (int i = 0; i < ntiles; ++i) {
-    if (i * TOPK_THREADS + tid < N) atomicAdd(&sh.hist[((key_at(i) - kmin) >> shift) & 255u], 1u);
+    if (i * TOPK_THREADS + tid < N) atomicAdd(&sh.hist[(key_at(i) - kmin) >> shift], 1u);
   }
   __syncthreads();
-  if (wave == 0) pick_bin(sh, lane, need);
-  __syncthreads();
-  prefix = sh.bcast[0] << shift;
-  mask = 255u << shift;
-  need -= sh.bcast[1];
+  pick_bin(sh, tid, lane, wave, (uint32_t)K);
+  const uint32_t d1 = sh.bcast[0];
+  uint32_t need = (uint32_t)K - sh.bcast[1];
   uint32_t ncand = sh.bcast[2];
+  uint32_t need_eq = 0;
 
-  // ---- 3. exact threshold inside the bin
-  uint32_t tau = prefix, need_eq = need;  // valid as is when no bits are left (shift == 0)
-  while (shift > 0) {
-    if (ncand <= (uint32_t)TOPK_MAX_CAND) {
-      // few candidates: list them, rank them by (key desc, index asc)
+  if (shift == 0 || ncand <= (uint32_t)TOPK_MAX_CAND) {
+    // ---- 3. keys above the bin are selected; keys inside it become candidates
+    // (with shift == 0 the bin is a single key value: its members tie, lowest index first)
+    const bool list_cands = ncand <= (uint32_t)TOPK_MAX_CAND;
 #pragma unroll
-      for (int i = 0; i < ntiles; ++i) {
-        const int j = i * TOPK_THREADS + tid;
-        if (j < N) {
-          const uint32_t rel = key_at(i) - kmin;
-          if ((rel & mask) == prefix) {
-            const uint32_t slot = atomicAdd(&sh.cand_n, 1u);
-            sh.cand_key[slot] = rel;
-            sh.cand_idx[slot] = (uint32_t)j;
-          }
+    for (int i = 0; i < ntiles; ++i) {
+      const int j = i * TOPK_THREADS + tid;
+      const uint32_t rel = key_at(i) - kmin;
+      const uint32_t dg = rel >> shift;
+      if (j < N && dg >= d1) {
+        if (dg > d1) {
+          atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
+        } else if (list_cands) {
+          const uint32_t slot = atomicAdd(&sh.cand_n, 1u);
+          sh.cand_key[slot] = rel;
+          sh.cand_idx[slot] = (uint32_t)j;
+        } else {
+          atomicOr(&bm_eq[j >> 5], 1u << (j & 31));
         }
       }
-      __syncthreads();
+    }
+    __syncthreads();
+    if (list_cands) {
       if ((uint32_t)tid < ncand) {
         const uint32_t mk = sh.cand_key[tid], mi = sh.cand_idx[tid];
-        uint32_t rank = 0, gtk = 0;
+        uint32_t rank = 0;
+#pragma unroll 4
         for (uint32_t u = 0; u < ncand; ++u) {
           const uint32_t ok = sh.cand_key[u], oi = sh.cand_idx[u];
-          gtk += ok > mk;
           rank += (ok > mk) || (ok == mk && oi < mi);
         }
-        if (rank == need - 1) {
-          sh.bcast[0] = mk;
-          sh.bcast[1] = need - gtk;  // how many blocks with key == tau are taken
-        }
+        if (rank < need) atomicOr(&bm_gt[mi >> 5], 1u << (mi & 31));
+      }
+    } else {
+      need_eq = need;  // bin == one key value: admit its first `need` members by index
+    }
+    __syncthreads();
+  } else {
+    // ---- slow path: crowded bin.  More radix digits until the bin is a single key value.
+    uint32_t prefix = d1 << shift, mask = (uint32_t)(TOPK_BINS - 1) << shift;
+    while (shift > 0) {
+      shift = shift > TOPK_DIGIT_BITS ? shift - TOPK_DIGIT_BITS : 0;
+      sh.hist[tid] = 0;
+      sh.hist[tid + TOPK_THREADS] = 0;
+      __syncthreads();
+#pragma unroll 1
+      for (int j = tid; j < N; j += TOPK_THREADS) {
+        const uint32_t rel = ordered_key(sc[j]) - kmin;
+        if ((rel & mask) == prefix) atomicAdd(&sh.hist[(rel >> shift) & (uint32_t)(TOPK_BINS - 1)], 1u);
       }
       __syncthreads();
-      tau = sh.bcast[0];
-      need_eq = sh.bcast[1];
-      break;
+      pick_bin(sh, tid, lane, wave, need);
+      prefix |= sh.bcast[0] << shift;
+      mask |= (uint32_t)(TOPK_BINS - 1) << shift;
+      need -= sh.bcast[1];
+      __syncthreads();  // bcast is rewritten by the next round
     }
-    // crowded bin: next 8-bit digit
-    shift = shift > 8 ? shift - 8 : 0;
-    if (tid < 256) sh.hist[tid] = 0;
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < ntiles; ++i) {
-      if (i * TOPK_THREADS + tid < N) {
-        const uint32_t rel = key_at(i) - kmin;
-        if ((rel & mask) == prefix) atomicAdd(&sh.hist[(rel >> shift) & 255u], 1u);
-      }
-    }
-    __syncthreads();
-    if (wave == 0) pick_bin(sh, lane, need);
-    __syncthreads();
-    prefix |= sh.bcast[0] << shift;
-    mask |= 255u << shift;
-    need -= sh.bcast[1];
-    ncand = sh.bcast[2];
-    tau = prefix;
+    const uint32_t tau = prefix;
     need_eq = need;
-    __syncthreads();  // bcast is rewritten by the next round
+#pragma unroll 1
+    for (int j = tid; j < N; j += TOPK_THREADS) {
+      const uint32_t rel = ordered_key(sc[j]) - kmin;
+      if (rel > tau)
+        atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
+      else if (rel == tau)
+        atomicOr(&bm_eq[j >> 5], 1u << (j & 31));
+    }
+    __syncthreads();
   }
 
-  // ---- 4. ordered compaction
-  const uint64_t lt_mask = (1ull << lane) - 1ull;
-  if (KPT > 0) {
-    // per-(tile, wave) counts -> one exclusive scan in index order -> slots
-#pragma unroll
-    for (int i = 0; i < R; ++i) {
-      const int j = i * TOPK_THREADS + tid;
-      const uint32_t rel = key[i] - kmin;
-      const bool v = j < N;
-      const uint64_t bgt = __ballot(v && rel > tau), beq = __ballot(v && rel == tau);
-      if (lane == 0) {
-        sh.cnt_gt[i * TOPK_WAVES + wave] = (uint32_t)__popcll(bgt);
-        sh.cnt_eq[i * TOPK_WAVES + wave] = (uint32_t)__popcll(beq);
-      }
-    }
-    __syncthreads();
-    if (wave < 2) {  // wave 0 scans cnt_gt, wave 1 scans cnt_eq; lane owns R*16/64 consecutive entries
-      uint32_t* arr = wave == 0 ? sh.cnt_gt : sh.cnt_eq;
-      constexpr int PER = (R * TOPK_WAVES + 63) / 64;
-      uint32_t v[PER], tot = 0;
-#pragma unroll
-      for (int e = 0; e < PER; ++e) {
-        const int idx = lane * PER + e;
-        v[e] = idx < R * TOPK_WAVES ? arr[idx] : 0u;
-        tot += v[e];
-      }
-      uint32_t incl = tot;
-      for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = (uint32_t)__shfl_up((int)incl, d);
-        if (lane >= d) incl += o;
-      }
-      uint32_t run = incl - tot;
-#pragma unroll
-      for (int e = 0; e < PER; ++e) {
-        const int idx = lane * PER + e;
-        if (idx < R * TOPK_WAVES) arr[idx] = run;
-        run += v[e];
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < R; ++i) {
-      const int j = i * TOPK_THREADS + tid;
-      const uint32_t rel = key[i] - kmin;
-      const bool v = j < N;
-      const bool gt = v && rel > tau, eq = v && rel == tau;
-      const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
-      const uint32_t gt_before = sh.cnt_gt[i * TOPK_WAVES + wave] + (uint32_t)__popcll(bgt & lt_mask);
-      const uint32_t eq_before = sh.cnt_eq[i * TOPK_WAVES + wave] + (uint32_t)__popcll(beq & lt_mask);
-      if (gt || (eq && eq_before < need_eq)) {
-        const uint32_t slot = gt_before + min(eq_before, need_eq);
-        if (slot < (uint32_t)K) out[slot] = j;  // always true for consistent counts; keeps stores in bounds
-      }
-    }
-  } else {
-    // long segments: tile by tile with running bases
-    uint32_t base_gt = 0, base_eq = 0;
-    for (int i = 0; i < ntiles; ++i) {
-      const int j = i * TOPK_THREADS + tid;
-      const bool v = j < N;
-      const uint32_t rel = v ? key_at(i) - kmin : 0u;
-      const bool gt = v && rel > tau, eq = v && rel == tau;
-      const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
-      if (lane == 0) {
-        sh.cnt_gt[wave] = (uint32_t)__popcll(bgt);
-        sh.cnt_eq[wave] = (uint32_t)__popcll(beq);
-      }
-      __syncthreads();
-      uint32_t gt_before = base_gt, eq_before = base_eq, gt_tile = 0, eq_tile = 0;
-#pragma unroll
-      for (int w = 0; w < TOPK_WAVES; ++w) {
-        const uint32_t cg = sh.cnt_gt[w], ce = sh.cnt_eq[w];
-        if (w < wave) {
-          gt_before += cg;
-          eq_before += ce;
+  // ---- 4. bitmaps -> ascending index list
+  uint32_t base_gt = 0, base_eq = 0;
+#pragma unroll 1
+  for (int w0 = 0; w0 < nwords; w0 += TOPK_THREADS) {
+    const int w = w0 + tid;
+    const uint32_t g = w < nwords ? bm_gt[w] : 0u;
+    const uint32_t e = (need_eq > 0 && w < nwords) ? bm_eq[w] : 0u;
+    uint32_t tot_gt, tot_eq = 0;
+    uint32_t G = base_gt + block_excl_scan((uint32_t)__popc(g), sh.wave_a, lane, wave, &tot_gt);
+    uint32_t E = base_eq;
+    if (need_eq > 0) E += block_excl_scan((uint32_t)__popc(e), sh.wave_b, lane, wave, &tot_eq);
+    uint32_t bitsleft = g | e;
+#pragma unroll 1
+    while (bitsleft) {
+      const int bpos = __builtin_ctz(bitsleft);
+      bitsleft &= bitsleft - 1;
+      const int idx = (w << 5) + bpos;
+      if ((g >> bpos) & 1u) {
+        const uint32_t slot = G + min(E, need_eq);
+        if (slot < (uint32_t)K) out[slot] = idx;  // always true for consistent counts; keeps stores in bounds
+        ++G;
+      } else {
+        if (E < need_eq) {
+          const uint32_t slot = G + E;
+          if (slot < (uint32_t)K) out[slot] = idx;
         }
-        gt_tile += cg;
-        eq_tile += ce;
+        ++E;
       }
-      gt_before += (uint32_t)__popcll(bgt & lt_mask);
-      eq_before += (uint32_t)__popcll(beq & lt_mask);
-      if (gt || (eq && eq_before < need_eq)) {
-        const uint32_t slot = gt_before + min(eq_before, need_eq);
-        if (slot < (uint32_t)K) out[slot] = j;
-      }
-      base_gt += gt_tile;
-      base_eq += eq_tile;
-      __syncthreads();
     }
+    base_gt += tot_gt;
+    base_eq += tot_eq;
+    __syncthreads();  // the scan scratch is reused by the next tile of words
   }
 }
 
 int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const int32_t* cent_off,
                 const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride,
                 hipStream_t stream) {
+  if (pl.max_blocks > TOPK_MAX_BLOCKS) return ABSB_ERR_UNSUPPORTED;
   TopkParams p;
   p.scores = scores;
   p.cent_off = cent_off;
@@ -331,19 +301,20 @@ int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const 
   p.Hkv = g.Hkv;
   p.heads = g.heads;
   const dim3 grid((unsigned)pl.nseg), block(TOPK_THREADS);
+  const size_t lds = (size_t)2 * ((pl.max_blocks + 31) / 32) * sizeof(uint32_t);
   const int tiles = (pl.max_blocks + TOPK_THREADS - 1) / TOPK_THREADS;
   if (tiles <= 1)
-    hipLaunchKernelGGL(topk_kernel<1>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL(topk_kernel<1>, grid, block, lds, stream, p);
   else if (tiles <= 2)
-    hipLaunchKernelGGL(topk_kernel<2>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL(topk_kernel<2>, grid, block, lds, stream, p);
   else if (tiles <= 4)
-    hipLaunchKernelGGL(topk_kernel<4>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL(topk_kernel<4>, grid, block, lds, stream, p);
   else if (tiles <= 8)
-    hipLaunchKernelGGL(topk_kernel<8>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL(topk_kernel<8>, grid, block, lds, stream, p);
   else if (tiles <= 16)
-    hipLaunchKernelGGL(topk_kernel<16>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL(topk_kernel<16>, grid, block, lds, stream, p);
   else
-    hipLaunchKernelGGL(topk_kernel<0>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL(topk_kernel<0>, grid, block, lds, stream, p);
   return check_launch();
 }
 
