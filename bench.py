@@ -28,6 +28,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 METRIC = "decode attention µs/step/layer + achieved HBM GB/s at 128K ctx (8B-shaped GQA)"
+# HBM bytes moved by one absb_sparse_decode call on the headline workload, from rocprofv3 --pmc
+# (FETCH_SIZE, then WRITE_SIZE, each scaled by a 1 GiB copy in the same run): partials kernel
+# 17.06 MB read + 1.06 MB written, merge kernel 1.19 MB + 0.01 MB.
+# Source: profiles/decode_fused_config3_hbm_counters.md
+HEADLINE_TRAFFIC_BYTES = 19_320_000
 
 
 def useful_bytes(wl, plan_off, sel_cnt):
@@ -83,6 +88,9 @@ def main():
     ap.add_argument("--budget", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also time each entry point on its own")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="run one device-to-device copy of this many MiB first (a kernel of known traffic, for "
+                         "scaling hardware byte counters collected with rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -96,6 +104,14 @@ def main():
         sys.exit(2)
     absb.load()
     torch.cuda.set_device(0)
+
+    if args.copy_calibration > 0:
+        src = torch.full((args.copy_calibration << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     base_seed = {1: 0, 2: 1, 3: 2, 4: 3, 5: 4}[args.config]
     wl0 = synth.make_workload(args.config, context=args.context, batch=args.batch, budget=args.budget)
@@ -141,6 +157,7 @@ def main():
         stages.update(score_us=ms_sc * 1e3, topk_us=ms_tk * 1e3)
 
     wl = wl0
+    headline = args.config == 3 and args.context is None and args.batch is None and args.budget is None
     result = {
         "metric": METRIC,
         "value": round(gbps, 2),
@@ -169,12 +186,16 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "sparse decode stage (decode_partial_kernel + decode_merge_kernel) via absb_sparse_decode",
+            # the event-timed unit is the entry point absb_sparse_decode = the dominant kernel
+            # (decode_partial_kernel, which reads the K/V rows) plus the small LSE merge kernel
+            "kernel": "decode_partial_kernel + decode_merge_kernel (one absb_sparse_decode call)",
             "achieved": round(dec_gbps, 2),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
-            "traffic": None,
+            "algorithmic_bytes_per_launch": int(mean_bytes["decode"]),
+            "us_per_launch": round(ms_dec * 1e3, 3),
+            "traffic": HEADLINE_TRAFFIC_BYTES if headline else None,
         },
     }
 

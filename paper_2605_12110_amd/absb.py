@@ -114,11 +114,19 @@ class Layer:
     kv_strides: Sequence[int]          # (page, head, token) in elements
     sm_scale: float = 0.0
 
+    def __setattr__(self, name, value):
+        object.__setattr__(self, name, value)
+        if not name.startswith("_"):
+            object.__setattr__(self, "_c", None)       # any field change invalidates the cached C struct
+
     def c(self) -> _Layer:
-        self._bs, bs_p = _i32_host(self.block_size)
-        sp, sh, st = (int(x) for x in self.kv_strides)
-        return _Layer(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size, self.dtype, 0,
-                      bs_p, sp, sh, st, float(self.sm_scale), 0)
+        """The absb_layer record (built once per set of field values: marshalling stays off the hot path)."""
+        if getattr(self, "_c", None) is None:
+            self._bs, bs_p = _i32_host(self.block_size)
+            sp, sh, st = (int(x) for x in self.kv_strides)
+            self._c = _Layer(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size, self.dtype, 0,
+                             bs_p, sp, sh, st, float(self.sm_scale), 0)
+        return self._c
 
 
 @dataclass
@@ -133,14 +141,22 @@ class Batch:
     budget: object = None
     pt_stride: Optional[int] = None
 
+    def __setattr__(self, name, value):
+        object.__setattr__(self, name, value)
+        if not name.startswith("_"):
+            object.__setattr__(self, "_c", None)
+
     def c(self) -> _Batch:
-        self._sl, sl_p = _i32_host(self.seq_lens_host)
-        self._bg, bg_p = _i32_host(self.budget_host)
-        pts = self.pt_stride
-        if pts is None:
-            pts = int(self.page_table.shape[1]) if self.page_table is not None else 0
-        return _Batch(len(self._sl), int(pts), sl_p, _ptr(self.seq_lens), _ptr(self.page_table),
-                      _ptr(self.cent_off), bg_p, _ptr(self.budget))
+        """The absb_batch record (cached until a field is reassigned; the tensors must stay alive)."""
+        if getattr(self, "_c", None) is None:
+            self._sl, sl_p = _i32_host(self.seq_lens_host)
+            self._bg, bg_p = _i32_host(self.budget_host)
+            pts = self.pt_stride
+            if pts is None:
+                pts = int(self.page_table.shape[1]) if self.page_table is not None else 0
+            self._c = _Batch(len(self._sl), int(pts), sl_p, _ptr(self.seq_lens), _ptr(self.page_table),
+                             _ptr(self.cent_off), bg_p, _ptr(self.budget))
+        return self._c
 
 
 @dataclass

@@ -154,19 +154,35 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
   }
 
   // ---- merge the work-group's 16 row-group states through LDS and write the split's partial.
-  // Rolled loops on purpose: this code runs once per work-group, and straight-line code that runs
-  // once costs more in instruction fetch than it saves in issue slots.
+  // Three short phases, each a batch of independent LDS accesses (one round trip each): publish
+  // the maxima; rescale the own state to the common maximum and publish it; add the 16 states up.
   constexpr int PARTS = DEC_WAVES * 4;
   constexpr int GC = G < 4 ? G : 4;  // heads staged per pass (bounds LDS at 32 KiB)
   __shared__ float s_o[PARTS][GC][ABSB_HEAD_DIM];
-  __shared__ float s_m[PARTS][G], s_l[PARTS][G];
+  __shared__ float s_m[G][PARTS], s_l[G][PARTS];
   const int part = wave * 4 + grp;
   if (li == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      s_m[part][g] = m[g];
-      s_l[part][g] = l[g];
-    }
+    for (int g = 0; g < G; ++g) s_m[g][part] = m[g];
+  }
+  __syncthreads();
+  // every lane: the work-group maximum per head, and its own state rescaled to it, so that the
+  // 16 states can then be added up as they are (all LDS reads below are independent: one round trip)
+  float Mg[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float mx = s_m[g][0];
+#pragma unroll
+    for (int q = 1; q < PARTS; ++q) mx = fmaxf(mx, s_m[g][q]);
+    Mg[g] = mx;
+    const float a = fast_exp2(m[g] - mx);
+    l[g] *= a;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[g][c] *= a;
+  }
+  if (li == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) s_l[g][part] = l[g];  // own slot: nobody else reads or writes it before the barrier
   }
   const size_t slot = (size_t)s * p.max_splits + split;
 #pragma unroll
@@ -181,24 +197,27 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
       }
     }
     __syncthreads();
+    constexpr int NOUT = (G - 0 < GC ? G : GC) * ABSB_HEAD_DIM;  // outputs of a full pass
     const int nout = (G - g0 < GC ? G - g0 : GC) * ABSB_HEAD_DIM;
-#pragma unroll 1
-    for (int i = tid; i < nout; i += DEC_THREADS) {
-      const int k = i >> 7, c = i & 127, g = g0 + k;
-      float M = M_INIT;
-#pragma unroll 1
-      for (int q = 0; q < PARTS; ++q) M = fmaxf(M, s_m[q][g]);
-      float Lsum = 0.0f, O = 0.0f;
-#pragma unroll 1
-      for (int q = 0; q < PARTS; ++q) {
-        const float a = fast_exp2(s_m[q][g] - M);
-        Lsum = __builtin_fmaf(s_l[q][g], a, Lsum);
-        O = __builtin_fmaf(s_o[q][k][c], a, O);
-      }
-      p.part_o[(slot * G + g) * ABSB_HEAD_DIM + c] = O;
-      if (c == 0) {
-        p.part_ml[(slot * G + g) * 2 + 0] = M;
-        p.part_ml[(slot * G + g) * 2 + 1] = Lsum;
+#pragma unroll
+    for (int i0 = 0; i0 < NOUT; i0 += DEC_THREADS) {
+      const int i = i0 + tid;
+      if (i < nout) {
+        const int k = i >> 7, c = i & 127, g = g0 + k;
+        float O = s_o[0][k][c], Lsum = s_l[g][0];
+#pragma unroll
+        for (int q = 1; q < PARTS; ++q) {
+          O += s_o[q][k][c];
+          Lsum += s_l[g][q];
+        }
+        p.part_o[(slot * G + g) * ABSB_HEAD_DIM + c] = O;
+        if (c == 0) {
+          float mx = Mg[0];
+#pragma unroll
+          for (int gg = 1; gg < G; ++gg) mx = (gg == g) ? Mg[gg] : mx;
+          p.part_ml[(slot * G + g) * 2 + 0] = mx;
+          p.part_ml[(slot * G + g) * 2 + 1] = Lsum;
+        }
       }
     }
   }
