@@ -171,6 +171,8 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
   int shift = bits > TOPK_DIGIT_BITS ? bits - TOPK_DIGIT_BITS : 0;  // first digit = the top significant bits
 
   // ---- 2. histogram of the first digit, threshold bin
+  // (slots past the end hold copies of the last key: counting them would pile thousands of LDS
+  // atomics on one bin, so they are skipped, not corrected for afterwards)
 #pragma unroll
   for (int i = 0; i < ntiles; ++i) {
     if (i * TOPK_THREADS + tid < N) atomicAdd(&sh.hist[(key_at(i) - kmin) >> shift], 1u);
@@ -191,7 +193,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
       const int j = i * TOPK_THREADS + tid;
       const uint32_t rel = key_at(i) - kmin;
       const uint32_t dg = rel >> shift;
-      if (j < N && dg >= d1) {
+      if (dg >= d1 && j < N) {  // the digit test comes first: it fails for almost every key
         if (dg > d1) {
           atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
         } else if (list_cands) {
