@@ -10,7 +10,9 @@ per-head block sizes from {8,...,128}, budget 4096 tokens.
 Cold-cache discipline: the step cycles over R independent layer instances (own KV pages, codes,
 query) so that no step re-reads lines the previous ones left in L2 / Infinity Cache.
 
-Prints ONE JSON line.  `value` = useful (algorithmic) bytes per step / step time, in GB/s.
+Default run: prints ONE JSON line.  `value` = useful (algorithmic) bytes per step / step time, GB/s.
+`--matrix`: runs every benchmark configuration (and the config-5 budget sweep with selection
+recall and error against dense attention) and prints a markdown table instead.
 """
 from __future__ import annotations
 
@@ -33,6 +35,7 @@ METRIC = "decode attention µs/step/layer + achieved HBM GB/s at 128K ctx (8B-sh
 # 17.06 MB read + 1.06 MB written, merge kernel 1.19 MB + 0.01 MB.
 # Source: profiles/decode_fused_config3_hbm_counters.md
 HEADLINE_TRAFFIC_BYTES = 19_320_000
+BASE_SEED = {1: 0, 2: 1, 3: 2, 4: 3, 5: 4}
 
 
 def useful_bytes(wl, plan_off, sel_cnt):
@@ -76,6 +79,153 @@ def time_loop(fn, n_warm, n_steps):
     return ev0.elapsed_time(ev1) / n_steps, wall
 
 
+def per_step_percentiles(fn, n_steps):
+    """Per-step durations from an event between consecutive steps: (p10, median, p90) in us."""
+    import torch
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_steps + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(n_steps):
+        fn(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    d = np.array([evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n_steps)])
+    return float(np.percentile(d, 10)), float(np.median(d)), float(np.percentile(d, 90))
+
+
+def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, uniform_block=None, max_bytes=24 << 30):
+    """R independent layer instances of a workload, resident on the GPU, centroid stores built."""
+    import torch
+    from paper_2605_12110_amd import synth
+    from paper_2605_12110_amd.device import DeviceWorkload
+    kw = dict(context=context, batch=batch, budget=budget, uniform_block=uniform_block)
+    wl0 = synth.make_workload(config, **kw)
+    R = rotate
+    if R <= 0:
+        R = max(1, min(8, -(-(2 << 30) // wl0.kv_bytes())))
+    R = max(1, min(R, max_bytes // max(wl0.kv_bytes(), 1)))
+    insts = [DeviceWorkload(wl0)]
+    for r in range(1, R):
+        wl = synth.make_workload(config, seed=BASE_SEED[config] + 100 * r, **kw)
+        insts.append(DeviceWorkload(wl))
+        wl.k_cache = wl.v_cache = None      # free the host copies of the extra instances
+    for dw in insts:
+        dw.build()
+    torch.cuda.synchronize()
+    return wl0, insts
+
+
+def measure(wl0, insts, steps, warmup, stages=False, percentiles=False):
+    import torch
+    R = len(insts)
+    ub = []
+    for dw in insts:        # one untimed step per instance: selection sizes for the byte count
+        dw.decode_fused()
+        torch.cuda.synchronize()
+        ub.append(useful_bytes(dw.wl, dw.plan.cent_off, dw.sel_cnt.cpu().numpy()))
+    mean_bytes = {k: float(np.mean([u[k] for u in ub])) for k in ub[0]}
+
+    def step(i):
+        insts[i % R].decode_fused(want_sel=False)
+
+    ms, wall_ms = time_loop(step, warmup, steps)
+    out = dict(ms=ms, wall_ms=wall_ms, bytes=mean_bytes, bytes0=ub[0], R=R)
+    # dominant stage on its own: sparse decode (split-K partials + merge) on the fused step's selection
+    ms_dec, _ = time_loop(lambda i: insts[i % R].sparse_decode(), warmup, steps)
+    out["ms_decode"] = ms_dec
+    st = {"sparse_decode_us": ms_dec * 1e3}
+    if stages:
+        ms_sc, _ = time_loop(lambda i: insts[i % R].score(), warmup, steps)
+        ms_tk, _ = time_loop(lambda i: insts[i % R].topk(), warmup, steps)
+        st.update(score_us=ms_sc * 1e3, topk_us=ms_tk * 1e3)
+    out["stages"] = st
+    if percentiles:
+        out["p10_med_p90_us"] = per_step_percentiles(step, min(steps, 200))
+    return out
+
+
+def cpu_baseline(wl0, bytes0, seconds=10.0):
+    from oracle import oracle as O
+    st = O.build_centroids(wl0)
+    O.decode_step(wl0, st)                       # warm
+    t0 = time.perf_counter()
+    n = 0
+    while True:
+        O.decode_step(wl0, st)
+        n += 1
+        el = time.perf_counter() - t0
+        if el > seconds or n >= 2000:
+            break
+    cpu_s = el / n
+    return {
+        "value": round(bytes0["total"] / cpu_s / 1e9, 3),
+        "unit": "GB/s",
+        "us_per_step": round(cpu_s * 1e6, 1),
+        "cores": O.num_threads(),
+        "kind": "oracle",
+        "sample": f"{n} full steps (score -> top-k -> attention over the selection) of the same workload, "
+                  f"instance 0, prebuilt codes, {el:.1f} s of wall time",
+    }
+
+
+def run_matrix(args):
+    """Every benchmark configuration, then the config-5 sweep (uniform 16 vs adaptive block sizes)."""
+    import torch
+    from oracle import oracle as O
+    rows = []
+    print("| workload | batch | dtype | useful MB/step | us/step (mean; p10/med/p90) | GB/s | % of 8 TB/s | decode stage us | "
+          "decode GB/s | oracle us/step (cores) |")
+    print("|---|---|---|---|---|---|---|---|---|---|", flush=True)
+    for cfg in (1, 2, 3, 4):
+        wl0, insts = make_instances(cfg)
+        m = measure(wl0, insts, args.steps, args.warmup, percentiles=True)
+        cb = cpu_baseline(wl0, m["bytes0"], seconds=3.0)
+        gb = m["bytes"]["total"] / (m["ms"] * 1e-3) / 1e9
+        dgb = m["bytes"]["decode"] / (m["ms_decode"] * 1e-3) / 1e9
+        p = m["p10_med_p90_us"]
+        print(f"| config {cfg} (x{m['R']} layers) | {wl0.batch} | {'f16' if wl0.dtype == 0 else 'bf16'} | "
+              f"{m['bytes']['total'] / 1e6:.1f} | {m['ms'] * 1e3:.1f}; {p[0]:.1f}/{p[1]:.1f}/{p[2]:.1f} | {gb:.0f} | "
+              f"{100 * gb / HBM_PEAK_GBPS:.1f} | {m['ms_decode'] * 1e3:.1f} | {dgb:.0f} | {cb['us_per_step']:.0f} ({cb['cores']}) |",
+              flush=True)
+        del insts
+        torch.cuda.empty_cache()
+    # dense reference through the same kernels: budget >= context on the headline cache
+    wl0, insts = make_instances(3, budget=131072, rotate=2)
+    m = measure(wl0, insts, 50, 5)
+    dgb = m["bytes"]["decode"] / (m["ms_decode"] * 1e-3) / 1e9
+    print(f"| config 3, budget = context (dense read of 512 MiB) | 1 | f16 | {m['bytes']['total'] / 1e6:.1f} | "
+          f"{m['ms'] * 1e3:.1f} | {m['bytes']['total'] / (m['ms'] * 1e-3) / 1e9:.0f} | "
+          f"{100 * m['bytes']['total'] / (m['ms'] * 1e-3) / 1e9 / HBM_PEAK_GBPS:.1f} | {m['ms_decode'] * 1e3:.1f} | {dgb:.0f} | - |",
+          flush=True)
+    del insts
+    torch.cuda.empty_cache()
+
+    print("\nConfig 5 sweep (batch 4, context 65536, fp16): uniform block 16 vs adaptive per-head sizes\n")
+    print("| blocks | budget | us/step | GB/s | planted-token recall | attention recall (mean) | max abs err vs dense | "
+          "rel L2 err vs dense |")
+    print("|---|---|---|---|---|---|---|---|", flush=True)
+    for label, ub in (("uniform 16", 16), ("adaptive", None)):
+        for T in (1024, 2048, 4096, 8192):
+            wl0, insts = make_instances(5, budget=T, uniform_block=ub, rotate=2)
+            m = measure(wl0, insts, args.steps, args.warmup)
+            dw = insts[0]
+            dw.decode_fused()
+            torch.cuda.synchronize()
+            sel, cnt = dw.sel_idx.cpu().numpy(), dw.sel_cnt.cpu().numpy()
+            got = dw.out_f32().astype(np.float64)
+            dense, _ = O.dense_attention(wl0)
+            rec_p = O.planted_recall(wl0, sel, cnt)
+            rec_a = float(O.attention_recall(wl0, sel, cnt).mean())
+            err = float(np.abs(got - dense).max())
+            rel = float(np.linalg.norm(got - dense) / np.linalg.norm(dense))
+            gb = m["bytes"]["total"] / (m["ms"] * 1e-3) / 1e9
+            print(f"| {label} {wl0.block_size.tolist()} | {T} | {m['ms'] * 1e3:.1f} | {gb:.0f} | {rec_p:.3f} | {rec_a:.3f} | "
+                  f"{err:.3e} | {rel:.3e} |", flush=True)
+            del insts, dw
+            torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -88,6 +238,7 @@ def main():
     ap.add_argument("--budget", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also time each entry point on its own")
+    ap.add_argument("--matrix", action="store_true", help="run all configurations and the config-5 sweep; markdown out")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="run one device-to-device copy of this many MiB first (a kernel of known traffic, for "
                          "scaling hardware byte counters collected with rocprofv3 --pmc)")
@@ -98,7 +249,6 @@ def main():
 
     import torch
     from paper_2605_12110_amd import absb, synth
-    from paper_2605_12110_amd.device import DeviceWorkload
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
@@ -113,56 +263,23 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    base_seed = {1: 0, 2: 1, 3: 2, 4: 3, 5: 4}[args.config]
-    wl0 = synth.make_workload(args.config, context=args.context, batch=args.batch, budget=args.budget)
-    R = args.rotate
-    if R <= 0:
-        R = max(1, min(8, -(-(2 << 30) // wl0.kv_bytes())))
-    insts = [DeviceWorkload(wl0)]
-    for r in range(1, R):
-        wl = synth.make_workload(args.config, context=args.context, batch=args.batch, budget=args.budget,
-                                 seed=base_seed + 100 * r)
-        insts.append(DeviceWorkload(wl))
-        if r > 0:
-            insts[-1].wl.k_cache = insts[-1].wl.v_cache = None     # free host copies of the extra instances
-    for dw in insts:
-        dw.build()
-    torch.cuda.synchronize()
+    if args.matrix:
+        run_matrix(args)
+        return
 
-    # one untimed step per instance to learn the selection sizes (for the byte count)
-    ub = []
-    for dw in insts:
-        dw.decode_fused()
-        torch.cuda.synchronize()
-        ub.append(useful_bytes(dw.wl, dw.plan.cent_off, dw.sel_cnt.cpu().numpy()))
-    mean_bytes = {k: float(np.mean([u[k] for u in ub])) for k in ub[0]}
-
-    def step(i):
-        insts[i % R].decode_fused(want_sel=False)
-
-    ms, wall_ms = time_loop(step, args.warmup, args.steps)
-    us = ms * 1e3
+    wl0, insts = make_instances(args.config, context=args.context, batch=args.batch, budget=args.budget,
+                                rotate=args.rotate)
+    m = measure(wl0, insts, args.steps, args.warmup, stages=args.stages, percentiles=True)
+    ms, mean_bytes, R = m["ms"], m["bytes"], m["R"]
     gbps = mean_bytes["total"] / (ms * 1e-3) / 1e9
-
-    # dominant stage on its own: sparse decode (split-K partials + merge) on the fused step's selection
-    def step_decode(i):
-        insts[i % R].sparse_decode()
-
-    ms_dec, _ = time_loop(step_decode, args.warmup, args.steps)
-    dec_gbps = mean_bytes["decode"] / (ms_dec * 1e-3) / 1e9
-    stages = {"sparse_decode_us": ms_dec * 1e3}
-    if args.stages:
-        ms_sc, _ = time_loop(lambda i: insts[i % R].score(), args.warmup, args.steps)
-        ms_tk, _ = time_loop(lambda i: insts[i % R].topk(), args.warmup, args.steps)
-        stages.update(score_us=ms_sc * 1e3, topk_us=ms_tk * 1e3)
-
+    dec_gbps = mean_bytes["decode"] / (m["ms_decode"] * 1e-3) / 1e9
     wl = wl0
     headline = args.config == 3 and args.context is None and args.batch is None and args.budget is None
     result = {
         "metric": METRIC,
         "value": round(gbps, 2),
         "unit": "GB/s",
-        "us_per_step": round(us, 3),
+        "us_per_step": round(ms * 1e3, 3),
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -181,8 +298,9 @@ def main():
             "resident_kv_bytes": int(sum(i.k_cache.numel() * 2 * 2 for i in insts)),
             "useful_bytes_per_step": {k: int(v) for k, v in mean_bytes.items()},
             "fraction_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-            "host_wall_us_per_step": round(wall_ms * 1e3, 2),
-            "stages": {k: round(v, 3) for k, v in stages.items()},
+            "host_wall_us_per_step": round(m["wall_ms"] * 1e3, 2),
+            "us_per_step_p10_median_p90": [round(x, 2) for x in m["p10_med_p90_us"]],
+            "stages": {k: round(v, 3) for k, v in m["stages"].items()},
         },
         "roofline": {
             "bound": "hbm",
@@ -194,33 +312,12 @@ def main():
             "unit": "GB/s",
             "frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
             "algorithmic_bytes_per_launch": int(mean_bytes["decode"]),
-            "us_per_launch": round(ms_dec * 1e3, 3),
+            "us_per_launch": round(m["ms_decode"] * 1e3, 3),
             "traffic": HEADLINE_TRAFFIC_BYTES if headline else None,
         },
     }
-
     if not args.no_cpu_baseline:
-        from oracle import oracle as O
-        st = O.build_centroids(wl0)
-        O.decode_step(wl0, st)                       # warm
-        t0 = time.perf_counter()
-        n = 0
-        while True:
-            O.decode_step(wl0, st)
-            n += 1
-            el = time.perf_counter() - t0
-            if el > 10.0 or n >= 2000:
-                break
-        cpu_s = el / n
-        result["cpu_baseline"] = {
-            "value": round(ub[0]["total"] / cpu_s / 1e9, 3),
-            "unit": "GB/s",
-            "us_per_step": round(cpu_s * 1e6, 1),
-            "cores": O.num_threads(),
-            "kind": "oracle",
-            "sample": f"{n} full steps (score -> top-k -> attention over the selection) of the same workload, "
-                      f"instance 0, prebuilt codes, {el:.1f} s of wall time",
-        }
+        result["cpu_baseline"] = cpu_baseline(wl0, m["bytes0"])
     print(json.dumps(result))
 
 

@@ -160,6 +160,15 @@ def test_config2_full():
     run_all_stages(synth.make_workload(2), "config2 full (8 x 32K)")
 
 
+def test_config4_full_mixed_batch():
+    """16 requests of 8K..128K tokens, 40 query / 8 KV heads (group of 5), bf16, budget 3 % of each context."""
+    run_all_stages(synth.make_workload(4), "config4 full (16 mixed lengths)")
+
+
+def test_config5_full_adaptive():
+    run_all_stages(synth.make_workload(5), "config5 full (4 x 64K, adaptive)")
+
+
 # ------------------------------------------------------------------ edge cases
 def test_budget_covering_the_context_is_dense_attention():
     wl = synth.tiny_workload(seed=31, dtype=synth.F16, Bt=2, Hq=8, Hkv=2, P=16, seq_lens=(300, 129),
