@@ -9,10 +9,19 @@
 // of its segment's selection and emits an unnormalised partial (m, l, o~) for the G query heads
 // of the group; a second kernel merges the partials with the log-sum-exp rule.
 //
-// Thread mapping: a K/V row is 256 bytes = 16 lanes x 16 bytes, so one wave load instruction
-// covers four whole rows with 128-bit loads.  Each 16-lane row-group owns one row per step, keeps
-// its own online-softmax state for the G heads (no cross-lane traffic in the main loop except the
-// 16-lane DPP reduction of q.k), and each lane accumulates the 8 output channels it loaded.
+// Data path of one wave step (16 rows):
+//   * global -> registers: a row is 256 bytes = 16 lanes x 16 bytes; each 16-lane group loads
+//     four consecutive rows with 128-bit loads, so every wave load instruction covers whole rows;
+//   * registers -> LDS: K rows as they are (row pitch 272 B, conflict-free for the reads below),
+//     V transposed in registers first (4 rows x 8 channels per lane -> 8 channels x 4 rows), so
+//     that the four rows a matrix operand needs at one channel sit in one 8-byte LDS word;
+//   * the next step's global loads are issued here, and fly while this step computes from LDS;
+//   * S = K Q^T and O += P V run on the 16x16x16 matrix instruction: with G <= 8 query rows
+//     per K/V row the tile is mostly padding, but the vector pipeline (q.k dots, lane reductions,
+//     P.V multiply-adds) was measured to cost as much time as the HBM stream itself, and the
+//     matrix pipeline is idle otherwise.  The logits tile comes out in exactly the lane layout
+//     the P operand of the second product needs (head = lane % 16, rows 4*(lane/16)..+3), so the
+//     softmax runs in place with two cross-group maxima per step.
 #include "common.h"
 
 namespace absb {
@@ -37,9 +46,38 @@ struct DecodeParams {
 constexpr float M_INIT = -1.0e30f;  // finite stand-in for "no token seen yet"
 constexpr int DEC_THREADS = 256;
 constexpr int DEC_WAVES = DEC_THREADS / 64;
-constexpr int ROWS_PER_WAVE_STEP = 16;  // 4 row-groups x 4 rows
+constexpr int ROWS_PER_WAVE_STEP = 16;        // 4 row-groups x 4 consecutive rows
+constexpr int K_PITCH = 272;                  // bytes per staged K row (256 + 16: spreads rows over banks)
+constexpr int K_TILE_BYTES = ROWS_PER_WAVE_STEP * K_PITCH;
+constexpr int V_TILE_BYTES = 8 * 512;         // [channel % 8][channel / 8][16 rows] 16-bit
+constexpr int STAGE_BYTES = K_TILE_BYTES + V_TILE_BYTES;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// D(16x16) += A(16x16) B(16x16), operands as four 16-bit values per lane:
+// A[m = lane%16][k = 4*(lane/16)+i], B[k = 4*(lane/16)+i][n = lane%16], D[m = 4*(lane/16)+i][n = lane%16].
+template <int DT>
+__device__ __forceinline__ float4_t mma16(uint2 a, uint2 b, float4_t c) {
+  if (DT == ABSB_F16)
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(bitcast<half4_t>(a), bitcast<half4_t>(b), c, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(bitcast<short4_t>(a), bitcast<short4_t>(b), c, 0, 0, 0);
+}
+
+// The same 32-bit word (two adjacent channels) of four consecutive V rows -> two LDS words, one per
+// channel, each holding that channel's four rows.  `dst` addresses the even channel's word.
+__device__ __forceinline__ void stage_v_word(char* dst, uint32_t r0, uint32_t r1, uint32_t r2, uint32_t r3) {
+  const uint32_t e01 = __builtin_amdgcn_perm(r1, r0, 0x05040100u);  // low halves: even channel, rows 0,1
+  const uint32_t e23 = __builtin_amdgcn_perm(r3, r2, 0x05040100u);
+  const uint32_t o01 = __builtin_amdgcn_perm(r1, r0, 0x07060302u);  // high halves: odd channel
+  const uint32_t o23 = __builtin_amdgcn_perm(r3, r2, 0x07060302u);
+  *reinterpret_cast<uint2*>(dst) = make_uint2(e01, e23);
+  *reinterpret_cast<uint2*>(dst + 512) = make_uint2(o01, o23);
+}
 
 template <int DT, int G>
 __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParams p) {
@@ -54,10 +92,9 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
   // clamped to the list's storage, so the read is always legal); this takes one memory round
   // trip off the dependent chain count -> entry -> page -> row.
   const int maxpos = (p.sel_stride << lb) - 1;
-  int selj[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r)
-    selj[r] = sel[min(pos_begin + wave * ROWS_PER_WAVE_STEP + r * 4 + grp, maxpos) >> lb];
+  const int pos0 = pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4;
+  int sj0 = sel[min(pos0 + 0, maxpos) >> lb], sj1 = sel[min(pos0 + 1, maxpos) >> lb];
+  int sj2 = sel[min(pos0 + 2, maxpos) >> lb], sj3 = sel[min(pos0 + 3, maxpos) >> lb];
 
   // never beyond what the launch covers (a list longer than promised is cut, not overrun)
   const int ntok = min(p.sel_cnt[s] << lb, p.max_splits * p.split_tokens);
@@ -69,155 +106,175 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
   const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
   const size_t lane_off = (size_t)h * p.g.s_head + (size_t)li * 8;
 
-  // the lane's 8 channels of the G queries, as packed pairs
-  uint32_t qr[G][4];
+  __shared__ __align__(16) char s_stage[DEC_WAVES * STAGE_BYTES];  // reused by the epilogue
+  __shared__ float s_m[ABSB_MAX_GROUP][DEC_WAVES], s_l[ABSB_MAX_GROUP][DEC_WAVES];
+  char* kt = s_stage + wave * STAGE_BYTES;
+  char* vt = kt + K_TILE_BYTES;
+
+  // Q as the B operand of S = K Q^T: lane (head = li, k-group = grp) holds Q[head][16*ks + 4*grp + i];
+  // heads beyond G are zero rows of the tile
+  uint2 qb[8];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const uint4 t = *reinterpret_cast<const uint4*>(p.q + ((size_t)b * p.g.Hq + (size_t)h * G + g) * ABSB_HEAD_DIM +
-                                                    li * 8);
-    qr[g][0] = t.x;
-    qr[g][1] = t.y;
-    qr[g][2] = t.z;
-    qr[g][3] = t.w;
+  for (int ks = 0; ks < 8; ++ks) {
+    qb[ks] = make_uint2(0u, 0u);
+    if (li < G)
+      qb[ks] = *reinterpret_cast<const uint2*>(p.q + ((size_t)b * p.g.Hq + (size_t)h * G + li) * ABSB_HEAD_DIM + 16 * ks +
+                                               4 * grp);
   }
 
-  float m[G], l[G], o[G][8];
+  float m = M_INIT, l = 0.0f;  // per head (= li), common to the four groups / partial over the lane's rows
+  float4_t oacc[8];            // O[head = 4*grp + i][channel = 8*li + j], j = 0..7
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = M_INIT;
-    l[g] = 0.0f;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) o[g][c] = 0.0f;
+  for (int j = 0; j < 8; ++j) oacc[j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+  constexpr int STEP = DEC_WAVES * ROWS_PER_WAVE_STEP;  // positions per work-group step
+  u32x4 k0, k1, k2, k3, v0, v1, v2, v3;
+
+  // Issue the 8 row loads of the step at `base` (block -> page mapping, then K and V), and put the
+  // list entries of the following step in flight behind them.  Sets the rows' validity bits.
+#define ABSB_ROW_OFFSET(r, selj, off)                                                                   \
+  {                                                                                                     \
+    const int pos = (base_) + grp * 4 + (r);                                                            \
+    const int t = ((selj) << lb) + (pos & ((1 << lb) - 1));                                             \
+    valid_next |= (uint32_t)(pos < pos_end && t < L) << (r); /* a selected last block may be partial */ \
+    const int tc = max(0, min(t, L - 1)); /* addresses stay inside the request's pages */               \
+    off = (size_t)pt[tc >> lP] * p.g.s_page + lane_off + (size_t)(tc & ((1 << lP) - 1)) * p.g.s_tok;    \
+  }
+#define ABSB_ISSUE(base_expr)                                              \
+  {                                                                        \
+    const int base_ = (base_expr);                                         \
+    size_t off0, off1, off2, off3;                                         \
+    valid_next = 0;                                                        \
+    ABSB_ROW_OFFSET(0, sj0, off0)                                          \
+    ABSB_ROW_OFFSET(1, sj1, off1)                                          \
+    ABSB_ROW_OFFSET(2, sj2, off2)                                          \
+    ABSB_ROW_OFFSET(3, sj3, off3)                                          \
+    k0 = *reinterpret_cast<const u32x4*>(p.k + off0);                      \
+    k1 = *reinterpret_cast<const u32x4*>(p.k + off1);                      \
+    k2 = *reinterpret_cast<const u32x4*>(p.k + off2);                      \
+    k3 = *reinterpret_cast<const u32x4*>(p.k + off3);                      \
+    v0 = *reinterpret_cast<const u32x4*>(p.v + off0);                      \
+    v1 = *reinterpret_cast<const u32x4*>(p.v + off1);                      \
+    v2 = *reinterpret_cast<const u32x4*>(p.v + off2);                      \
+    v3 = *reinterpret_cast<const u32x4*>(p.v + off3);                      \
+    sj0 = sel[min(base_ + STEP + grp * 4 + 0, maxpos) >> lb];              \
+    sj1 = sel[min(base_ + STEP + grp * 4 + 1, maxpos) >> lb];              \
+    sj2 = sel[min(base_ + STEP + grp * 4 + 2, maxpos) >> lb];              \
+    sj3 = sel[min(base_ + STEP + grp * 4 + 3, maxpos) >> lb];              \
   }
 
-  for (int base = pos_begin + wave * ROWS_PER_WAVE_STEP; base < pos_end; base += DEC_WAVES * ROWS_PER_WAVE_STEP) {
-    // ---- block -> page mapping for this group's four rows
-    size_t off[4];
-    bool valid[4];
+  int base = pos_begin + wave * ROWS_PER_WAVE_STEP;
+  uint32_t valid_next = 0;
+  if (base < pos_end) ABSB_ISSUE(base)
+  while (base < pos_end) {  // trip count depends on the wave only: every branch here is wave-uniform
+    // ---- stage the step's rows in LDS
+    const uint32_t valid = valid_next;
+    *reinterpret_cast<u32x4*>(kt + (grp * 4 + 0) * K_PITCH + li * 16) = k0;
+    *reinterpret_cast<u32x4*>(kt + (grp * 4 + 1) * K_PITCH + li * 16) = k1;
+    *reinterpret_cast<u32x4*>(kt + (grp * 4 + 2) * K_PITCH + li * 16) = k2;
+    *reinterpret_cast<u32x4*>(kt + (grp * 4 + 3) * K_PITCH + li * 16) = k3;
+    // 32-bit word d of a row = channels 2d, 2d+1 of the lane's eight
+    stage_v_word(vt + 0 * 1024 + li * 32 + grp * 8, v0.x, v1.x, v2.x, v3.x);
+    stage_v_word(vt + 1 * 1024 + li * 32 + grp * 8, v0.y, v1.y, v2.y, v3.y);
+    stage_v_word(vt + 2 * 1024 + li * 32 + grp * 8, v0.z, v1.z, v2.z, v3.z);
+    stage_v_word(vt + 3 * 1024 + li * 32 + grp * 8, v0.w, v1.w, v2.w, v3.w);
+    // ---- next step's rows go in flight now; they land while this step computes
+    const int next = base + STEP;
+    if (next < pos_end) ABSB_ISSUE(next)
+
+    // ---- S[row][head] = K Q^T over the 128 channels (two accumulators: shorter dependent chain)
+    float4_t s0 = {0.0f, 0.0f, 0.0f, 0.0f}, s1 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int pos = base + r * 4 + grp;
-      const bool in = pos < pos_end;
-      const int t = (selj[r] << lb) + (pos & ((1 << lb) - 1));
-      valid[r] = in && t < L;                // a selected last block may be partial
-      const int tc = max(0, min(t, L - 1));  // addresses stay inside the request's pages
-      const int page = pt[tc >> lP];
-      off[r] = (size_t)page * p.g.s_page + lane_off + (size_t)(tc & ((1 << lP) - 1)) * p.g.s_tok;
+    for (int ks = 0; ks < 8; ks += 2) {
+      const uint2 a0 = *reinterpret_cast<const uint2*>(kt + li * K_PITCH + (16 * ks + 4 * grp) * 2);
+      const uint2 a1 = *reinterpret_cast<const uint2*>(kt + li * K_PITCH + (16 * (ks + 1) + 4 * grp) * 2);
+      s0 = mma16<DT>(a0, qb[ks], s0);
+      s1 = mma16<DT>(a1, qb[ks + 1], s1);
     }
-    uint4 kk[4], vv[4];
+    // ---- online softmax in place: this lane holds rows 4*grp..4*grp+3 of head li
+    float sc[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) kk[r] = *reinterpret_cast<const uint4*>(p.k + off[r]);
+    for (int i = 0; i < 4; ++i) sc[i] = ((valid >> i) & 1u) ? (s0[i] + s1[i]) * p.scale_log2 : -__builtin_inff();
+    float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mn = fmaxf(m, mx);
+    const float alpha = fast_exp2(m - mn);
+    m = mn;
+    uint32_t pb[4];
+    float psum = 0.0f;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) vv[r] = *reinterpret_cast<const uint4*>(p.v + off[r]);
-    // list entries of the next step, in flight behind the rows
+    for (int i = 0; i < 4; ++i) {
+      const uint16_t ph = Elem<DT>::narrow(fast_exp2(sc[i] - mn));  // the weight as the product will see it
+      psum += Elem<DT>::widen(ph);
+      pb[i] = ph;
+    }
+    l = __builtin_fmaf(l, alpha, psum);
+    const uint2 pa = make_uint2(pb[0] | (pb[1] << 16), pb[2] | (pb[3] << 16));
+    // ---- rescale O when some head's maximum moved (rare once the maxima have settled)
+    if (__any(alpha != 1.0f)) {
+      float ah[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      selj[r] = sel[min(base + DEC_WAVES * ROWS_PER_WAVE_STEP + r * 4 + grp, maxpos) >> lb];
-
-    // ---- logits (log2 units) of the four rows for the G heads
-    float sc[G][4];
+      for (int i = 0; i < 4; ++i) {
+        const float a_lo = bitcast<float>(__builtin_amdgcn_readlane(bitcast<int>(alpha), i));
+        const float a_hi = bitcast<float>(__builtin_amdgcn_readlane(bitcast<int>(alpha), (G > 4 ? 4 + i : i)));
+        ah[i] = (G > 4 && grp == 1) ? a_hi : a_lo;  // groups beyond the heads hold zeros: any factor does
+      }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+      for (int j = 0; j < 8; ++j) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float a = Elem<DT>::dot2(qr[g][0], kk[r].x, 0.0f);
-        a = Elem<DT>::dot2(qr[g][1], kk[r].y, a);
-        a = Elem<DT>::dot2(qr[g][2], kk[r].z, a);
-        a = Elem<DT>::dot2(qr[g][3], kk[r].w, a);
-        a = row16_sum(a);
-        sc[g][r] = valid[r] ? a * p.scale_log2 : -__builtin_inff();
+        for (int i = 0; i < 4; ++i) oacc[j][i] *= ah[i];
       }
     }
+    // ---- O[head][channel] += P V: B operand = four rows of one channel, one LDS word
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint2 bv = *reinterpret_cast<const uint2*>(vt + j * 512 + li * 32 + grp * 8);
+      oacc[j] = mma16<DT>(pa, bv, oacc[j]);
+    }
+    base = next;
+  }
+#undef ABSB_ISSUE
+#undef ABSB_ROW_OFFSET
 
-    // ---- online softmax over the tile and P.V
+  // ---- the wave's state: m per head (lane li), l summed over the four groups, O in groups 0 (and 1)
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (grp == 0 && li < G) s_m[li][wave] = m;
+  __syncthreads();  // also: every wave is done with its staging area, which the merge reuses below
+  // work-group maximum per head; own state rescaled to it, so that the four states simply add up
+  float* s_o = reinterpret_cast<float*>(s_stage);  // [DEC_WAVES][G][128]
+  if (grp == 0 && li < G) {
+    const float M = fmaxf(fmaxf(s_m[li][0], s_m[li][1]), fmaxf(s_m[li][2], s_m[li][3]));
+    s_l[li][wave] = l * fast_exp2(m - M);
+  }
+  if (grp * 4 < G) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float mn = fmaxf(fmaxf(m[g], fmaxf(sc[g][0], sc[g][1])), fmaxf(sc[g][2], sc[g][3]));
-      const float alpha = fast_exp2(m[g] - mn);
-      float pr[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) pr[r] = fast_exp2(sc[g][r] - mn);
-      l[g] = __builtin_fmaf(l[g], alpha, (pr[0] + pr[1]) + (pr[2] + pr[3]));
-      m[g] = mn;
-#pragma unroll
-      for (int c = 0; c < 8; ++c) o[g][c] *= alpha;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const uint32_t vw[4] = {vv[r].x, vv[r].y, vv[r].z, vv[r].w};
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          o[g][2 * c] = __builtin_fmaf(pr[r], Elem<DT>::lo(vw[c]), o[g][2 * c]);
-          o[g][2 * c + 1] = __builtin_fmaf(pr[r], Elem<DT>::hi(vw[c]), o[g][2 * c + 1]);
-        }
+    for (int i = 0; i < 4; ++i) {
+      const int hd = grp * 4 + i;
+      if (hd < G) {
+        const float M = fmaxf(fmaxf(s_m[hd][0], s_m[hd][1]), fmaxf(s_m[hd][2], s_m[hd][3]));
+        const float a = fast_exp2(s_m[hd][wave] - M);
+        float4* dst = reinterpret_cast<float4*>(s_o + ((size_t)wave * G + hd) * ABSB_HEAD_DIM + li * 8);
+        dst[0] = make_float4(oacc[0][i] * a, oacc[1][i] * a, oacc[2][i] * a, oacc[3][i] * a);
+        dst[1] = make_float4(oacc[4][i] * a, oacc[5][i] * a, oacc[6][i] * a, oacc[7][i] * a);
       }
     }
-  }
-
-  // ---- merge the work-group's 16 row-group states through LDS and write the split's partial.
-  // Three short phases, each a batch of independent LDS accesses (one round trip each): publish
-  // the maxima; rescale the own state to the common maximum and publish it; add the 16 states up.
-  constexpr int PARTS = DEC_WAVES * 4;
-  constexpr int GC = G < 4 ? G : 4;  // heads staged per pass (bounds LDS at 32 KiB)
-  __shared__ float s_o[PARTS][GC][ABSB_HEAD_DIM];
-  __shared__ float s_m[G][PARTS], s_l[G][PARTS];
-  const int part = wave * 4 + grp;
-  if (li == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) s_m[g][part] = m[g];
   }
   __syncthreads();
-  // every lane: the work-group maximum per head, and its own state rescaled to it, so that the
-  // 16 states can then be added up as they are (all LDS reads below are independent: one round trip)
-  float Mg[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float mx = s_m[g][0];
-#pragma unroll
-    for (int q = 1; q < PARTS; ++q) mx = fmaxf(mx, s_m[g][q]);
-    Mg[g] = mx;
-    const float a = fast_exp2(m[g] - mx);
-    l[g] *= a;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) o[g][c] *= a;
-  }
-  if (li == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) s_l[g][part] = l[g];  // own slot: nobody else reads or writes it before the barrier
-  }
   const size_t slot = (size_t)s * p.max_splits + split;
 #pragma unroll
-  for (int g0 = 0; g0 < G; g0 += GC) {
-    if (g0 > 0) __syncthreads();
+  for (int i0 = 0; i0 < G * ABSB_HEAD_DIM; i0 += DEC_THREADS) {
+    const int i = i0 + tid;
+    if (i < G * ABSB_HEAD_DIM) {
+      const int g = i >> 7, c = i & 127;
+      float O = 0.0f;
 #pragma unroll
-    for (int k = 0; k < GC; ++k) {
-      if (g0 + k < G) {
-        float4* dst = reinterpret_cast<float4*>(&s_o[part][k][li * 8]);
-        dst[0] = make_float4(o[g0 + k][0], o[g0 + k][1], o[g0 + k][2], o[g0 + k][3]);
-        dst[1] = make_float4(o[g0 + k][4], o[g0 + k][5], o[g0 + k][6], o[g0 + k][7]);
-      }
-    }
-    __syncthreads();
-    constexpr int NOUT = (G - 0 < GC ? G : GC) * ABSB_HEAD_DIM;  // outputs of a full pass
-    const int nout = (G - g0 < GC ? G - g0 : GC) * ABSB_HEAD_DIM;
-#pragma unroll
-    for (int i0 = 0; i0 < NOUT; i0 += DEC_THREADS) {
-      const int i = i0 + tid;
-      if (i < nout) {
-        const int k = i >> 7, c = i & 127, g = g0 + k;
-        float O = s_o[0][k][c], Lsum = s_l[g][0];
-#pragma unroll
-        for (int q = 1; q < PARTS; ++q) {
-          O += s_o[q][k][c];
-          Lsum += s_l[g][q];
-        }
-        p.part_o[(slot * G + g) * ABSB_HEAD_DIM + c] = O;
-        if (c == 0) {
-          float mx = Mg[0];
-#pragma unroll
-          for (int gg = 1; gg < G; ++gg) mx = (gg == g) ? Mg[gg] : mx;
-          p.part_ml[(slot * G + g) * 2 + 0] = mx;
-          p.part_ml[(slot * G + g) * 2 + 1] = Lsum;
-        }
+      for (int w = 0; w < DEC_WAVES; ++w) O += s_o[((size_t)w * G + g) * ABSB_HEAD_DIM + c];
+      p.part_o[(slot * G + g) * ABSB_HEAD_DIM + c] = O;
+      if (c == 0) {
+        p.part_ml[(slot * G + g) * 2 + 0] = fmaxf(fmaxf(s_m[g][0], s_m[g][1]), fmaxf(s_m[g][2], s_m[g][3]));
+        p.part_ml[(slot * G + g) * 2 + 1] = (s_l[g][0] + s_l[g][1]) + (s_l[g][2] + s_l[g][3]);
       }
     }
   }
