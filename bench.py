@@ -131,7 +131,14 @@ def measure(wl0, insts, steps, warmup, stages=False, percentiles=False):
     ms, wall_ms = time_loop(step, warmup, steps)
     out = dict(ms=ms, wall_ms=wall_ms, bytes=mean_bytes, bytes0=ub[0], R=R)
     # dominant stage on its own: sparse decode (split-K partials + merge) on the fused step's selection
-    ms_dec, _ = time_loop(lambda i: insts[i % R].sparse_decode(), warmup, steps)
+    # (every instance has completed a fused step on its workspace, so its split counters are zero and
+    # the stage is the attention kernel alone, as in the fused step)
+    from paper_2605_12110_amd import absb
+    absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 1)
+    try:
+        ms_dec, _ = time_loop(lambda i: insts[i % R].sparse_decode(), warmup, steps)
+    finally:
+        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
     out["ms_decode"] = ms_dec
     st = {"sparse_decode_us": ms_dec * 1e3}
     if stages:

@@ -164,8 +164,15 @@ ABSB_API const char* absb_strerror(int status);
 /* Launch-shape knobs for benchmarking sweeps (process-wide; not needed for correct use).
  *   ABSB_TUNE_SPLIT_TOKENS : tokens per split-K work-group in decode (multiple of 64; 0 = auto)
  *   ABSB_TUNE_SCORE_CHUNK  : centroids per work-group in score (multiple of 64; 0 = auto)
+ *   ABSB_TUNE_COUNTERS_ZERO: 1 = absb_sparse_decode may assume that the split counters in the
+ *                            workspace are zero and skips the kernel that clears them; 0 (default)
+ *                            = it clears them.  The assumption holds after any completed
+ *                            absb_sparse_decode / absb_decode_fused call for the same batch size
+ *                            and KV head count on that workspace: the counters sit at its start,
+ *                            no other stage writes there, and the attention kernel leaves every
+ *                            counter it used at zero.  absb_decode_fused never needs the knob.
  * Returns ABSB_ERR_BAD_SHAPE for an unknown key or an invalid value. */
-enum { ABSB_TUNE_SPLIT_TOKENS = 0, ABSB_TUNE_SCORE_CHUNK = 1, ABSB_TUNE_COUNT_ = 2 };
+enum { ABSB_TUNE_SPLIT_TOKENS = 0, ABSB_TUNE_SCORE_CHUNK = 1, ABSB_TUNE_COUNTERS_ZERO = 2, ABSB_TUNE_COUNT_ = 3 };
 ABSB_API int absb_set_tuning(int key, int value);
 
 #ifdef __cplusplus

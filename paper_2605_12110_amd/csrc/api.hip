@@ -84,13 +84,19 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   if (p.total >= (int64_t(1) << 31) - 1) return ABSB_ERR_BAD_SHAPE;
   if ((int64_t)batch->pt_stride < ceil_div(max_len, P)) return ABSB_ERR_BAD_SHAPE;
 
-  // split-K shape: enough work-groups to cover the chip a few times over, 64-token granules
+  // split-K shape, in 64-token granules (one work-group step).  Measured on MI355X (256 CUs, three
+  // resident work-groups each): the kernel is fastest with about two work-groups per CU, all
+  // resident at once and each streaming as long as possible; a work-group needs at least two steps
+  // to amortise its set-up; and since one work-group merges a segment's partials, a segment should
+  // not be cut into more than 64.
   int st_tok = tuning(ABSB_TUNE_SPLIT_TOKENS);
   if (st_tok <= 0) {
-    const int64_t target_wgs = 1024;
-    st_tok = (int)(ceil_div(ceil_div(p.sum_tokens, target_wgs), 64) * 64);
-    if (st_tok < 64) st_tok = 64;
-    if (st_tok > 1024) st_tok = 1024;
+    const int64_t target_wgs = 512;
+    int64_t t = ceil_div(ceil_div(p.sum_tokens, target_wgs), 64) * 64;
+    if (t < 128) t = 128;
+    const int64_t cap_tok = ceil_div(ceil_div(p.max_tokens, 64), 64) * 64;
+    if (t < cap_tok) t = cap_tok;
+    st_tok = (int)t;
   }
   p.split_tokens = st_tok;
   p.max_splits = (int32_t)ceil_div(p.max_tokens, st_tok);
@@ -102,8 +108,12 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   p.build_chunk = 64;
   p.build_max_chunks = (int32_t)ceil_div(p.max_blocks, p.build_chunk);
 
-  // workspace: the three users never run concurrently on one workspace, so they overlap
-  size_t o = 0;
+  // workspace: the split counters of the attention kernel come first, at the same place in every
+  // carving (nothing else ever writes there); behind them the three users overlap, since they
+  // never run concurrently on one workspace
+  p.ws_tickets = 0;
+  const size_t head = align256((size_t)p.nseg * 4);
+  size_t o = head;
   p.ws_scores = o;
   o += align256((size_t)p.total * 4);
   p.ws_sel_idx = o;
@@ -118,7 +128,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   p.ws_fused_bytes = o;
   p.ws_decode_bytes = o;  // the stand-alone decode uses the same offsets (the head is left unused)
   (void)fused_head;
-  size_t bo = 0;
+  size_t bo = head;
   p.ws_cent = bo;
   bo += align256((size_t)p.total * ABSB_HEAD_DIM * 4);
   p.ws_minmax = bo;
@@ -206,7 +216,7 @@ int absb_topk(const absb_layer* layer, const absb_batch* batch, const int32_t* s
   if (rc != ABSB_OK) return rc;
   if (!scores || !sel_idx || !sel_cnt || !batch->cent_off || !batch->budget) return ABSB_ERR_NULL;
   if (sel_stride < p.sel_stride) return ABSB_ERR_BAD_SHAPE;
-  return launch_topk(g, p, scores, batch->cent_off, batch->budget, sel_idx, sel_cnt, sel_stride,
+  return launch_topk(g, p, scores, batch->cent_off, batch->budget, sel_idx, sel_cnt, sel_stride, nullptr,
                      static_cast<hipStream_t>(stream));
 }
 
@@ -224,7 +234,7 @@ int absb_sparse_decode(const absb_layer* layer, const absb_batch* batch, const v
   if (rc != ABSB_OK) return rc;
   return launch_decode(g, p, layer->dtype, resolve_scale(layer), q, k_cache, v_cache, batch->page_table,
                        batch->seq_lens, sel_idx, sel_cnt, sel_stride, out, lse, static_cast<char*>(workspace),
-                       static_cast<hipStream_t>(stream));
+                       tuning(ABSB_TUNE_COUNTERS_ZERO) == 1, static_cast<hipStream_t>(stream));
 }
 
 int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
@@ -247,10 +257,12 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   int32_t* sel_cnt = sel_cnt_out ? sel_cnt_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_cnt);
   rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, scores, nullptr, st);
   if (rc != ABSB_OK) return rc;
-  rc = launch_topk(g, p, scores, batch->cent_off, batch->budget, sel_idx, sel_cnt, p.sel_stride, st);
+  // the selection kernel also clears the split counters of the attention kernel behind it
+  rc = launch_topk(g, p, scores, batch->cent_off, batch->budget, sel_idx, sel_cnt, p.sel_stride,
+                   reinterpret_cast<int32_t*>(ws + p.ws_tickets), st);
   if (rc != ABSB_OK) return rc;
   return launch_decode(g, p, layer->dtype, resolve_scale(layer), q, k_cache, v_cache, batch->page_table,
-                       batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, st);
+                       batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, true, st);
 }
 
 const char* absb_strerror(int status) {
@@ -268,7 +280,7 @@ const char* absb_strerror(int status) {
 
 int absb_set_tuning(int key, int value) {
   if (key < 0 || key >= ABSB_TUNE_COUNT_ || value < 0) return ABSB_ERR_BAD_SHAPE;
-  if (value % 64 != 0) return ABSB_ERR_BAD_SHAPE;
+  if (key == ABSB_TUNE_COUNTERS_ZERO ? value > 1 : value % 64 != 0) return ABSB_ERR_BAD_SHAPE;
   g_tuning[key].store(value, std::memory_order_relaxed);
   return ABSB_OK;
 }

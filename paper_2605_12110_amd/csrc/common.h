@@ -41,7 +41,7 @@ struct Plan {
   int32_t build_chunk;      // blocks per work-group in build
   int32_t build_max_chunks; // max_s ceil(N_s / build_chunk)
   // workspace carving (byte offsets, 256-aligned)
-  size_t ws_part_o, ws_part_ml;                   // decode partials
+  size_t ws_part_o, ws_part_ml, ws_tickets;       // decode partials, per-segment split counters
   size_t ws_scores, ws_sel_idx, ws_sel_cnt;       // fused step intermediates
   size_t ws_cent, ws_minmax, ws_qinv;             // build intermediates
   size_t ws_decode_bytes, ws_fused_bytes, ws_build_bytes, ws_bytes;
@@ -63,11 +63,12 @@ ABSB_HIDDEN int launch_score(const Geometry& g, const Plan& pl, int dtype, const
                              hipStream_t stream);
 ABSB_HIDDEN int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const int32_t* cent_off,
                             const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride,
-                            hipStream_t stream);
+                            int32_t* tickets, hipStream_t stream);
 ABSB_HIDDEN int launch_decode(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
                               const void* k_cache, const void* v_cache, const int32_t* page_table,
                               const int32_t* seq_lens, const int32_t* sel_idx, const int32_t* sel_cnt,
-                              int32_t sel_stride, void* out, float* lse, char* ws, hipStream_t stream);
+                              int32_t sel_stride, void* out, float* lse, char* ws, bool tickets_cleared,
+                              hipStream_t stream);
 
 inline int check_launch() { return hipGetLastError() == hipSuccess ? ABSB_OK : ABSB_ERR_HIP; }
 

@@ -5,9 +5,14 @@
 // token sequence (position -> block list entry -> token -> page/slot) and reads K and V rows in
 // place: no gather, no per-head page list, any mix of block sizes in one launch.
 //
-// Split-K flash decoding: work-group (split, segment) handles `split_tokens` consecutive positions
-// of its segment's selection and emits an unnormalised partial (m, l, o~) for the G query heads
-// of the group; a second kernel merges the partials with the log-sum-exp rule.
+// Split-K flash decoding in one kernel: work-group (split, segment) handles `split_tokens`
+// consecutive positions of its segment's selection and produces an unnormalised partial (m, l, o~)
+// for the G query heads of the group.  A segment with one split normalises and writes its output
+// rows directly; otherwise the partial goes to the workspace, the work-group draws a ticket from
+// the segment's counter, and the one that draws the last ticket merges the segment's partials with
+// the log-sum-exp rule.  No work-group ever waits for another, so the grid drains whatever the
+// counters hold; they must be zero at launch (the selection kernel of the fused step clears them,
+// the stand-alone entry point runs a clearing kernel first).
 //
 // Data path of one wave step (16 rows):
 //   * global -> registers: a row is 256 bytes = 16 lanes x 16 bytes; each 16-lane group loads
@@ -36,6 +41,7 @@ struct DecodeParams {
   const int32_t* sel_cnt;
   float* part_o;   // [nseg][max_splits][G][128]
   float* part_ml;  // [nseg][max_splits][G][2]  (running max in log2 units, sum)
+  int32_t* tickets;  // [nseg], zero when the kernel starts
   void* out;       // [Bt][Hq][128]
   float* lse;      // [Bt][Hq] or null
   int32_t sel_stride, split_tokens, max_splits;
@@ -51,6 +57,7 @@ constexpr int K_PITCH = 272;                  // bytes per staged K row (256 + 1
 constexpr int K_TILE_BYTES = ROWS_PER_WAVE_STEP * K_PITCH;
 constexpr int V_TILE_BYTES = 8 * 512;         // [channel % 8][channel / 8][16 rows] 16-bit
 constexpr int STAGE_BYTES = K_TILE_BYTES + V_TILE_BYTES;
+constexpr int MRG_UNROLL = 16;                // splits a thread merges per memory round trip
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -58,6 +65,8 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
 
 // D(16x16) += A(16x16) B(16x16), operands as four 16-bit values per lane:
 // A[m = lane%16][k = 4*(lane/16)+i], B[k = 4*(lane/16)+i][n = lane%16], D[m = 4*(lane/16)+i][n = lane%16].
@@ -80,7 +89,7 @@ __device__ __forceinline__ void stage_v_word(char* dst, uint32_t r0, uint32_t r1
 }
 
 template <int DT, int G>
-__global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParams p) {
+__global__ __launch_bounds__(DEC_THREADS, 3) void decode_kernel(DecodeParams p) {
   const int s = blockIdx.y, split = blockIdx.x;
   const int b = s / p.g.Hkv, h = s % p.g.Hkv;
   const int lb = p.g.heads.log2_block[h];
@@ -98,6 +107,13 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
 
   // never beyond what the launch covers (a list longer than promised is cut, not overrun)
   const int ntok = min(p.sel_cnt[s] << lb, p.max_splits * p.split_tokens);
+  if (ntok == 0 && split == 0) {  // empty selection: the output rows are zero, the log-sum-exp -inf
+    for (int i = tid; i < G * ABSB_HEAD_DIM; i += DEC_THREADS) {
+      const size_t row = (size_t)b * p.g.Hq + (size_t)h * G + (i >> 7);
+      static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + (i & 127)] = 0;
+      if (p.lse && (i & 127) == 0) p.lse[row] = -__builtin_inff();
+    }
+  }
   if (pos_begin >= ntok) return;
   const int pos_end = min(ntok, pos_begin + p.split_tokens);
   const int L = p.seq_lens[b];
@@ -262,132 +278,143 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_partial_kernel(DecodeParam
     }
   }
   __syncthreads();
-  const size_t slot = (size_t)s * p.max_splits + split;
+  // ---- the work-group's partial: thread -> column (head g, channels 4*c4..4*c4+3), G*32 columns
+  constexpr int NCOL = G * 32;
+  constexpr int CP = NCOL <= 32 ? 32 : NCOL <= 64 ? 64 : NCOL <= 128 ? 128 : 256;  // columns, padded to 2^k
+  constexpr int SL = DEC_THREADS / CP;                                             // split lanes per column
+  const int nsplit = (ntok + p.split_tokens - 1) / p.split_tokens;
+  const int col = tid & (CP - 1), sl = tid / CP;
+  const int g = min(col, NCOL - 1) >> 5, c4 = col & 31;
+  float4_t O = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-  for (int i0 = 0; i0 < G * ABSB_HEAD_DIM; i0 += DEC_THREADS) {
-    const int i = i0 + tid;
-    if (i < G * ABSB_HEAD_DIM) {
-      const int g = i >> 7, c = i & 127;
-      float O = 0.0f;
+  for (int w = 0; w < DEC_WAVES; ++w)
+    O += *reinterpret_cast<const float4_t*>(s_o + ((size_t)w * G + g) * ABSB_HEAD_DIM + c4 * 4);
+  float M = fmaxf(fmaxf(s_m[g][0], s_m[g][1]), fmaxf(s_m[g][2], s_m[g][3]));
+  float Lsum = (s_l[g][0] + s_l[g][1]) + (s_l[g][2] + s_l[g][3]);
+
+  if (nsplit > 1) {
+    // Publish the partial, take a ticket; the work-group that draws the segment's last ticket merges.
+    // Visibility across the chip's L2 slices without a cache write-back: partials are written and
+    // read with device-coherent accesses (the sc1 cache policy, which the non-coherent cache levels
+    // do not serve), a writer waits for its stores to be acknowledged before it draws its ticket,
+    // and the merging group issues its reads only after its ticket has come back.  Nobody waits
+    // for anybody.
+    constexpr int COHERENT = 16;  // cache-policy operand of the buffer instructions: sc1
+    const size_t slot0 = (size_t)s * p.max_splits;
+    const __amdgpu_buffer_rsrc_t part_o = __builtin_amdgcn_make_buffer_rsrc(
+        p.part_o + slot0 * G * ABSB_HEAD_DIM, 0, p.max_splits * G * ABSB_HEAD_DIM * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t part_ml =
+        __builtin_amdgcn_make_buffer_rsrc(p.part_ml + slot0 * G * 2, 0, p.max_splits * G * 8, 0x00020000);
+    if (tid < NCOL) {
+      __builtin_amdgcn_raw_buffer_store_b128(bitcast<u32x4>(O), part_o, ((split * G + g) * ABSB_HEAD_DIM + c4 * 4) * 4,
+                                             0, COHERENT);
+      if (c4 == 0)
+        __builtin_amdgcn_raw_buffer_store_b64(bitcast<u32x2>(float2_t{M, Lsum}), part_ml, (split * G + g) * 8, 0,
+                                              COHERENT);
+    }
+    __shared__ int s_last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's stores have been acknowledged
+    __syncthreads();                                   // ... and so have everybody's
+    if (tid == 0)
+      s_last = __hip_atomic_fetch_add(p.tickets + s, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1;
+    __syncthreads();
+    if (!s_last) return;
+    // every counter a launch touches is back at zero when the launch ends
+    if (tid == 0) __hip_atomic_store(p.tickets + s, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // log-sum-exp merge: split lane `sl` of a column takes splits sl, sl + SL, ...; MRG_UNROLL of
+    // them per memory round trip, folded into a running (M, Lsum, O)
+    M = M_INIT;
+    Lsum = 0.0f;
+    O = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int i0 = sl; i0 < nsplit; i0 += SL * MRG_UNROLL) {
+      float2_t mlv[MRG_UNROLL];
+      float4_t ov[MRG_UNROLL];
 #pragma unroll
-      for (int w = 0; w < DEC_WAVES; ++w) O += s_o[((size_t)w * G + g) * ABSB_HEAD_DIM + c];
-      p.part_o[(slot * G + g) * ABSB_HEAD_DIM + c] = O;
-      if (c == 0) {
-        p.part_ml[(slot * G + g) * 2 + 0] = fmaxf(fmaxf(s_m[g][0], s_m[g][1]), fmaxf(s_m[g][2], s_m[g][3]));
-        p.part_ml[(slot * G + g) * 2 + 1] = (s_l[g][0] + s_l[g][1]) + (s_l[g][2] + s_l[g][3]);
+      for (int u = 0; u < MRG_UNROLL; ++u) {
+        const int i = min(i0 + u * SL, nsplit - 1);  // the tail repeats the last slot, with weight 0
+        mlv[u] = bitcast<float2_t>(__builtin_amdgcn_raw_buffer_load_b64(part_ml, (i * G + g) * 8, 0, COHERENT));
+        ov[u] = bitcast<float4_t>(
+            __builtin_amdgcn_raw_buffer_load_b128(part_o, ((i * G + g) * ABSB_HEAD_DIM + c4 * 4) * 4, 0, COHERENT));
+      }
+      float bm = M;
+#pragma unroll
+      for (int u = 0; u < MRG_UNROLL; ++u) bm = fmaxf(bm, mlv[u].x);
+      const float a = fast_exp2(M - bm);
+      O *= a;
+      Lsum *= a;
+      M = bm;
+#pragma unroll
+      for (int u = 0; u < MRG_UNROLL; ++u) {
+        const float w = i0 + u * SL < nsplit ? fast_exp2(mlv[u].x - bm) : 0.0f;
+        O += ov[u] * w;
+        Lsum = __builtin_fmaf(mlv[u].y, w, Lsum);
+      }
+    }
+    if (SL > 1) {  // fold the split lanes of a column (the staging area is free again)
+      float* s_red = reinterpret_cast<float*>(s_stage);  // [SL][CP][6]
+      __syncthreads();
+      float* mine = s_red + ((size_t)sl * CP + col) * 6;
+      *reinterpret_cast<float2_t*>(mine) = float2_t{M, Lsum};
+      *reinterpret_cast<float2_t*>(mine + 2) = float2_t{O[0], O[1]};
+      *reinterpret_cast<float2_t*>(mine + 4) = float2_t{O[2], O[3]};
+      __syncthreads();
+      if (sl == 0) {
+        float bm = M;
+#pragma unroll
+        for (int k = 1; k < SL; ++k) bm = fmaxf(bm, s_red[((size_t)k * CP + col) * 6]);
+        const float a = fast_exp2(M - bm);
+        O *= a;
+        Lsum *= a;
+        M = bm;
+#pragma unroll
+        for (int k = 1; k < SL; ++k) {
+          const float* st = s_red + ((size_t)k * CP + col) * 6;
+          const float w = fast_exp2(st[0] - bm);
+          Lsum = __builtin_fmaf(st[1], w, Lsum);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) O[j] = __builtin_fmaf(st[2 + j], w, O[j]);
+        }
       }
     }
   }
+
+  // ---- normalise and write the group's output rows
+  if (tid < NCOL) {
+    const size_t row = (size_t)b * p.g.Hq + (size_t)h * G + g;
+    const bool any = Lsum > 0.0f;
+    const float inv = any ? 1.0f / Lsum : 0.0f;
+    const uint32_t lo = (uint32_t)Elem<DT>::narrow(O[0] * inv) | ((uint32_t)Elem<DT>::narrow(O[1] * inv) << 16);
+    const uint32_t hi = (uint32_t)Elem<DT>::narrow(O[2] * inv) | ((uint32_t)Elem<DT>::narrow(O[3] * inv) << 16);
+    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + row * ABSB_HEAD_DIM + c4 * 4) = make_uint2(lo, hi);
+    if (p.lse && c4 == 0) p.lse[row] = any ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
+  }
 }
 
-// Log-sum-exp merge of a segment's split partials.  One work-group per (query head, segment):
-// 128 channels x 8 split lanes; a thread takes every 8th split, with up to MRG_UNROLL independent
-// loads in flight, so the whole merge costs about one memory round trip.
-constexpr int MRG_THREADS = 1024;
-constexpr int MRG_LANES = MRG_THREADS / ABSB_HEAD_DIM;
-constexpr int MRG_UNROLL = 8;
-
-template <int DT>
-__global__ __launch_bounds__(MRG_THREADS) void decode_merge_kernel(DecodeParams p) {
-  const int s = blockIdx.y, g = blockIdx.x;
-  const int G = p.g.G;
-  const int b = s / p.g.Hkv, h = s % p.g.Hkv;
-  const int lb = p.g.heads.log2_block[h];
-  const int tid = threadIdx.x, c = tid & 127, sl = tid >> 7, lane = tid & 63, wave = tid >> 6;
-  const size_t slot0 = (size_t)s * p.max_splits;
-  const float2* ml = reinterpret_cast<const float2*>(p.part_ml);
-
-  // first batch of partials: issued before the split count is known (slots up to max_splits
-  // exist for every segment; unused ones hold stale bytes and are masked out below)
-  float2 mlv[MRG_UNROLL];
-  float ov[MRG_UNROLL];
-#pragma unroll
-  for (int u = 0; u < MRG_UNROLL; ++u) {
-    const int i = min(sl + u * MRG_LANES, p.max_splits - 1);
-    mlv[u] = ml[(slot0 + i) * G + g];
-    ov[u] = p.part_o[((slot0 + i) * G + g) * ABSB_HEAD_DIM + c];
-  }
-  const int ntok = min(p.sel_cnt[s] << lb, p.max_splits * p.split_tokens);
-  const int nsplit = (ntok + p.split_tokens - 1) / p.split_tokens;
-#pragma unroll
-  for (int u = 0; u < MRG_UNROLL; ++u) {
-    const bool in = sl + u * MRG_LANES < nsplit;
-    mlv[u] = in ? mlv[u] : make_float2(M_INIT, 0.0f);
-    ov[u] = in ? ov[u] : 0.0f;
-  }
-
-  // global maximum over the splits
-  float M = M_INIT;
-#pragma unroll
-  for (int u = 0; u < MRG_UNROLL; ++u) M = fmaxf(M, mlv[u].x);  // the work-group's lanes cover splits 0..63
-  for (int i = MRG_UNROLL * MRG_LANES + tid; i < nsplit; i += MRG_THREADS) M = fmaxf(M, ml[(slot0 + i) * G + g].x);
-  for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
-  __shared__ float s_max[MRG_THREADS / 64];
-  __shared__ float s_acc[MRG_LANES][ABSB_HEAD_DIM], s_l[MRG_LANES];
-  if (lane == 0) s_max[wave] = M;
-  __syncthreads();
-#pragma unroll
-  for (int w = 0; w < MRG_THREADS / 64; ++w) M = fmaxf(M, s_max[w]);
-
-  float acc = 0.0f, lacc = 0.0f;
-#pragma unroll
-  for (int u = 0; u < MRG_UNROLL; ++u) {
-    const float w = fast_exp2(mlv[u].x - M);
-    acc = __builtin_fmaf(ov[u], w, acc);
-    lacc = __builtin_fmaf(mlv[u].y, w, lacc);
-  }
-  for (int i0 = sl + MRG_UNROLL * MRG_LANES; i0 < nsplit; i0 += MRG_UNROLL * MRG_LANES) {
-#pragma unroll
-    for (int u = 0; u < MRG_UNROLL; ++u) {
-      const int i = i0 + u * MRG_LANES;
-      const bool in = i < nsplit;
-      mlv[u] = in ? ml[(slot0 + i) * G + g] : make_float2(M_INIT, 0.0f);
-      ov[u] = in ? p.part_o[((slot0 + i) * G + g) * ABSB_HEAD_DIM + c] : 0.0f;
-    }
-#pragma unroll
-    for (int u = 0; u < MRG_UNROLL; ++u) {
-      const float w = fast_exp2(mlv[u].x - M);
-      acc = __builtin_fmaf(ov[u], w, acc);
-      lacc = __builtin_fmaf(mlv[u].y, w, lacc);
-    }
-  }
-  s_acc[sl][c] = acc;
-  if (c == 0) s_l[sl] = lacc;
-  __syncthreads();
-  if (sl == 0) {
-    float O = s_acc[0][c], Lsum = s_l[0];
-#pragma unroll
-    for (int k = 1; k < MRG_LANES; ++k) {
-      O += s_acc[k][c];
-      Lsum += s_l[k];
-    }
-    const bool any = Lsum > 0.0f;
-    const float res = any ? O / Lsum : 0.0f;
-    const size_t row = (size_t)b * p.g.Hq + (size_t)h * G + g;
-    static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + c] = Elem<DT>::narrow(res);
-    if (p.lse && c == 0)
-      p.lse[row] = any ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
-  }
+// Zeroes the per-segment ticket counters when no earlier kernel of the same call has done it.
+__global__ void decode_clear_tickets_kernel(int32_t* tickets, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) tickets[i] = 0;
 }
 
 template <int DT>
 static void launch_partial(const DecodeParams& p, dim3 grid, hipStream_t stream) {
   switch (p.g.G) {
-    case 1: hipLaunchKernelGGL((decode_partial_kernel<DT, 1>), grid, dim3(DEC_THREADS), 0, stream, p); break;
-    case 2: hipLaunchKernelGGL((decode_partial_kernel<DT, 2>), grid, dim3(DEC_THREADS), 0, stream, p); break;
-    case 3: hipLaunchKernelGGL((decode_partial_kernel<DT, 3>), grid, dim3(DEC_THREADS), 0, stream, p); break;
-    case 4: hipLaunchKernelGGL((decode_partial_kernel<DT, 4>), grid, dim3(DEC_THREADS), 0, stream, p); break;
-    case 5: hipLaunchKernelGGL((decode_partial_kernel<DT, 5>), grid, dim3(DEC_THREADS), 0, stream, p); break;
-    case 6: hipLaunchKernelGGL((decode_partial_kernel<DT, 6>), grid, dim3(DEC_THREADS), 0, stream, p); break;
-    case 7: hipLaunchKernelGGL((decode_partial_kernel<DT, 7>), grid, dim3(DEC_THREADS), 0, stream, p); break;
-    default: hipLaunchKernelGGL((decode_partial_kernel<DT, 8>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 1: hipLaunchKernelGGL((decode_kernel<DT, 1>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((decode_kernel<DT, 2>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 3: hipLaunchKernelGGL((decode_kernel<DT, 3>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((decode_kernel<DT, 4>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 5: hipLaunchKernelGGL((decode_kernel<DT, 5>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 6: hipLaunchKernelGGL((decode_kernel<DT, 6>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    case 7: hipLaunchKernelGGL((decode_kernel<DT, 7>), grid, dim3(DEC_THREADS), 0, stream, p); break;
+    default: hipLaunchKernelGGL((decode_kernel<DT, 8>), grid, dim3(DEC_THREADS), 0, stream, p); break;
   }
 }
 
 int launch_decode(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
                   const void* k_cache, const void* v_cache, const int32_t* page_table, const int32_t* seq_lens,
                   const int32_t* sel_idx, const int32_t* sel_cnt, int32_t sel_stride, void* out, float* lse,
-                  char* ws, hipStream_t stream) {
+                  char* ws, bool tickets_cleared, hipStream_t stream) {
   DecodeParams p;
   p.q = static_cast<const uint16_t*>(q);
   p.k = static_cast<const uint16_t*>(k_cache);
@@ -398,6 +425,7 @@ int launch_decode(const Geometry& g, const Plan& pl, int dtype, float sm_scale, 
   p.sel_cnt = sel_cnt;
   p.part_o = reinterpret_cast<float*>(ws + pl.ws_part_o);
   p.part_ml = reinterpret_cast<float*>(ws + pl.ws_part_ml);
+  p.tickets = reinterpret_cast<int32_t*>(ws + pl.ws_tickets);
   p.out = out;
   p.lse = lse;
   p.sel_stride = sel_stride;
@@ -405,17 +433,17 @@ int launch_decode(const Geometry& g, const Plan& pl, int dtype, float sm_scale, 
   p.max_splits = pl.max_splits;
   p.scale_log2 = sm_scale * 1.4426950408889634f;
   p.g = g;
+  if (!tickets_cleared && pl.max_splits > 1) {
+    hipLaunchKernelGGL(decode_clear_tickets_kernel, dim3((unsigned)((pl.nseg + 255) / 256)), dim3(256), 0, stream,
+                       p.tickets, (int)pl.nseg);
+    int rc = check_launch();
+    if (rc != ABSB_OK) return rc;
+  }
   dim3 grid((unsigned)pl.max_splits, (unsigned)pl.nseg);
   if (dtype == ABSB_F16)
     launch_partial<ABSB_F16>(p, grid, stream);
   else
     launch_partial<ABSB_BF16>(p, grid, stream);
-  int rc = check_launch();
-  if (rc != ABSB_OK) return rc;
-  if (dtype == ABSB_F16)
-    hipLaunchKernelGGL(decode_merge_kernel<ABSB_F16>, dim3((unsigned)g.G, (unsigned)pl.nseg), dim3(MRG_THREADS), 0, stream, p);
-  else
-    hipLaunchKernelGGL(decode_merge_kernel<ABSB_BF16>, dim3((unsigned)g.G, (unsigned)pl.nseg), dim3(MRG_THREADS), 0, stream, p);
   return check_launch();
 }
 

@@ -28,6 +28,7 @@ struct TopkParams {
   const int32_t* budget;  // [Bt]
   int32_t* sel_idx;
   int32_t* sel_cnt;
+  int32_t* tickets;  // [nseg] or null: split counters of the attention kernel that follows, cleared here
   int32_t sel_stride, Hkv;
   HeadTable heads;
 };
@@ -134,7 +135,10 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
     return ordered_key(sc[min(i * TOPK_THREADS + tid, N - 1)]);
   };
 
-  if (tid == 0) p.sel_cnt[s] = K;
+  if (tid == 0) {
+    p.sel_cnt[s] = K;
+    if (p.tickets) p.tickets[s] = 0;
+  }
 #pragma unroll 1
   for (int i = K + tid; i < p.sel_stride; i += TOPK_THREADS) out[i] = -1;
   if (K >= N) {  // everything is selected
@@ -291,7 +295,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
 
 int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const int32_t* cent_off,
                 const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride,
-                hipStream_t stream) {
+                int32_t* tickets, hipStream_t stream) {
   if (pl.max_blocks > TOPK_MAX_BLOCKS) return ABSB_ERR_UNSUPPORTED;
   TopkParams p;
   p.scores = scores;
@@ -299,6 +303,7 @@ int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const 
   p.budget = budget;
   p.sel_idx = sel_idx;
   p.sel_cnt = sel_cnt;
+  p.tickets = tickets;
   p.sel_stride = sel_stride;
   p.Hkv = g.Hkv;
   p.heads = g.heads;

@@ -158,6 +158,10 @@ def test_tuning_knobs_validate():
         absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 100)
     with pytest.raises(absb.AbsbError):
         absb.set_tuning(99, 64)
+    absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 1)
+    absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
+    with pytest.raises(absb.AbsbError):
+        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 64)
 
 
 def test_product_package_does_not_reach_the_oracle():

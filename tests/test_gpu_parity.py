@@ -281,3 +281,33 @@ def test_nonstandard_cache_strides_nhd_layout():
     dw.decode_fused()
     _check_out(dw, ref["out"], ref["lse"], "NHD strides")
     assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+
+
+def test_many_splits_per_segment_and_split_counters_left_at_zero():
+    """More splits than one merge round trip covers; then the stand-alone attention call with the
+    caller's promise that the split counters are zero (they are: every launch leaves them so, and
+    a rebuild of the centroid store in between does not touch them)."""
+    from paper_2605_12110_amd import absb
+    wl = synth.make_workload(1, context=8192, budget=8192)       # every block selected: 8192 tokens per segment
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    try:
+        absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 64)              # 128 splits per segment
+        dw = _dev(wl)
+        dw.build()
+        dw.decode_fused()
+        _check_out(dw, ref["out"], ref["lse"], "128 splits, fused")
+        dw.build()
+        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 1)
+        for rep in range(3):
+            dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+            dw.sparse_decode()
+            _check_out(dw, ref["out"], ref["lse"], f"128 splits, stand-alone call {rep}, counters promised zero")
+        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
+        dw.workspace.fill_(0x5A)                                 # garbage counters: the default path clears them
+        dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+        dw.sparse_decode()
+        _check_out(dw, ref["out"], ref["lse"], "128 splits, stand-alone call on a scribbled workspace")
+    finally:
+        absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 0)
+        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
