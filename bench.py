@@ -30,11 +30,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 METRIC = "decode attention µs/step/layer + achieved HBM GB/s at 128K ctx (8B-shaped GQA)"
-# HBM bytes moved by one absb_sparse_decode call on the headline workload, from rocprofv3 --pmc
-# (FETCH_SIZE, then WRITE_SIZE, each scaled by a 1 GiB copy in the same run): partials kernel
-# 17.06 MB read + 1.06 MB written, merge kernel 1.19 MB + 0.01 MB.
+# HBM bytes moved by one launch of the attention kernel on the headline workload, from rocprofv3
+# --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled by a 1 GiB copy in the same run): 17.57 MB read
+# (K/V rows, lists, page table, the merging groups' re-read of the partials) + 0.56 MB written.
 # Source: profiles/decode_fused_config3_hbm_counters.md
-HEADLINE_TRAFFIC_BYTES = 19_320_000
+HEADLINE_TRAFFIC_BYTES = 18_130_000
 BASE_SEED = {1: 0, 2: 1, 3: 2, 4: 3, 5: 4}
 
 
@@ -130,7 +130,8 @@ def measure(wl0, insts, steps, warmup, stages=False, percentiles=False):
 
     ms, wall_ms = time_loop(step, warmup, steps)
     out = dict(ms=ms, wall_ms=wall_ms, bytes=mean_bytes, bytes0=ub[0], R=R)
-    # dominant stage on its own: sparse decode (split-K partials + merge) on the fused step's selection
+    # dominant kernel on its own: attention over the fused step's selection (split-K partials and
+    # their merge happen inside the one kernel)
     # (every instance has completed a fused step on its workspace, so its split counters are zero and
     # the stage is the attention kernel alone, as in the fused step)
     from paper_2605_12110_amd import absb
@@ -311,9 +312,9 @@ def main():
         },
         "roofline": {
             "bound": "hbm",
-            # the event-timed unit is the entry point absb_sparse_decode = the dominant kernel
-            # (decode_partial_kernel, which reads the K/V rows) plus the small LSE merge kernel
-            "kernel": "decode_partial_kernel + decode_merge_kernel (one absb_sparse_decode call)",
+            # the event-timed unit is the entry point absb_sparse_decode with the split counters
+            # known to be zero: exactly one launch of the attention kernel per call
+            "kernel": "decode_kernel (one absb_sparse_decode call = one launch)",
             "achieved": round(dec_gbps, 2),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
