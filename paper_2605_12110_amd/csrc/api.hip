@@ -1,5 +1,6 @@
 // Host side of libabsb.so: argument validation, size planning, workspace carving and the
 // extern "C" entry points.  Nothing here touches the device except through the launchers.
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 
@@ -57,6 +58,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
 
   Plan p = {};
   p.nseg = Bt * Hkv;
+  p.build_chunk_tokens = 1024;
   int64_t max_len = 0;
   for (int b = 0; b < Bt; ++b) {
     const int64_t L = batch->seq_lens_host[b];
@@ -74,6 +76,8 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
       }
       if (sel_stride_in > 0 && sel_stride_in < K) K = sel_stride_in;
       p.total += N;
+      const int64_t cb = std::max<int64_t>(16, p.build_chunk_tokens / B);  // as build_chunk_blocks() on the device
+      if (ceil_div(N, cb) > p.build_max_chunks) p.build_max_chunks = (int32_t)ceil_div(N, cb);
       if (N > p.max_blocks) p.max_blocks = (int32_t)N;
       const int64_t tok = K * B;
       if (tok > p.max_tokens) p.max_tokens = tok;
@@ -105,8 +109,6 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
 
   int sc = tuning(ABSB_TUNE_SCORE_CHUNK);
   p.score_chunk = sc > 0 ? sc : 256;
-  p.build_chunk = 64;
-  p.build_max_chunks = (int32_t)ceil_div(p.max_blocks, p.build_chunk);
 
   // workspace: the split counters of the attention kernel come first, at the same place in every
   // carving (nothing else ever writes there); behind them the three users overlap, since they

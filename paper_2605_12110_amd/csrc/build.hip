@@ -8,9 +8,12 @@
 // code = clamp(round-half-even((c - min) * (15/(max-min)))).  Compiled with -ffp-contract=off.
 //
 // Three launches:
-//   1. means: a 16-lane row-group owns a block (each lane 8 channels = one 128-bit load per key),
-//      walks its tokens in order, writes the binary32 centroid to the workspace and folds it into
-//      per-work-group channel minima/maxima;
+//   1. means: a work-group owns `chunk_tokens` consecutive tokens of a segment (a power-of-two number
+//      of whole blocks, at least one per 16-lane row-group), so work per group is the same for every
+//      block size.  A row-group (each lane 8 channels = one 128-bit load per key) streams its 64+
+//      consecutive tokens eight rows at a time, the next eight in flight while these are summed,
+//      closes a block whenever the running token index reaches a block boundary, writes the binary32
+//      centroid to the workspace and folds it into per-work-group channel minima/maxima;
 //   2. params: reduces the partial extrema per segment and writes qscale, qmin (and 15/range);
 //   3. codes: quantizes the centroids, eight channels per lane packed into one 32-bit store.
 #include "common.h"
@@ -28,23 +31,30 @@ struct BuildParams {
   float* qscale;   // [nseg][128]
   float* qmin;     // [nseg][128]
   uint8_t* codes;  // [total][64]
-  int32_t chunk, max_chunks;
+  int32_t chunk_tokens, max_chunks;
   Geometry g;
 };
 
 constexpr int BUILD_THREADS = 256;
 constexpr int BUILD_GROUPS = BUILD_THREADS / 16;
+constexpr int BUILD_ROWS = 8;  // rows per step: B >= 8 and P >= 8, so a step never straddles a block or a page
+
+// blocks per work-group for a head with blocks of 2^lb tokens
+__device__ __forceinline__ int build_chunk_blocks(int chunk_tokens, int lb) {
+  return max(BUILD_GROUPS, chunk_tokens >> lb);
+}
 
 template <int DT>
 __global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams p) {
   const int s = blockIdx.y, chunk = blockIdx.x;
   const int off = p.cent_off[s];
   const int N = p.cent_off[s + 1] - off;
-  const int j0 = chunk * p.chunk;
-  if (j0 >= N) return;
-  const int jend = min(N, j0 + p.chunk);
   const int b = s / p.g.Hkv, h = s % p.g.Hkv;
   const int lb = p.g.heads.log2_block[h], lP = p.g.log2_page;
+  const int cb = build_chunk_blocks(p.chunk_tokens, lb);
+  const int j0 = chunk * cb;
+  if (j0 >= N) return;
+  const int jend = min(N, j0 + cb);
   const int B = 1 << lb;
   const int L = p.seq_lens[b];
   const int tid = threadIdx.x, grp = tid >> 4, li = tid & 15;
@@ -58,25 +68,41 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams 
     mx[c] = -__builtin_inff();
   }
 
-  for (int j = j0 + grp; j < jend; j += BUILD_GROUPS) {
-    const int t0 = j << lb;
-    const int n = min(B, L - t0);
+  // this row-group's blocks [ja, jb) = consecutive tokens [tA, tB)
+  const int per = cb / BUILD_GROUPS;
+  const int ja = min(jend, j0 + grp * per), jb = min(jend, ja + per);
+  const int tA = ja << lb, tB = min(jb << lb, L);
+
+  auto row_base = [&](int t) -> const uint16_t* {  // first row of the 8-row step at token t (t < L)
+    const int page = pt[t >> lP];
+    return p.k + (size_t)page * p.g.s_page + lane_off + (size_t)(t & ((1 << lP) - 1)) * p.g.s_tok;
+  };
+
+  if (tA < tB) {
+    uint4 cur[BUILD_ROWS], nxt[BUILD_ROWS];
+    const uint16_t* base = row_base(tA);
+#pragma unroll
+    for (int r = 0; r < BUILD_ROWS; ++r)  // rows past the end repeat the last one (a legal address), masked below
+      cur[r] = *reinterpret_cast<const uint4*>(base + (size_t)min(r, tB - 1 - tA) * p.g.s_tok);
+#pragma unroll
+    for (int r = 0; r < BUILD_ROWS; ++r) nxt[r] = cur[r];
+    const uint16_t* base_next = row_base(min(tA + BUILD_ROWS, tB - 1));
+
     float sum[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) sum[c] = 0.0f;
-    for (int i = 0; i < n; i += 4) {
-      uint4 row[4];
+    for (int i = tA; i < tB; i += BUILD_ROWS) {
+      const int in = i + BUILD_ROWS;
+      if (in < tB) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int t = min(t0 + i + r, L - 1);
-        const int page = pt[t >> lP];
-        row[r] = *reinterpret_cast<const uint4*>(p.k + (size_t)page * p.g.s_page + lane_off +
-                                                 (size_t)(t & ((1 << lP) - 1)) * p.g.s_tok);
+        for (int r = 0; r < BUILD_ROWS; ++r)
+          nxt[r] = *reinterpret_cast<const uint4*>(base_next + (size_t)min(r, tB - 1 - in) * p.g.s_tok);
+        base_next = row_base(min(in + BUILD_ROWS, tB - 1));
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        if (i + r < n) {
-          const uint32_t w[4] = {row[r].x, row[r].y, row[r].z, row[r].w};
+      for (int r = 0; r < BUILD_ROWS; ++r) {
+        if (i + r < tB) {
+          const uint32_t w[4] = {cur[r].x, cur[r].y, cur[r].z, cur[r].w};
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             sum[2 * c] = sum[2 * c] + Elem<DT>::lo(w[c]);
@@ -84,18 +110,24 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams 
           }
         }
       }
-    }
-    const float fn = (float)n;
-    float cen[8];
+      if ((in & (B - 1)) == 0 || in >= tB) {  // the block that holds token i is complete
+        const int j = i >> lb;
+        const float fn = (float)min(B, L - (j << lb));
+        float cen[8];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      cen[c] = sum[c] / fn;
-      mn[c] = fminf(mn[c], cen[c]);
-      mx[c] = fmaxf(mx[c], cen[c]);
+        for (int c = 0; c < 8; ++c) {
+          cen[c] = sum[c] / fn;
+          mn[c] = fminf(mn[c], cen[c]);
+          mx[c] = fmaxf(mx[c], cen[c]);
+          sum[c] = 0.0f;
+        }
+        float4* dst = reinterpret_cast<float4*>(p.cent + ((size_t)off + j) * ABSB_HEAD_DIM + li * 8);
+        dst[0] = make_float4(cen[0], cen[1], cen[2], cen[3]);
+        dst[1] = make_float4(cen[4], cen[5], cen[6], cen[7]);
+      }
+#pragma unroll
+      for (int r = 0; r < BUILD_ROWS; ++r) cur[r] = nxt[r];
     }
-    float4* dst = reinterpret_cast<float4*>(p.cent + ((size_t)off + j) * ABSB_HEAD_DIM + li * 8);
-    dst[0] = make_float4(cen[0], cen[1], cen[2], cen[3]);
-    dst[1] = make_float4(cen[4], cen[5], cen[6], cen[7]);
   }
 
   // fold the 16 row-groups: channel ch = li*8 + c
@@ -108,6 +140,7 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams 
   __syncthreads();
   if (tid < ABSB_HEAD_DIM) {
     float a = s_mn[0][tid], z = s_mx[0][tid];
+#pragma unroll
     for (int g2 = 1; g2 < BUILD_GROUPS; ++g2) {
       a = fminf(a, s_mn[g2][tid]);
       z = fmaxf(z, s_mx[g2][tid]);
@@ -118,15 +151,41 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams 
   }
 }
 
-__global__ __launch_bounds__(ABSB_HEAD_DIM) void build_params_kernel(BuildParams p) {
-  const int s = blockIdx.x, ch = threadIdx.x;
+// One work-group per segment: 128 channels x 8 chunk lanes, min/max are exact in any order.
+constexpr int PARAMS_THREADS = 1024;
+constexpr int PARAMS_LANES = PARAMS_THREADS / ABSB_HEAD_DIM;
+
+__global__ __launch_bounds__(PARAMS_THREADS) void build_params_kernel(BuildParams p) {
+  const int s = blockIdx.x, ch = threadIdx.x & (ABSB_HEAD_DIM - 1), cl = threadIdx.x / ABSB_HEAD_DIM;
+  const int h = s % p.g.Hkv;
   const int N = p.cent_off[s + 1] - p.cent_off[s];
-  const int nchunks = (N + p.chunk - 1) / p.chunk;
+  const int cb = build_chunk_blocks(p.chunk_tokens, p.g.heads.log2_block[h]);
+  const int nchunks = (N + cb - 1) / cb;
   float mn = __builtin_inff(), mx = -__builtin_inff();
-  for (int i = 0; i < nchunks; ++i) {
-    const float* src = p.minmax + ((size_t)s * p.max_chunks + i) * 2 * ABSB_HEAD_DIM;
-    mn = fminf(mn, src[ch]);
-    mx = fmaxf(mx, src[ABSB_HEAD_DIM + ch]);
+  for (int i0 = cl; i0 < nchunks; i0 += 4 * PARAMS_LANES) {
+    float a[4], z[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = min(i0 + u * PARAMS_LANES, nchunks - 1);  // the tail repeats a chunk: harmless for min/max
+      const float* src = p.minmax + ((size_t)s * p.max_chunks + i) * 2 * ABSB_HEAD_DIM;
+      a[u] = src[ch];
+      z[u] = src[ABSB_HEAD_DIM + ch];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      mn = fminf(mn, a[u]);
+      mx = fmaxf(mx, z[u]);
+    }
+  }
+  __shared__ float s_mn[PARAMS_LANES][ABSB_HEAD_DIM], s_mx[PARAMS_LANES][ABSB_HEAD_DIM];
+  s_mn[cl][ch] = mn;
+  s_mx[cl][ch] = mx;
+  __syncthreads();
+  if (cl != 0) return;
+#pragma unroll
+  for (int k = 1; k < PARAMS_LANES; ++k) {
+    mn = fminf(mn, s_mn[k][ch]);
+    mx = fmaxf(mx, s_mx[k][ch]);
   }
   const float rng = mx - mn;
   float sc = 0.0f, inv = 0.0f;
@@ -144,9 +203,10 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_codes_kernel(BuildParams 
   const int s = blockIdx.y;
   const int off = p.cent_off[s];
   const int N = p.cent_off[s + 1] - off;
-  const int j0 = blockIdx.x * p.chunk;
+  const int cb = build_chunk_blocks(p.chunk_tokens, p.g.heads.log2_block[s % p.g.Hkv]);
+  const int j0 = blockIdx.x * cb;
   if (j0 >= N) return;
-  const int jend = min(N, j0 + p.chunk);
+  const int jend = min(N, j0 + cb);
   const int tid = threadIdx.x, grp = tid >> 4, li = tid & 15;
   float mn[8], inv[8];
 #pragma unroll
@@ -187,7 +247,7 @@ int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cac
   p.qscale = qscale;
   p.qmin = qmin;
   p.codes = codes;
-  p.chunk = pl.build_chunk;
+  p.chunk_tokens = pl.build_chunk_tokens;
   p.max_chunks = pl.build_max_chunks;
   p.g = g;
   dim3 grid((unsigned)pl.build_max_chunks, (unsigned)pl.nseg);
@@ -197,7 +257,7 @@ int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cac
     hipLaunchKernelGGL(build_means_kernel<ABSB_BF16>, grid, dim3(BUILD_THREADS), 0, stream, p);
   int rc = check_launch();
   if (rc != ABSB_OK) return rc;
-  hipLaunchKernelGGL(build_params_kernel, dim3((unsigned)pl.nseg), dim3(ABSB_HEAD_DIM), 0, stream, p);
+  hipLaunchKernelGGL(build_params_kernel, dim3((unsigned)pl.nseg), dim3(PARAMS_THREADS), 0, stream, p);
   rc = check_launch();
   if (rc != ABSB_OK) return rc;
   hipLaunchKernelGGL(build_codes_kernel, grid, dim3(BUILD_THREADS), 0, stream, p);

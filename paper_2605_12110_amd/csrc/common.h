@@ -38,8 +38,8 @@ struct Plan {
   int32_t split_tokens;     // tokens per split-K work-group
   int32_t max_splits;       // grid.x of the decode kernels
   int32_t score_chunk;      // centroids per work-group in score
-  int32_t build_chunk;      // blocks per work-group in build
-  int32_t build_max_chunks; // max_s ceil(N_s / build_chunk)
+  int32_t build_chunk_tokens;  // tokens per work-group in build (a head's chunk: max(16, that / B_h) blocks)
+  int32_t build_max_chunks;    // max_s ceil(N_s / chunk_h)
   // workspace carving (byte offsets, 256-aligned)
   size_t ws_part_o, ws_part_ml, ws_tickets;       // decode partials, per-segment split counters
   size_t ws_scores, ws_sel_idx, ws_sel_cnt;       // fused step intermediates
