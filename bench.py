@@ -152,27 +152,53 @@ def measure(wl0, insts, steps, warmup, stages=False, percentiles=False):
     return out
 
 
-def cpu_baseline(wl0, bytes0, seconds=10.0):
-    from oracle import oracle as O
-    st = O.build_centroids(wl0)
-    O.decode_step(wl0, st)                       # warm
+def stream_read_ceiling(gib=2, reps=10):
+    """GB/s of a plain 128-bit-load read of `gib` GiB (larger than every cache), event-timed."""
+    import torch
+    from paper_2605_12110_amd import absb
+    buf = torch.full((gib << 30,), 3, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ms, _ = time_loop(lambda i: absb.absb_stream_read(buf, sink), 2, reps)
+    del buf
+    torch.cuda.empty_cache()
+    return (gib << 30) / (ms * 1e-3) / 1e9
+
+
+def _time_oracle(fn, seconds, max_n=2000):
     t0 = time.perf_counter()
     n = 0
     while True:
-        O.decode_step(wl0, st)
+        fn()
         n += 1
         el = time.perf_counter() - t0
-        if el > seconds or n >= 2000:
-            break
-    cpu_s = el / n
+        if el > seconds or n >= max_n:
+            return el / n, n, el
+
+
+def cpu_baseline(wl0, bytes0, seconds=10.0):
+    from oracle import oracle as O
+    t0 = time.perf_counter()
+    st = O.build_centroids(wl0)
+    build_s = time.perf_counter() - t0
+    O.decode_step(wl0, st)                       # warm
+    cpu_s, n, el = _time_oracle(lambda: O.decode_step(wl0, st), seconds)
+    threads = O.num_threads()
+    O.set_threads(1)
+    try:
+        one_s, n1, el1 = _time_oracle(lambda: O.decode_step(wl0, st), min(3.0, seconds))
+    finally:
+        O.set_threads(threads)
     return {
         "value": round(bytes0["total"] / cpu_s / 1e9, 3),
         "unit": "GB/s",
         "us_per_step": round(cpu_s * 1e6, 1),
-        "cores": O.num_threads(),
+        "cores": threads,
         "kind": "oracle",
         "sample": f"{n} full steps (score -> top-k -> attention over the selection) of the same workload, "
                   f"instance 0, prebuilt codes, {el:.1f} s of wall time",
+        "single_thread_us_per_step": round(one_s * 1e6, 1),
+        "single_thread_sample": f"{n1} steps, {el1:.1f} s",
+        "oracle_build_seconds_once": round(build_s, 3),
     }
 
 
@@ -208,6 +234,8 @@ def run_matrix(args):
     del insts
     torch.cuda.empty_cache()
 
+    print(f"\nStreaming-read ceiling measured in this run (absb_stream_read, 2 GiB, 128-bit loads): "
+          f"{stream_read_ceiling():.0f} GB/s of {HBM_PEAK_GBPS:.0f} GB/s published peak.")
     print("\nConfig 5 sweep (batch 4, context 65536, fp16): uniform block 16 vs adaptive per-head sizes\n")
     print("| blocks | budget | us/step | GB/s | planted-token recall | attention recall (mean) | max abs err vs dense | "
           "rel L2 err vs dense |")
@@ -281,6 +309,7 @@ def main():
     ms, mean_bytes, R = m["ms"], m["bytes"], m["R"]
     gbps = mean_bytes["total"] / (ms * 1e-3) / 1e9
     dec_gbps = mean_bytes["decode"] / (m["ms_decode"] * 1e-3) / 1e9
+    ceiling = stream_read_ceiling()
     wl = wl0
     headline = args.config == 3 and args.context is None and args.batch is None and args.budget is None
     result = {
@@ -322,6 +351,9 @@ def main():
             "algorithmic_bytes_per_launch": int(mean_bytes["decode"]),
             "us_per_launch": round(m["ms_decode"] * 1e3, 3),
             "traffic": HEADLINE_TRAFFIC_BYTES if headline else None,
+            # practical ceiling measured in this run: a plain 128-bit-load read of 2 GiB
+            "stream_read_ceiling": round(ceiling, 1),
+            "frac_of_stream_read_ceiling": round(dec_gbps / ceiling, 4),
         },
     }
     if not args.no_cpu_baseline:

@@ -158,6 +158,12 @@ ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
                                int32_t* sel_cnt_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement helper, not a step of the method: reads `bytes` (a multiple of 16; the tail is
+ * ignored) of the device buffer `src` (16-byte aligned) once with 128-bit loads and discards them.
+ * Timing it gives the practical streaming-read ceiling of the device, against which the attention
+ * kernel's bandwidth can be stated.  `sink`: 4 bytes of device memory (practically never written). */
+ABSB_API int absb_stream_read(const void* src, size_t bytes, void* sink, void* stream);
+
 /* Static string for a status code. */
 ABSB_API const char* absb_strerror(int status);
 

@@ -22,7 +22,7 @@ TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO = 0, 1, 2
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("absb_plan", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
-           "absb_decode_fused", "absb_strerror", "absb_set_tuning")
+           "absb_decode_fused", "absb_stream_read", "absb_strerror", "absb_set_tuning")
 
 
 class AbsbError(RuntimeError):
@@ -214,6 +214,11 @@ def absb_decode_fused(layer: Layer, batch: Batch, q, codes, qscale, k_cache, v_c
                                     _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(sel_idx_out), _ptr(sel_cnt_out),
                                     _ptr(workspace), C.c_size_t(_nbytes(workspace)), _stream(stream)),
            "absb_decode_fused")
+
+
+def absb_stream_read(src, sink, stream=None) -> None:
+    _check(load().absb_stream_read(_ptr(src), C.c_size_t(_nbytes(src)), _ptr(sink), _stream(stream)),
+           "absb_stream_read")
 
 
 def _nbytes(t) -> int:

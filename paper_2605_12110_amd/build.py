@@ -24,6 +24,7 @@ _SOURCES = {
     "score.hip": ["-ffp-contract=off"],
     "topk.hip": [],
     "decode.hip": ["-ffp-contract=off"],   # FMAs are written explicitly there
+    "util.hip": [],
 }
 
 

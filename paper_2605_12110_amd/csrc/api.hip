@@ -267,6 +267,16 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
                        batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, true, st);
 }
 
+int absb_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink) return ABSB_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(src) & 15) return ABSB_ERR_BAD_SHAPE;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    return ABSB_ERR_HIP;
+  return launch_stream_read(src, bytes, static_cast<uint32_t*>(sink), cus, static_cast<hipStream_t>(stream));
+}
+
 const char* absb_strerror(int status) {
   switch (status) {
     case ABSB_OK: return "ok";

@@ -70,6 +70,8 @@ ABSB_HIDDEN int launch_decode(const Geometry& g, const Plan& pl, int dtype, floa
                               int32_t sel_stride, void* out, float* lse, char* ws, bool tickets_cleared,
                               hipStream_t stream);
 
+ABSB_HIDDEN int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int num_cus, hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? ABSB_OK : ABSB_ERR_HIP; }
 
 // ------------------------------------------------------------------ device helpers

@@ -311,3 +311,15 @@ def test_many_splits_per_segment_and_split_counters_left_at_zero():
     finally:
         absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 0)
         absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
+
+
+def test_stream_read_helper_runs_and_leaves_its_sink_alone():
+    import torch
+    from paper_2605_12110_amd import absb
+    buf = torch.arange(0, (1 << 20) + 48, dtype=torch.int32, device="cuda")   # a ragged tile count
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    absb.absb_stream_read(buf, sink)
+    _sync()
+    assert int(sink.item()) == 0
+    with pytest.raises(absb.AbsbError):
+        absb.absb_stream_read(buf.view(torch.uint8)[4:], sink)                # misaligned source
