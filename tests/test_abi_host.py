@@ -172,3 +172,16 @@ def test_product_package_does_not_reach_the_oracle():
         for f in files:
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 assert not bad.search(open(os.path.join(dirpath, f)).read()), f
+
+
+def test_selection_rejects_segments_beyond_its_capacity_before_any_launch():
+    """A segment of more than 2^17 blocks does not fit the selection kernel's bitmap: the call must
+    say so on the host (nothing is launched, so plain host buffers serve as arguments here)."""
+    import torch
+    L = (8 << 17) + 1                                        # 131073 blocks of 8 tokens
+    layer = _layer(num_q_heads=1, num_kv_heads=1, block_size=[8], kv_strides=(64 * 128, 64 * 128, 128))
+    fake = torch.zeros(4, dtype=torch.int32)
+    batch = absb.Batch(seq_lens_host=[L], budget_host=[64], pt_stride=(L + 63) // 64, cent_off=fake, budget=fake)
+    with pytest.raises(absb.AbsbError) as e:
+        absb.absb_topk(layer, batch, fake, fake, fake, 8, stream=0)
+    assert e.value.status == absb.ERR_UNSUPPORTED

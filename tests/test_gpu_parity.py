@@ -323,3 +323,41 @@ def test_stream_read_helper_runs_and_leaves_its_sink_alone():
     assert int(sink.item()) == 0
     with pytest.raises(absb.AbsbError):
         absb.absb_stream_read(buf.view(torch.uint8)[4:], sink)                # misaligned source
+
+
+@pytest.mark.parametrize("kind", ["random", "few_values", "all_equal"])
+def test_selection_at_the_largest_supported_segment(kind):
+    """2^17 blocks in one segment (the selection kernel's capacity), two segments of different
+    size side by side; heavy ties push the kernel onto its multi-digit path."""
+    import torch
+    from paper_2605_12110_amd import absb
+    B = np.array([8, 16], np.int32)
+    L = np.array([8 << 17], np.int32)                       # 131072 blocks of 8, 65536 blocks of 16
+    T = np.array([160000], np.int32)                        # K = 20000 and 10000 blocks
+    layer = absb.Layer(2, 2, 128, 64, synth.F16, B, (2 * 64 * 128, 64 * 128, 128))
+    dev = "cuda:0"
+    batch = absb.Batch(seq_lens_host=L, budget_host=T, seq_lens=torch.from_numpy(L).to(dev),
+                       page_table=None, budget=torch.from_numpy(T).to(dev), pt_stride=int(L[0]) // 64)
+    plan = absb.absb_plan(layer, batch)
+    off = plan.cent_off.astype(np.int64)
+    assert off.tolist() == [0, 1 << 17, (1 << 17) + (1 << 16)]
+    batch.cent_off = torch.from_numpy(plan.cent_off).to(dev)
+    rng = np.random.default_rng(77)
+    total = int(off[-1])
+    if kind == "random":
+        sc = rng.integers(-2 ** 31, 2 ** 31, size=total, dtype=np.int64)
+    elif kind == "few_values":
+        sc = rng.integers(-3, 4, size=total, dtype=np.int64) * 1000003
+    else:
+        sc = np.full(total, -17, np.int64)
+    sc = sc.astype(np.int32)
+    stride = plan.sel_stride
+    assert stride == 20000
+    sel_idx = torch.full((2, stride), -7, dtype=torch.int32, device=dev)
+    sel_cnt = torch.full((2,), -7, dtype=torch.int32, device=dev)
+    _say(f"[case top-k capacity/{kind}] blocks={np.diff(off).tolist()} K={[20000, 10000]}")
+    absb.absb_topk(layer, batch, torch.from_numpy(sc).to(dev), sel_idx, sel_cnt, stride)
+    _sync()
+    want_idx, want_cnt = O.topk_raw(1, 2, off, B, T, sc, stride)
+    assert np.array_equal(sel_cnt.cpu().numpy(), want_cnt) and want_cnt.tolist() == [20000, 10000]
+    assert np.array_equal(sel_idx.cpu().numpy(), want_idx)
