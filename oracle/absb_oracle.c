@@ -10,7 +10,9 @@
  *   - block-sparse workflow (Sec. 2.2): partition each head's keys into blocks of size
  *     B_h, one centroid c_j per block, importance r_j = q . c_j^T, Top-K blocks, attention
  *     over the selected blocks only;
- *   - centroid = mean pooling of the block's keys (Sec. 2.2, footnote on pooling);
+ *   - centroid = mean pooling of the block's keys (Sec. 2.2, footnote on pooling); as a
+ *     second representation, the max-min pooling the same footnote names (channel-wise
+ *     maxima and minima of the block, scored by their channel-wise upper bound of q . k);
  *   - INT4 asymmetric per-channel centroid quantization: one scale and one zero-point
  *     offset per head-dim channel, shared by all blocks of a head (Sec. 3.3);
  *   - flattened 1-D centroid layout, offset[s+1] = offset[s] + N_s (Sec. 3.4, kernel 1);
@@ -36,7 +38,9 @@
  * other than itself - fp64 means, quantization error bound/idempotence/extremes,
  * an independent fp64 dot-product bound for the scores, numpy lexsort and exhaustive
  * tiny cases for Top-K, an independent numpy dense softmax (Eq. 1) for attention with
- * K = all blocks, page-permutation invariance, and single-token / equal-key closed forms.
+ * K = all blocks, page-permutation invariance, and single-token / equal-key closed forms;
+ * the max-min representation to numpy extrema, to the bound property q . k_t <= score for
+ * every token of the block, and to an fp64 evaluation of the max formula.
  */
 #include <math.h>
 #include <stdint.h>
@@ -251,6 +255,97 @@ void orc_score(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t *q /* [
                 uint8_t byte = codes[j * (d / 2) + ch / 2];
                 int32_t code = (ch % 2 == 0) ? (byte & 15) : (byte >> 4);
                 acc += wq[ch] * code;
+            }
+            scores[j] = acc;
+        }
+    }
+}
+
+/* ---- block representation by channel-wise extrema (max-min pooling, the other pooling the
+ * footnote of Sec. 2.2 names; the baseline of Sec. 4.1 scores blocks with it).
+ * rep[j] = (max_t k_t[0..d-1], min_t k_t[0..d-1]) over the block's valid tokens: 2d values,
+ * maxima first.  Exact (comparisons only). */
+void orc_minmax_pool(int dtype, int Bt, int Hkv, int d, int P, int64_t s_page, int64_t s_head, int64_t s_tok,
+                     const uint16_t *k_cache, const int32_t *page_table, int pt_stride, const int32_t *seq_lens,
+                     const int32_t *block_size, const int64_t *off, float *rep /* [total][2d] */) {
+    paged_t kc = {k_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        int64_t L = seq_lens[b], B = block_size[h];
+        int64_t N = off[s + 1] - off[s];
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t t0 = j * B;
+            int64_t n = (L - t0 < B) ? (L - t0) : B;
+            float *mx = rep + (off[s] + j) * 2 * d, *mn = mx + d;
+            for (int ch = 0; ch < d; ++ch) {
+                mx[ch] = -INFINITY;
+                mn[ch] = INFINITY;
+            }
+            for (int64_t t = t0; t < t0 + n; ++t) {
+                const uint16_t *row = row_of(&kc, b, h, t);
+                for (int ch = 0; ch < d; ++ch) {
+                    float v = widen(row[ch], dtype);
+                    if (v > mx[ch]) mx[ch] = v;
+                    if (v < mn[ch]) mn[ch] = v;
+                }
+            }
+        }
+    }
+}
+
+/* ---- importance score for the max-min representation ------------------------------
+ * Per query head the block's score is the channel-wise upper bound of q . k over the block,
+ *   sum_c max(q_c * M^_jc, q_c * m^_jc),
+ * M^, m^ the dequantized maxima and minima; the group's score is the sum over its heads.
+ * For M^ >= m^ the larger product is the one whose bound matches the sign of q_c; that
+ * sign-matched product is what is taken here also where quantization makes M^ and m^ cross
+ * (by less than a quantization step), so that the group score stays linear in the codes:
+ *   sum_c [ P_c * (codeM_jc * scaleM_c + minM_c) + Q_c * (codem_jc * scalem_c + minm_c) ],
+ * P_c = sum of the group's positive q_gc, Q_c = sum of its negative q_gc.  The offset terms
+ * are constant within a segment.  What remains is the fixed-point dot of O4 over 2d weights
+ * w = (P * scaleM, Q * scalem) and 2d codes (maxima first). */
+void orc_score_minmax(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t *q /* [Bt][Hq][d] */,
+                      const uint8_t *codes /* [total][d] bytes: d/2 of maxima, d/2 of minima */,
+                      const float *qscale /* [Bt*Hkv][2d] */, const int64_t *off, int32_t *scores,
+                      int32_t *score_exp, int32_t *wq_out /* [Bt*Hkv][2d] or NULL */) {
+    int G = Hq / Hkv, d2 = 2 * d;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        float w[2048];
+        int32_t wq[2048];
+        float A = 0.0f;
+        for (int ch = 0; ch < d; ++ch) {
+            float pos = 0.0f, neg = 0.0f;
+            for (int g = 0; g < G; ++g) {
+                float v = widen(q[((int64_t)b * Hq + h * G + g) * d + ch], dtype);
+                if (v > 0.0f) pos = pos + v;
+                if (v < 0.0f) neg = neg + v;
+            }
+            w[ch] = pos * qscale[(int64_t)s * d2 + ch];
+            w[d + ch] = neg * qscale[(int64_t)s * d2 + d + ch];
+        }
+        for (int c = 0; c < d2; ++c) {
+            float a = fabsf(w[c]);
+            if (a > A) A = a;
+        }
+        int ex = 0;
+        if (!(A >= 0x1p-100f) || isinf(A)) {
+            for (int c = 0; c < d2; ++c) wq[c] = 0;
+        } else {
+            ex = ilogbf(A) - 14;
+            for (int c = 0; c < d2; ++c) wq[c] = (int32_t)rintf(ldexpf(w[c], -ex));
+        }
+        score_exp[s] = ex;
+        if (wq_out)
+            for (int c = 0; c < d2; ++c) wq_out[(int64_t)s * d2 + c] = wq[c];
+        for (int64_t j = off[s]; j < off[s + 1]; ++j) {
+            int32_t acc = 0;
+            for (int c = 0; c < d2; ++c) {
+                uint8_t byte = codes[j * d + c / 2];
+                int32_t code = (c % 2 == 0) ? (byte & 15) : (byte >> 4);
+                acc += wq[c] * code;
             }
             scores[j] = acc;
         }

@@ -64,14 +64,20 @@ def set_threads(n: int) -> None:
     lib().orc_set_threads(C.c_int(n))
 
 
+MEAN, MINMAX = 0, 1         # block representation: mean pooling / channel-wise maxima and minima
+
+
 @dataclass
 class CentroidStore:
+    """Widths below are for mean pooling; with max-min pooling every row is twice as wide
+    (maxima first, then minima)."""
     off: np.ndarray        # int64 [nseg+1]
-    cent: np.ndarray       # float32 [total, d]   (unquantized block means)
+    cent: np.ndarray       # float32 [total, d]   (unquantized block representation)
     qscale: np.ndarray     # float32 [nseg, d]
     qmin: np.ndarray       # float32 [nseg, d]
     qinv: np.ndarray       # float32 [nseg, d]
     codes: np.ndarray      # uint8 [total, d/2]
+    repr: int = MEAN
 
 
 def _geom(wl):
@@ -95,6 +101,15 @@ def centroids(wl, off: np.ndarray) -> np.ndarray:
     lib().orc_centroids(dt, Bt, Hkv, d, P, sp, sh, st, _p(wl.k_cache), _p(pt), C.c_int(pt.shape[1]),
                         _p(_i32(wl.seq_lens)), _p(_i32(wl.block_size)), _p(off), _p(cent))
     return cent
+
+
+def minmax_pool(wl, off: np.ndarray) -> np.ndarray:
+    dt, Bt, _, Hkv, d, P, sp, sh, st = _geom(wl)
+    rep = np.empty((int(off[-1]), 2 * wl.head_dim), dtype=np.float32)
+    pt = _i32(wl.page_table)
+    lib().orc_minmax_pool(dt, Bt, Hkv, d, P, sp, sh, st, _p(wl.k_cache), _p(pt), C.c_int(pt.shape[1]),
+                          _p(_i32(wl.seq_lens)), _p(_i32(wl.block_size)), _p(off), _p(rep))
+    return rep
 
 
 def quant_params(off, cent):
@@ -121,13 +136,13 @@ def dequantize(off, codes, qscale, qmin) -> np.ndarray:
     return out
 
 
-def build_centroids(wl) -> CentroidStore:
-    """O1-O3: means, per-channel ranges, INT4 codes."""
+def build_centroids(wl, repr: int = MEAN) -> CentroidStore:
+    """O1-O3: block representation (means, or maxima and minima), per-channel ranges, INT4 codes."""
     off = offsets(wl)
-    cent = centroids(wl, off)
+    cent = centroids(wl, off) if repr == MEAN else minmax_pool(wl, off)
     qscale, qmin, qinv = quant_params(off, cent)
     codes = quantize(off, cent, qmin, qinv)
-    return CentroidStore(off, cent, qscale, qmin, qinv, codes)
+    return CentroidStore(off, cent, qscale, qmin, qinv, codes, repr)
 
 
 def score(wl, store: CentroidStore, q: Optional[np.ndarray] = None, want_weights: bool = False):
@@ -136,10 +151,12 @@ def score(wl, store: CentroidStore, q: Optional[np.ndarray] = None, want_weights
     nseg = wl.batch * wl.num_kv_heads
     scores = np.empty(int(store.off[-1]), np.int32)
     ex = np.empty(nseg, np.int32)
-    wq = np.empty((nseg, wl.head_dim), np.int32) if want_weights else None
-    lib().orc_score(C.c_int(wl.dtype), C.c_int(wl.batch), C.c_int(wl.num_q_heads), C.c_int(wl.num_kv_heads),
-                    C.c_int(wl.head_dim), _p(np.ascontiguousarray(q)), _p(store.codes), _p(store.qscale),
-                    _p(store.off), _p(scores), _p(ex), _p(wq))
+    width = wl.head_dim * (2 if store.repr == MINMAX else 1)
+    wq = np.empty((nseg, width), np.int32) if want_weights else None
+    fn = lib().orc_score_minmax if store.repr == MINMAX else lib().orc_score
+    fn(C.c_int(wl.dtype), C.c_int(wl.batch), C.c_int(wl.num_q_heads), C.c_int(wl.num_kv_heads),
+       C.c_int(wl.head_dim), _p(np.ascontiguousarray(q)), _p(store.codes), _p(store.qscale),
+       _p(store.off), _p(scores), _p(ex), _p(wq))
     return (scores, ex, wq) if want_weights else (scores, ex)
 
 
