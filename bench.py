@@ -38,16 +38,17 @@ HEADLINE_TRAFFIC_BYTES = 18_130_000
 BASE_SEED = {1: 0, 2: 1, 3: 2, 4: 3, 5: 4}
 
 
-def useful_bytes(wl, plan_off, sel_cnt):
+def useful_bytes(wl, plan_off, sel_cnt, vectors=1):
     """Algorithmic bytes of one step: what the method itself must move.
-    score : INT4 codes of every centroid (d/2 bytes each) + per-channel scales + queries
+    score : INT4 codes of every block (d/2 bytes per vector: one for mean pooling, two for
+            max-min pooling) + per-channel scales + queries
     select: the index list
     decode: K and V rows of the selected tokens + page-table entries touched + queries + outputs
     Intermediate arrays (int32 scores, split-K partials) are not counted."""
     d, e = wl.head_dim, 2
     nseg = wl.batch * wl.num_kv_heads
     total = int(plan_off[-1])
-    b_score = total * (d // 2) + nseg * d * 4 + wl.batch * wl.num_q_heads * d * e
+    b_score = vectors * (total * (d // 2) + nseg * d * 4) + wl.batch * wl.num_q_heads * d * e
     b_select = int(sel_cnt.sum()) * 4
     tokens = 0
     pt_entries = 0
@@ -93,7 +94,8 @@ def per_step_percentiles(fn, n_steps):
     return float(np.percentile(d, 10)), float(np.median(d)), float(np.percentile(d, 90))
 
 
-def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, uniform_block=None, max_bytes=24 << 30):
+def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, uniform_block=None, max_bytes=24 << 30,
+                   block_repr=0):
     """R independent layer instances of a workload, resident on the GPU, centroid stores built."""
     import torch
     from paper_2605_12110_amd import synth
@@ -104,10 +106,10 @@ def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, u
     if R <= 0:
         R = max(1, min(8, -(-(2 << 30) // wl0.kv_bytes())))
     R = max(1, min(R, max_bytes // max(wl0.kv_bytes(), 1)))
-    insts = [DeviceWorkload(wl0)]
+    insts = [DeviceWorkload(wl0, block_repr=block_repr)]
     for r in range(1, R):
         wl = synth.make_workload(config, seed=BASE_SEED[config] + 100 * r, **kw)
-        insts.append(DeviceWorkload(wl))
+        insts.append(DeviceWorkload(wl, block_repr=block_repr))
         wl.k_cache = wl.v_cache = None      # free the host copies of the extra instances
     for dw in insts:
         dw.build()
@@ -122,7 +124,7 @@ def measure(wl0, insts, steps, warmup, stages=False, percentiles=False):
     for dw in insts:        # one untimed step per instance: selection sizes for the byte count
         dw.decode_fused()
         torch.cuda.synchronize()
-        ub.append(useful_bytes(dw.wl, dw.plan.cent_off, dw.sel_cnt.cpu().numpy()))
+        ub.append(useful_bytes(dw.wl, dw.plan.cent_off, dw.sel_cnt.cpu().numpy(), dw.layer.block_repr + 1))
     mean_bytes = {k: float(np.mean([u[k] for u in ub])) for k in ub[0]}
 
     def step(i):
@@ -175,10 +177,10 @@ def _time_oracle(fn, seconds, max_n=2000):
             return el / n, n, el
 
 
-def cpu_baseline(wl0, bytes0, seconds=10.0):
+def cpu_baseline(wl0, bytes0, seconds=10.0, block_repr=0):
     from oracle import oracle as O
     t0 = time.perf_counter()
-    st = O.build_centroids(wl0)
+    st = O.build_centroids(wl0, block_repr)
     build_s = time.perf_counter() - t0
     O.decode_step(wl0, st)                       # warm
     cpu_s, n, el = _time_oracle(lambda: O.decode_step(wl0, st), seconds)
@@ -234,6 +236,24 @@ def run_matrix(args):
     del insts
     torch.cuda.empty_cache()
 
+    print("\nMax-min block representation (two INT4 vectors per block, twice the code stream), same workloads\n")
+    print("| workload | useful MB/step | us/step | GB/s | planted-token recall: max-min / mean |")
+    print("|---|---|---|---|---|", flush=True)
+    for cfg in (1, 2, 3, 4):
+        wl0, insts = make_instances(cfg, block_repr=1)
+        m = measure(wl0, insts, args.steps, args.warmup)
+        dw = insts[0]
+        dw.decode_fused()
+        torch.cuda.synchronize()
+        rec2 = O.planted_recall(wl0, dw.sel_idx.cpu().numpy(), dw.sel_cnt.cpu().numpy()) if wl0.planted else float("nan")
+        r1 = O.decode_step(wl0, O.build_centroids(wl0, O.MEAN))
+        rec1 = O.planted_recall(wl0, r1["sel_idx"], r1["sel_cnt"]) if wl0.planted else float("nan")
+        gb = m["bytes"]["total"] / (m["ms"] * 1e-3) / 1e9
+        print(f"| config {cfg} | {m['bytes']['total'] / 1e6:.1f} | {m['ms'] * 1e3:.1f} | {gb:.0f} | {rec2:.3f} / {rec1:.3f} |",
+              flush=True)
+        del insts, dw
+        torch.cuda.empty_cache()
+
     print(f"\nStreaming-read ceiling measured in this run (absb_stream_read, 2 GiB, 128-bit loads): "
           f"{stream_read_ceiling():.0f} GB/s of {HBM_PEAK_GBPS:.0f} GB/s published peak.")
     print("\nConfig 5 sweep (batch 4, context 65536, fp16): uniform block 16 vs adaptive per-head sizes\n")
@@ -272,6 +292,8 @@ def main():
     ap.add_argument("--context", type=int, default=None)
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--budget", type=int, default=None)
+    ap.add_argument("--repr", choices=("mean", "minmax"), default="mean",
+                    help="block representation: mean pooling (headline) or channel-wise maxima and minima")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also time each entry point on its own")
     ap.add_argument("--matrix", action="store_true", help="run all configurations and the config-5 sweep; markdown out")
@@ -303,15 +325,17 @@ def main():
         run_matrix(args)
         return
 
+    block_repr = 1 if args.repr == "minmax" else 0
     wl0, insts = make_instances(args.config, context=args.context, batch=args.batch, budget=args.budget,
-                                rotate=args.rotate)
+                                rotate=args.rotate, block_repr=block_repr)
     m = measure(wl0, insts, args.steps, args.warmup, stages=args.stages, percentiles=True)
     ms, mean_bytes, R = m["ms"], m["bytes"], m["R"]
     gbps = mean_bytes["total"] / (ms * 1e-3) / 1e9
     dec_gbps = mean_bytes["decode"] / (m["ms_decode"] * 1e-3) / 1e9
     ceiling = stream_read_ceiling()
     wl = wl0
-    headline = args.config == 3 and args.context is None and args.batch is None and args.budget is None
+    headline = (args.config == 3 and args.context is None and args.batch is None and args.budget is None
+                and block_repr == 0)
     result = {
         "metric": METRIC,
         "value": round(gbps, 2),
@@ -329,7 +353,8 @@ def main():
         "config": {
             "workload": f"config{args.config}: batch {wl.batch}, context {int(wl.seq_lens.max())}, "
                         f"{wl.num_q_heads}q/{wl.num_kv_heads}kv heads, d={wl.head_dim}, page {wl.page_size}, "
-                        f"block sizes {wl.block_size.tolist()}, budget {int(wl.budget.max())} tokens",
+                        f"block sizes {wl.block_size.tolist()}, budget {int(wl.budget.max())} tokens, "
+                        f"{args.repr} pooling",
             "entry_point": "absb_decode_fused",
             "layer_instances_rotated": R,
             "resident_kv_bytes": int(sum(i.k_cache.numel() * 2 * 2 for i in insts)),
@@ -357,7 +382,7 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl0, m["bytes0"])
+        result["cpu_baseline"] = cpu_baseline(wl0, m["bytes0"], block_repr=block_repr)
     print(json.dumps(result))
 
 

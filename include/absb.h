@@ -52,6 +52,14 @@ extern "C" {
 
 typedef enum absb_dtype { ABSB_F16 = 0, ABSB_BF16 = 1 } absb_dtype;
 
+/* How a block of keys is represented for the estimation stage (Sec. 2.2, footnote on pooling):
+ *   ABSB_REPR_MEAN   : the mean of the block's keys, scored by q . c^T (the paper's running example);
+ *   ABSB_REPR_MINMAX : the channel-wise maxima and minima of the block's keys (the max-min pooling
+ *                      of the baseline the paper's evaluation builds on, Sec. 4.1), scored by the
+ *                      channel-wise upper bound sum_c max(q_c * max_c, q_c * min_c) of q . k.
+ * R below is the number of vectors per block: 1 for MEAN, 2 for MINMAX (maxima first). */
+typedef enum absb_repr { ABSB_REPR_MEAN = 0, ABSB_REPR_MINMAX = 1 } absb_repr;
+
 typedef enum absb_status {
   ABSB_OK = 0,
   ABSB_ERR_NULL = -1,           /* a required pointer is NULL                                   */
@@ -70,7 +78,7 @@ typedef struct absb_layer {
   int32_t head_dim;          /* d; 128                                                          */
   int32_t page_size;         /* P tokens per physical page; power of two, >= 8                  */
   int32_t dtype;             /* absb_dtype of q, K, V and out                                   */
-  int32_t reserved0;
+  int32_t block_repr;        /* absb_repr; 0 = mean pooling                                     */
   const int32_t* block_size; /* host [Hkv]: B_h, power of two in [8,128]; B_h | P or P | B_h    */
   /* K/V cache addressing, in elements: element (page, head, slot, c) of either cache is at
      page*kv_stride_page + head*kv_stride_head + slot*kv_stride_tok + c (channels contiguous).
@@ -103,14 +111,15 @@ typedef struct absb_batch {
 ABSB_API int absb_plan(const absb_layer* layer, const absb_batch* batch, int32_t* cent_off_host,
                        int64_t* total_centroids, int32_t* sel_stride, size_t* workspace_bytes);
 
-/* Centroid store build (Sec. 2.2 mean pooling; Sec. 3.3 INT4 asymmetric per-channel; Sec. 3.4
- * flattened layout).  Reads every key of every request once.
+/* Centroid store build (Sec. 2.2 pooling; Sec. 3.3 INT4 asymmetric per-channel; Sec. 3.4
+ * flattened layout).  Reads every key of every request once.  With R vectors per block
+ * (see absb_repr) a block is a row of R*d values:
  *   k_cache          : paged K cache (layout above)
- *   codes [total][d/2] u8 : centroid j of segment s at byte (off[s]+j)*(d/2); byte i holds
- *                      channel 2i in its low nibble and channel 2i+1 in its high nibble
- *   qscale [Bt*Hkv][d] f32: per (segment, channel) step (max-min)/15 over that segment's centroids
- *   qmin   [Bt*Hkv][d] f32: per (segment, channel) minimum (the asymmetric zero-point offset)
- * A last block shorter than B_h is the mean of its valid keys.  Arithmetic is binary32 in a
+ *   codes [total][R*d/2] u8 : block j of segment s at byte (off[s]+j)*(R*d/2); byte i holds
+ *                      value 2i in its low nibble and value 2i+1 in its high nibble
+ *   qscale [Bt*Hkv][R*d] f32: per (segment, value) step (max-min)/15 over that segment's blocks
+ *   qmin   [Bt*Hkv][R*d] f32: per (segment, value) minimum (the asymmetric zero-point offset)
+ * A last block shorter than B_h is pooled over its valid keys.  Arithmetic is binary32 in a
  * fixed order (keys summed in token order, one division, round-half-even codes), so the codes
  * are reproducible bit for bit. */
 ABSB_API int absb_build_centroids(const absb_layer* layer, const absb_batch* batch, const void* k_cache,
@@ -123,6 +132,10 @@ ABSB_API int absb_build_centroids(const absb_layer* layer, const absb_batch* bat
  *                       (largest magnitude in [2^14, 2^15]) of w_c = (sum_g q_g[c]) * qscale[s][c].
  *                       Within a segment S_j ranks the blocks exactly as the dequantized
  *                       score does (the zero-point term is constant per segment).
+ *                       ABSB_REPR_MINMAX: the same over 2d weights, w = (P * qscale[s][0..d),
+ *                       Q * qscale[s][d..2d)), P_c / Q_c the sums of the group's positive /
+ *                       negative q_g[c]: the bound's larger product is the one whose extremum
+ *                       matches the sign of q_c, which keeps the group score linear in the codes.
  *   score_exp [Bt*Hkv] i32, optional (NULL ok): e with w ~= wq * 2^e */
 ABSB_API int absb_score(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
                         const float* qscale, int32_t* scores, int32_t* score_exp, void* stream);

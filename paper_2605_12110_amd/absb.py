@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libabsb.so")
 
 F16, BF16 = 0, 1
+REPR_MEAN, REPR_MINMAX = 0, 1
 TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO = 0, 1, 2
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
@@ -33,7 +34,7 @@ class AbsbError(RuntimeError):
 
 class _Layer(C.Structure):
     _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
-                ("page_size", C.c_int32), ("dtype", C.c_int32), ("reserved0", C.c_int32),
+                ("page_size", C.c_int32), ("dtype", C.c_int32), ("block_repr", C.c_int32),
                 ("block_size", C.POINTER(C.c_int32)),
                 ("kv_stride_page", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64),
                 ("sm_scale", C.c_float), ("reserved1", C.c_int32)]
@@ -113,6 +114,7 @@ class Layer:
     block_size: Sequence[int]
     kv_strides: Sequence[int]          # (page, head, token) in elements
     sm_scale: float = 0.0
+    block_repr: int = REPR_MEAN
 
     def __setattr__(self, name, value):
         object.__setattr__(self, name, value)
@@ -124,7 +126,8 @@ class Layer:
         if getattr(self, "_c", None) is None:
             self._bs, bs_p = _i32_host(self.block_size)
             sp, sh, st = (int(x) for x in self.kv_strides)
-            self._c = _Layer(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size, self.dtype, 0,
+            self._c = _Layer(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size, self.dtype,
+                             int(self.block_repr),
                              bs_p, sp, sh, st, float(self.sm_scale), 0)
         return self._c
 

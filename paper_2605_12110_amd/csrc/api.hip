@@ -31,6 +31,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   const int Hq = layer->num_q_heads, Hkv = layer->num_kv_heads;
   if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0) return ABSB_ERR_BAD_SHAPE;
   if (Hq / Hkv > ABSB_MAX_GROUP || Hkv > ABSB_MAX_KV_HEADS) return ABSB_ERR_UNSUPPORTED;
+  if (layer->block_repr != ABSB_REPR_MEAN && layer->block_repr != ABSB_REPR_MINMAX) return ABSB_ERR_UNSUPPORTED;
   const int P = layer->page_size;
   if (!is_pow2(P) || P < 8 || P > 65536) return ABSB_ERR_BAD_SHAPE;
   const int64_t sp = layer->kv_stride_page, sh = layer->kv_stride_head, st = layer->kv_stride_tok;
@@ -46,6 +47,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   g.G = Hq / Hkv;
   g.log2_page = ilog2(P);
   g.pt_stride = batch->pt_stride;
+  g.repr = layer->block_repr;
   g.s_page = sp;
   g.s_head = sh;
   g.s_tok = st;
@@ -132,11 +134,12 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   (void)fused_head;
   size_t bo = head;
   p.ws_cent = bo;
-  bo += align256((size_t)p.total * ABSB_HEAD_DIM * 4);
+  const size_t width = (size_t)ABSB_HEAD_DIM * (g.repr + 1);  // values per block
+  bo += align256((size_t)p.total * width * 4);
   p.ws_minmax = bo;
-  bo += align256((size_t)p.nseg * p.build_max_chunks * 2 * ABSB_HEAD_DIM * 4);
+  bo += align256((size_t)p.nseg * p.build_max_chunks * 2 * width * 4);
   p.ws_qinv = bo;
-  bo += align256((size_t)p.nseg * ABSB_HEAD_DIM * 4);
+  bo += align256((size_t)p.nseg * width * 4);
   p.ws_build_bytes = bo;
   p.ws_bytes = p.ws_fused_bytes > p.ws_build_bytes ? p.ws_fused_bytes : p.ws_build_bytes;
 

@@ -1,21 +1,25 @@
-// Centroid store build: block means (mean pooling, Sec. 2.2), per-channel asymmetric INT4
-// quantization (Sec. 3.3) and the flattened, prefix-sum-delimited code array (Sec. 3.4, kernel 1).
-// Runs once per context (prefill side), reads every key once.
+// Centroid store build: block pooling (mean pooling, or channel-wise maxima and minima: Sec. 2.2 and
+// its footnote), per-channel asymmetric INT4 quantization (Sec. 3.3) and the flattened,
+// prefix-sum-delimited code array (Sec. 3.4, kernel 1).  Runs once per context (prefill side), reads
+// every key once.
+//
+// A block is a row of W = 128 * R values: R = 1 the mean, R = 2 the maxima followed by the minima.
 //
 // Arithmetic is fixed so that the 4-bit codes are reproducible bit for bit: binary32 running sum
-// of a block's keys in token order, one IEEE division by the number of valid tokens, exact
-// min/max per (segment, channel), scale = (max-min)/15 and 15/(max-min) as two IEEE divisions,
-// code = clamp(round-half-even((c - min) * (15/(max-min)))).  Compiled with -ffp-contract=off.
+// of a block's keys in token order, one IEEE division by the number of valid tokens (extrema need
+// comparisons only), exact min/max per (segment, value), scale = (max-min)/15 and 15/(max-min) as two
+// IEEE divisions, code = clamp(round-half-even((c - min) * (15/(max-min)))).  Compiled with
+// -ffp-contract=off.
 //
 // Three launches:
-//   1. means: a work-group owns `chunk_tokens` consecutive tokens of a segment (a power-of-two number
+//   1. pool: a work-group owns `chunk_tokens` consecutive tokens of a segment (a power-of-two number
 //      of whole blocks, at least one per 16-lane row-group), so work per group is the same for every
 //      block size.  A row-group (each lane 8 channels = one 128-bit load per key) streams its 64+
-//      consecutive tokens eight rows at a time, the next eight in flight while these are summed,
+//      consecutive tokens eight rows at a time, the next eight in flight while these are pooled,
 //      closes a block whenever the running token index reaches a block boundary, writes the binary32
-//      centroid to the workspace and folds it into per-work-group channel minima/maxima;
+//      row to the workspace and folds it into per-work-group minima/maxima per value;
 //   2. params: reduces the partial extrema per segment and writes qscale, qmin (and 15/range);
-//   3. codes: quantizes the centroids, eight channels per lane packed into one 32-bit store.
+//   3. codes: quantizes the rows, eight values per lane packed into one 32-bit store.
 #include "common.h"
 
 namespace absb {
@@ -25,12 +29,12 @@ struct BuildParams {
   const int32_t* page_table;
   const int32_t* seq_lens;
   const int32_t* cent_off;
-  float* cent;     // [total][128]
-  float* minmax;   // [nseg][max_chunks][2][128]
-  float* qinv;     // [nseg][128]
-  float* qscale;   // [nseg][128]
-  float* qmin;     // [nseg][128]
-  uint8_t* codes;  // [total][64]
+  float* cent;     // [total][W]
+  float* minmax;   // [nseg][max_chunks][2][W]
+  float* qinv;     // [nseg][W]
+  float* qscale;   // [nseg][W]
+  float* qmin;     // [nseg][W]
+  uint8_t* codes;  // [total][W/2]
   int32_t chunk_tokens, max_chunks;
   Geometry g;
 };
@@ -44,8 +48,9 @@ __device__ __forceinline__ int build_chunk_blocks(int chunk_tokens, int lb) {
   return max(BUILD_GROUPS, chunk_tokens >> lb);
 }
 
-template <int DT>
-__global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams p) {
+template <int DT, int REP>
+__global__ __launch_bounds__(BUILD_THREADS) void build_pool_kernel(BuildParams p) {
+  constexpr int W = ABSB_HEAD_DIM * (REP + 1);
   const int s = blockIdx.y, chunk = blockIdx.x;
   const int off = p.cent_off[s];
   const int N = p.cent_off[s + 1] - off;
@@ -61,12 +66,15 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams 
   const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
   const size_t lane_off = (size_t)h * p.g.s_head + (size_t)li * 8;
 
-  float mn[8], mx[8];
+  // running extrema over this row-group's blocks, per vector of the row (v = 0: mean or maxima, 1: minima)
+  float mn[REP + 1][8], mx[REP + 1][8];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    mn[c] = __builtin_inff();
-    mx[c] = -__builtin_inff();
-  }
+  for (int v = 0; v <= REP; ++v)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      mn[v][c] = __builtin_inff();
+      mx[v][c] = -__builtin_inff();
+    }
 
   // this row-group's blocks [ja, jb) = consecutive tokens [tA, tB)
   const int per = cb / BUILD_GROUPS;
@@ -88,9 +96,16 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams 
     for (int r = 0; r < BUILD_ROWS; ++r) nxt[r] = cur[r];
     const uint16_t* base_next = row_base(min(tA + BUILD_ROWS, tB - 1));
 
-    float sum[8];
+    // the open block: its running sum (mean pooling) or its maxima / minima so far
+    float acc[REP + 1][8];
+    auto reset = [&]() {
 #pragma unroll
-    for (int c = 0; c < 8; ++c) sum[c] = 0.0f;
+      for (int c = 0; c < 8; ++c) {
+        acc[0][c] = REP ? -__builtin_inff() : 0.0f;
+        if (REP) acc[REP][c] = __builtin_inff();
+      }
+    };
+    reset();
     for (int i = tA; i < tB; i += BUILD_ROWS) {
       const int in = i + BUILD_ROWS;
       if (in < tB) {
@@ -105,58 +120,74 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_means_kernel(BuildParams 
           const uint32_t w[4] = {cur[r].x, cur[r].y, cur[r].z, cur[r].w};
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
-            sum[2 * c] = sum[2 * c] + Elem<DT>::lo(w[c]);
-            sum[2 * c + 1] = sum[2 * c + 1] + Elem<DT>::hi(w[c]);
+            const float lo = Elem<DT>::lo(w[c]), hi = Elem<DT>::hi(w[c]);
+            if (REP) {
+              acc[0][2 * c] = fmaxf(acc[0][2 * c], lo);
+              acc[0][2 * c + 1] = fmaxf(acc[0][2 * c + 1], hi);
+              acc[REP][2 * c] = fminf(acc[REP][2 * c], lo);
+              acc[REP][2 * c + 1] = fminf(acc[REP][2 * c + 1], hi);
+            } else {
+              acc[0][2 * c] = acc[0][2 * c] + lo;
+              acc[0][2 * c + 1] = acc[0][2 * c + 1] + hi;
+            }
           }
         }
       }
       if ((in & (B - 1)) == 0 || in >= tB) {  // the block that holds token i is complete
         const int j = i >> lb;
         const float fn = (float)min(B, L - (j << lb));
-        float cen[8];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          cen[c] = sum[c] / fn;
-          mn[c] = fminf(mn[c], cen[c]);
-          mx[c] = fmaxf(mx[c], cen[c]);
-          sum[c] = 0.0f;
+        for (int v = 0; v <= REP; ++v) {
+          float val[8];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) {
+            val[c] = REP ? acc[v][c] : acc[v][c] / fn;
+            mn[v][c] = fminf(mn[v][c], val[c]);
+            mx[v][c] = fmaxf(mx[v][c], val[c]);
+          }
+          float4* dst = reinterpret_cast<float4*>(p.cent + ((size_t)off + j) * W + v * ABSB_HEAD_DIM + li * 8);
+          dst[0] = make_float4(val[0], val[1], val[2], val[3]);
+          dst[1] = make_float4(val[4], val[5], val[6], val[7]);
         }
-        float4* dst = reinterpret_cast<float4*>(p.cent + ((size_t)off + j) * ABSB_HEAD_DIM + li * 8);
-        dst[0] = make_float4(cen[0], cen[1], cen[2], cen[3]);
-        dst[1] = make_float4(cen[4], cen[5], cen[6], cen[7]);
+        reset();
       }
 #pragma unroll
       for (int r = 0; r < BUILD_ROWS; ++r) cur[r] = nxt[r];
     }
   }
 
-  // fold the 16 row-groups: channel ch = li*8 + c
-  __shared__ float s_mn[BUILD_GROUPS][ABSB_HEAD_DIM], s_mx[BUILD_GROUPS][ABSB_HEAD_DIM];
+  // fold the 16 row-groups: value index = v*128 + li*8 + c
+  __shared__ float s_mn[BUILD_GROUPS][W], s_mx[BUILD_GROUPS][W];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    s_mn[grp][li * 8 + c] = mn[c];
-    s_mx[grp][li * 8 + c] = mx[c];
-  }
+  for (int v = 0; v <= REP; ++v)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      s_mn[grp][v * ABSB_HEAD_DIM + li * 8 + c] = mn[v][c];
+      s_mx[grp][v * ABSB_HEAD_DIM + li * 8 + c] = mx[v][c];
+    }
   __syncthreads();
-  if (tid < ABSB_HEAD_DIM) {
+  if (tid < W) {
     float a = s_mn[0][tid], z = s_mx[0][tid];
 #pragma unroll
     for (int g2 = 1; g2 < BUILD_GROUPS; ++g2) {
       a = fminf(a, s_mn[g2][tid]);
       z = fmaxf(z, s_mx[g2][tid]);
     }
-    float* dst = p.minmax + ((size_t)s * p.max_chunks + chunk) * 2 * ABSB_HEAD_DIM;
+    float* dst = p.minmax + ((size_t)s * p.max_chunks + chunk) * 2 * W;
     dst[tid] = a;
-    dst[ABSB_HEAD_DIM + tid] = z;
+    dst[W + tid] = z;
   }
 }
 
-// One work-group per segment: 128 channels x 8 chunk lanes, min/max are exact in any order.
+// One work-group per (segment, vector of the row): 128 values x 8 chunk lanes; min/max are exact
+// in any order.
 constexpr int PARAMS_THREADS = 1024;
 constexpr int PARAMS_LANES = PARAMS_THREADS / ABSB_HEAD_DIM;
 
 __global__ __launch_bounds__(PARAMS_THREADS) void build_params_kernel(BuildParams p) {
-  const int s = blockIdx.x, ch = threadIdx.x & (ABSB_HEAD_DIM - 1), cl = threadIdx.x / ABSB_HEAD_DIM;
+  const int W = ABSB_HEAD_DIM * (p.g.repr + 1);
+  const int s = blockIdx.x, cl = threadIdx.x / ABSB_HEAD_DIM;
+  const int ch = blockIdx.y * ABSB_HEAD_DIM + (threadIdx.x & (ABSB_HEAD_DIM - 1));  // value index in the row
   const int h = s % p.g.Hkv;
   const int N = p.cent_off[s + 1] - p.cent_off[s];
   const int cb = build_chunk_blocks(p.chunk_tokens, p.g.heads.log2_block[h]);
@@ -167,9 +198,9 @@ __global__ __launch_bounds__(PARAMS_THREADS) void build_params_kernel(BuildParam
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = min(i0 + u * PARAMS_LANES, nchunks - 1);  // the tail repeats a chunk: harmless for min/max
-      const float* src = p.minmax + ((size_t)s * p.max_chunks + i) * 2 * ABSB_HEAD_DIM;
+      const float* src = p.minmax + ((size_t)s * p.max_chunks + i) * 2 * W;
       a[u] = src[ch];
-      z[u] = src[ABSB_HEAD_DIM + ch];
+      z[u] = src[W + ch];
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -178,14 +209,15 @@ __global__ __launch_bounds__(PARAMS_THREADS) void build_params_kernel(BuildParam
     }
   }
   __shared__ float s_mn[PARAMS_LANES][ABSB_HEAD_DIM], s_mx[PARAMS_LANES][ABSB_HEAD_DIM];
-  s_mn[cl][ch] = mn;
-  s_mx[cl][ch] = mx;
+  const int c = threadIdx.x & (ABSB_HEAD_DIM - 1);
+  s_mn[cl][c] = mn;
+  s_mx[cl][c] = mx;
   __syncthreads();
   if (cl != 0) return;
 #pragma unroll
   for (int k = 1; k < PARAMS_LANES; ++k) {
-    mn = fminf(mn, s_mn[k][ch]);
-    mx = fmaxf(mx, s_mx[k][ch]);
+    mn = fminf(mn, s_mn[k][c]);
+    mx = fmaxf(mx, s_mx[k][c]);
   }
   const float rng = mx - mn;
   float sc = 0.0f, inv = 0.0f;
@@ -194,13 +226,15 @@ __global__ __launch_bounds__(PARAMS_THREADS) void build_params_kernel(BuildParam
     inv = 15.0f / rng;
   }
   if (N == 0) mn = 0.0f;
-  p.qscale[(size_t)s * ABSB_HEAD_DIM + ch] = sc;
-  p.qmin[(size_t)s * ABSB_HEAD_DIM + ch] = mn;
-  p.qinv[(size_t)s * ABSB_HEAD_DIM + ch] = inv;
+  p.qscale[(size_t)s * W + ch] = sc;
+  p.qmin[(size_t)s * W + ch] = mn;
+  p.qinv[(size_t)s * W + ch] = inv;
 }
 
+// grid (chunk, segment, vector of the row)
 __global__ __launch_bounds__(BUILD_THREADS) void build_codes_kernel(BuildParams p) {
-  const int s = blockIdx.y;
+  const int W = ABSB_HEAD_DIM * (p.g.repr + 1);
+  const int s = blockIdx.y, v = blockIdx.z;
   const int off = p.cent_off[s];
   const int N = p.cent_off[s + 1] - off;
   const int cb = build_chunk_blocks(p.chunk_tokens, p.g.heads.log2_block[s % p.g.Hkv]);
@@ -208,14 +242,15 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_codes_kernel(BuildParams 
   if (j0 >= N) return;
   const int jend = min(N, j0 + cb);
   const int tid = threadIdx.x, grp = tid >> 4, li = tid & 15;
+  const int col = v * ABSB_HEAD_DIM + li * 8;  // first of this lane's eight values in the row
   float mn[8], inv[8];
 #pragma unroll
   for (int c = 0; c < 8; ++c) {
-    mn[c] = p.qmin[(size_t)s * ABSB_HEAD_DIM + li * 8 + c];
-    inv[c] = p.qinv[(size_t)s * ABSB_HEAD_DIM + li * 8 + c];
+    mn[c] = p.qmin[(size_t)s * W + col + c];
+    inv[c] = p.qinv[(size_t)s * W + col + c];
   }
   for (int j = j0 + grp; j < jend; j += BUILD_GROUPS) {
-    const float4* src = reinterpret_cast<const float4*>(p.cent + ((size_t)off + j) * ABSB_HEAD_DIM + li * 8);
+    const float4* src = reinterpret_cast<const float4*>(p.cent + ((size_t)off + j) * W + col);
     const float4 a = src[0], z = src[1];
     const float cen[8] = {a.x, a.y, a.z, a.w, z.x, z.y, z.z, z.w};
     uint32_t packed = 0;
@@ -227,9 +262,9 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_codes_kernel(BuildParams 
       r = fminf(fmaxf(r, 0.0f), 15.0f);
       packed |= (uint32_t)r << (4 * c);
     }
-    // byte i of a centroid holds channel 2i (low nibble) and 2i+1 (high nibble): little-endian
-    // nibble n of this word is channel li*8 + n
-    *reinterpret_cast<uint32_t*>(p.codes + ((size_t)off + j) * 64 + li * 4) = packed;
+    // byte i of a row holds value 2i (low nibble) and 2i+1 (high nibble): little-endian nibble n
+    // of this word is value col + n
+    *reinterpret_cast<uint32_t*>(p.codes + ((size_t)off + j) * (W / 2) + col / 2) = packed;
   }
 }
 
@@ -250,17 +285,22 @@ int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cac
   p.chunk_tokens = pl.build_chunk_tokens;
   p.max_chunks = pl.build_max_chunks;
   p.g = g;
-  dim3 grid((unsigned)pl.build_max_chunks, (unsigned)pl.nseg);
-  if (dtype == ABSB_F16)
-    hipLaunchKernelGGL(build_means_kernel<ABSB_F16>, grid, dim3(BUILD_THREADS), 0, stream, p);
+  const unsigned R = (unsigned)g.repr + 1;
+  const dim3 grid((unsigned)pl.build_max_chunks, (unsigned)pl.nseg), block(BUILD_THREADS);
+  if (dtype == ABSB_F16 && g.repr == ABSB_REPR_MEAN)
+    hipLaunchKernelGGL((build_pool_kernel<ABSB_F16, 0>), grid, block, 0, stream, p);
+  else if (dtype == ABSB_F16)
+    hipLaunchKernelGGL((build_pool_kernel<ABSB_F16, 1>), grid, block, 0, stream, p);
+  else if (g.repr == ABSB_REPR_MEAN)
+    hipLaunchKernelGGL((build_pool_kernel<ABSB_BF16, 0>), grid, block, 0, stream, p);
   else
-    hipLaunchKernelGGL(build_means_kernel<ABSB_BF16>, grid, dim3(BUILD_THREADS), 0, stream, p);
+    hipLaunchKernelGGL((build_pool_kernel<ABSB_BF16, 1>), grid, block, 0, stream, p);
   int rc = check_launch();
   if (rc != ABSB_OK) return rc;
-  hipLaunchKernelGGL(build_params_kernel, dim3((unsigned)pl.nseg), dim3(PARAMS_THREADS), 0, stream, p);
+  hipLaunchKernelGGL(build_params_kernel, dim3((unsigned)pl.nseg, R), dim3(PARAMS_THREADS), 0, stream, p);
   rc = check_launch();
   if (rc != ABSB_OK) return rc;
-  hipLaunchKernelGGL(build_codes_kernel, grid, dim3(BUILD_THREADS), 0, stream, p);
+  hipLaunchKernelGGL(build_codes_kernel, dim3(grid.x, grid.y, R), block, 0, stream, p);
   return check_launch();
 }
 

@@ -23,6 +23,8 @@ struct Geometry {
   int32_t Bt, Hq, Hkv, G;
   int32_t log2_page;  // P = 1 << log2_page
   int32_t pt_stride;
+  int32_t repr;       // absb_repr: vectors per block = repr + 1
+  int32_t pad_;
   int64_t s_page, s_head, s_tok;  // element strides of the K/V caches
   HeadTable heads;
 };

@@ -20,14 +20,16 @@ def _up(a: np.ndarray, dtype=None, device="cuda:0"):
 class DeviceWorkload:
     """Everything one layer's decode step needs, resident on the GPU."""
 
-    def __init__(self, wl, device: str = "cuda:0", budget: Optional[np.ndarray] = None):
+    def __init__(self, wl, device: str = "cuda:0", budget: Optional[np.ndarray] = None,
+                 block_repr: int = absb.REPR_MEAN):
         self.wl = wl
         self.device = device
         tdt = torch.float16 if wl.dtype == absb.F16 else torch.bfloat16
         self.torch_dtype = tdt
         budget = wl.budget if budget is None else np.asarray(budget, dtype=np.int32)
         self.layer = absb.Layer(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.dtype,
-                                wl.block_size, wl.strides)
+                                wl.block_size, wl.strides, block_repr=block_repr)
+        width = wl.head_dim * (2 if block_repr == absb.REPR_MINMAX else 1)      # values per block
         self.k_cache = _up(wl.k_cache.view(np.int16), tdt, device)
         self.v_cache = _up(wl.v_cache.view(np.int16), tdt, device)
         self.q = _up(wl.q.view(np.int16), tdt, device)
@@ -42,9 +44,9 @@ class DeviceWorkload:
         nseg = wl.batch * wl.num_kv_heads
         self.nseg = nseg
         total = self.plan.total_centroids
-        self.codes = torch.empty((total, wl.head_dim // 2), dtype=torch.uint8, device=device)
-        self.qscale = torch.empty((nseg, wl.head_dim), dtype=torch.float32, device=device)
-        self.qmin = torch.empty((nseg, wl.head_dim), dtype=torch.float32, device=device)
+        self.codes = torch.empty((total, width // 2), dtype=torch.uint8, device=device)
+        self.qscale = torch.empty((nseg, width), dtype=torch.float32, device=device)
+        self.qmin = torch.empty((nseg, width), dtype=torch.float32, device=device)
         self.scores = torch.empty((total,), dtype=torch.int32, device=device)
         self.score_exp = torch.empty((nseg,), dtype=torch.int32, device=device)
         self.sel_stride = max(self.plan.sel_stride, 1)

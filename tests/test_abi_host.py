@@ -61,6 +61,15 @@ def test_plan_matches_the_papers_layout_rules():
     assert np.array_equal(O.offsets(wl), plan.cent_off.astype(np.int64))
 
 
+def test_plan_sizes_the_build_scratch_for_two_vectors_per_block_with_max_min_pooling():
+    lens = (131072,)
+    one = absb.absb_plan(_layer(), _batch(lens, (64,)))
+    two = absb.absb_plan(_layer(block_repr=absb.REPR_MINMAX), _batch(lens, (64,)))
+    assert np.array_equal(one.cent_off, two.cent_off) and one.sel_stride == two.sel_stride
+    # the build's binary32 rows dominate the workspace here: 512 B per block and vector
+    assert two.workspace_bytes - one.workspace_bytes >= one.total_centroids * 512
+
+
 def test_plan_without_budget_sizes_for_every_block():
     plan = absb.absb_plan(_layer(), _batch((4096,), None))
     assert plan.sel_stride == 4096 // 8
@@ -69,6 +78,8 @@ def test_plan_without_budget_sizes_for_every_block():
 @pytest.mark.parametrize("kw,status", [
     (dict(head_dim=64), absb.ERR_UNSUPPORTED),
     (dict(dtype=7), absb.ERR_UNSUPPORTED),
+    (dict(block_repr=2), absb.ERR_UNSUPPORTED),
+    (dict(block_repr=-1), absb.ERR_UNSUPPORTED),
     (dict(num_q_heads=30), absb.ERR_BAD_SHAPE),
     (dict(num_q_heads=128), absb.ERR_UNSUPPORTED),            # group of 16
     (dict(num_q_heads=0), absb.ERR_BAD_SHAPE),

@@ -48,15 +48,15 @@ def _check_out(dw, want_out, want_lse, what):
     assert np.array_equal(np.isneginf(lse), np.isneginf(want_lse))
 
 
-def run_all_stages(wl, name):
+def run_all_stages(wl, name, block_repr=O.MEAN):
     """Stage by stage (each GPU stage fed the oracle's inputs), then the fused call end to end."""
-    _say(f"[case {name}] Bt={wl.batch} Hq={wl.num_q_heads} Hkv={wl.num_kv_heads} P={wl.page_size} "
+    _say(f"[case {name}] repr={block_repr} Bt={wl.batch} Hq={wl.num_q_heads} Hkv={wl.num_kv_heads} P={wl.page_size} "
          f"L={wl.seq_lens.tolist()[:4]}.. B={wl.block_size.tolist()} T={wl.budget.tolist()[:4]}.. dtype={wl.dtype}")
     t0 = time.time()
-    st = O.build_centroids(wl)
+    st = O.build_centroids(wl, block_repr)
     ref = O.decode_step(wl, st, sel_stride=None)
     _say(f"    oracle: build+step {time.time() - t0:.2f}s, centroids={int(st.off[-1])}")
-    dw = _dev(wl)
+    dw = _dev(wl, block_repr=block_repr)      # the two enumerations agree: 0 mean, 1 maxima and minima
     assert np.array_equal(dw.plan.cent_off.astype(np.int64), st.off)
     K = dw.sel_stride
     assert K == int(ref["sel_cnt"].max())
@@ -361,3 +361,30 @@ def test_selection_at_the_largest_supported_segment(kind):
     want_idx, want_cnt = O.topk_raw(1, 2, off, B, T, sc, stride)
     assert np.array_equal(sel_cnt.cpu().numpy(), want_cnt) and want_cnt.tolist() == [20000, 10000]
     assert np.array_equal(sel_idx.cpu().numpy(), want_idx)
+
+
+# ------------------------------------------------------------------ max-min block representation
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_minmax_ragged_small_batch(dtype):
+    wl = synth.tiny_workload(seed=41, dtype=dtype, Bt=3, Hq=8, Hkv=2, P=16, seq_lens=(37, 64, 1301),
+                             block_size=(8, 32), budget=(16, 24, 400))
+    run_all_stages(wl, f"max-min ragged dtype={dtype}", O.MINMAX)
+
+
+@pytest.mark.parametrize("G", [1, 5, 8])
+def test_minmax_group_sizes_and_blocks_larger_than_a_page(G):
+    wl = synth.tiny_workload(seed=42 + G, dtype=synth.BF16, Bt=2, Hq=4 * G, Hkv=4, P=16, seq_lens=(999, 2500),
+                             block_size=(128, 8, 64, 16), budget=(300, 520))
+    run_all_stages(wl, f"max-min G={G}, B>P", O.MINMAX)
+
+
+def test_minmax_config1_full():
+    run_all_stages(synth.make_workload(1), "max-min config1", O.MINMAX)
+
+
+def test_minmax_config3_full_headline():
+    run_all_stages(synth.make_workload(3), "max-min config3 (headline shape)", O.MINMAX)
+
+
+def test_minmax_config4_scaled_mixed_lengths():
+    run_all_stages(synth.make_workload(4, context=16384, batch=5), "max-min config4 (<=16K ctx, batch 5)", O.MINMAX)
