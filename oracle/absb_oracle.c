@@ -525,3 +525,27 @@ void orc_attention_recall(int dtype, int Bt, int Hq, int Hkv, int d, int P, int6
         free(picked);
     }
 }
+
+/* ---- offline calibration (Sec. 3.2, Eq. (2)): per head the largest candidate block size whose
+ * recall keeps at least the share tau of the recall at the smallest candidate,
+ *   B*_h = max { B : Recall(h, B) >= tau * Recall(h, B_min) }.
+ * recall[i][h][k] is the attention recall of head h on calibration sample i with candidate k
+ * (candidates ascending, cand[0] = B_min); Recall(h, B) is its mean over the samples, taken in
+ * binary64 in sample order.  The set is read literally: a larger candidate that passes wins even
+ * if a smaller one in between fails.  mean_out [nh][nB] (may be NULL) receives the means. */
+void orc_assign_block_sizes(int n_samples, int nh, int nB, const double *recall, const int32_t *cand, double tau,
+                            int32_t *block_size /* [nh] */, double *mean_out) {
+    for (int h = 0; h < nh; ++h) {
+        double base = 0.0;
+        int best = 0;
+        for (int k = 0; k < nB; ++k) {
+            double acc = 0.0;
+            for (int i = 0; i < n_samples; ++i) acc += recall[((int64_t)i * nh + h) * nB + k];
+            double mean = acc / (double)n_samples;
+            if (mean_out) mean_out[(int64_t)h * nB + k] = mean;
+            if (k == 0) base = mean;
+            if (mean >= tau * base) best = k;
+        }
+        block_size[h] = cand[best];
+    }
+}

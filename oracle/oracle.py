@@ -218,6 +218,25 @@ def attention_recall(wl, sel_idx, sel_cnt, sm_scale: Optional[float] = None):
     return rec
 
 
+def head_recall(wl, sel_idx, sel_cnt, sm_scale: Optional[float] = None) -> np.ndarray:
+    """Attention recall per (request, KV head): the mean over the group's query heads."""
+    rec = attention_recall(wl, sel_idx, sel_cnt, sm_scale)
+    return rec.reshape(wl.batch, wl.num_kv_heads, wl.group).mean(axis=2)
+
+
+def assign_block_sizes(recall, candidates, tau: float):
+    """Eq. (2).  recall [n_samples, n_heads, n_candidates] -> (block size per head, mean recall [heads, cands])."""
+    recall = np.ascontiguousarray(recall, dtype=np.float64)
+    n, nh, nB = recall.shape
+    cand = _i32(candidates)
+    assert len(cand) == nB and np.all(np.diff(cand) > 0)
+    out = np.empty(nh, np.int32)
+    mean = np.empty((nh, nB), np.float64)
+    lib().orc_assign_block_sizes(C.c_int(n), C.c_int(nh), C.c_int(nB), _p(recall), _p(cand), C.c_double(tau),
+                                 _p(out), _p(mean))
+    return out, mean
+
+
 def planted_recall(wl, sel_idx, sel_cnt) -> float:
     """Fraction of the generator's planted heavy tokens whose block was selected (diagnostic)."""
     hit = tot = 0
