@@ -282,6 +282,45 @@ def run_matrix(args):
     return rows
 
 
+def run_calibration(args):
+    """Sec. 3.2 on synthetic inputs: calibrate per-head block sizes on one set of samples, then compare
+    the recall of the assignment with uniform sizes on held-out samples (markdown out)."""
+    import torch
+    from paper_2605_12110_amd import absb, calibrate, synth
+    cand = calibrate.DEFAULT_CANDIDATES
+    roles = (1, 1, 4, 4, 16, 16, 64, 64)          # run length of the heavy tokens per KV head: fixed head roles
+    L, T = 32768, 1024
+
+    def sample(seed):
+        return synth.make_workload(5, batch=1, context=L, budget=T, seed=seed, run_lengths=roles)
+
+    print(f"Calibration inputs: config-5 recipe, batch 1, context {L}, budget {T} tokens, fp16; heavy tokens of KV head h "
+          f"sit in runs of {list(roles)} consecutive positions in every sample (head roles are a property of the "
+          f"'model'); 8 calibration samples (seeds 300-307), 4 held-out samples (seeds 400-403).\n")
+    t0 = time.perf_counter()
+    per_sample = np.stack([calibrate.measure_recall(sample(300 + i), cand) for i in range(8)])
+    torch.cuda.synchronize()
+    print(f"Recall(h, B), mean over the calibration samples ({time.perf_counter() - t0:.1f} s for 8 samples x "
+          f"{len(cand)} candidates, generation included):\n")
+    _, mean = absb.absb_assign_block_sizes(per_sample, cand, 1.0)
+    print("| KV head (run length) | " + " | ".join(f"B={b}" for b in cand) + " |")
+    print("|---|" + "---|" * len(cand))
+    for h in range(8):
+        print(f"| {h} ({roles[h]}) | " + " | ".join(f"{mean[h, k]:.3f}" for k in range(len(cand))) + " |")
+    held = np.stack([calibrate.measure_recall(sample(400 + i), cand) for i in range(4)]).mean(axis=0)   # [Hkv, cand]
+    print("\nEq. (2) assignments and their recall on the held-out samples (mean over heads), against uniform sizes:\n")
+    print("| assignment | block sizes | mean block size | blocks per 1K tokens (mean over heads) | held-out recall |")
+    print("|---|---|---|---|---|")
+    for k, b in enumerate(cand):
+        print(f"| uniform | {b} | {b} | {1024 / b:.1f} | {held[:, k].mean():.3f} |")
+    for tau in (0.98, 0.9, 0.8, 0.7, 0.6):
+        sizes, _ = absb.absb_assign_block_sizes(per_sample, cand, tau)
+        idx = [cand.index(int(s)) for s in sizes]
+        rec = float(np.mean([held[h, idx[h]] for h in range(8)]))
+        print(f"| Eq. (2), tau = {tau} | {sizes.tolist()} | {float(np.mean(sizes)):.1f} | "
+              f"{float(np.mean(1024 / sizes)):.1f} | {rec:.3f} |", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -297,6 +336,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also time each entry point on its own")
     ap.add_argument("--matrix", action="store_true", help="run all configurations and the config-5 sweep; markdown out")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="per-head block-size calibration (Eq. 2) on synthetic samples, with held-out validation; markdown out")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="run one device-to-device copy of this many MiB first (a kernel of known traffic, for "
                          "scaling hardware byte counters collected with rocprofv3 --pmc)")
@@ -323,6 +364,9 @@ def main():
 
     if args.matrix:
         run_matrix(args)
+        return
+    if args.calibrate:
+        run_calibration(args)
         return
 
     block_repr = 1 if args.repr == "minmax" else 0

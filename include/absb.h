@@ -171,6 +171,24 @@ ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
                                int32_t* sel_cnt_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Offline calibration of the per-head block sizes (Sec. 3.2).  Two pieces; the loop over
+ * calibration samples and candidate sizes around them uses the entry points above.
+ *
+ * absb_head_recall: attention recall (Sec. 2.3) of a selection per (request, KV head), from two
+ * log-sum-exp arrays of the same queries over the same cache: `lse_selected` as written by
+ * absb_sparse_decode / absb_decode_fused for the selection, `lse_dense` as written by the same
+ * entry points with a budget >= the context length.  recall[s] = mean over the group's query heads
+ * of exp(lse_selected - lse_dense).  All three device arrays: lse [Bt][Hq] f32, recall [Bt*Hkv] f32.
+ *
+ * absb_assign_block_sizes (host only, no device work): Eq. (2).  recall_host
+ * [n_samples][n_heads][n_cand] f32 holds Recall(h, B) per calibration sample, candidates ascending
+ * (cand[0] = B_min); block_size_out[h] = the largest candidate whose mean recall over the samples is
+ * >= tau * the mean recall at B_min.  mean_out [n_heads][n_cand] f64 (NULL ok) receives the means. */
+ABSB_API int absb_head_recall(const absb_layer* layer, const absb_batch* batch, const float* lse_selected,
+                              const float* lse_dense, float* recall, void* stream);
+ABSB_API int absb_assign_block_sizes(int32_t n_samples, int32_t n_heads, int32_t n_cand, const float* recall_host,
+                                     const int32_t* cand, double tau, int32_t* block_size_out, double* mean_out);
+
 /* Measurement helper, not a step of the method: reads `bytes` (a multiple of 16; the tail is
  * ignored) of the device buffer `src` (16-byte aligned) once with 128-bit loads and discards them.
  * Timing it gives the practical streaming-read ceiling of the device, against which the attention

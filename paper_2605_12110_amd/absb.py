@@ -23,7 +23,8 @@ TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO = 0, 1, 2
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("absb_plan", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
-           "absb_decode_fused", "absb_stream_read", "absb_strerror", "absb_set_tuning")
+           "absb_decode_fused", "absb_head_recall", "absb_assign_block_sizes", "absb_stream_read",
+           "absb_strerror", "absb_set_tuning")
 
 
 class AbsbError(RuntimeError):
@@ -217,6 +218,26 @@ def absb_decode_fused(layer: Layer, batch: Batch, q, codes, qscale, k_cache, v_c
                                     _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(sel_idx_out), _ptr(sel_cnt_out),
                                     _ptr(workspace), C.c_size_t(_nbytes(workspace)), _stream(stream)),
            "absb_decode_fused")
+
+
+def absb_head_recall(layer: Layer, batch: Batch, lse_selected, lse_dense, recall, stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_head_recall(C.byref(cl), C.byref(cb), _ptr(lse_selected), _ptr(lse_dense), _ptr(recall),
+                                   _stream(stream)), "absb_head_recall")
+
+
+def absb_assign_block_sizes(recall: np.ndarray, candidates: Sequence[int], tau: float):
+    """recall [n_samples, n_heads, n_cand] f32 (host) -> (block size per head, mean recall [heads, cands])."""
+    rec = np.ascontiguousarray(recall, dtype=np.float32)
+    n, nh, nc = rec.shape
+    cand = np.ascontiguousarray(candidates, dtype=np.int32)
+    out = np.empty(nh, np.int32)
+    mean = np.empty((nh, nc), np.float64)
+    _check(load().absb_assign_block_sizes(C.c_int32(n), C.c_int32(nh), C.c_int32(nc),
+                                          rec.ctypes.data_as(C.c_void_p), cand.ctypes.data_as(C.c_void_p),
+                                          C.c_double(tau), out.ctypes.data_as(C.c_void_p),
+                                          mean.ctypes.data_as(C.c_void_p)), "absb_assign_block_sizes")
+    return out, mean
 
 
 def absb_stream_read(src, sink, stream=None) -> None:

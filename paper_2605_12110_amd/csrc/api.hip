@@ -270,6 +270,40 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
                        batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, true, st);
 }
 
+int absb_head_recall(const absb_layer* layer, const absb_batch* batch, const float* lse_selected,
+                     const float* lse_dense, float* recall, void* stream) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!lse_selected || !lse_dense || !recall) return ABSB_ERR_NULL;
+  return launch_head_recall(lse_selected, lse_dense, recall, p.nseg, g.G, static_cast<hipStream_t>(stream));
+}
+
+int absb_assign_block_sizes(int32_t n_samples, int32_t n_heads, int32_t n_cand, const float* recall_host,
+                            const int32_t* cand, double tau, int32_t* block_size_out, double* mean_out) {
+  if (!recall_host || !cand || !block_size_out) return ABSB_ERR_NULL;
+  if (n_samples < 1 || n_heads < 1 || n_cand < 1 || !(tau >= 0.0)) return ABSB_ERR_BAD_SHAPE;
+  for (int k = 0; k < n_cand; ++k) {
+    if (!is_pow2(cand[k]) || cand[k] < 8 || cand[k] > 128) return ABSB_ERR_BAD_BLOCK_SIZE;
+    if (k > 0 && cand[k] <= cand[k - 1]) return ABSB_ERR_BAD_SHAPE;
+  }
+  for (int h = 0; h < n_heads; ++h) {
+    double base = 0.0;
+    int best = 0;
+    for (int k = 0; k < n_cand; ++k) {
+      double acc = 0.0;
+      for (int i = 0; i < n_samples; ++i) acc += (double)recall_host[((size_t)i * n_heads + h) * n_cand + k];
+      const double mean = acc / (double)n_samples;
+      if (mean_out) mean_out[(size_t)h * n_cand + k] = mean;
+      if (k == 0) base = mean;
+      if (mean >= tau * base) best = k;  // the smallest candidate always qualifies for tau <= 1
+    }
+    block_size_out[h] = cand[best];
+  }
+  return ABSB_OK;
+}
+
 int absb_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
   if (!src || !sink) return ABSB_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(src) & 15) return ABSB_ERR_BAD_SHAPE;

@@ -74,6 +74,9 @@ ABSB_HIDDEN int launch_decode(const Geometry& g, const Plan& pl, int dtype, floa
 
 ABSB_HIDDEN int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int num_cus, hipStream_t stream);
 
+ABSB_HIDDEN int launch_head_recall(const float* lse_sel, const float* lse_all, float* recall, int nseg, int G,
+                                   hipStream_t stream);
+
 inline int check_launch() { return hipGetLastError() == hipSuccess ? ABSB_OK : ABSB_ERR_HIP; }
 
 // ------------------------------------------------------------------ device helpers

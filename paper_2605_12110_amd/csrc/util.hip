@@ -38,4 +38,25 @@ int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int num_cu
   return check_launch();
 }
 
+// Attention recall of a selection (Sec. 2.3): the share of the dense softmax mass that falls on
+// the selected tokens is exp(lse over the selection - lse over the whole context); per
+// (request, KV head) the mean over the group's query heads, in order.
+__global__ void head_recall_kernel(const float* lse_sel, const float* lse_all, float* recall, int nseg, int G) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= nseg) return;
+  float acc = 0.0f;
+  for (int g = 0; g < G; ++g) {
+    const float a = lse_sel[(size_t)s * G + g], z = lse_all[(size_t)s * G + g];
+    acc += (a == -__builtin_inff()) ? 0.0f : __expf(a - z);  // an empty selection holds no mass
+  }
+  recall[s] = acc / (float)G;
+}
+
+int launch_head_recall(const float* lse_sel, const float* lse_all, float* recall, int nseg, int G,
+                       hipStream_t stream) {
+  hipLaunchKernelGGL(head_recall_kernel, dim3((unsigned)((nseg + 255) / 256)), dim3(256), 0, stream, lse_sel, lse_all,
+                     recall, nseg, G);
+  return check_launch();
+}
+
 }  // namespace absb

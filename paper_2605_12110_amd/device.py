@@ -21,20 +21,29 @@ class DeviceWorkload:
     """Everything one layer's decode step needs, resident on the GPU."""
 
     def __init__(self, wl, device: str = "cuda:0", budget: Optional[np.ndarray] = None,
-                 block_repr: int = absb.REPR_MEAN):
+                 block_repr: int = absb.REPR_MEAN, block_size: Optional[np.ndarray] = None,
+                 share: Optional["DeviceWorkload"] = None):
+        """`block_size` / `budget` override the workload's; `share` reuses another holder's resident
+        caches, queries, lengths and page table (same workload under other block sizes or budgets)."""
         self.wl = wl
         self.device = device
         tdt = torch.float16 if wl.dtype == absb.F16 else torch.bfloat16
         self.torch_dtype = tdt
         budget = wl.budget if budget is None else np.asarray(budget, dtype=np.int32)
+        self.block_size = np.asarray(wl.block_size if block_size is None else block_size, dtype=np.int32)
         self.layer = absb.Layer(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.dtype,
-                                wl.block_size, wl.strides, block_repr=block_repr)
+                                self.block_size, wl.strides, block_repr=block_repr)
         width = wl.head_dim * (2 if block_repr == absb.REPR_MINMAX else 1)      # values per block
-        self.k_cache = _up(wl.k_cache.view(np.int16), tdt, device)
-        self.v_cache = _up(wl.v_cache.view(np.int16), tdt, device)
-        self.q = _up(wl.q.view(np.int16), tdt, device)
-        self.seq_lens = _up(wl.seq_lens.astype(np.int32), None, device)
-        self.page_table = _up(wl.page_table.astype(np.int32), None, device)
+        if share is None:
+            self.k_cache = _up(wl.k_cache.view(np.int16), tdt, device)
+            self.v_cache = _up(wl.v_cache.view(np.int16), tdt, device)
+            self.q = _up(wl.q.view(np.int16), tdt, device)
+            self.seq_lens = _up(wl.seq_lens.astype(np.int32), None, device)
+            self.page_table = _up(wl.page_table.astype(np.int32), None, device)
+        else:
+            assert share.wl is wl
+            self.k_cache, self.v_cache, self.q = share.k_cache, share.v_cache, share.q
+            self.seq_lens, self.page_table = share.seq_lens, share.page_table
         self.budget = _up(budget.astype(np.int32), None, device)
         self.batch = absb.Batch(seq_lens_host=wl.seq_lens, budget_host=budget, seq_lens=self.seq_lens,
                                 page_table=self.page_table, budget=self.budget)

@@ -167,7 +167,7 @@ def _plant_fixed(rng, wl: Workload, q32, n_plant, gain, unit):
             wl.planted[(b, h)] = pos.astype(np.int64)
 
 
-def _plant_zipf(rng, wl: Workload, q32, n_heavy, z_top, exponent, run_choices):
+def _plant_zipf(rng, wl: Workload, q32, n_heavy, z_top, exponent, run_choices, run_lengths=None):
     """Config-3 style planting.  Per (request, KV head): `n_heavy` heavy tokens ranked
     r = 1..n_heavy get a target logit z_r = z_top - exponent*ln r along the group-mean
     query direction, so their dense-softmax mass falls off as r^-exponent.  Heavy tokens
@@ -176,6 +176,9 @@ def _plant_zipf(rng, wl: Workload, q32, n_heavy, z_top, exponent, run_choices):
     G, P, d = wl.group, wl.page_size, wl.head_dim
     sm = 1.0 / np.sqrt(d)
     rho_of_head = rng.choice(np.asarray(run_choices), size=wl.num_kv_heads)
+    if run_lengths is not None:       # fixed head roles (the draw above is still taken: the streams stay aligned)
+        rho_of_head = np.asarray(run_lengths, dtype=rho_of_head.dtype)
+        assert rho_of_head.shape == (wl.num_kv_heads,)
     wl.knobs["run_length"] = [int(x) for x in rho_of_head]
     for b in range(wl.batch):
         L = int(wl.seq_lens[b])
@@ -215,7 +218,8 @@ def make_workload(config: int, *, seed: Optional[int] = None, context: Optional[
                   batch: Optional[int] = None, budget: Optional[int] = None,
                   block_sizes: Optional[Sequence[int]] = None, uniform_block: Optional[int] = None,
                   shuffle_pages: bool = True, plant_unit: str = "rms",
-                  seq_lens: Optional[Sequence[int]] = None) -> Workload:
+                  seq_lens: Optional[Sequence[int]] = None,
+                  run_lengths: Optional[Sequence[int]] = None) -> Workload:
     """Build one of the five benchmark-shaped workloads (1-based `config`), optionally
     scaled down (context / batch / budget overrides) for quick tests.
 
@@ -285,7 +289,8 @@ def make_workload(config: int, *, seed: Optional[int] = None, context: Optional[
         _plant_fixed(r_plant, wl, q32, n_plant=16, gain=4.0, unit=plant_unit)
         wl.knobs.update(planting="fixed", n_plant=16, gain=4.0, unit=plant_unit)
     elif config in (3, 5):
-        _plant_zipf(r_plant, wl, q32, n_heavy=4096, z_top=16.0, exponent=1.1, run_choices=(1, 4, 16, 64))
+        _plant_zipf(r_plant, wl, q32, n_heavy=4096, z_top=16.0, exponent=1.1, run_choices=(1, 4, 16, 64),
+                    run_lengths=run_lengths)
         wl.knobs.update(planting="zipf", n_heavy=4096, z_top=16.0, exponent=1.1)
     wl.q = f32_to_bits(q32, dtype)
     return wl

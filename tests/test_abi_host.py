@@ -196,3 +196,22 @@ def test_selection_rejects_segments_beyond_its_capacity_before_any_launch():
     with pytest.raises(absb.AbsbError) as e:
         absb.absb_topk(layer, batch, fake, fake, fake, 8, stream=0)
     assert e.value.status == absb.ERR_UNSUPPORTED
+
+
+def test_block_size_assignment_rule_matches_the_oracle_on_the_host():
+    """Eq. (2) is host-only integer work in the library: identical to the oracle on identical recalls."""
+    from oracle import oracle as O
+    rng = np.random.default_rng(5)
+    cand = [8, 16, 32, 64, 128]
+    for tau in (0.5, 0.9, 0.98, 1.0):
+        rec = rng.uniform(0.0, 1.0, size=(7, 9, 5)).astype(np.float32)
+        rec[:, :, 0] = np.maximum(rec[:, :, 0], 0.8)
+        got, mean = absb.absb_assign_block_sizes(rec, cand, tau)
+        want, wmean = O.assign_block_sizes(rec.astype(np.float64), cand, tau)
+        assert np.array_equal(got, want) and np.array_equal(mean, wmean)
+    with pytest.raises(absb.AbsbError) as e:
+        absb.absb_assign_block_sizes(rec, [8, 16, 32, 64, 96], 0.9)
+    assert e.value.status == absb.ERR_BAD_BLOCK_SIZE
+    with pytest.raises(absb.AbsbError) as e:
+        absb.absb_assign_block_sizes(rec, [8, 32, 16, 64, 128], 0.9)
+    assert e.value.status == absb.ERR_BAD_SHAPE

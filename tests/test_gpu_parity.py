@@ -388,3 +388,33 @@ def test_minmax_config3_full_headline():
 
 def test_minmax_config4_scaled_mixed_lengths():
     run_all_stages(synth.make_workload(4, context=16384, batch=5), "max-min config4 (<=16K ctx, batch 5)", O.MINMAX)
+
+
+# ------------------------------------------------------------------ calibration (Sec. 3.2)
+def test_calibration_recall_and_assignment_match_the_oracle():
+    """Recall(h, B) measured through the library (two log-sum-exp arrays per candidate) against the
+    oracle's fp64 recall of the oracle's own selection, and Eq. (2) on both sides."""
+    from paper_2605_12110_amd import absb, calibrate
+    cand = (8, 16, 32, 64, 128)
+    samples = [synth.make_workload(3, context=8192, budget=512, seed=100 + i) for i in range(3)]
+    sizes, mean, per_sample = calibrate.calibrate(samples, cand, tau=0.6)
+    want = np.empty((len(samples), samples[0].num_kv_heads, len(cand)))
+    for i, wl in enumerate(samples):
+        for k, B in enumerate(cand):
+            wl_b = synth.make_workload(3, context=8192, budget=512, seed=100 + i, uniform_block=B)
+            assert np.array_equal(wl_b.k_cache, wl.k_cache) and np.array_equal(wl_b.q, wl.q)
+            r = O.decode_step(wl_b, O.build_centroids(wl_b))
+            want[i, :, k] = O.head_recall(wl_b, r["sel_idx"], r["sel_cnt"]).mean(axis=0)
+    err = np.abs(per_sample - want).max()
+    _say(f"[case calibration] max |recall - oracle| = {err:.2e}; mean recall per head x candidate:\n{np.round(mean, 3)}")
+    assert err <= 2e-3
+    # the rule itself is integer work: identical on identical (float32) recalls
+    o_sizes, o_mean = O.assign_block_sizes(per_sample.astype(np.float64), cand, 0.6)
+    assert np.array_equal(sizes, o_sizes) and np.allclose(mean, o_mean, rtol=1e-15, atol=0)
+    # and from the oracle's own recalls, wherever no mean sits within the recall tolerance of its threshold
+    w_sizes, w_mean = O.assign_block_sizes(want, cand, 0.6)
+    margin = np.abs(w_mean - 0.6 * w_mean[:, :1]).min(axis=1)
+    safe = margin > 4e-3
+    assert safe.any() and np.array_equal(sizes[safe], w_sizes[safe])
+    assert len(set(w_sizes.tolist())) >= 3                   # the heads of this input do not all want the same size
+    _say(f"    block sizes: library {sizes.tolist()}, oracle {w_sizes.tolist()} (compared on {int(safe.sum())} heads)")
