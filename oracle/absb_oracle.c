@@ -370,19 +370,30 @@ static int by_index(const void *a, const void *b) {
     return (x > y) - (x < y);
 }
 
+/* Forced blocks (a selection policy on top of the paper's pure Top-K, off by default): the
+ * blocks that hold any of the first `sink_tokens` or of the last `recent_tokens` tokens of the
+ * context rank as if their score were INT32_MAX; they still count towards K_s.  seq_lens may be
+ * NULL when recent_tokens is 0. */
 void orc_topk(int Bt, int Hkv, const int64_t *off, const int32_t *block_size, const int32_t *budget,
               const int32_t *scores, int32_t *sel_idx /* [Bt*Hkv][sel_stride] */, int32_t *sel_cnt,
-              int sel_stride) {
+              int sel_stride, const int32_t *seq_lens, int sink_tokens, int recent_tokens) {
 #pragma omp parallel for schedule(dynamic, 1)
     for (int s = 0; s < Bt * Hkv; ++s) {
         int b = s / Hkv, h = s % Hkv;
         int64_t N = off[s + 1] - off[s];
-        int64_t K = ceil_div64(budget[b], block_size[h]);
+        int64_t B = block_size[h];
+        int64_t K = ceil_div64(budget[b], B);
         if (K > N) K = N;
         if (K > sel_stride) K = sel_stride;
         pair_t *p = (pair_t *)malloc(sizeof(pair_t) * (size_t)(N > 0 ? N : 1));
         for (int64_t j = 0; j < N; ++j) {
-            p[j].score = scores[off[s] + j];
+            int forced = j * B < sink_tokens; /* the block's first token is among the first sink_tokens */
+            if (recent_tokens > 0) {
+                int64_t L = seq_lens[b];
+                int64_t last = (j + 1) * B < L ? (j + 1) * B : L; /* one past the block's last token */
+                if (last > L - recent_tokens) forced = 1;        /* it holds one of the last recent_tokens */
+            }
+            p[j].score = forced ? INT32_MAX : scores[off[s] + j];
             p[j].idx = (int32_t)j;
         }
         qsort(p, (size_t)N, sizeof(pair_t), by_score_desc_then_index);

@@ -160,23 +160,27 @@ def score(wl, store: CentroidStore, q: Optional[np.ndarray] = None, want_weights
     return (scores, ex, wq) if want_weights else (scores, ex)
 
 
-def topk_raw(Bt, Hkv, off, block_size, budget, scores, sel_stride):
+def topk_raw(Bt, Hkv, off, block_size, budget, scores, sel_stride, seq_lens=None, sink_tokens=0, recent_tokens=0):
     nseg = Bt * Hkv
     sel_idx = np.empty((nseg, sel_stride), np.int32)
     sel_cnt = np.empty(nseg, np.int32)
+    lens = None if seq_lens is None else _i32(seq_lens)
     lib().orc_topk(C.c_int(Bt), C.c_int(Hkv), _p(np.ascontiguousarray(off, dtype=np.int64)), _p(_i32(block_size)),
-                   _p(_i32(budget)), _p(_i32(scores)), _p(sel_idx), _p(sel_cnt), C.c_int(sel_stride))
+                   _p(_i32(budget)), _p(_i32(scores)), _p(sel_idx), _p(sel_cnt), C.c_int(sel_stride),
+                   _p(lens), C.c_int(sink_tokens), C.c_int(recent_tokens))
     return sel_idx, sel_cnt
 
 
-def topk(wl, off, scores, sel_stride: Optional[int] = None, budget=None):
-    """O5: per segment the K_s best blocks (score desc, index asc), emitted ascending, -1 padded."""
+def topk(wl, off, scores, sel_stride: Optional[int] = None, budget=None, sink_tokens=0, recent_tokens=0):
+    """O5: per segment the K_s best blocks (score desc, index asc), emitted ascending, -1 padded.
+    Blocks holding the first `sink_tokens` / last `recent_tokens` tokens rank first (forced)."""
     budget = wl.budget if budget is None else budget
     if sel_stride is None:
         # widest possible list: every block of the longest segment (always enough)
         sel_stride = int(np.max(np.diff(off))) if len(off) > 1 else 1
         sel_stride = max(sel_stride, 1)
-    return topk_raw(wl.batch, wl.num_kv_heads, off, wl.block_size, budget, scores, sel_stride)
+    return topk_raw(wl.batch, wl.num_kv_heads, off, wl.block_size, budget, scores, sel_stride, wl.seq_lens,
+                    sink_tokens, recent_tokens)
 
 
 def sparse_attention(wl, sel_idx, sel_cnt, sm_scale: Optional[float] = None, q=None):
@@ -249,9 +253,9 @@ def planted_recall(wl, sel_idx, sel_cnt) -> float:
     return hit / max(tot, 1)
 
 
-def decode_step(wl, store: CentroidStore, sel_stride: Optional[int] = None):
+def decode_step(wl, store: CentroidStore, sel_stride: Optional[int] = None, sink_tokens=0, recent_tokens=0):
     """O4 -> O5 -> O6 given a prebuilt centroid store: the per-step hot path."""
     scores, ex = score(wl, store)
-    sel_idx, sel_cnt = topk(wl, store.off, scores, sel_stride)
+    sel_idx, sel_cnt = topk(wl, store.off, scores, sel_stride, sink_tokens=sink_tokens, recent_tokens=recent_tokens)
     out, lse = sparse_attention(wl, sel_idx, sel_cnt)
     return dict(scores=scores, score_exp=ex, sel_idx=sel_idx, sel_cnt=sel_cnt, out=out, lse=lse)

@@ -108,6 +108,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   p.max_splits = (int32_t)ceil_div(p.max_tokens, st_tok);
   if (p.max_splits < 1) p.max_splits = 1;
   if (p.max_splits > 65535) return ABSB_ERR_BAD_SHAPE;
+  if ((int64_t)p.max_splits * st_tok >= (int64_t(1) << 31)) return ABSB_ERR_BAD_SHAPE;  // positions are 32-bit
 
   int sc = tuning(ABSB_TUNE_SCORE_CHUNK);
   p.score_chunk = sc > 0 ? sc : 256;
