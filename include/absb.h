@@ -86,6 +86,11 @@ typedef struct absb_layer {
      [page][Hkv][P][d] are {Hkv*P*d, P*d, d}. */
   int64_t kv_stride_page, kv_stride_head, kv_stride_tok;
   float sm_scale;            /* softmax scale; 0 selects 1/sqrt(head_dim) as in Eq. (1)         */
+  /* Selection policy on top of the paper's pure Top-K (both 0 = pure Top-K): every block that holds
+     one of the first sink_tokens or of the last recent_tokens tokens of the context ranks ahead of
+     every score (lowest index first among themselves).  Forced blocks count towards K_s.        */
+  int32_t sink_tokens;       /* >= 0                                                            */
+  int32_t recent_tokens;     /* >= 0; > 0 makes absb_topk read batch->seq_lens                  */
   int32_t reserved1;
 } absb_layer;
 
@@ -144,7 +149,9 @@ ABSB_API int absb_score(const absb_layer* layer, const absb_batch* batch, const 
  * highest score; equal scores go to the lower block index.
  *   sel_idx [Bt*Hkv][sel_stride] i32: chosen block indices in ascending order, padded with -1
  *   sel_cnt [Bt*Hkv] i32            : K_s
- *   sel_stride >= the value absb_plan reports, else ABSB_ERR_BAD_SHAPE */
+ *   sel_stride >= the value absb_plan reports, else ABSB_ERR_BAD_SHAPE
+ * With layer->sink_tokens / recent_tokens set, the blocks holding those tokens are selected first
+ * (lowest index first if there are more of them than K_s), the rest of K_s by score. */
 ABSB_API int absb_topk(const absb_layer* layer, const absb_batch* batch, const int32_t* scores,
                        int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride, void* workspace,
                        size_t workspace_bytes, void* stream);

@@ -356,10 +356,13 @@ void orc_score_minmax(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t 
 typedef struct {
     int32_t score;
     int32_t idx;
+    int32_t forced;
 } pair_t;
 
 static int by_score_desc_then_index(const void *a, const void *b) {
     const pair_t *x = (const pair_t *)a, *y = (const pair_t *)b;
+    if (x->forced != y->forced) return x->forced > y->forced ? -1 : 1; /* forced blocks ahead of every score */
+    if (x->forced) return x->idx < y->idx ? -1 : (x->idx > y->idx ? 1 : 0);
     if (x->score != y->score) return x->score > y->score ? -1 : 1;
     if (x->idx != y->idx) return x->idx < y->idx ? -1 : 1;
     return 0;
@@ -372,8 +375,8 @@ static int by_index(const void *a, const void *b) {
 
 /* Forced blocks (a selection policy on top of the paper's pure Top-K, off by default): the
  * blocks that hold any of the first `sink_tokens` or of the last `recent_tokens` tokens of the
- * context rank as if their score were INT32_MAX; they still count towards K_s.  seq_lens may be
- * NULL when recent_tokens is 0. */
+ * context rank ahead of every score, lowest index first among themselves; they still count
+ * towards K_s.  seq_lens may be NULL when recent_tokens is 0. */
 void orc_topk(int Bt, int Hkv, const int64_t *off, const int32_t *block_size, const int32_t *budget,
               const int32_t *scores, int32_t *sel_idx /* [Bt*Hkv][sel_stride] */, int32_t *sel_cnt,
               int sel_stride, const int32_t *seq_lens, int sink_tokens, int recent_tokens) {
@@ -393,7 +396,8 @@ void orc_topk(int Bt, int Hkv, const int64_t *off, const int32_t *block_size, co
                 int64_t last = (j + 1) * B < L ? (j + 1) * B : L; /* one past the block's last token */
                 if (last > L - recent_tokens) forced = 1;        /* it holds one of the last recent_tokens */
             }
-            p[j].score = forced ? INT32_MAX : scores[off[s] + j];
+            p[j].score = scores[off[s] + j];
+            p[j].forced = forced;
             p[j].idx = (int32_t)j;
         }
         qsort(p, (size_t)N, sizeof(pair_t), by_score_desc_then_index);

@@ -38,7 +38,8 @@ class _Layer(C.Structure):
                 ("page_size", C.c_int32), ("dtype", C.c_int32), ("block_repr", C.c_int32),
                 ("block_size", C.POINTER(C.c_int32)),
                 ("kv_stride_page", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64),
-                ("sm_scale", C.c_float), ("reserved1", C.c_int32)]
+                ("sm_scale", C.c_float), ("sink_tokens", C.c_int32), ("recent_tokens", C.c_int32),
+                ("reserved1", C.c_int32)]
 
 
 class _Batch(C.Structure):
@@ -116,6 +117,8 @@ class Layer:
     kv_strides: Sequence[int]          # (page, head, token) in elements
     sm_scale: float = 0.0
     block_repr: int = REPR_MEAN
+    sink_tokens: int = 0
+    recent_tokens: int = 0
 
     def __setattr__(self, name, value):
         object.__setattr__(self, name, value)
@@ -129,7 +132,8 @@ class Layer:
             sp, sh, st = (int(x) for x in self.kv_strides)
             self._c = _Layer(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size, self.dtype,
                              int(self.block_repr),
-                             bs_p, sp, sh, st, float(self.sm_scale), 0)
+                             bs_p, sp, sh, st, float(self.sm_scale), int(self.sink_tokens),
+                             int(self.recent_tokens), 0)
         return self._c
 
 

@@ -37,6 +37,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   const int64_t sp = layer->kv_stride_page, sh = layer->kv_stride_head, st = layer->kv_stride_tok;
   if (sp <= 0 || sh <= 0 || st < ABSB_HEAD_DIM || (sp % 8) || (sh % 8) || (st % 8)) return ABSB_ERR_BAD_SHAPE;
   if (!(layer->sm_scale >= 0.0f) || std::isinf(layer->sm_scale)) return ABSB_ERR_BAD_SHAPE;
+  if (layer->sink_tokens < 0 || layer->recent_tokens < 0) return ABSB_ERR_BAD_SHAPE;
   const int Bt = batch->batch;
   if (Bt < 1 || (int64_t)Bt * Hkv > 65535) return ABSB_ERR_BAD_SHAPE;  // segments index grid.y
 
@@ -48,6 +49,8 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   g.log2_page = ilog2(P);
   g.pt_stride = batch->pt_stride;
   g.repr = layer->block_repr;
+  g.sink_tokens = layer->sink_tokens;
+  g.recent_tokens = layer->recent_tokens;
   g.s_page = sp;
   g.s_head = sh;
   g.s_tok = st;
@@ -221,8 +224,9 @@ int absb_topk(const absb_layer* layer, const absb_batch* batch, const int32_t* s
   int rc = make_plan(layer, batch, true, 0, &g, &p);
   if (rc != ABSB_OK) return rc;
   if (!scores || !sel_idx || !sel_cnt || !batch->cent_off || !batch->budget) return ABSB_ERR_NULL;
+  if (g.recent_tokens > 0 && !batch->seq_lens) return ABSB_ERR_NULL;
   if (sel_stride < p.sel_stride) return ABSB_ERR_BAD_SHAPE;
-  return launch_topk(g, p, scores, batch->cent_off, batch->budget, sel_idx, sel_cnt, sel_stride, nullptr,
+  return launch_topk(g, p, scores, batch->cent_off, batch->budget, batch->seq_lens, sel_idx, sel_cnt, sel_stride, nullptr,
                      static_cast<hipStream_t>(stream));
 }
 
@@ -264,7 +268,7 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, scores, nullptr, st);
   if (rc != ABSB_OK) return rc;
   // the selection kernel also clears the split counters of the attention kernel behind it
-  rc = launch_topk(g, p, scores, batch->cent_off, batch->budget, sel_idx, sel_cnt, p.sel_stride,
+  rc = launch_topk(g, p, scores, batch->cent_off, batch->budget, batch->seq_lens, sel_idx, sel_cnt, p.sel_stride,
                    reinterpret_cast<int32_t*>(ws + p.ws_tickets), st);
   if (rc != ABSB_OK) return rc;
   return launch_decode(g, p, layer->dtype, resolve_scale(layer), q, k_cache, v_cache, batch->page_table,

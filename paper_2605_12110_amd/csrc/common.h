@@ -24,6 +24,7 @@ struct Geometry {
   int32_t log2_page;  // P = 1 << log2_page
   int32_t pt_stride;
   int32_t repr;       // absb_repr: vectors per block = repr + 1
+  int32_t sink_tokens, recent_tokens;  // forced blocks of the selection (0 = none)
   int32_t pad_;
   int64_t s_page, s_head, s_tok;  // element strides of the K/V caches
   HeadTable heads;
@@ -64,7 +65,8 @@ ABSB_HIDDEN int launch_score(const Geometry& g, const Plan& pl, int dtype, const
                              const float* qscale, const int32_t* cent_off, int32_t* scores, int32_t* score_exp,
                              hipStream_t stream);
 ABSB_HIDDEN int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const int32_t* cent_off,
-                            const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride,
+                            const int32_t* budget, const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
+                            int32_t sel_stride,
                             int32_t* tickets, hipStream_t stream);
 ABSB_HIDDEN int launch_decode(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
                               const void* k_cache, const void* v_cache, const int32_t* page_table,

@@ -26,6 +26,8 @@ struct TopkParams {
   const int32_t* scores;
   const int32_t* cent_off;
   const int32_t* budget;  // [Bt]
+  const int32_t* seq_lens;  // [Bt]; read only when recent_tokens > 0
+  int32_t sink_tokens, recent_tokens;  // blocks holding these tokens are selected ahead of every score
   int32_t* sel_idx;
   int32_t* sel_cnt;
   int32_t* tickets;  // [nseg] or null: split counters of the attention kernel that follows, cleared here
@@ -109,13 +111,21 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
   const int s = blockIdx.x;
   const int b = s / p.Hkv, h = s % p.Hkv;
   const int off = p.cent_off[s];
-  const int N = p.cent_off[s + 1] - off;
+  const int Nall = p.cent_off[s + 1] - off;
   const int lb = p.heads.log2_block[h];
   const int T = p.budget[b];
   int K = (int)(((int64_t)T + (1 << lb) - 1) >> lb);
-  K = min(min(K, N), p.sel_stride);
+  K = min(min(K, Nall), p.sel_stride);
+  // Forced blocks are a prefix [0, lo) (they hold the first sink_tokens tokens) and a suffix
+  // [hi, Nall) (the last recent_tokens tokens) of the segment; they are selected ahead of every
+  // score, lowest index first, and the blocks [lo, hi) compete by score for what is left of K.
+  int lo = 0, hi = Nall;
+  if (p.sink_tokens > 0) lo = min(Nall, (int)(((int64_t)p.sink_tokens + (1 << lb) - 1) >> lb));
+  if (p.recent_tokens > 0) hi = max(lo, min(Nall, max(0, p.seq_lens[b] - p.recent_tokens) >> lb));
+  const int nforced = lo + (Nall - hi);
+  const int N = hi - lo;  // competing blocks; the code below indexes them from 0
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int32_t* sc = p.scores + off;
+  const int32_t* sc = p.scores + off + (N > 0 ? lo : 0);
   int32_t* out = p.sel_idx + (size_t)s * p.sel_stride;
   constexpr int R = KPT > 0 ? KPT : 1;
   const int ntiles = KPT > 0 ? KPT : (N + TOPK_THREADS - 1) / TOPK_THREADS;
@@ -124,15 +134,16 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
   uint32_t* bm_eq = s_bitmap + nwords;
 
   // keys first: everything else waits on them.  The index is clamped instead of the load being
-  // predicated, so the loads issue back to back (N >= 1 always).
+  // predicated, so the loads issue back to back (the clamp keeps them legal when nothing competes).
+  const int jlast = max(N - 1, 0);
   uint32_t key[R];
   if (KPT > 0) {
 #pragma unroll
-    for (int i = 0; i < R; ++i) key[i] = ordered_key(sc[min(i * TOPK_THREADS + tid, N - 1)]);
+    for (int i = 0; i < R; ++i) key[i] = ordered_key(sc[min(i * TOPK_THREADS + tid, jlast)]);
   }
   auto key_at = [&](int i) -> uint32_t {  // meaningful only for i*1024+tid < N
     if (KPT > 0) return key[i];
-    return ordered_key(sc[min(i * TOPK_THREADS + tid, N - 1)]);
+    return ordered_key(sc[min(i * TOPK_THREADS + tid, jlast)]);
   };
 
   if (tid == 0) {
@@ -141,11 +152,24 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
   }
 #pragma unroll 1
   for (int i = K + tid; i < p.sel_stride; i += TOPK_THREADS) out[i] = -1;
-  if (K >= N) {  // everything is selected
+  if (K >= Nall) {  // everything is selected
 #pragma unroll 1
-    for (int i = tid; i < N; i += TOPK_THREADS) out[i] = i;
+    for (int i = tid; i < Nall; i += TOPK_THREADS) out[i] = i;
     return;
   }
+  if (nforced >= K) {  // the forced blocks alone fill the list: lowest indices first
+#pragma unroll 1
+    for (int i = tid; i < K; i += TOPK_THREADS) out[i] = i < lo ? i : hi + (i - lo);
+    return;
+  }
+  // list = forced prefix, then the chosen ones of [lo, hi) (written below, relative to `out`), then
+  // the forced suffix
+  K -= nforced;
+#pragma unroll 1
+  for (int i = tid; i < lo; i += TOPK_THREADS) out[i] = i;
+#pragma unroll 1
+  for (int i = tid; i < Nall - hi; i += TOPK_THREADS) out[lo + K + i] = hi + i;
+  out += lo;
 
   sh.hist[tid] = 0;
   sh.hist[tid + TOPK_THREADS] = 0;
@@ -277,12 +301,12 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
       const int idx = (w << 5) + bpos;
       if ((g >> bpos) & 1u) {
         const uint32_t slot = G + min(E, need_eq);
-        if (slot < (uint32_t)K) out[slot] = idx;  // always true for consistent counts; keeps stores in bounds
+        if (slot < (uint32_t)K) out[slot] = idx + lo;  // always true for consistent counts; keeps stores in bounds
         ++G;
       } else {
         if (E < need_eq) {
           const uint32_t slot = G + E;
-          if (slot < (uint32_t)K) out[slot] = idx;
+          if (slot < (uint32_t)K) out[slot] = idx + lo;
         }
         ++E;
       }
@@ -294,13 +318,16 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
 }
 
 int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const int32_t* cent_off,
-                const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride,
-                int32_t* tickets, hipStream_t stream) {
+                const int32_t* budget, const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
+                int32_t sel_stride, int32_t* tickets, hipStream_t stream) {
   if (pl.max_blocks > TOPK_MAX_BLOCKS) return ABSB_ERR_UNSUPPORTED;
   TopkParams p;
   p.scores = scores;
   p.cent_off = cent_off;
   p.budget = budget;
+  p.seq_lens = seq_lens;
+  p.sink_tokens = g.sink_tokens;
+  p.recent_tokens = g.recent_tokens;
   p.sel_idx = sel_idx;
   p.sel_cnt = sel_cnt;
   p.tickets = tickets;

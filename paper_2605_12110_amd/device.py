@@ -22,7 +22,7 @@ class DeviceWorkload:
 
     def __init__(self, wl, device: str = "cuda:0", budget: Optional[np.ndarray] = None,
                  block_repr: int = absb.REPR_MEAN, block_size: Optional[np.ndarray] = None,
-                 share: Optional["DeviceWorkload"] = None):
+                 share: Optional["DeviceWorkload"] = None, sink_tokens: int = 0, recent_tokens: int = 0):
         """`block_size` / `budget` override the workload's; `share` reuses another holder's resident
         caches, queries, lengths and page table (same workload under other block sizes or budgets)."""
         self.wl = wl
@@ -32,7 +32,8 @@ class DeviceWorkload:
         budget = wl.budget if budget is None else np.asarray(budget, dtype=np.int32)
         self.block_size = np.asarray(wl.block_size if block_size is None else block_size, dtype=np.int32)
         self.layer = absb.Layer(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.dtype,
-                                self.block_size, wl.strides, block_repr=block_repr)
+                                self.block_size, wl.strides, block_repr=block_repr, sink_tokens=sink_tokens,
+                                recent_tokens=recent_tokens)
         width = wl.head_dim * (2 if block_repr == absb.REPR_MINMAX else 1)      # values per block
         if share is None:
             self.k_cache = _up(wl.k_cache.view(np.int16), tdt, device)

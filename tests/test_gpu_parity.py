@@ -325,7 +325,7 @@ def test_stream_read_helper_runs_and_leaves_its_sink_alone():
         absb.absb_stream_read(buf.view(torch.uint8)[4:], sink)                # misaligned source
 
 
-@pytest.mark.parametrize("kind", ["random", "few_values", "all_equal"])
+@pytest.mark.parametrize("kind", ["random", "few_values", "all_equal", "few_values_forced", "random_forced"])
 def test_selection_at_the_largest_supported_segment(kind):
     """2^17 blocks in one segment (the selection kernel's capacity), two segments of different
     size side by side; heavy ties push the kernel onto its multi-digit path."""
@@ -334,7 +334,9 @@ def test_selection_at_the_largest_supported_segment(kind):
     B = np.array([8, 16], np.int32)
     L = np.array([8 << 17], np.int32)                       # 131072 blocks of 8, 65536 blocks of 16
     T = np.array([160000], np.int32)                        # K = 20000 and 10000 blocks
-    layer = absb.Layer(2, 2, 128, 64, synth.F16, B, (2 * 64 * 128, 64 * 128, 128))
+    sink, recent = (1000, 40000) if kind.endswith("forced") else (0, 0)
+    layer = absb.Layer(2, 2, 128, 64, synth.F16, B, (2 * 64 * 128, 64 * 128, 128), sink_tokens=sink,
+                       recent_tokens=recent)
     dev = "cuda:0"
     batch = absb.Batch(seq_lens_host=L, budget_host=T, seq_lens=torch.from_numpy(L).to(dev),
                        page_table=None, budget=torch.from_numpy(T).to(dev), pt_stride=int(L[0]) // 64)
@@ -344,9 +346,9 @@ def test_selection_at_the_largest_supported_segment(kind):
     batch.cent_off = torch.from_numpy(plan.cent_off).to(dev)
     rng = np.random.default_rng(77)
     total = int(off[-1])
-    if kind == "random":
+    if kind.startswith("random"):
         sc = rng.integers(-2 ** 31, 2 ** 31, size=total, dtype=np.int64)
-    elif kind == "few_values":
+    elif kind.startswith("few_values"):
         sc = rng.integers(-3, 4, size=total, dtype=np.int64) * 1000003
     else:
         sc = np.full(total, -17, np.int64)
@@ -358,7 +360,7 @@ def test_selection_at_the_largest_supported_segment(kind):
     _say(f"[case top-k capacity/{kind}] blocks={np.diff(off).tolist()} K={[20000, 10000]}")
     absb.absb_topk(layer, batch, torch.from_numpy(sc).to(dev), sel_idx, sel_cnt, stride)
     _sync()
-    want_idx, want_cnt = O.topk_raw(1, 2, off, B, T, sc, stride)
+    want_idx, want_cnt = O.topk_raw(1, 2, off, B, T, sc, stride, L, sink, recent)
     assert np.array_equal(sel_cnt.cpu().numpy(), want_cnt) and want_cnt.tolist() == [20000, 10000]
     assert np.array_equal(sel_idx.cpu().numpy(), want_idx)
 
@@ -418,3 +420,46 @@ def test_calibration_recall_and_assignment_match_the_oracle():
     assert safe.any() and np.array_equal(sizes[safe], w_sizes[safe])
     assert len(set(w_sizes.tolist())) >= 3                   # the heads of this input do not all want the same size
     _say(f"    block sizes: library {sizes.tolist()}, oracle {w_sizes.tolist()} (compared on {int(safe.sum())} heads)")
+
+
+# ------------------------------------------------------------------ forced sink / recent blocks
+@pytest.mark.parametrize("sink,recent", [(1, 0), (0, 1), (64, 200), (5000, 5000)])
+def test_forced_sink_and_recent_blocks(sink, recent):
+    """Selection policy knob: blocks holding the first / last tokens always rank first.  Bit-exact
+    selection against the oracle, attention within tolerance, through the stand-alone and fused calls."""
+    wl = synth.tiny_workload(seed=51, dtype=synth.F16, Bt=3, Hq=8, Hkv=4, P=16, seq_lens=(37, 640, 2301),
+                             block_size=(8, 32, 128, 16), budget=(16, 96, 400))
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st, sink_tokens=sink, recent_tokens=recent)
+    plain = O.decode_step(wl, st)
+    assert not np.array_equal(ref["sel_idx"], plain["sel_idx"])          # the knob changes something here
+    dw = _dev(wl, sink_tokens=sink, recent_tokens=recent)
+    K = dw.sel_stride
+    _say(f"[case forced sink={sink} recent={recent}] K={K}")
+    dw.load_store(st.codes, st.qscale, st.qmin)
+    dw.score(); dw.topk(); _sync()
+    assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
+    dw.build()
+    dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7)
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "decode_fused with forced blocks")
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
+
+
+def test_forced_blocks_on_a_long_segment_with_many_tiles():
+    wl = synth.make_workload(3, context=65536, budget=2048)              # up to 8192 blocks per segment
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st, sink_tokens=128, recent_tokens=1024)
+    dw = _dev(wl, sink_tokens=128, recent_tokens=1024)
+    dw.build()
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "forced blocks, 64K context")
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+    # every segment holds its first block and its last ones
+    sel, cnt = dw.sel_idx.cpu().numpy(), dw.sel_cnt.cpu().numpy()
+    for s in range(8):
+        B = int(wl.block_size[s])
+        chosen = set(sel[s, :cnt[s]].tolist())
+        want = set(range(-(-128 // B))) | set(range((65536 - 1024) // B, 65536 // B))
+        assert (want <= chosen) if len(want) <= cnt[s] else (chosen <= want)

@@ -57,11 +57,10 @@ def test_forced_blocks_match_the_token_level_construction_exhaustively():
                 assert cnt == min(N, -(-T // B))
 
 
-def test_forced_block_outranks_every_genuine_score_but_ties_with_the_largest_integer():
-    big = 2 ** 31 - 2
+def test_forced_block_outranks_every_score_even_the_largest_integer():
+    big = 2 ** 31 - 1
     assert _select([big, big, 0, 0], 8, 8, 32, 0, 1)[0] == [3]
-    # a genuine score of INT32_MAX ties with a forced block: the lower index wins (documented)
-    assert _select([2 ** 31 - 1, 0, 0, 0], 8, 8, 32, 0, 1)[0] == [0]
+    assert _select([big, big, 0, -2 ** 31], 8, 16, 32, 0, 1)[0] == [0, 3]
 
 
 def test_no_forcing_is_the_plain_selection():
