@@ -564,3 +564,86 @@ void orc_assign_block_sizes(int n_samples, int nh, int nB, const double *recall,
         block_size[h] = cand[best];
     }
 }
+
+/* ---- keeping the store current while decoding (upstream of the per-step path; the paper only
+ * notes that recomputing every centroid is too expensive, Sec. 1 and Sec. 3.2, and leaves the
+ * mechanism open).  Reading taken: the pooled state of each segment's LAST block is kept in
+ * binary32 (running sum in token order for mean pooling; running maxima then minima for max-min
+ * pooling); a new token is folded into it with the same single operations a rebuild would use,
+ * so the block's value is bit-identical to a rebuild's; its 4-bit row is re-emitted under the
+ * FROZEN per-channel (scale, min) of the store with clamping to [0, 15]:
+ *   code = clamp(rint((value - min) * (1 / scale))), 0 where scale == 0.
+ * Rows of closed blocks never change.  The ranges are only refreshed by a rebuild.
+ *
+ * orc_tail_state: state [nseg][R*d] of the last block of every segment at the given lengths. */
+void orc_tail_state(int dtype, int repr, int Bt, int Hkv, int d, int P, int64_t s_page, int64_t s_head,
+                    int64_t s_tok, const uint16_t *k_cache, const int32_t *page_table, int pt_stride,
+                    const int32_t *seq_lens, const int32_t *block_size, float *tail) {
+    paged_t kc = {k_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+    int W = d * (repr + 1);
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        int64_t L = seq_lens[b], B = block_size[h];
+        int64_t t0 = ((L - 1) / B) * B;
+        float *st = tail + (int64_t)s * W;
+        for (int64_t t = t0; t < L; ++t) {
+            const uint16_t *row = row_of(&kc, b, h, t);
+            for (int ch = 0; ch < d; ++ch) {
+                float v = widen(row[ch], dtype);
+                if (repr == 0) {
+                    st[ch] = (t == t0) ? v : st[ch] + v;
+                } else {
+                    st[ch] = (t == t0 || v > st[ch]) ? v : st[ch];
+                    st[d + ch] = (t == t0 || v < st[d + ch]) ? v : st[d + ch];
+                }
+            }
+        }
+    }
+}
+
+/* orc_append_token: the token at position L_b - 1 (lengths already include it) joins the store.
+ * tail: in/out state as above.  row_out [nseg][R*d/2]: the re-emitted 4-bit row of the block that
+ * holds the token; value_out [nseg][R*d] (may be NULL): that block's pooled value (mean, or
+ * maxima and minima). */
+void orc_append_token(int dtype, int repr, int Bt, int Hkv, int d, int P, int64_t s_page, int64_t s_head,
+                      int64_t s_tok, const uint16_t *k_cache, const int32_t *page_table, int pt_stride,
+                      const int32_t *seq_lens, const int32_t *block_size, const float *qscale,
+                      const float *qmin, float *tail, uint8_t *row_out, float *value_out) {
+    paged_t kc = {k_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
+    int W = d * (repr + 1);
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        int64_t L = seq_lens[b], B = block_size[h];
+        int64_t t = L - 1, t0 = (t / B) * B;
+        const uint16_t *row = row_of(&kc, b, h, t);
+        float *st = tail + (int64_t)s * W;
+        float n = (float)(t - t0 + 1);
+        uint8_t *codes = row_out + (int64_t)s * (W / 2);
+        for (int c = 0; c < W; ++c) {
+            int ch = c % d;
+            float v = widen(row[ch], dtype);
+            if (repr == 0)
+                st[c] = (t == t0) ? v : st[c] + v;
+            else if (c < d)
+                st[c] = (t == t0 || v > st[c]) ? v : st[c];
+            else
+                st[c] = (t == t0 || v < st[c]) ? v : st[c];
+            float value = (repr == 0) ? st[c] / n : st[c];
+            if (value_out) value_out[(int64_t)s * W + c] = value;
+            float sc = qscale[(int64_t)s * W + c];
+            float r = 0.0f;
+            if (sc > 0.0f) {
+                float inv = 1.0f / sc;
+                float x = value - qmin[(int64_t)s * W + c];
+                r = rintf(x * inv);
+                if (!(r >= 0.0f)) r = 0.0f;
+                if (r > 15.0f) r = 15.0f;
+            }
+            uint8_t code = (uint8_t)r;
+            if (c % 2 == 0)
+                codes[c / 2] = code;
+            else
+                codes[c / 2] = (uint8_t)(codes[c / 2] | (code << 4));
+        }
+    }
+}

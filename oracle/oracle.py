@@ -145,6 +145,46 @@ def build_centroids(wl, repr: int = MEAN) -> CentroidStore:
     return CentroidStore(off, cent, qscale, qmin, qinv, codes, repr)
 
 
+def tail_state(wl, repr: int = MEAN) -> np.ndarray:
+    """Pooled state of every segment's last block (running sum, or running maxima and minima)."""
+    dt, Bt, _, Hkv, d, P, sp, sh, st = _geom(wl)
+    nseg = wl.batch * wl.num_kv_heads
+    tail = np.zeros((nseg, wl.head_dim * (repr + 1)), np.float32)
+    pt = _i32(wl.page_table)
+    lib().orc_tail_state(dt, C.c_int(repr), Bt, Hkv, d, P, sp, sh, st, _p(wl.k_cache), _p(pt), C.c_int(pt.shape[1]),
+                         _p(_i32(wl.seq_lens)), _p(_i32(wl.block_size)), _p(tail))
+    return tail
+
+
+def append_token(wl, store: CentroidStore, tail: np.ndarray):
+    """The token at position L_b - 1 of every request (wl.seq_lens already counts it, the key is in
+    wl.k_cache) joins the store under its frozen ranges.  Returns (new store in the tight layout of
+    the new lengths, block values [nseg, W]); `tail` is updated in place."""
+    dt, Bt, _, Hkv, d, P, sp, sh, st = _geom(wl)
+    nseg = wl.batch * wl.num_kv_heads
+    W = wl.head_dim * (store.repr + 1)
+    rows = np.zeros((nseg, W // 2), np.uint8)
+    values = np.empty((nseg, W), np.float32)
+    pt = _i32(wl.page_table)
+    lib().orc_append_token(dt, C.c_int(store.repr), Bt, Hkv, d, P, sp, sh, st, _p(wl.k_cache), _p(pt),
+                           C.c_int(pt.shape[1]), _p(_i32(wl.seq_lens)), _p(_i32(wl.block_size)), _p(store.qscale),
+                           _p(store.qmin), _p(tail), _p(rows), _p(values))
+    new_off = offsets(wl)
+    codes = np.zeros((int(new_off[-1]), W // 2), np.uint8)
+    cent = None if store.cent is None else np.zeros((int(new_off[-1]), W), np.float32)
+    for s in range(nseg):
+        n_old = int(store.off[s + 1] - store.off[s])
+        n_new = int(new_off[s + 1] - new_off[s])
+        assert n_new in (n_old, n_old + 1)
+        keep = n_new - 1                               # rows of closed blocks carry over unchanged
+        codes[new_off[s]:new_off[s] + keep] = store.codes[store.off[s]:store.off[s] + keep]
+        codes[new_off[s] + keep] = rows[s]
+        if cent is not None:
+            cent[new_off[s]:new_off[s] + keep] = store.cent[store.off[s]:store.off[s] + keep]
+            cent[new_off[s] + keep] = values[s]
+    return CentroidStore(new_off, cent, store.qscale, store.qmin, store.qinv, codes, store.repr), values
+
+
 def score(wl, store: CentroidStore, q: Optional[np.ndarray] = None, want_weights: bool = False):
     """O4: int32 fixed-point scores for every centroid, per-segment exponent."""
     q = wl.q if q is None else q
