@@ -204,6 +204,11 @@ def cpu_baseline(wl0, bytes0, seconds=10.0, block_repr=0):
     }
 
 
+def synth_workload(cfg):
+    from paper_2605_12110_amd import synth
+    return synth.make_workload(cfg)
+
+
 def run_matrix(args):
     """Every benchmark configuration, then the config-5 sweep (uniform 16 vs adaptive block sizes)."""
     import torch
@@ -252,6 +257,25 @@ def run_matrix(args):
         print(f"| config {cfg} | {m['bytes']['total'] / 1e6:.1f} | {m['ms'] * 1e3:.1f} | {gb:.0f} | {rec2:.3f} / {rec1:.3f} |",
               flush=True)
         del insts, dw
+        torch.cuda.empty_cache()
+
+    print("\nStore maintenance while decoding (absb_append_token: one new token per request folded into the store, "
+          "no rebuild) next to a full rebuild (absb_build_centroids)\n")
+    print("| workload | segments | append us/call | rebuild us/call |")
+    print("|---|---|---|---|", flush=True)
+    from paper_2605_12110_amd.device import DeviceWorkload
+    for cfg in (3, 4):
+        import copy
+        full = synth_workload(cfg)
+        wl0 = copy.copy(full)                       # the same caches, 64 tokens before their final lengths
+        wl0.seq_lens = full.seq_lens - 64
+        dw = DeviceWorkload(wl0, cap_lens=full.seq_lens)
+        dw.build()
+        dw.tail_init()
+        ms_app, _ = time_loop(lambda i: dw.append_token(), 10, 100)      # the same token again and again: timing only
+        ms_bld, _ = time_loop(lambda i: dw.build(), 2, 10)
+        print(f"| config {cfg} | {dw.nseg} | {ms_app * 1e3:.1f} | {ms_bld * 1e3:.1f} |", flush=True)
+        del dw
         torch.cuda.empty_cache()
 
     print(f"\nStreaming-read ceiling measured in this run (absb_stream_read, 2 GiB, 128-bit loads): "

@@ -90,7 +90,7 @@ typedef struct absb_layer {
      one of the first sink_tokens or of the last recent_tokens tokens of the context ranks ahead of
      every score (lowest index first among themselves).  Forced blocks count towards K_s.        */
   int32_t sink_tokens;       /* >= 0                                                            */
-  int32_t recent_tokens;     /* >= 0; > 0 makes absb_topk read batch->seq_lens                  */
+  int32_t recent_tokens;     /* >= 0                                                            */
   int32_t reserved1;
 } absb_layer;
 
@@ -105,12 +105,18 @@ typedef struct absb_batch {
                                    (Sec. 3.4 kernel 1); absb_plan computes the host copy        */
   const int32_t* budget_host;   /* host [Bt]: token budget T_b >= 1 per KV head                 */
   const int32_t* budget;        /* device [Bt], same values                                     */
+  const int32_t* cap_lens_host; /* host [Bt] or NULL: the lengths the block layout is sized for,
+                                   >= seq_lens_host.  With it, cent_off is laid out for
+                                   ceil(cap_b/B_h) blocks per segment, of which the first
+                                   N_s = ceil(L_b/B_h) are in use: contexts can then grow in place
+                                   (absb_append_token).  NULL = the tight layout of Sec. 3.4.   */
 } absb_batch;
 
 /* Sizes derived on the host from a (layer, batch) pair.  Only the host fields of `batch`
  * are read (seq_lens_host, budget_host); device pointers may be NULL here.
- *   cent_off_host [Bt*Hkv+1] : prefix sums of N_s = ceil(L_b/B_h)           (may be NULL)
- *   total_centroids          : off[Bt*Hkv]
+ *   cent_off_host [Bt*Hkv+1] : prefix sums of N_s = ceil(L_b/B_h), or of ceil(cap_b/B_h) when
+ *                              cap_lens_host is given                          (may be NULL)
+ *   total_centroids          : off[Bt*Hkv] (rows of the code array, used or not)
  *   sel_stride               : max_s K_s, K_s = min(N_s, ceil(T_b/B_h)) (Sec. 3.4 kernel 2)
  *   workspace_bytes          : enough for any entry point below on this (layer, batch) */
 ABSB_API int absb_plan(const absb_layer* layer, const absb_batch* batch, int32_t* cent_off_host,
@@ -141,7 +147,8 @@ ABSB_API int absb_build_centroids(const absb_layer* layer, const absb_batch* bat
  *                       Q * qscale[s][d..2d)), P_c / Q_c the sums of the group's positive /
  *                       negative q_g[c]: the bound's larger product is the one whose extremum
  *                       matches the sign of q_c, which keeps the group score linear in the codes.
- *   score_exp [Bt*Hkv] i32, optional (NULL ok): e with w ~= wq * 2^e */
+ *   score_exp [Bt*Hkv] i32, optional (NULL ok): e with w ~= wq * 2^e
+ * Reads batch->seq_lens and batch->cent_off. */
 ABSB_API int absb_score(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
                         const float* qscale, int32_t* scores, int32_t* score_exp, void* stream);
 
@@ -177,6 +184,29 @@ ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch,
                                const uint8_t* codes, const float* qscale, const void* k_cache,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
                                int32_t* sel_cnt_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Keeping the store current while decoding, without a rebuild (the paper notes that recomputing
+ * every centroid is too expensive, Sec. 1 and 3.2, and leaves the mechanism open; this is the
+ * reading taken here).  The pooled state of each segment's LAST block is kept in binary32 in
+ * `tail` [Bt*Hkv][R*d]: the running sum of its keys in token order (mean pooling), or its running
+ * maxima then minima (max-min pooling).
+ *
+ * absb_tail_init: computes `tail` from the K cache at the lengths in batch->seq_lens (call once
+ * after absb_build_centroids).
+ *
+ * absb_append_token: every request has grown by ONE token: batch->seq_lens(_host) already count
+ * it and its key is in the K cache at position L_b - 1.  The key is folded into `tail` with the
+ * single binary32 operations a rebuild would use (so the block's value is bit-identical to a
+ * rebuild's), and the 4-bit row of the block that holds it is re-emitted under the store's FROZEN
+ * qscale/qmin: code = clamp(rint((value - qmin) * (1/qscale)), 0, 15), 0 where qscale is 0.  Rows
+ * of closed blocks never change; qscale/qmin are only refreshed by absb_build_centroids.  When the
+ * token opens a new block the row off[s] + N_s - 1 is written for the first time: the layout must
+ * have room for it (batch->cap_lens_host). */
+ABSB_API int absb_tail_init(const absb_layer* layer, const absb_batch* batch, const void* k_cache, float* tail,
+                            void* stream);
+ABSB_API int absb_append_token(const absb_layer* layer, const absb_batch* batch, const void* k_cache,
+                               uint8_t* codes, const float* qscale, const float* qmin, float* tail,
+                               void* stream);
 
 /* Offline calibration of the per-head block sizes (Sec. 3.2).  Two pieces; the loop over
  * calibration samples and candidate sizes around them uses the entry points above.

@@ -23,7 +23,7 @@ TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO = 0, 1, 2
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = ("absb_plan", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
-           "absb_decode_fused", "absb_head_recall", "absb_assign_block_sizes", "absb_stream_read",
+           "absb_decode_fused", "absb_tail_init", "absb_append_token", "absb_head_recall", "absb_assign_block_sizes", "absb_stream_read",
            "absb_strerror", "absb_set_tuning")
 
 
@@ -46,7 +46,8 @@ class _Batch(C.Structure):
     _fields_ = [("batch", C.c_int32), ("pt_stride", C.c_int32),
                 ("seq_lens_host", C.POINTER(C.c_int32)), ("seq_lens", C.c_void_p),
                 ("page_table", C.c_void_p), ("cent_off", C.c_void_p),
-                ("budget_host", C.POINTER(C.c_int32)), ("budget", C.c_void_p)]
+                ("budget_host", C.POINTER(C.c_int32)), ("budget", C.c_void_p),
+                ("cap_lens_host", C.POINTER(C.c_int32))]
 
 
 _lib = None
@@ -148,6 +149,7 @@ class Batch:
     cent_off: object = None
     budget: object = None
     pt_stride: Optional[int] = None
+    cap_lens_host: Optional[Sequence[int]] = None
 
     def __setattr__(self, name, value):
         object.__setattr__(self, name, value)
@@ -162,8 +164,9 @@ class Batch:
             pts = self.pt_stride
             if pts is None:
                 pts = int(self.page_table.shape[1]) if self.page_table is not None else 0
+            self._cl, cl_p = _i32_host(self.cap_lens_host)
             self._c = _Batch(len(self._sl), int(pts), sl_p, _ptr(self.seq_lens), _ptr(self.page_table),
-                             _ptr(self.cent_off), bg_p, _ptr(self.budget))
+                             _ptr(self.cent_off), bg_p, _ptr(self.budget), cl_p)
         return self._c
 
 
@@ -222,6 +225,18 @@ def absb_decode_fused(layer: Layer, batch: Batch, q, codes, qscale, k_cache, v_c
                                     _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(sel_idx_out), _ptr(sel_cnt_out),
                                     _ptr(workspace), C.c_size_t(_nbytes(workspace)), _stream(stream)),
            "absb_decode_fused")
+
+
+def absb_tail_init(layer: Layer, batch: Batch, k_cache, tail, stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_tail_init(C.byref(cl), C.byref(cb), _ptr(k_cache), _ptr(tail), _stream(stream)),
+           "absb_tail_init")
+
+
+def absb_append_token(layer: Layer, batch: Batch, k_cache, codes, qscale, qmin, tail, stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_append_token(C.byref(cl), C.byref(cb), _ptr(k_cache), _ptr(codes), _ptr(qscale), _ptr(qmin),
+                                    _ptr(tail), _stream(stream)), "absb_append_token")
 
 
 def absb_head_recall(layer: Layer, batch: Batch, lse_selected, lse_dense, recall, stream=None) -> None:

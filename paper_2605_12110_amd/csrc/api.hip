@@ -49,6 +49,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   g.log2_page = ilog2(P);
   g.pt_stride = batch->pt_stride;
   g.repr = layer->block_repr;
+  g.tight = batch->cap_lens_host ? 0 : 1;
   g.sink_tokens = layer->sink_tokens;
   g.recent_tokens = layer->recent_tokens;
   g.s_page = sp;
@@ -68,6 +69,8 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   for (int b = 0; b < Bt; ++b) {
     const int64_t L = batch->seq_lens_host[b];
     if (L < 1) return ABSB_ERR_BAD_SHAPE;
+    const int64_t cap = batch->cap_lens_host ? batch->cap_lens_host[b] : L;  // the layout's length
+    if (cap < L) return ABSB_ERR_BAD_SHAPE;
     if (L > max_len) max_len = L;
     if (batch->budget_host && batch->budget_host[b] < 1) return ABSB_ERR_BAD_SHAPE;
     for (int h = 0; h < Hkv; ++h) {
@@ -80,7 +83,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
         if (K > p.sel_stride) p.sel_stride = (int32_t)K;
       }
       if (sel_stride_in > 0 && sel_stride_in < K) K = sel_stride_in;
-      p.total += N;
+      p.total += ceil_div(cap, B);
       const int64_t cb = std::max<int64_t>(16, p.build_chunk_tokens / B);  // as build_chunk_blocks() on the device
       if (ceil_div(N, cb) > p.build_max_chunks) p.build_max_chunks = (int32_t)ceil_div(N, cb);
       if (N > p.max_blocks) p.max_blocks = (int32_t)N;
@@ -180,7 +183,8 @@ int absb_plan(const absb_layer* layer, const absb_batch* batch, int32_t* cent_of
     for (int b = 0; b < g.Bt; ++b)
       for (int h = 0; h < g.Hkv; ++h) {
         const int64_t B = layer->block_size[h];
-        acc += (int32_t)((batch->seq_lens_host[b] + B - 1) / B);
+        const int64_t cap = batch->cap_lens_host ? batch->cap_lens_host[b] : batch->seq_lens_host[b];
+        acc += (int32_t)((cap + B - 1) / B);
         cent_off_host[b * g.Hkv + h + 1] = acc;
       }
   }
@@ -210,8 +214,8 @@ int absb_score(const absb_layer* layer, const absb_batch* batch, const void* q, 
   Plan p;
   int rc = make_plan(layer, batch, false, 0, &g, &p);
   if (rc != ABSB_OK) return rc;
-  if (!q || !codes || !qscale || !scores || !batch->cent_off) return ABSB_ERR_NULL;
-  return launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, scores, score_exp,
+  if (!q || !codes || !qscale || !scores || !batch->cent_off || !batch->seq_lens) return ABSB_ERR_NULL;
+  return launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, batch->seq_lens, scores, score_exp,
                       static_cast<hipStream_t>(stream));
 }
 
@@ -224,7 +228,7 @@ int absb_topk(const absb_layer* layer, const absb_batch* batch, const int32_t* s
   int rc = make_plan(layer, batch, true, 0, &g, &p);
   if (rc != ABSB_OK) return rc;
   if (!scores || !sel_idx || !sel_cnt || !batch->cent_off || !batch->budget) return ABSB_ERR_NULL;
-  if (g.recent_tokens > 0 && !batch->seq_lens) return ABSB_ERR_NULL;
+  if (!batch->seq_lens) return ABSB_ERR_NULL;
   if (sel_stride < p.sel_stride) return ABSB_ERR_BAD_SHAPE;
   return launch_topk(g, p, scores, batch->cent_off, batch->budget, batch->seq_lens, sel_idx, sel_cnt, sel_stride, nullptr,
                      static_cast<hipStream_t>(stream));
@@ -265,7 +269,7 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   int32_t* scores = reinterpret_cast<int32_t*>(ws + p.ws_scores);
   int32_t* sel_idx = sel_idx_out ? sel_idx_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_idx);
   int32_t* sel_cnt = sel_cnt_out ? sel_cnt_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_cnt);
-  rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, scores, nullptr, st);
+  rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, batch->seq_lens, scores, nullptr, st);
   if (rc != ABSB_OK) return rc;
   // the selection kernel also clears the split counters of the attention kernel behind it
   rc = launch_topk(g, p, scores, batch->cent_off, batch->budget, batch->seq_lens, sel_idx, sel_cnt, p.sel_stride,
@@ -273,6 +277,28 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   if (rc != ABSB_OK) return rc;
   return launch_decode(g, p, layer->dtype, resolve_scale(layer), q, k_cache, v_cache, batch->page_table,
                        batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, true, st);
+}
+
+int absb_tail_init(const absb_layer* layer, const absb_batch* batch, const void* k_cache, float* tail, void* stream) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!k_cache || !tail || !batch->seq_lens || !batch->page_table) return ABSB_ERR_NULL;
+  return launch_append(g, p, layer->dtype, false, k_cache, batch->page_table, batch->seq_lens, nullptr, nullptr,
+                       nullptr, nullptr, tail, static_cast<hipStream_t>(stream));
+}
+
+int absb_append_token(const absb_layer* layer, const absb_batch* batch, const void* k_cache, uint8_t* codes,
+                      const float* qscale, const float* qmin, float* tail, void* stream) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!k_cache || !codes || !qscale || !qmin || !tail || !batch->seq_lens || !batch->page_table || !batch->cent_off)
+    return ABSB_ERR_NULL;
+  return launch_append(g, p, layer->dtype, true, k_cache, batch->page_table, batch->seq_lens, batch->cent_off, codes,
+                       qscale, qmin, tail, static_cast<hipStream_t>(stream));
 }
 
 int absb_head_recall(const absb_layer* layer, const absb_batch* batch, const float* lse_selected,

@@ -53,15 +53,15 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_pool_kernel(BuildParams p
   constexpr int W = ABSB_HEAD_DIM * (REP + 1);
   const int s = blockIdx.y, chunk = blockIdx.x;
   const int off = p.cent_off[s];
-  const int N = p.cent_off[s + 1] - off;
   const int b = s / p.g.Hkv, h = s % p.g.Hkv;
   const int lb = p.g.heads.log2_block[h], lP = p.g.log2_page;
+  const int L = p.seq_lens[b];
+  const int N = blocks_in_use(p.g.tight, p.cent_off[s + 1] - off, p.seq_lens, b, lb);
   const int cb = build_chunk_blocks(p.chunk_tokens, lb);
   const int j0 = chunk * cb;
   if (j0 >= N) return;
   const int jend = min(N, j0 + cb);
   const int B = 1 << lb;
-  const int L = p.seq_lens[b];
   const int tid = threadIdx.x, grp = tid >> 4, li = tid & 15;
   const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
   const size_t lane_off = (size_t)h * p.g.s_head + (size_t)li * 8;
@@ -189,7 +189,8 @@ __global__ __launch_bounds__(PARAMS_THREADS) void build_params_kernel(BuildParam
   const int s = blockIdx.x, cl = threadIdx.x / ABSB_HEAD_DIM;
   const int ch = blockIdx.y * ABSB_HEAD_DIM + (threadIdx.x & (ABSB_HEAD_DIM - 1));  // value index in the row
   const int h = s % p.g.Hkv;
-  const int N = p.cent_off[s + 1] - p.cent_off[s];
+  const int N = blocks_in_use(p.g.tight, p.cent_off[s + 1] - p.cent_off[s], p.seq_lens, s / p.g.Hkv,
+                              p.g.heads.log2_block[h]);
   const int cb = build_chunk_blocks(p.chunk_tokens, p.g.heads.log2_block[h]);
   const int nchunks = (N + cb - 1) / cb;
   float mn = __builtin_inff(), mx = -__builtin_inff();
@@ -236,8 +237,9 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_codes_kernel(BuildParams 
   const int W = ABSB_HEAD_DIM * (p.g.repr + 1);
   const int s = blockIdx.y, v = blockIdx.z;
   const int off = p.cent_off[s];
-  const int N = p.cent_off[s + 1] - off;
-  const int cb = build_chunk_blocks(p.chunk_tokens, p.g.heads.log2_block[s % p.g.Hkv]);
+  const int lb = p.g.heads.log2_block[s % p.g.Hkv];
+  const int N = blocks_in_use(p.g.tight, p.cent_off[s + 1] - off, p.seq_lens, s / p.g.Hkv, lb);
+  const int cb = build_chunk_blocks(p.chunk_tokens, lb);
   const int j0 = blockIdx.x * cb;
   if (j0 >= N) return;
   const int jend = min(N, j0 + cb);
@@ -266,6 +268,132 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_codes_kernel(BuildParams 
     // of this word is value col + n
     *reinterpret_cast<uint32_t*>(p.codes + ((size_t)off + j) * (W / 2) + col / 2) = packed;
   }
+}
+
+// Decode-time maintenance.  A 16-lane row-group per segment (each lane 8 channels): folds the key
+// of the newest token (position L - 1) into the pooled state of the segment's last block and
+// re-emits that block's 4-bit row under the store's frozen ranges; with APPEND == false it only
+// recomputes the state from the cache (the tokens of the last block, in order).
+struct AppendParams {
+  const uint16_t* k;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  const int32_t* cent_off;
+  uint8_t* codes;
+  const float* qscale;
+  const float* qmin;
+  float* tail;  // [nseg][W]
+  int32_t nseg;
+  Geometry g;
+};
+
+template <int DT, int REP, bool APPEND>
+__global__ __launch_bounds__(BUILD_THREADS) void append_kernel(AppendParams p) {
+  constexpr int W = ABSB_HEAD_DIM * (REP + 1);
+  const int tid = threadIdx.x, grp = tid >> 4, li = tid & 15;
+  const int s = blockIdx.x * BUILD_GROUPS + grp;
+  if (s >= p.nseg) return;
+  const int b = s / p.g.Hkv, h = s % p.g.Hkv;
+  const int lb = p.g.heads.log2_block[h], lP = p.g.log2_page;
+  const int L = p.seq_lens[b];
+  const int t_new = L - 1, j = t_new >> lb, t0 = j << lb;
+  const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
+  const size_t lane_off = (size_t)h * p.g.s_head + (size_t)li * 8;
+  float* tail = p.tail + (size_t)s * W + li * 8;
+
+  float st[REP + 1][8];
+  const int t_first = APPEND ? t_new : t0;  // APPEND: one key on top of the stored state
+  if (APPEND && t_new != t0) {
+#pragma unroll
+    for (int v = 0; v <= REP; ++v) {
+      const float4 a = *reinterpret_cast<const float4*>(tail + v * ABSB_HEAD_DIM);
+      const float4 z = *reinterpret_cast<const float4*>(tail + v * ABSB_HEAD_DIM + 4);
+      st[v][0] = a.x, st[v][1] = a.y, st[v][2] = a.z, st[v][3] = a.w;
+      st[v][4] = z.x, st[v][5] = z.y, st[v][6] = z.z, st[v][7] = z.w;
+    }
+  }
+  for (int t = t_first; t <= t_new; ++t) {
+    const int page = pt[t >> lP];
+    const uint4 row = *reinterpret_cast<const uint4*>(p.k + (size_t)page * p.g.s_page + lane_off +
+                                                      (size_t)(t & ((1 << lP) - 1)) * p.g.s_tok);
+    const uint32_t w[4] = {row.x, row.y, row.z, row.w};
+    const bool first = t == t0;  // the block's first key starts the state
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const float lo = Elem<DT>::lo(w[c]), hi = Elem<DT>::hi(w[c]);
+      if (REP) {
+        st[0][2 * c] = first ? lo : fmaxf(st[0][2 * c], lo);
+        st[0][2 * c + 1] = first ? hi : fmaxf(st[0][2 * c + 1], hi);
+        st[REP][2 * c] = first ? lo : fminf(st[REP][2 * c], lo);
+        st[REP][2 * c + 1] = first ? hi : fminf(st[REP][2 * c + 1], hi);
+      } else {
+        st[0][2 * c] = first ? lo : st[0][2 * c] + lo;
+        st[0][2 * c + 1] = first ? hi : st[0][2 * c + 1] + hi;
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v <= REP; ++v) {
+    *reinterpret_cast<float4*>(tail + v * ABSB_HEAD_DIM) = make_float4(st[v][0], st[v][1], st[v][2], st[v][3]);
+    *reinterpret_cast<float4*>(tail + v * ABSB_HEAD_DIM + 4) = make_float4(st[v][4], st[v][5], st[v][6], st[v][7]);
+  }
+  if (!APPEND) return;
+
+  const float fn = (float)(t_new - t0 + 1);
+  const size_t row_at = ((size_t)p.cent_off[s] + j) * (W / 2);
+#pragma unroll
+  for (int v = 0; v <= REP; ++v) {
+    const int col = v * ABSB_HEAD_DIM + li * 8;
+    uint32_t packed = 0;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const float value = REP ? st[v][c] : st[v][c] / fn;
+      const float sc = p.qscale[(size_t)s * W + col + c];
+      float r = 0.0f;
+      if (sc > 0.0f) {
+        const float inv = 1.0f / sc;
+        const float x = value - p.qmin[(size_t)s * W + col + c];
+        r = __builtin_rintf(x * inv);
+        r = fminf(fmaxf(r, 0.0f), 15.0f);  // a NaN ends up at 0
+      }
+      packed |= (uint32_t)r << (4 * c);
+    }
+    *reinterpret_cast<uint32_t*>(p.codes + row_at + col / 2) = packed;
+  }
+}
+
+template <int DT, int REP>
+static void launch_append_kernel(bool append, const AppendParams& p, hipStream_t stream) {
+  const dim3 grid((unsigned)((p.nseg + BUILD_GROUPS - 1) / BUILD_GROUPS)), block(BUILD_THREADS);
+  if (append)
+    hipLaunchKernelGGL((append_kernel<DT, REP, true>), grid, block, 0, stream, p);
+  else
+    hipLaunchKernelGGL((append_kernel<DT, REP, false>), grid, block, 0, stream, p);
+}
+
+int launch_append(const Geometry& g, const Plan& pl, int dtype, bool append, const void* k_cache,
+                  const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off, uint8_t* codes,
+                  const float* qscale, const float* qmin, float* tail, hipStream_t stream) {
+  AppendParams p;
+  p.k = static_cast<const uint16_t*>(k_cache);
+  p.page_table = page_table;
+  p.seq_lens = seq_lens;
+  p.cent_off = cent_off;
+  p.codes = codes;
+  p.qscale = qscale;
+  p.qmin = qmin;
+  p.tail = tail;
+  p.nseg = pl.nseg;
+  p.g = g;
+  if (dtype == ABSB_F16 && g.repr == ABSB_REPR_MEAN)
+    launch_append_kernel<ABSB_F16, 0>(append, p, stream);
+  else if (dtype == ABSB_F16)
+    launch_append_kernel<ABSB_F16, 1>(append, p, stream);
+  else if (g.repr == ABSB_REPR_MEAN)
+    launch_append_kernel<ABSB_BF16, 0>(append, p, stream);
+  else
+    launch_append_kernel<ABSB_BF16, 1>(append, p, stream);
+  return check_launch();
 }
 
 int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cache, const int32_t* page_table,

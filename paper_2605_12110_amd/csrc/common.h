@@ -25,7 +25,7 @@ struct Geometry {
   int32_t pt_stride;
   int32_t repr;       // absb_repr: vectors per block = repr + 1
   int32_t sink_tokens, recent_tokens;  // forced blocks of the selection (0 = none)
-  int32_t pad_;
+  int32_t tight;      // 1: the block layout is that of the current lengths (off[s+1] - off[s] = N_s)
   int64_t s_page, s_head, s_tok;  // element strides of the K/V caches
   HeadTable heads;
 };
@@ -62,8 +62,13 @@ ABSB_HIDDEN int launch_build(const Geometry& g, const Plan& pl, int dtype, const
                              const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
                              uint8_t* codes, float* qscale, float* qmin, char* ws, hipStream_t stream);
 ABSB_HIDDEN int launch_score(const Geometry& g, const Plan& pl, int dtype, const void* q, const uint8_t* codes,
-                             const float* qscale, const int32_t* cent_off, int32_t* scores, int32_t* score_exp,
-                             hipStream_t stream);
+                             const float* qscale, const int32_t* cent_off, const int32_t* seq_lens, int32_t* scores,
+                             int32_t* score_exp, hipStream_t stream);
+// append == false: only (re)compute the tail state from the cache
+ABSB_HIDDEN int launch_append(const Geometry& g, const Plan& pl, int dtype, bool append, const void* k_cache,
+                              const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
+                              uint8_t* codes, const float* qscale, const float* qmin, float* tail,
+                              hipStream_t stream);
 ABSB_HIDDEN int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const int32_t* cent_off,
                             const int32_t* budget, const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
                             int32_t sel_stride,
@@ -83,6 +88,13 @@ inline int check_launch() { return hipGetLastError() == hipSuccess ? ABSB_OK : A
 
 // ------------------------------------------------------------------ device helpers
 #ifdef __HIPCC__
+// Blocks in use of a segment: all rows of a tight layout (no need to wait for the length then);
+// otherwise N_s = ceil(L_b / B_h), never more than the layout has rows for.
+__device__ __forceinline__ int blocks_in_use(bool tight, int rows, const int32_t* seq_lens, int b, int log2_block) {
+  if (tight) return rows;
+  return min(rows, (int)(((int64_t)seq_lens[b] + (1 << log2_block) - 1) >> log2_block));
+}
+
 template <typename To, typename From>
 __device__ __forceinline__ To bitcast(From v) {
   return __builtin_bit_cast(To, v);

@@ -29,9 +29,11 @@ struct ScoreParams {
   const uint8_t* codes;     // [total][64 * R], R vectors per block
   const float* qscale;      // [nseg][128 * R]
   const int32_t* cent_off;  // [nseg+1]
+  const int32_t* seq_lens;  // [Bt]
+  HeadTable heads;
   int32_t* scores;          // [total]
   int32_t* score_exp;       // [nseg] or null
-  int32_t Hq, Hkv, G, chunk;
+  int32_t Hq, Hkv, G, chunk, tight;
 };
 
 constexpr int SCORE_PLANES = 5;
@@ -49,11 +51,11 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
   constexpr int W = ABSB_HEAD_DIM * R;       // weights = values per block
   constexpr int ROW_BYTES = W / 2;
   const int s = blockIdx.y;
+  const int b = s / p.Hkv, h = s % p.Hkv;
   const int off = p.cent_off[s];
-  const int N = p.cent_off[s + 1] - off;
+  const int N = blocks_in_use(p.tight, p.cent_off[s + 1] - off, p.seq_lens, b, p.heads.log2_block[h]);
   const int j0 = blockIdx.x * p.chunk;
   if (j0 >= N) return;
-  const int b = s / p.Hkv, h = s % p.Hkv;
   const int tid = threadIdx.x;
 
   __shared__ float s_absmax[4];
@@ -172,13 +174,16 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
 }
 
 int launch_score(const Geometry& g, const Plan& pl, int dtype, const void* q, const uint8_t* codes,
-                 const float* qscale, const int32_t* cent_off, int32_t* scores, int32_t* score_exp,
-                 hipStream_t stream) {
+                 const float* qscale, const int32_t* cent_off, const int32_t* seq_lens, int32_t* scores,
+                 int32_t* score_exp, hipStream_t stream) {
   ScoreParams p;
   p.q = static_cast<const uint16_t*>(q);
   p.codes = codes;
   p.qscale = qscale;
   p.cent_off = cent_off;
+  p.seq_lens = seq_lens;
+  p.heads = g.heads;
+  p.tight = g.tight;
   p.scores = scores;
   p.score_exp = score_exp;
   p.Hq = g.Hq;

@@ -26,12 +26,12 @@ struct TopkParams {
   const int32_t* scores;
   const int32_t* cent_off;
   const int32_t* budget;  // [Bt]
-  const int32_t* seq_lens;  // [Bt]; read only when recent_tokens > 0
+  const int32_t* seq_lens;  // [Bt]
   int32_t sink_tokens, recent_tokens;  // blocks holding these tokens are selected ahead of every score
   int32_t* sel_idx;
   int32_t* sel_cnt;
   int32_t* tickets;  // [nseg] or null: split counters of the attention kernel that follows, cleared here
-  int32_t sel_stride, Hkv;
+  int32_t sel_stride, Hkv, tight;
   HeadTable heads;
 };
 
@@ -111,8 +111,8 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
   const int s = blockIdx.x;
   const int b = s / p.Hkv, h = s % p.Hkv;
   const int off = p.cent_off[s];
-  const int Nall = p.cent_off[s + 1] - off;
   const int lb = p.heads.log2_block[h];
+  const int Nall = blocks_in_use(p.tight, p.cent_off[s + 1] - off, p.seq_lens, b, lb);
   const int T = p.budget[b];
   int K = (int)(((int64_t)T + (1 << lb) - 1) >> lb);
   K = min(min(K, Nall), p.sel_stride);
@@ -326,6 +326,7 @@ int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const 
   p.cent_off = cent_off;
   p.budget = budget;
   p.seq_lens = seq_lens;
+  p.tight = g.tight;
   p.sink_tokens = g.sink_tokens;
   p.recent_tokens = g.recent_tokens;
   p.sel_idx = sel_idx;

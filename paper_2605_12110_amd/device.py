@@ -22,9 +22,11 @@ class DeviceWorkload:
 
     def __init__(self, wl, device: str = "cuda:0", budget: Optional[np.ndarray] = None,
                  block_repr: int = absb.REPR_MEAN, block_size: Optional[np.ndarray] = None,
-                 share: Optional["DeviceWorkload"] = None, sink_tokens: int = 0, recent_tokens: int = 0):
+                 share: Optional["DeviceWorkload"] = None, sink_tokens: int = 0, recent_tokens: int = 0,
+                 cap_lens: Optional[np.ndarray] = None):
         """`block_size` / `budget` override the workload's; `share` reuses another holder's resident
-        caches, queries, lengths and page table (same workload under other block sizes or budgets)."""
+        caches, queries, lengths and page table (same workload under other block sizes or budgets);
+        `cap_lens` lays the store out for contexts that grow up to those lengths (set_lens/append)."""
         self.wl = wl
         self.device = device
         tdt = torch.float16 if wl.dtype == absb.F16 else torch.bfloat16
@@ -48,7 +50,15 @@ class DeviceWorkload:
         self.budget = _up(budget.astype(np.int32), None, device)
         self.batch = absb.Batch(seq_lens_host=wl.seq_lens, budget_host=budget, seq_lens=self.seq_lens,
                                 page_table=self.page_table, budget=self.budget)
-        self.plan = absb.absb_plan(self.layer, self.batch)
+        if cap_lens is not None:
+            # buffers are sized for the longest contexts; the layout (offsets) stays that of cap_lens
+            cap = np.asarray(cap_lens, dtype=np.int32)
+            self.batch.cap_lens_host = cap
+            self.batch.seq_lens_host = cap
+            self.plan = absb.absb_plan(self.layer, self.batch)
+            self.batch.seq_lens_host = wl.seq_lens
+        else:
+            self.plan = absb.absb_plan(self.layer, self.batch)
         self.cent_off = _up(self.plan.cent_off, None, device)
         self.batch.cent_off = self.cent_off
         nseg = wl.batch * wl.num_kv_heads
@@ -64,6 +74,7 @@ class DeviceWorkload:
         self.sel_cnt = torch.empty((nseg,), dtype=torch.int32, device=device)
         self.out = torch.empty((wl.batch, wl.num_q_heads, wl.head_dim), dtype=tdt, device=device)
         self.lse = torch.empty((wl.batch, wl.num_q_heads), dtype=torch.float32, device=device)
+        self.tail = torch.empty((nseg, width), dtype=torch.float32, device=device)
         # poison the workspace: no entry point may depend on its previous contents
         self.workspace = torch.full((self.plan.workspace_bytes + 256,), 0xA5, dtype=torch.uint8, device=device)
 
@@ -71,6 +82,20 @@ class DeviceWorkload:
     def build(self, stream=None):
         absb.absb_build_centroids(self.layer, self.batch, self.k_cache, self.codes, self.qscale, self.qmin,
                                   self.workspace, stream)
+
+    # -- growing contexts
+    def set_lens(self, lens):
+        """New context lengths (within cap_lens); the keys of the new tokens are already in the cache."""
+        lens = np.asarray(lens, dtype=np.int32)
+        self.seq_lens.copy_(torch.from_numpy(lens))
+        self.batch.seq_lens_host = lens
+
+    def tail_init(self, stream=None):
+        absb.absb_tail_init(self.layer, self.batch, self.k_cache, self.tail, stream)
+
+    def append_token(self, stream=None):
+        absb.absb_append_token(self.layer, self.batch, self.k_cache, self.codes, self.qscale, self.qmin,
+                               self.tail, stream)
 
     def load_store(self, codes: np.ndarray, qscale: np.ndarray, qmin: np.ndarray):
         """Install a centroid store computed elsewhere (e.g. by the oracle, for stage-isolated tests)."""

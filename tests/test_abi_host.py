@@ -192,7 +192,8 @@ def test_selection_rejects_segments_beyond_its_capacity_before_any_launch():
     L = (8 << 17) + 1                                        # 131073 blocks of 8 tokens
     layer = _layer(num_q_heads=1, num_kv_heads=1, block_size=[8], kv_strides=(64 * 128, 64 * 128, 128))
     fake = torch.zeros(4, dtype=torch.int32)
-    batch = absb.Batch(seq_lens_host=[L], budget_host=[64], pt_stride=(L + 63) // 64, cent_off=fake, budget=fake)
+    batch = absb.Batch(seq_lens_host=[L], budget_host=[64], pt_stride=(L + 63) // 64, cent_off=fake, budget=fake,
+                       seq_lens=fake)
     with pytest.raises(absb.AbsbError) as e:
         absb.absb_topk(layer, batch, fake, fake, fake, 8, stream=0)
     assert e.value.status == absb.ERR_UNSUPPORTED
@@ -214,4 +215,16 @@ def test_block_size_assignment_rule_matches_the_oracle_on_the_host():
     assert e.value.status == absb.ERR_BAD_BLOCK_SIZE
     with pytest.raises(absb.AbsbError) as e:
         absb.absb_assign_block_sizes(rec, [8, 32, 16, 64, 128], 0.9)
+    assert e.value.status == absb.ERR_BAD_SHAPE
+
+
+def test_plan_lays_the_store_out_for_the_capacity_lengths_when_given():
+    layer = _layer()
+    tight = absb.absb_plan(layer, _batch((1000,), (64,)))
+    roomy = absb.absb_plan(layer, absb.Batch(seq_lens_host=[1000], budget_host=[64], pt_stride=64, cap_lens_host=[4096]))
+    full = absb.absb_plan(layer, _batch((4096,), (64,)))
+    assert np.array_equal(roomy.cent_off, full.cent_off) and roomy.total_centroids == full.total_centroids
+    assert roomy.sel_stride == tight.sel_stride                       # selection sizes follow the current lengths
+    with pytest.raises(absb.AbsbError) as e:                          # a layout shorter than the context
+        absb.absb_plan(layer, absb.Batch(seq_lens_host=[1000], budget_host=[64], pt_stride=64, cap_lens_host=[999]))
     assert e.value.status == absb.ERR_BAD_SHAPE

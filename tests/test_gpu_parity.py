@@ -463,3 +463,85 @@ def test_forced_blocks_on_a_long_segment_with_many_tiles():
         chosen = set(sel[s, :cnt[s]].tolist())
         want = set(range(-(-128 // B))) | set(range((65536 - 1024) // B, 65536 // B))
         assert (want <= chosen) if len(want) <= cnt[s] else (chosen <= want)
+
+
+# ------------------------------------------------------------------ growing contexts (store maintenance)
+def _view_at(wl, lens):
+    import copy
+    v = copy.copy(wl)
+    v.seq_lens = np.asarray(lens, np.int32)
+    return v
+
+
+def _tight(dw, lens):
+    """Rows in use of the capacity-layout code array, in the tight layout of the given lengths."""
+    codes = dw.codes.cpu().numpy()
+    off = dw.plan.cent_off
+    rows = []
+    Hkv = dw.wl.num_kv_heads
+    for s in range(dw.nseg):
+        b, h = divmod(s, Hkv)
+        n = -(-int(lens[b]) // int(dw.block_size[h]))
+        rows.append(codes[off[s]:off[s] + n])
+    return np.concatenate(rows)
+
+
+@pytest.mark.parametrize("repr_,dtype", [(O.MEAN, synth.F16), (O.MEAN, synth.BF16), (O.MINMAX, synth.F16)])
+def test_appending_tokens_keeps_the_store_and_the_step_in_parity(repr_, dtype):
+    """Contexts grow token by token inside a layout sized for the final lengths: tail state and code
+    rows bit-exact against the oracle after every token, and the fused step on the grown store
+    (selection bit-exact, outputs within tolerance) at a few points on the way."""
+    full = synth.tiny_workload(seed=71, dtype=dtype, Bt=3, Hq=8, Hkv=2, P=16, seq_lens=(150, 97, 1300),
+                               block_size=(8, 32), budget=(32, 24, 200))
+    grow = 45
+    start = full.seq_lens - grow
+    view = _view_at(full, start)
+    dw = _dev(view, block_repr=repr_, cap_lens=full.seq_lens)
+    assert dw.plan.cent_off[-1] == O.offsets(full)[-1]                # laid out for the final lengths
+    _say(f"[case append repr={repr_} dtype={dtype}] start={start.tolist()} -> {full.seq_lens.tolist()}")
+    dw.build(); dw.tail_init(); _sync()
+    store = O.build_centroids(view, repr_)
+    tail = O.tail_state(view, repr_)
+    assert np.array_equal(_tight(dw, start), store.codes) and np.array_equal(dw.qscale.cpu().numpy(), store.qscale)
+    assert np.array_equal(dw.tail.cpu().numpy(), tail)
+    for step in range(1, grow + 1):
+        lens = start + step
+        view = _view_at(full, lens)
+        dw.wl = view
+        dw.set_lens(lens)
+        dw.append_token()
+        store, _ = O.append_token(view, store, tail)
+        _sync()
+        assert np.array_equal(dw.tail.cpu().numpy(), tail), f"tail state after {step} tokens"
+        assert np.array_equal(_tight(dw, lens), store.codes), f"code rows after {step} tokens"
+        if step in (1, 7, 8, 9, 32, grow):
+            ref = O.decode_step(view, store)
+            dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+            dw.decode_fused()
+            _check_out(dw, ref["out"], ref["lse"], f"fused step after {step} appended tokens")
+            K = dw.sel_stride
+            assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+            got = dw.sel_idx.cpu().numpy()
+            kk = min(K, ref["sel_idx"].shape[1])
+            assert np.array_equal(got[:, :kk], ref["sel_idx"][:, :kk]) and np.all(got[:, kk:] == -1)
+
+
+def test_stages_ignore_the_unused_rows_of_a_layout_sized_for_longer_contexts():
+    """A store laid out for longer contexts than the current ones: build, score, selection and the
+    step give the same results as the tight layout (the unused rows hold garbage)."""
+    full = synth.tiny_workload(seed=72, dtype=synth.F16, Bt=2, Hq=8, Hkv=4, P=16, seq_lens=(999, 2500),
+                               block_size=(128, 8, 64, 16), budget=(300, 520))
+    lens = np.array([700, 1801], np.int32)
+    view = _view_at(full, lens)
+    st = O.build_centroids(view)
+    ref = O.decode_step(view, st)
+    dw = _dev(view, cap_lens=full.seq_lens)
+    dw.codes.fill_(0xEE); dw.scores.fill_(2 ** 31 - 1)               # garbage in every row, used or not
+    dw.build(); _sync()
+    assert np.array_equal(_tight(dw, lens), st.codes)
+    assert np.array_equal(dw.qscale.cpu().numpy(), st.qscale) and np.array_equal(dw.qmin.cpu().numpy(), st.qmin)
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "capacity layout")
+    kk = min(dw.sel_stride, ref["sel_idx"].shape[1])
+    assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+    assert np.array_equal(dw.sel_idx.cpu().numpy()[:, :kk], ref["sel_idx"][:, :kk])
