@@ -18,6 +18,10 @@
 // digits give the exact threshold tau, and blocks equal to tau are admitted in index order through
 // a second bitmap.  Segments longer than 16384 blocks run the same code with keys re-read from L2.
 // Wave-level reductions and scans use DPP row operations, not LDS-crossbar shuffles.
+//
+// Optional policy (off by default): the blocks that hold the first sink_tokens or the last
+// recent_tokens tokens are always selected.  They form a prefix and a suffix of the segment, so
+// they are written to the list directly and the blocks in between compete for what is left of K_s.
 #include "common.h"
 
 namespace absb {
