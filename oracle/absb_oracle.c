@@ -647,3 +647,84 @@ void orc_append_token(int dtype, int repr, int Bt, int Hkv, int d, int P, int64_
         }
     }
 }
+
+/* ---- quantization variants for the design-space study of Sec. 3.3 (bit widths 2 / 4 / 8,
+ * symmetric or asymmetric, always one scale per (segment, channel)).  Codes are kept one per
+ * byte.  Asymmetric: code in [0, 2^bits - 1], value ~= code * scale + min, scale = (max - min) /
+ * (2^bits - 1): with bits = 4 this is O2/O3 above.  Symmetric: zero-centred, code in
+ * [-(2^(bits-1) - 1), 2^(bits-1) - 1] stored with that offset added, value ~= signed code * scale,
+ * scale = max|x| / (2^(bits-1) - 1), no zero-point.  Same binary32 steps as O2/O3. */
+void orc_quantize_variant(int nseg, int d, const int64_t *off, const float *cent, int bits, int symmetric,
+                          float *qscale, float *qmin /* [nseg][d]; 0 when symmetric */,
+                          uint8_t *codes /* [total][d] */) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < nseg; ++s) {
+        for (int ch = 0; ch < d; ++ch) {
+            float mn = INFINITY, mx = -INFINITY;
+            for (int64_t j = off[s]; j < off[s + 1]; ++j) {
+                float v = cent[j * d + ch];
+                if (v < mn) mn = v;
+                if (v > mx) mx = v;
+            }
+            float top, rng, base;
+            if (symmetric) {
+                top = (float)((1 << (bits - 1)) - 1);
+                rng = fabsf(mn) > fabsf(mx) ? fabsf(mn) : fabsf(mx);
+                base = 0.0f;
+            } else {
+                top = (float)((1 << bits) - 1);
+                rng = mx - mn;
+                base = mn;
+            }
+            float sc = 0.0f, inv = 0.0f;
+            if (off[s + 1] > off[s] && rng > 0.0f) {
+                sc = rng / top;
+                inv = top / rng;
+            }
+            if (off[s + 1] == off[s]) base = 0.0f;
+            qscale[(int64_t)s * d + ch] = sc;
+            qmin[(int64_t)s * d + ch] = base;
+            for (int64_t j = off[s]; j < off[s + 1]; ++j) {
+                float r = rintf((cent[j * d + ch] - base) * inv);
+                float lo = symmetric ? -top : 0.0f;
+                if (r < lo) r = lo;
+                if (r > top) r = top;
+                codes[j * d + ch] = (uint8_t)(int)(symmetric ? r + top : r);
+            }
+        }
+    }
+}
+
+/* Fixed-point score (as O4) on one-code-per-byte stores of either kind.  `zero` is the stored
+ * code that stands for 0 (2^(bits-1) - 1 for symmetric stores, 0 for asymmetric ones). */
+void orc_score_variant(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t *q, const uint8_t *codes,
+                       const float *qscale, int zero, const int64_t *off, int32_t *scores, int32_t *score_exp) {
+    int G = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        float w[1024];
+        int32_t wq[1024];
+        float A = 0.0f;
+        for (int ch = 0; ch < d; ++ch) {
+            float u = widen(q[((int64_t)b * Hq + h * G) * d + ch], dtype);
+            for (int g = 1; g < G; ++g) u = u + widen(q[((int64_t)b * Hq + h * G + g) * d + ch], dtype);
+            w[ch] = u * qscale[(int64_t)s * d + ch];
+            float a = fabsf(w[ch]);
+            if (a > A) A = a;
+        }
+        int ex = 0;
+        if (!(A >= 0x1p-100f) || isinf(A)) {
+            for (int ch = 0; ch < d; ++ch) wq[ch] = 0;
+        } else {
+            ex = ilogbf(A) - 14;
+            for (int ch = 0; ch < d; ++ch) wq[ch] = (int32_t)rintf(ldexpf(w[ch], -ex));
+        }
+        score_exp[s] = ex;
+        for (int64_t j = off[s]; j < off[s + 1]; ++j) {
+            int64_t acc = 0;
+            for (int ch = 0; ch < d; ++ch) acc += (int64_t)wq[ch] * ((int)codes[j * d + ch] - zero);
+            scores[j] = (int32_t)acc; /* |acc| <= 128 * 2^15 * 255 < 2^31 */
+        }
+    }
+}

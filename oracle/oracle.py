@@ -145,6 +145,28 @@ def build_centroids(wl, repr: int = MEAN) -> CentroidStore:
     return CentroidStore(off, cent, qscale, qmin, qinv, codes, repr)
 
 
+def quantize_variant(off, cent, bits: int, symmetric: bool):
+    """Sec. 3.3 design space: (qscale, qmin, codes one per byte, stored code of zero)."""
+    nseg, d = len(off) - 1, cent.shape[1]
+    cent = np.ascontiguousarray(cent, dtype=np.float32)
+    qscale = np.empty((nseg, d), np.float32)
+    qmin = np.empty((nseg, d), np.float32)
+    codes = np.zeros((cent.shape[0], d), np.uint8)
+    lib().orc_quantize_variant(C.c_int(nseg), C.c_int(d), _p(off), _p(cent), C.c_int(bits), C.c_int(int(symmetric)),
+                               _p(qscale), _p(qmin), _p(codes))
+    return qscale, qmin, codes, ((1 << (bits - 1)) - 1 if symmetric else 0)
+
+
+def score_variant(wl, off, codes, qscale, zero: int):
+    nseg = wl.batch * wl.num_kv_heads
+    scores = np.empty(int(off[-1]), np.int32)
+    ex = np.empty(nseg, np.int32)
+    lib().orc_score_variant(C.c_int(wl.dtype), C.c_int(wl.batch), C.c_int(wl.num_q_heads), C.c_int(wl.num_kv_heads),
+                            C.c_int(wl.head_dim), _p(np.ascontiguousarray(wl.q)), _p(codes), _p(qscale), C.c_int(zero),
+                            _p(off), _p(scores), _p(ex))
+    return scores, ex
+
+
 def tail_state(wl, repr: int = MEAN) -> np.ndarray:
     """Pooled state of every segment's last block (running sum, or running maxima and minima)."""
     dt, Bt, _, Hkv, d, P, sp, sh, st = _geom(wl)
