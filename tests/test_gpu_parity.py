@@ -545,3 +545,44 @@ def test_stages_ignore_the_unused_rows_of_a_layout_sized_for_longer_contexts():
     kk = min(dw.sel_stride, ref["sel_idx"].shape[1])
     assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
     assert np.array_equal(dw.sel_idx.cpu().numpy()[:, :kk], ref["sel_idx"][:, :kk])
+
+
+# ------------------------------------------------------------------ graph capture
+def test_fused_step_replays_from_a_captured_graph():
+    """The fused step enqueues kernels only (no memsets, no allocation, no synchronisation), so it can
+    be captured once and replayed: every replay, with eager work and synchronisations in between,
+    must give the eager step's bits, also after the query has changed in place."""
+    import torch
+    wl = synth.make_workload(1, context=8192, budget=1024)
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    dw = _dev(wl)
+    dw.build()
+    dw.decode_fused(); _sync()
+    eager = dw.out.clone(); eager_sel = dw.sel_idx.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        dw.decode_fused()                                   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            dw.decode_fused()
+    torch.cuda.current_stream().wait_stream(side)
+    _sync()
+    for rep in range(4):
+        dw.out.fill_(float("nan")); dw.sel_idx.fill_(-7)
+        dw.workspace.fill_(0x11 * (rep + 1))                # eager work between the replays
+        _sync()
+        graph.replay()
+        _sync()
+        assert torch.equal(dw.out, eager) and torch.equal(dw.sel_idx, eager_sel), f"replay {rep}"
+    _check_out(dw, ref["out"], ref["lse"], "graph replay")
+    # new inputs in place (the next decode step's query): the replay follows them
+    wl2 = synth.make_workload(1, context=8192, budget=1024, seed=999)
+    dw.q.copy_(torch.from_numpy(wl2.q.view(np.int16)).view(dw.torch_dtype).to(dw.q.device))
+    wl.q = wl2.q
+    ref2 = O.decode_step(wl, st)
+    graph.replay()
+    _check_out(dw, ref2["out"], ref2["lse"], "graph replay, new query")
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref2["sel_idx"][:, :dw.sel_stride])
