@@ -105,7 +105,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   if (st_tok <= 0) {
     const int64_t target_wgs = 512;
     int64_t t = ceil_div(ceil_div(p.sum_tokens, target_wgs), 64) * 64;
-    if (t < 128) t = 128;
+    if (t < 128) t = p.sum_tokens / 128 >= 128 ? 128 : 64;  // one step only when two would leave the chip idle
     const int64_t cap_tok = ceil_div(ceil_div(p.max_tokens, 64), 64) * 64;
     if (t < cap_tok) t = cap_tok;
     st_tok = (int)t;
@@ -123,7 +123,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   // carving (nothing else ever writes there); behind them the three users overlap, since they
   // never run concurrently on one workspace
   p.ws_tickets = 0;
-  const size_t head = align256((size_t)p.nseg * 4);
+  const size_t head = align256((size_t)p.nseg * ABSB_TICKET_STRIDE * 4);
   size_t o = head;
   p.ws_scores = o;
   o += align256((size_t)p.total * 4);

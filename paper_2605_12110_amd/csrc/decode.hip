@@ -316,11 +316,13 @@ __global__ __launch_bounds__(DEC_THREADS, 3) void decode_kernel(DecodeParams p) 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's stores have been acknowledged
     __syncthreads();                                   // ... and so have everybody's
     if (tid == 0)
-      s_last = __hip_atomic_fetch_add(p.tickets + s, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1;
+      s_last = __hip_atomic_fetch_add(p.tickets + (size_t)s * ABSB_TICKET_STRIDE, 1, __ATOMIC_RELAXED,
+                                      __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1;
     __syncthreads();
     if (!s_last) return;
     // every counter a launch touches is back at zero when the launch ends
-    if (tid == 0) __hip_atomic_store(p.tickets + s, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0)
+      __hip_atomic_store(p.tickets + (size_t)s * ABSB_TICKET_STRIDE, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     // log-sum-exp merge: split lane `sl` of a column takes splits sl, sl + SL, ...; MRG_UNROLL of
     // them per memory round trip, folded into a running (M, Lsum, O)
@@ -394,7 +396,7 @@ __global__ __launch_bounds__(DEC_THREADS, 3) void decode_kernel(DecodeParams p) 
 // Zeroes the per-segment ticket counters when no earlier kernel of the same call has done it.
 __global__ void decode_clear_tickets_kernel(int32_t* tickets, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) tickets[i] = 0;
+  if (i < n) tickets[(size_t)i * ABSB_TICKET_STRIDE] = 0;
 }
 
 template <int DT>

@@ -152,7 +152,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_kernel(TopkParams p) {
 
   if (tid == 0) {
     p.sel_cnt[s] = K;
-    if (p.tickets) p.tickets[s] = 0;
+    if (p.tickets) p.tickets[(size_t)s * ABSB_TICKET_STRIDE] = 0;
   }
 #pragma unroll 1
   for (int i = K + tid; i < p.sel_stride; i += TOPK_THREADS) out[i] = -1;
