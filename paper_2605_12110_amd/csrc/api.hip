@@ -103,7 +103,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   // not be cut into more than 64.
   int st_tok = tuning(ABSB_TUNE_SPLIT_TOKENS);
   if (st_tok <= 0) {
-    const int64_t target_wgs = 512;
+    const int64_t target_wgs = 640;
     int64_t t = ceil_div(ceil_div(p.sum_tokens, target_wgs), 64) * 64;
     if (t < 128) t = p.sum_tokens / 128 >= 128 ? 128 : 64;  // one step only when two would leave the chip idle
     const int64_t cap_tok = ceil_div(ceil_div(p.max_tokens, 64), 64) * 64;

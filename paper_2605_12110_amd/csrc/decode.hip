@@ -97,13 +97,13 @@ __global__ __launch_bounds__(DEC_THREADS, 3) void decode_kernel(DecodeParams p) 
   const int32_t* sel = p.sel_idx + (size_t)s * p.sel_stride;
   const int pos_begin = split * p.split_tokens;
 
-  // The first step's list entries are fetched before the list length is known (the address is
-  // clamped to the list's storage, so the read is always legal); this takes one memory round
-  // trip off the dependent chain count -> entry -> page -> row.
+  // A lane's four rows of a step are four consecutive positions starting at a multiple of four:
+  // they lie in one block (B >= 8) and one page (P >= 8), so one list entry and one page-table
+  // entry serve all four.  The first step's list entry is fetched before the list length is known
+  // (the address is clamped to the list's storage, so the read is always legal); this takes one
+  // memory round trip off the dependent chain count -> entry -> page -> row.
   const int maxpos = (p.sel_stride << lb) - 1;
-  const int pos0 = pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4;
-  int sj0 = sel[min(pos0 + 0, maxpos) >> lb], sj1 = sel[min(pos0 + 1, maxpos) >> lb];
-  int sj2 = sel[min(pos0 + 2, maxpos) >> lb], sj3 = sel[min(pos0 + 3, maxpos) >> lb];
+  int sj = sel[min(pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4, maxpos) >> lb];
 
   // never beyond what the launch covers (a list longer than promised is cut, not overrun)
   const int ntok = min(p.sel_cnt[s] << lb, p.max_splits * p.split_tokens);
@@ -146,41 +146,48 @@ __global__ __launch_bounds__(DEC_THREADS, 3) void decode_kernel(DecodeParams p) 
   constexpr int STEP = DEC_WAVES * ROWS_PER_WAVE_STEP;  // positions per work-group step
   u32x4 k0, k1, k2, k3, v0, v1, v2, v3;
 
-  // Issue the 8 row loads of the step at `base` (block -> page mapping, then K and V), and put the
-  // list entries of the following step in flight behind them.  Sets the rows' validity bits.
-#define ABSB_ROW_OFFSET(r, selj, off)                                                                   \
-  {                                                                                                     \
-    const int pos = (base_) + grp * 4 + (r);                                                            \
-    const int t = ((selj) << lb) + (pos & ((1 << lb) - 1));                                             \
-    valid_next |= (uint32_t)(pos < pos_end && t < L) << (r); /* a selected last block may be partial */ \
-    const int tc = max(0, min(t, L - 1)); /* addresses stay inside the request's pages */               \
-    off = (size_t)pt[tc >> lP] * p.g.s_page + lane_off + (size_t)(tc & ((1 << lP) - 1)) * p.g.s_tok;    \
+  // The address chain list entry -> page-table entry -> row is kept two steps deep so that only
+  // the row loads themselves wait on memory inside the loop: issuing step k's rows uses the page
+  // requested during step k-1, requests the page of step k+1 (whose list entry has arrived by
+  // then) and the list entry of step k+2.
+  //   tcb: first token of the lane's four rows (clamped into the context, so every address is
+  //        legal), pg: its physical page, vb: which of the four rows are real.
+#define ABSB_GROUP_TOKEN(base_of_step)                                                                \
+  {                                                                                                   \
+    const int pos = (base_of_step) + grp * 4;                                                         \
+    const int t = (sj << lb) + (pos & ((1 << lb) - 1));                                               \
+    vb = 0;                                                                                           \
+    _Pragma("unroll") for (int r = 0; r < 4; ++r)                                                     \
+        vb |= (uint32_t)(pos + r < pos_end && t + r < L) << r; /* a selected last block may be partial */ \
+    tcb = max(0, min(t, L - 1)) & ~3;                                                                 \
+    pg = pt[tcb >> lP];                                                                               \
   }
-#define ABSB_ISSUE(base_expr)                                              \
-  {                                                                        \
-    const int base_ = (base_expr);                                         \
-    size_t off0, off1, off2, off3;                                         \
-    valid_next = 0;                                                        \
-    ABSB_ROW_OFFSET(0, sj0, off0)                                          \
-    ABSB_ROW_OFFSET(1, sj1, off1)                                          \
-    ABSB_ROW_OFFSET(2, sj2, off2)                                          \
-    ABSB_ROW_OFFSET(3, sj3, off3)                                          \
-    k0 = *reinterpret_cast<const u32x4*>(p.k + off0);                      \
-    k1 = *reinterpret_cast<const u32x4*>(p.k + off1);                      \
-    k2 = *reinterpret_cast<const u32x4*>(p.k + off2);                      \
-    k3 = *reinterpret_cast<const u32x4*>(p.k + off3);                      \
-    v0 = *reinterpret_cast<const u32x4*>(p.v + off0);                      \
-    v1 = *reinterpret_cast<const u32x4*>(p.v + off1);                      \
-    v2 = *reinterpret_cast<const u32x4*>(p.v + off2);                      \
-    v3 = *reinterpret_cast<const u32x4*>(p.v + off3);                      \
-    sj0 = sel[min(base_ + STEP + grp * 4 + 0, maxpos) >> lb];              \
-    sj1 = sel[min(base_ + STEP + grp * 4 + 1, maxpos) >> lb];              \
-    sj2 = sel[min(base_ + STEP + grp * 4 + 2, maxpos) >> lb];              \
-    sj3 = sel[min(base_ + STEP + grp * 4 + 3, maxpos) >> lb];              \
+#define ABSB_ISSUE(base_expr)                                                                         \
+  {                                                                                                   \
+    const int base_ = (base_expr);                                                                    \
+    const size_t row0 = (size_t)pg * p.g.s_page + lane_off;                                           \
+    const size_t off0 = row0 + (size_t)(min(tcb + 0, L - 1) & ((1 << lP) - 1)) * p.g.s_tok;           \
+    const size_t off1 = row0 + (size_t)(min(tcb + 1, L - 1) & ((1 << lP) - 1)) * p.g.s_tok;           \
+    const size_t off2 = row0 + (size_t)(min(tcb + 2, L - 1) & ((1 << lP) - 1)) * p.g.s_tok;           \
+    const size_t off3 = row0 + (size_t)(min(tcb + 3, L - 1) & ((1 << lP) - 1)) * p.g.s_tok;           \
+    valid_next = vb;                                                                                  \
+    k0 = *reinterpret_cast<const u32x4*>(p.k + off0);                                                 \
+    k1 = *reinterpret_cast<const u32x4*>(p.k + off1);                                                 \
+    k2 = *reinterpret_cast<const u32x4*>(p.k + off2);                                                 \
+    k3 = *reinterpret_cast<const u32x4*>(p.k + off3);                                                 \
+    v0 = *reinterpret_cast<const u32x4*>(p.v + off0);                                                 \
+    v1 = *reinterpret_cast<const u32x4*>(p.v + off1);                                                 \
+    v2 = *reinterpret_cast<const u32x4*>(p.v + off2);                                                 \
+    v3 = *reinterpret_cast<const u32x4*>(p.v + off3);                                                 \
+    ABSB_GROUP_TOKEN(base_ + STEP)                                                                    \
+    sj = sel[min(base_ + 2 * STEP + grp * 4, maxpos) >> lb];                                          \
   }
 
   int base = pos_begin + wave * ROWS_PER_WAVE_STEP;
-  uint32_t valid_next = 0;
+  uint32_t valid_next = 0, vb;
+  int tcb, pg;
+  ABSB_GROUP_TOKEN(base)                                     // first step: entry -> page, in order
+  sj = sel[min(base + STEP + grp * 4, maxpos) >> lb];        // second step's entry
   if (base < pos_end) ABSB_ISSUE(base)
   while (base < pos_end) {  // trip count depends on the wave only: every branch here is wave-uniform
     // ---- stage the step's rows in LDS
@@ -251,7 +258,7 @@ __global__ __launch_bounds__(DEC_THREADS, 3) void decode_kernel(DecodeParams p) 
     base = next;
   }
 #undef ABSB_ISSUE
-#undef ABSB_ROW_OFFSET
+#undef ABSB_GROUP_TOKEN
 
   // ---- the wave's state: m per head (lane li), l summed over the four groups, O in groups 0 (and 1)
   l += __shfl_xor(l, 16);
