@@ -31,8 +31,12 @@
  *     G = num_q_heads/num_kv_heads query heads of a KV head share its blocks and its
  *     selection; their scores are summed (the score is linear in q).
  *   - Workspace: `absb_plan` reports the size that suffices for every entry point on that
- *     (layer, batch); 256-byte aligned; contents need not be preserved between calls and
- *     need no initialisation.  Calls that share a workspace must be ordered on one stream.
+ *     (layer, batch); 256-byte aligned.  Its first bytes hold the counters through which the
+ *     work-groups of absb_decode_fused hand work to each other: they must be zero when that
+ *     call starts.  absb_workspace_init clears them (once per workspace and (batch, KV head
+ *     count); a workspace allocated zero-filled needs no call), and every entry point leaves
+ *     them zero.  Nothing else in the workspace needs initialisation or survives a call.  Calls
+ *     that share a workspace must be ordered on one stream.
  */
 #ifndef ABSB_H
 #define ABSB_H
@@ -176,10 +180,20 @@ ABSB_API int absb_sparse_decode(const absb_layer* layer, const absb_batch* batch
                                 const int32_t* sel_cnt, int32_t sel_stride, void* out, float* lse,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
-/* The whole step: score -> topk -> sparse decode, enqueued back to back.  Produces exactly the
- * selection of absb_score + absb_topk and the output of absb_sparse_decode on it.
+/* Clears the counters at the start of `workspace` (see "Workspace" above).  One small launch. */
+ABSB_API int absb_workspace_init(const absb_layer* layer, const absb_batch* batch, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/* The whole step: score -> topk -> sparse decode (Sec. 3.4, kernels 1-3) in ONE launch: the grid
+ * holds the estimation work-groups, then the attention work-groups; a segment's last estimation
+ * work-group runs its selection and raises a flag, and the segment's attention work-groups start
+ * on that flag.  Produces exactly the selection of absb_score + absb_topk and the output of
+ * absb_sparse_decode on it.  The counters at the start of the workspace must be zero
+ * (absb_workspace_init) and are zero again afterwards.
  *   sel_idx_out [Bt*Hkv][plan's sel_stride], sel_cnt_out [Bt*Hkv]: optional copies of the
- *   selection (NULL ok: kept in the workspace). */
+ *   selection (NULL ok: kept in the workspace).
+ * With ABSB_TUNE_STEP_LAUNCHES = 3 (see absb_set_tuning) the three stages are enqueued as three
+ * launches instead; that path needs no cleared counters. */
 ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const void* q,
                                const uint8_t* codes, const float* qscale, const void* k_cache,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
@@ -245,8 +259,16 @@ ABSB_API const char* absb_strerror(int status);
  *                            and KV head count on that workspace: the counters sit at its start,
  *                            no other stage writes there, and the attention kernel leaves every
  *                            counter it used at zero.  absb_decode_fused never needs the knob.
+ *   ABSB_TUNE_STEP_LAUNCHES: how absb_decode_fused is enqueued: 0 or 1 = one launch (default),
+ *                            3 = one launch per stage.
  * Returns ABSB_ERR_BAD_SHAPE for an unknown key or an invalid value. */
-enum { ABSB_TUNE_SPLIT_TOKENS = 0, ABSB_TUNE_SCORE_CHUNK = 1, ABSB_TUNE_COUNTERS_ZERO = 2, ABSB_TUNE_COUNT_ = 3 };
+enum {
+  ABSB_TUNE_SPLIT_TOKENS = 0,
+  ABSB_TUNE_SCORE_CHUNK = 1,
+  ABSB_TUNE_COUNTERS_ZERO = 2,
+  ABSB_TUNE_STEP_LAUNCHES = 3,
+  ABSB_TUNE_COUNT_ = 4
+};
 ABSB_API int absb_set_tuning(int key, int value);
 
 #ifdef __cplusplus

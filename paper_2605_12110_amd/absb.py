@@ -18,11 +18,11 @@ LIB_PATH = os.path.join(_HERE, "libabsb.so")
 
 F16, BF16 = 0, 1
 REPR_MEAN, REPR_MINMAX = 0, 1
-TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO = 0, 1, 2
+TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO, TUNE_STEP_LAUNCHES = 0, 1, 2, 3
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
-EXPORTS = ("absb_plan", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
+EXPORTS = ("absb_plan", "absb_workspace_init", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
            "absb_decode_fused", "absb_tail_init", "absb_append_token", "absb_head_recall", "absb_assign_block_sizes", "absb_stream_read",
            "absb_strerror", "absb_set_tuning")
 
@@ -225,6 +225,12 @@ def absb_decode_fused(layer: Layer, batch: Batch, q, codes, qscale, k_cache, v_c
                                     _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(sel_idx_out), _ptr(sel_cnt_out),
                                     _ptr(workspace), C.c_size_t(_nbytes(workspace)), _stream(stream)),
            "absb_decode_fused")
+
+
+def absb_workspace_init(layer: Layer, batch: Batch, workspace, stream=None) -> None:
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_workspace_init(C.byref(cl), C.byref(cb), _ptr(workspace), C.c_size_t(_nbytes(workspace)),
+                                      _stream(stream)), "absb_workspace_init")
 
 
 def absb_tail_init(layer: Layer, batch: Batch, k_cache, tail, stream=None) -> None:

@@ -24,6 +24,7 @@ _SOURCES = {
     "score.hip": ["-ffp-contract=off"],
     "topk.hip": [],
     "decode.hip": ["-ffp-contract=off"],   # FMAs are written explicitly there
+    "fused.hip": ["-ffp-contract=off"],    # holds the estimation stage too
     "util.hip": [],
 }
 
@@ -49,8 +50,7 @@ def _compile(name: str, extra) -> str:
 
 def build_library(force: bool = True, jobs: int = 5) -> str:
     """Compile every HIP source and link libabsb.so.  `force=False` skips when up to date."""
-    srcs = [os.path.join(_CSRC, n) for n in _SOURCES] + [os.path.join(_CSRC, "common.h"),
-                                                          os.path.join(_INCLUDE, "absb.h")]
+    srcs = [os.path.join(_CSRC, n) for n in os.listdir(_CSRC)] + [os.path.join(_INCLUDE, "absb.h")]
     if not force and os.path.exists(LIB_PATH) and all(os.path.getmtime(LIB_PATH) >= os.path.getmtime(s) for s in srcs):
         return LIB_PATH
     os.makedirs(_OBJ, exist_ok=True)

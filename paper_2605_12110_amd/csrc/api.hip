@@ -123,7 +123,12 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   // carving (nothing else ever writes there); behind them the three users overlap, since they
   // never run concurrently on one workspace
   p.ws_tickets = 0;
-  const size_t head = align256((size_t)p.nseg * ABSB_TICKET_STRIDE * 4);
+  const size_t ctr = align256((size_t)p.nseg * ABSB_TICKET_STRIDE * 4);
+  p.ws_score_tickets = ctr;
+  p.ws_flags = 2 * ctr;
+  p.ws_status = 3 * ctr;
+  const size_t head = 3 * ctr + 256;
+  p.ws_head_bytes = head;
   size_t o = head;
   p.ws_scores = o;
   o += align256((size_t)p.total * 4);
@@ -269,6 +274,9 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   int32_t* scores = reinterpret_cast<int32_t*>(ws + p.ws_scores);
   int32_t* sel_idx = sel_idx_out ? sel_idx_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_idx);
   int32_t* sel_cnt = sel_cnt_out ? sel_cnt_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_cnt);
+  if (tuning(ABSB_TUNE_STEP_LAUNCHES) != 3 && fused_one_launch_fits(p))
+    return launch_fused(g, p, layer->dtype, resolve_scale(layer), q, codes, qscale, k_cache, v_cache, batch->page_table,
+                        batch->seq_lens, batch->cent_off, batch->budget, sel_idx, sel_cnt, out, lse, ws, st);
   rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, batch->seq_lens, scores, nullptr, st);
   if (rc != ABSB_OK) return rc;
   // the selection kernel also clears the split counters of the attention kernel behind it
@@ -277,6 +285,17 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   if (rc != ABSB_OK) return rc;
   return launch_decode(g, p, layer->dtype, resolve_scale(layer), q, k_cache, v_cache, batch->page_table,
                        batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, true, st);
+}
+
+int absb_workspace_init(const absb_layer* layer, const absb_batch* batch, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  rc = check_ws(workspace, workspace_bytes, p.ws_head_bytes);
+  if (rc != ABSB_OK) return rc;
+  return launch_workspace_init(p, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 int absb_tail_init(const absb_layer* layer, const absb_batch* batch, const void* k_cache, float* tail, void* stream) {
@@ -360,7 +379,13 @@ const char* absb_strerror(int status) {
 
 int absb_set_tuning(int key, int value) {
   if (key < 0 || key >= ABSB_TUNE_COUNT_ || value < 0) return ABSB_ERR_BAD_SHAPE;
-  if (key == ABSB_TUNE_COUNTERS_ZERO ? value > 1 : value % 64 != 0) return ABSB_ERR_BAD_SHAPE;
+  if (key == ABSB_TUNE_COUNTERS_ZERO) {
+    if (value > 1) return ABSB_ERR_BAD_SHAPE;
+  } else if (key == ABSB_TUNE_STEP_LAUNCHES) {
+    if (value != 0 && value != 1 && value != 3) return ABSB_ERR_BAD_SHAPE;
+  } else if (value % 64 != 0) {
+    return ABSB_ERR_BAD_SHAPE;
+  }
   g_tuning[key].store(value, std::memory_order_relaxed);
   return ABSB_OK;
 }

@@ -48,6 +48,8 @@ struct Plan {
   int32_t build_max_chunks;    // max_s ceil(N_s / chunk_h)
   // workspace carving (byte offsets, 256-aligned)
   size_t ws_part_o, ws_part_ml, ws_tickets;       // decode partials, per-segment split counters
+  size_t ws_score_tickets, ws_flags, ws_status;   // more counters of the one-launch step
+  size_t ws_head_bytes;                           // all counters: the part absb_workspace_init clears
   size_t ws_scores, ws_sel_idx, ws_sel_cnt;       // fused step intermediates
   size_t ws_cent, ws_minmax, ws_qinv;             // build intermediates
   size_t ws_decode_bytes, ws_fused_bytes, ws_build_bytes, ws_bytes;
@@ -82,6 +84,15 @@ ABSB_HIDDEN int launch_decode(const Geometry& g, const Plan& pl, int dtype, floa
                               int32_t sel_stride, void* out, float* lse, char* ws, bool tickets_cleared,
                               hipStream_t stream);
 
+// The whole step in one launch (estimation, selection and attention work-groups in one grid).
+ABSB_HIDDEN bool fused_one_launch_fits(const Plan& pl);
+ABSB_HIDDEN int launch_fused(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
+                             const uint8_t* codes, const float* qscale, const void* k_cache, const void* v_cache,
+                             const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
+                             const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, void* out, float* lse,
+                             char* ws, hipStream_t stream);
+ABSB_HIDDEN int launch_workspace_init(const Plan& pl, char* ws, hipStream_t stream);
+
 ABSB_HIDDEN int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int num_cus, hipStream_t stream);
 
 ABSB_HIDDEN int launch_head_recall(const float* lse_sel, const float* lse_all, float* recall, int nseg, int G,
@@ -91,6 +102,50 @@ inline int check_launch() { return hipGetLastError() == hipSuccess ? ABSB_OK : A
 
 // ------------------------------------------------------------------ device helpers
 #ifdef __HIPCC__
+// Development aid, compiled in only with -DABSB_TRACE: thread 0 of a work-group stamps the 100 MHz
+// wall clock into slot `k` of its row of a trace buffer.
+#ifdef ABSB_TRACE
+#define ABSB_STAMP(trace, k)                                                                   \
+  do {                                                                                         \
+    if ((trace) && threadIdx.x == 0) (trace)[(size_t)blockIdx.x * 32 + (k)] = wall_clock64();  \
+  } while (0)
+#define ABSB_NOTE(trace, k, v)                                                                 \
+  do {                                                                                         \
+    if ((trace) && threadIdx.x == 0) (trace)[(size_t)blockIdx.x * 32 + (k)] = (uint64_t)(v);   \
+  } while (0)
+#else
+#define ABSB_STAMP(trace, k) \
+  do {                       \
+  } while (0)
+#define ABSB_NOTE(trace, k, v) \
+  do {                         \
+  } while (0)
+#endif
+// Device-coherent 32-bit accesses for data handed from one work-group to another inside a launch
+// (relaxed, agent scope: served past the caches that are not coherent across the chip).  The
+// hand-off protocol around them: the writer waits until its stores are acknowledged
+// (s_waitcnt vmcnt(0) + work-group barrier), then publishes a counter or flag with a relaxed
+// agent-scope atomic; the reader issues its loads only after it has seen that counter or flag.
+template <bool COH>
+__device__ __forceinline__ int32_t ld_i32(const int32_t* p) {
+  if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return *p;
+}
+template <bool COH>
+__device__ __forceinline__ void st_i32(int32_t* p, int32_t v) {
+  if (COH)
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else
+    *p = v;
+}
+__device__ __forceinline__ void wait_stores_acknowledged() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// K_s = min(N_s, ceil(T_b / B_h)) (Sec. 3.4, kernel 2), never more than the list has room for.
+__device__ __forceinline__ int budget_blocks(int T, int log2_block, int blocks, int sel_stride) {
+  const int K = (int)(((int64_t)T + (1 << log2_block) - 1) >> log2_block);
+  return min(min(K, blocks), sel_stride);
+}
+
 // Blocks in use of a segment: all rows of a tight layout (no need to wait for the length then);
 // otherwise N_s = ceil(L_b / B_h), never more than the layout has rows for.
 __device__ __forceinline__ int blocks_in_use(bool tight, int rows, const int32_t* seq_lens, int b, int log2_block) {

@@ -1,0 +1,218 @@
+// Estimation stage, device side (Sec. 3.4, kernel 1): importance score of every block of every
+// (request, KV head) from the INT4 centroid codes, dequantization fused, one launch over the
+// flattened code array delimited by the prefix-sum offsets.
+//
+// The G query heads of a KV head are folded into one weight vector w_c = (sum_g q_g[c]) * scale_c
+// (the score r = q . c^T of Sec. 2.2 is linear in q; the zero-point term is constant within a
+// segment and cannot change the ranking).  w is imaged on integers wq with the largest magnitude
+// in [2^14, 2^15]; S_j = sum_c wq_c * code_jc is then exact in int32 in any summation order, so the
+// ranking has one answer on every machine.  The binary32 steps (sum over g in order, one multiply,
+// max, power-of-two scaling, round-half-even) are single IEEE operations: this file is compiled
+// with -ffp-contract=off.
+//
+// Memory: a block is 64 bytes of codes per vector (one vector for mean pooling; maxima then minima
+// for max-min pooling, whose score is the same dot over 256 weights: the maxima weighted by the sum
+// of the group's positive q_g, the minima by the sum of its negative q_g).  Four lanes share one
+// block (16 bytes = 32 values of each vector), so one wave load instruction reads 16 whole vectors.
+//
+// Arithmetic: the codes are unsigned 4-bit, so the dot product runs on the packed 4-bit dot
+// instruction (8 multiply-adds per lane and instruction).  The biased weight wq + 2^15 (17 bits,
+// unsigned) is cut into five 4-bit planes; S = sum_k 16^k * dot(plane_k, codes) - 2^15 * sum(codes).
+// Six packed dots per 8 channels replace 16 unpack-and-multiply steps, and the kernel stays short:
+// it is launched with one batch of work per lane, so instruction count is what bounds it.
+#pragma once
+#include "common.h"
+
+namespace absb {
+
+struct ScoreParams {
+  const uint16_t* q;        // [Bt][Hq][128]
+  const uint8_t* codes;     // [total][64 * R], R vectors per block
+  const float* qscale;      // [nseg][128 * R]
+  const int32_t* cent_off;  // [nseg+1]
+  const int32_t* seq_lens;  // [Bt]
+  HeadTable heads;
+  int32_t* scores;          // [total]
+  int32_t* score_exp;       // [nseg] or null
+  int32_t Hq, Hkv, G, chunk, tight;
+};
+
+constexpr int SCORE_PLANES = 5;
+
+inline ScoreParams make_score_params(const Geometry& g, const Plan& pl, const void* q, const uint8_t* codes,
+                                     const float* qscale, const int32_t* cent_off, const int32_t* seq_lens,
+                                     int32_t* scores, int32_t* score_exp) {
+  ScoreParams p;
+  p.q = static_cast<const uint16_t*>(q);
+  p.codes = codes;
+  p.qscale = qscale;
+  p.cent_off = cent_off;
+  p.seq_lens = seq_lens;
+  p.heads = g.heads;
+  p.tight = g.tight;
+  p.scores = scores;
+  p.score_exp = score_exp;
+  p.Hq = g.Hq;
+  p.Hkv = g.Hkv;
+  p.G = g.G;
+  p.chunk = pl.score_chunk;
+  return p;
+}
+
+__device__ __forceinline__ uint32_t or8(uint32_t v) {  // OR over aligned groups of 8 lanes
+  v |= (uint32_t)dpp_i<DPP_QUAD_XOR1>((int)v);
+  v |= (uint32_t)dpp_i<DPP_QUAD_XOR2>((int)v);
+  v |= (uint32_t)dpp_i<DPP_ROW_HALF_MIRROR>((int)v);
+  return v;
+}
+
+// LDS of one work-group: the four wave maxima, then the digit planes of the weights.
+template <int REP>
+__host__ __device__ constexpr size_t score_lds_bytes() {
+  return 16 + (size_t)SCORE_PLANES * (ABSB_HEAD_DIM * (REP + 1) / 8) * sizeof(uint32_t);
+}
+
+// Scores of blocks [chunk_idx*p.chunk, +p.chunk) of segment s by one work-group of 256 threads.
+// Returns the segment's block count N_s, or 0 (nothing done) when the segment has no such blocks.  COH: the scores are read by
+// another work-group of the same launch.  `lds`: score_lds_bytes<REP>() bytes, 16-byte aligned.
+template <int DT, int REP, bool COH>
+__device__ __forceinline__ int score_chunk(const ScoreParams& p, int s, int chunk_idx, char* lds) {
+  constexpr int R = REP + 1;                 // vectors per block: the mean, or maxima and minima
+  constexpr int W = ABSB_HEAD_DIM * R;       // weights = values per block
+  constexpr int ROW_BYTES = W / 2;
+  const int b = s / p.Hkv, h = s % p.Hkv;
+  const int tid = threadIdx.x;
+  // ---- the group's query values and the scale of this thread's weight go in flight first, all at
+  // once: their addresses need nothing from memory, and everything below waits for them
+  uint16_t qraw[ABSB_MAX_GROUP];
+  float scale = 0.0f;
+  if (tid < W) {
+    const uint16_t* qrow =
+        p.q + ((size_t)b * p.Hq + (size_t)h * p.G) * ABSB_HEAD_DIM + (tid & (ABSB_HEAD_DIM - 1));
+#pragma unroll
+    for (int g = 0; g < ABSB_MAX_GROUP; ++g) qraw[g] = g < p.G ? qrow[(size_t)g * ABSB_HEAD_DIM] : (uint16_t)0;
+    scale = p.qscale[(size_t)s * W + tid];
+  }
+  const int off = p.cent_off[s];
+  const int N = blocks_in_use(p.tight, p.cent_off[s + 1] - off, p.seq_lens, b, p.heads.log2_block[h]);
+  const int j0 = chunk_idx * p.chunk;
+  if (j0 >= N) return 0;
+
+  float* s_absmax = reinterpret_cast<float*>(lds);
+  uint32_t (*s_plane)[W / 8] = reinterpret_cast<uint32_t (*)[W / 8]>(lds + 16);
+
+  // ---- the work-group's first batch of codes goes in flight before anything else: the loads do
+  // not depend on the query, so their latency overlaps the prologue below
+  constexpr int PF = 4;  // 64 blocks per work-group step, PF steps per batch
+  const int quarter = tid & 3;
+  const int jend = min(N, j0 + p.chunk);
+  const uint8_t* base = p.codes + (size_t)off * ROW_BYTES + quarter * 16;
+  uint4 pre[PF][R];
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    const int j = min(j0 + u * 64 + (tid >> 2), jend - 1);  // clamped, not predicated: loads issue back to back
+#pragma unroll
+    for (int v = 0; v < R; ++v) pre[u][v] = *reinterpret_cast<const uint4*>(base + (size_t)j * ROW_BYTES + v * 64);
+  }
+
+  // ---- prologue: fixed-point image of the weights, by threads 0..W-1 (weight index = tid).
+  // Mean pooling: w = (sum_g q_g) * scale.  Maxima / minima: the maxima meet the sum of the
+  // group's positive q_g, the minima the sum of its negative q_g (each in order of g, from +0).
+  float w = 0.0f;
+  if (tid < W) {
+    const int v = tid >> 7;
+    float u;
+    if (REP == 0) {
+      u = Elem<DT>::widen(qraw[0]);
+#pragma unroll
+      for (int g = 1; g < ABSB_MAX_GROUP; ++g)
+        if (g < p.G) u = u + Elem<DT>::widen(qraw[g]);
+    } else {
+      u = 0.0f;
+#pragma unroll
+      for (int g = 0; g < ABSB_MAX_GROUP; ++g) {
+        const float x = Elem<DT>::widen(qraw[g]);
+        if (g < p.G && (v == 0 ? x > 0.0f : x < 0.0f)) u = u + x;
+      }
+    }
+    w = u * scale;
+    float a = __builtin_fabsf(w);
+    a = (a != a) ? 0.0f : a;  // a NaN never wins the maximum
+    a = wave_max_f32(a);  // exact, order-free
+    if ((tid & 63) == 0) s_absmax[tid >> 6] = a;
+  }
+  __syncthreads();
+  float A = fmaxf(s_absmax[0], s_absmax[1]);
+  if (REP) A = fmaxf(A, fmaxf(s_absmax[2], s_absmax[3]));
+  int ex = 0;
+  const bool live = (A >= 0x1p-100f) && (A <= 3.4028234663852886e38f);
+  if (live) ex = (int)((bitcast<uint32_t>(A) >> 23) & 0xffu) - 127 - 14;
+  if (tid < W) {
+    int32_t wq = 0;
+    if (live) wq = (int32_t)__builtin_rintf(__builtin_ldexpf(w, -ex));
+    // biased weight in [0, 2^16]; its five 4-bit digits, packed over 8 consecutive values
+    const uint32_t wo = (uint32_t)(wq + 32768);
+    const int sh = 4 * (tid & 7);
+#pragma unroll
+    for (int k = 0; k < SCORE_PLANES; ++k) {
+      const uint32_t packed = or8(((wo >> (4 * k)) & 15u) << sh);
+      if ((tid & 7) == 0) s_plane[k][tid >> 3] = packed;
+    }
+  }
+  if (tid == 0 && chunk_idx == 0 && p.score_exp) p.score_exp[s] = ex;
+  __syncthreads();
+
+  // ---- each lane: the digit planes of its quarter of each vector (4 words of 8 values)
+  uint4 wp[R][SCORE_PLANES];
+#pragma unroll
+  for (int v = 0; v < R; ++v)
+#pragma unroll
+    for (int k = 0; k < SCORE_PLANES; ++k)
+      wp[v][k] = *reinterpret_cast<const uint4*>(&s_plane[k][v * (ABSB_HEAD_DIM / 8) + quarter * 4]);
+
+  auto dot = [&](const uint4 (&cv)[R]) -> int32_t {
+    uint32_t acc = 0, ones = 0;
+#pragma unroll
+    for (int v = 0; v < R; ++v) {
+      const uint4 c = cv[v];
+#pragma unroll
+      for (int k = 0; k < SCORE_PLANES; ++k) {
+        uint32_t d = __builtin_amdgcn_udot8(c.x, wp[v][k].x, 0u, false);
+        d = __builtin_amdgcn_udot8(c.y, wp[v][k].y, d, false);
+        d = __builtin_amdgcn_udot8(c.z, wp[v][k].z, d, false);
+        d = __builtin_amdgcn_udot8(c.w, wp[v][k].w, d, false);
+        acc += d << (4 * k);
+      }
+      ones = __builtin_amdgcn_udot8(c.x, 0x11111111u, ones, false);
+      ones = __builtin_amdgcn_udot8(c.y, 0x11111111u, ones, false);
+      ones = __builtin_amdgcn_udot8(c.z, 0x11111111u, ones, false);
+      ones = __builtin_amdgcn_udot8(c.w, 0x11111111u, ones, false);
+    }
+    acc -= ones << 15;                 // two's complement: exact sum_c wq_c * code_c of this quarter
+    return quad_sum((int32_t)acc);     // the four lanes of a quad hold the four quarters of one block
+  };
+
+  // ---- main loop: 64 blocks per work-group step (16 per wave), PF steps per batch.
+  // Every lane of a quad shares j, so the quad reduction always sees four live lanes.
+#pragma unroll 1
+  for (int jb = j0;;) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int j = jb + u * 64 + (tid >> 2);
+      const int32_t sc = dot(pre[u]);
+      if (j < jend && quarter == 0) st_i32<COH>(p.scores + off + j, sc);
+    }
+    jb += PF * 64;
+    if (jb >= jend) break;
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int j = min(jb + u * 64 + (tid >> 2), jend - 1);
+#pragma unroll
+      for (int v = 0; v < R; ++v) pre[u][v] = *reinterpret_cast<const uint4*>(base + (size_t)j * ROW_BYTES + v * 64);
+    }
+  }
+  return N;
+}
+
+
+}  // namespace absb

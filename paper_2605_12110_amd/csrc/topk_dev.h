@@ -1,0 +1,454 @@
+// Selection stage, device side (Sec. 3.4, kernel 2): the work a work-group does for one
+// (request, KV head) segment.  Used by the stand-alone selection kernel (1024 threads) and by the
+// one-launch decode step (256 threads, the segment's scores arriving from other work-groups).
+//
+// Selection is an exact threshold search that touches every key three times with a handful of
+// instructions each (it runs on one CU per segment, so instructions per key and dependent
+// latencies, not bytes, bound it):
+//   1. the segment's scores are loaded once (coalesced, unconditional, all loads in flight
+//      together) and kept in registers as order-preserving unsigned keys; min/max give the range;
+//   2. a 2048-bin LDS histogram over the top 11 significant bits of (key - min) and a work-group
+//      scan find the bin d1 that holds the K-th largest key;
+//   3. keys above bin d1 set their bit in an LDS bitmap of selected blocks; the few keys inside
+//      d1 are appended to a candidate list; a long list is cut down by histogram rounds over
+//      further digits of the key, a short one is ranked exactly by (key desc, index asc), and the
+//      best `need` candidates set their bits too;
+//   4. the bitmap is scanned in index order (popcount prefix sums) and the indices written out.
+// A crowded bin (more than 1024 candidates, e.g. all scores equal) takes a slow path: further radix
+// digits give the exact threshold tau, and blocks equal to tau are admitted in index order through
+// a second bitmap.  Segments too long for the register tile run the same code with keys re-read.
+// Wave-level reductions and scans use DPP row operations, not LDS-crossbar shuffles.
+//
+// Optional policy (off by default): the blocks that hold the first sink_tokens or the last
+// recent_tokens tokens are always selected.  They form a prefix and a suffix of the segment, so
+// they are written to the list directly and the blocks in between compete for what is left of K_s.
+#pragma once
+#include "common.h"
+
+namespace absb {
+
+struct TopkParams {
+  const int32_t* scores;
+  const int32_t* cent_off;
+  const int32_t* budget;  // [Bt]
+  const int32_t* seq_lens;  // [Bt]
+  int32_t sink_tokens, recent_tokens;  // blocks holding these tokens are selected ahead of every score
+  int32_t* sel_idx;
+  int32_t* sel_cnt;
+  int32_t* tickets;  // [nseg] or null: split counters of the attention kernel that follows, cleared here
+  int32_t sel_stride, Hkv, tight;
+  HeadTable heads;
+  uint64_t* trace;  // development aid (ABSB_TRACE builds), else null
+};
+
+inline TopkParams make_topk_params(const Geometry& g, const int32_t* scores, const int32_t* cent_off,
+                                   const int32_t* budget, const int32_t* seq_lens, int32_t* sel_idx,
+                                   int32_t* sel_cnt, int32_t sel_stride, int32_t* tickets) {
+  TopkParams p;
+  p.scores = scores;
+  p.cent_off = cent_off;
+  p.budget = budget;
+  p.seq_lens = seq_lens;
+  p.tight = g.tight;
+  p.sink_tokens = g.sink_tokens;
+  p.recent_tokens = g.recent_tokens;
+  p.sel_idx = sel_idx;
+  p.sel_cnt = sel_cnt;
+  p.tickets = tickets;
+  p.sel_stride = sel_stride;
+  p.Hkv = g.Hkv;
+  p.heads = g.heads;
+  p.trace = nullptr;
+  return p;
+}
+
+constexpr int TOPK_MAX_CAND = 1024;       // longest candidate list
+constexpr int TOPK_RANK_MAX = 128;        // candidates ranked against each other (quadratic work)
+constexpr int TOPK_MAX_BLOCKS = 1 << 17;  // bitmap capacity (2 x 16 KiB of LDS)
+constexpr int TOPK_DIGIT_BITS = 11;
+constexpr int TOPK_BINS = 1 << TOPK_DIGIT_BITS;
+constexpr int TOPK_SLOTS = 16;            // per-wave scratch words: up to 16 waves per work-group
+
+__device__ __forceinline__ uint32_t ordered_key(int32_t score) { return (uint32_t)score ^ 0x80000000u; }
+
+struct TopkShared {
+  uint32_t red[2 * TOPK_SLOTS];
+  uint32_t hist[TOPK_BINS];
+  uint32_t bcast[4];
+  uint32_t cand_key[TOPK_MAX_CAND];
+  uint32_t cand_idx[TOPK_MAX_CAND];
+  uint32_t cand_n;
+  uint32_t wave_a[TOPK_SLOTS], wave_b[TOPK_SLOTS];
+};
+// LDS a segment's selection needs: the fixed part, then two bitmaps of one bit per block.
+__host__ __device__ constexpr size_t topk_lds_bytes(int max_blocks) {
+  return ((sizeof(TopkShared) + 15) & ~size_t(15)) + (size_t)2 * ((max_blocks + 31) / 32) * sizeof(uint32_t);
+}
+
+struct UMin {
+  __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a < b ? a : b; }
+};
+struct UMax {
+  __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a > b ? a : b; }
+};
+
+// Exclusive prefix sum of one value per thread over the work-group (thread order); *total = sum.
+// `slot` is 16 words of LDS scratch.  Contains one barrier: call from uniform control flow.
+template <int NT>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* slot, int lane, int wave, uint32_t* total) {
+  constexpr int WAVES = NT / 64;
+  static_assert(WAVES >= 1 && WAVES <= TOPK_SLOTS, "one scratch word per wave");
+  uint32_t wave_total;
+  const uint32_t incl = wave_incl_scan_u32(v, &wave_total);
+  if (lane == 0) slot[wave] = wave_total;
+  __syncthreads();
+  // the wave totals: every 16-lane row scans them again (cheaper than a second barrier)
+  const int r = lane & (TOPK_SLOTS - 1);
+  uint32_t s = r < WAVES ? slot[r] : 0u;
+  s += (uint32_t)dpp_i<0x111>((int)s);
+  s += (uint32_t)dpp_i<0x112>((int)s);
+  s += (uint32_t)dpp_i<0x114>((int)s);
+  s += (uint32_t)dpp_i<0x118>((int)s);  // inclusive over the row = over waves 0..(lane&15)
+  *total = (uint32_t)__builtin_amdgcn_readlane((int)s, 15);
+  // exclusive prefix of this thread's wave: lane `wave` holds the sum over waves 0..wave; drop own total
+  const uint32_t upto = (uint32_t)__builtin_amdgcn_readlane((int)s, __builtin_amdgcn_readfirstlane(wave));
+  return upto - wave_total + incl - v;
+}
+
+// A slot of an LDS list for every lane that calls it (any subset of a wave, from divergent code):
+// one atomic per wave, not per lane.
+__device__ __forceinline__ uint32_t append_slot(uint32_t* counter) {
+  const uint64_t m = __builtin_amdgcn_ballot_w64(true);  // the lanes that are here
+  const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+  uint32_t base = 0;
+  if (before == 0) base = atomicAdd(counter, (uint32_t)__popcll(m));
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)base) + before;
+}
+
+// From the histogram of the current digit among the candidates: the bin holding the `need`-th
+// largest candidate.  All threads take part (TOPK_BINS / NT bins each, highest bins first).
+// bcast = {bin, candidates above it, candidates in it}.  Two barriers inside.
+template <int NT>
+__device__ __forceinline__ void pick_bin(TopkShared& sh, int tid, int lane, int wave, uint32_t need) {
+  constexpr int BPT = TOPK_BINS / NT;
+  const int hi = TOPK_BINS - 1 - BPT * tid;  // descending: thread 0 owns the highest bins
+  uint32_t c[BPT], sum = 0;
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) {
+    c[k] = sh.hist[hi - k];
+    sum += c[k];
+  }
+  uint32_t total;
+  uint32_t above = block_excl_scan<NT>(sum, sh.wave_a, lane, wave, &total);
+#pragma unroll
+  for (int k = 0; k < BPT; ++k) {
+    if (above < need && need <= above + c[k]) {
+      sh.bcast[0] = (uint32_t)(hi - k);
+      sh.bcast[1] = above;
+      sh.bcast[2] = c[k];
+    }
+    above += c[k];
+  }
+  __syncthreads();
+}
+
+// The selection of segment s by one work-group of NT threads.
+//   KPT > 0: keys of the segment live in registers (competing blocks <= KPT*NT); KPT == 0: re-read.
+//   COH: the scores were written, and the list will be read, by other work-groups of this launch.
+//   sh, bitmap: LDS as sized by topk_lds_bytes().
+// Every thread of the work-group must call it; all of them return together.
+template <int NT, int KPT, bool COH>
+__device__ __forceinline__ void topk_segment(const TopkParams& p, int s, TopkShared& sh, uint32_t* s_bitmap) {
+  constexpr int WAVES = NT / 64;
+  const int b = s / p.Hkv, h = s % p.Hkv;
+  const int off = p.cent_off[s];
+  const int lb = p.heads.log2_block[h];
+  const int Nall = blocks_in_use(p.tight, p.cent_off[s + 1] - off, p.seq_lens, b, lb);
+  int K = budget_blocks(p.budget[b], lb, Nall, p.sel_stride);
+  // Forced blocks are a prefix [0, lo) (they hold the first sink_tokens tokens) and a suffix
+  // [hi, Nall) (the last recent_tokens tokens) of the segment; they are selected ahead of every
+  // score, lowest index first, and the blocks [lo, hi) compete by score for what is left of K.
+  int lo = 0, hi = Nall;
+  if (p.sink_tokens > 0) lo = min(Nall, (int)(((int64_t)p.sink_tokens + (1 << lb) - 1) >> lb));
+  if (p.recent_tokens > 0) hi = max(lo, min(Nall, max(0, p.seq_lens[b] - p.recent_tokens) >> lb));
+  const int nforced = lo + (Nall - hi);
+  const int N = hi - lo;  // competing blocks; the code below indexes them from 0
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int32_t* sc = p.scores + off + (N > 0 ? lo : 0);
+  int32_t* out = p.sel_idx + (size_t)s * p.sel_stride;
+  constexpr int R = KPT > 0 ? KPT : 1;
+  const int ntiles = KPT > 0 ? KPT : (N + NT - 1) / NT;
+  const int nwords = (N + 31) >> 5;
+  uint32_t* bm_gt = s_bitmap;
+  uint32_t* bm_eq = s_bitmap + nwords;
+
+  // keys first: everything else waits on them.  The index is clamped instead of the load being
+  // predicated, so the loads issue back to back (the clamp keeps them legal when nothing competes).
+  const int jlast = max(N - 1, 0);
+  uint32_t key[R];
+  if (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < R; ++i) key[i] = ordered_key(ld_i32<COH>(sc + min(i * NT + tid, jlast)));
+  }
+  auto key_at = [&](int i) -> uint32_t {  // meaningful only for i*NT+tid < N
+    if (KPT > 0) return key[i];
+    return ordered_key(ld_i32<COH>(sc + min(i * NT + tid, jlast)));
+  };
+
+  if (tid == 0) {
+    st_i32<COH>(p.sel_cnt + s, K);
+    if (p.tickets) p.tickets[(size_t)s * ABSB_TICKET_STRIDE] = 0;
+  }
+#pragma unroll 1
+  for (int i = K + tid; i < p.sel_stride; i += NT) st_i32<COH>(out + i, -1);
+  if (K >= Nall) {  // everything is selected
+#pragma unroll 1
+    for (int i = tid; i < Nall; i += NT) st_i32<COH>(out + i, i);
+    return;
+  }
+  if (nforced >= K) {  // the forced blocks alone fill the list: lowest indices first
+#pragma unroll 1
+    for (int i = tid; i < K; i += NT) st_i32<COH>(out + i, i < lo ? i : hi + (i - lo));
+    return;
+  }
+  // list = forced prefix, then the chosen ones of [lo, hi) (written below, relative to `out`), then
+  // the forced suffix
+  K -= nforced;
+#pragma unroll 1
+  for (int i = tid; i < lo; i += NT) st_i32<COH>(out + i, i);
+#pragma unroll 1
+  for (int i = tid; i < Nall - hi; i += NT) st_i32<COH>(out + lo + K + i, hi + i);
+  out += lo;
+
+#pragma unroll
+  for (int i = tid; i < TOPK_BINS; i += NT) sh.hist[i] = 0;
+  if (tid == 0) sh.cand_n = 0;
+#pragma unroll 1
+  for (int w = tid; w < 2 * nwords; w += NT) s_bitmap[w] = 0;
+
+  // ---- 1. range of the keys (clamped duplicates of the last key do not change min/max)
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+  for (int i = 0; i < ntiles; ++i) {
+    const uint32_t k = key_at(i);
+    kmin = min(kmin, k);
+    kmax = max(kmax, k);
+  }
+  ABSB_STAMP(p.trace, 6);
+  kmin = wave_reduce_u32(kmin, UMin());
+  kmax = wave_reduce_u32(kmax, UMax());
+  if (lane == 0) {
+    sh.red[wave] = kmin;
+    sh.red[TOPK_SLOTS + wave] = kmax;
+  }
+  __syncthreads();
+  {
+    const int r = lane & (TOPK_SLOTS - 1);
+    kmin = row16_reduce_u32(r < WAVES ? sh.red[r] : 0xffffffffu, UMin());
+    kmax = row16_reduce_u32(r < WAVES ? sh.red[TOPK_SLOTS + r] : 0u, UMax());
+  }
+  const uint32_t range = kmax - kmin;  // relative keys live in [0, range]
+  // from here on only key - min is needed: kept in place of the key (one register per key)
+  if (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < R; ++i) key[i] -= kmin;
+  }
+  auto rel_at = [&](int i) -> uint32_t {
+    if (KPT > 0) return key[i];
+    return ordered_key(ld_i32<COH>(sc + min(i * NT + tid, jlast))) - kmin;
+  };
+  const int bits = 32 - __builtin_clz(range | 1u);
+  int shift = bits > TOPK_DIGIT_BITS ? bits - TOPK_DIGIT_BITS : 0;  // first digit = the top significant bits
+
+  // ---- 2. histogram of the first digit, threshold bin
+  // (slots past the end hold copies of the last key: counting them would pile thousands of LDS
+  // atomics on one bin, so they are skipped, not corrected for afterwards)
+#pragma unroll
+  for (int i = 0; i < ntiles; ++i) {
+    if (i * NT + tid < N) atomicAdd(&sh.hist[rel_at(i) >> shift], 1u);
+  }
+  __syncthreads();
+  ABSB_STAMP(p.trace, 7);
+  // The next pass over the keys recomputes digits and bounds tests instead of carrying one more
+  // register per key (and one lane mask per key) across the barrier: with a long register tile
+  // that carrying spills.  The empty statements make the values opaque to the optimiser.
+  int Nc = __builtin_amdgcn_readfirstlane(N);
+  if (KPT > 8) {
+    asm volatile("" : "+s"(Nc));
+#pragma unroll
+    for (int i = 0; i < R; ++i) asm volatile("" : "+v"(key[i]));
+  }
+  pick_bin<NT>(sh, tid, lane, wave, (uint32_t)K);
+  ABSB_STAMP(p.trace, 14);
+  const uint32_t d1 = sh.bcast[0];
+  uint32_t need = (uint32_t)K - sh.bcast[1];
+  uint32_t ncand = sh.bcast[2];
+  ABSB_NOTE(p.trace, 16, ncand);
+  ABSB_NOTE(p.trace, 17, shift);
+  ABSB_NOTE(p.trace, 18, N);
+  ABSB_NOTE(p.trace, 19, K);
+  uint32_t need_eq = 0;
+
+  if (shift == 0 || ncand <= (uint32_t)TOPK_MAX_CAND) {
+    // ---- 3. keys above the bin are selected; keys inside it become candidates
+    // (with shift == 0 the bin is a single key value: its members tie, lowest index first)
+    const bool list_cands = ncand <= (uint32_t)TOPK_MAX_CAND;
+#pragma unroll
+    for (int i = 0; i < ntiles; ++i) {
+      const int j = i * NT + tid;
+      const uint32_t rel = rel_at(i);
+      const uint32_t dg = rel >> shift;
+      if (dg >= d1 && j < Nc) {  // the digit test comes first: it fails for almost every key
+        if (dg > d1) {
+          atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
+        } else if (list_cands) {
+          const uint32_t slot = append_slot(&sh.cand_n);
+          sh.cand_key[slot] = rel;
+          sh.cand_idx[slot] = (uint32_t)j;
+        } else {
+          atomicOr(&bm_eq[j >> 5], 1u << (j & 31));
+        }
+      }
+    }
+    __syncthreads();
+    ABSB_STAMP(p.trace, 20);
+    if (list_cands) {
+      // A long candidate list (a range stretched by a few outliers packs the bulk of the keys into
+      // few bins) is cut down by further digits of the key, a histogram round per digit over the
+      // list alone: candidates above the new threshold bin are selected, those inside it form the
+      // next list.  Each thread carries its candidates through a round in registers.
+      constexpr int CPT = (TOPK_MAX_CAND + NT - 1) / NT;
+      uint32_t cshift = (uint32_t)shift;  // bits of the key not yet looked at
+      while (ncand > (uint32_t)TOPK_RANK_MAX && cshift > 0) {
+        const uint32_t nshift = cshift > TOPK_DIGIT_BITS ? cshift - TOPK_DIGIT_BITS : 0;
+        uint32_t ck[CPT], ci[CPT];
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+          const uint32_t c = (uint32_t)(i * NT + tid);
+          ck[i] = c < ncand ? sh.cand_key[c] : 0u;
+          ci[i] = c < ncand ? sh.cand_idx[c] : 0u;
+        }
+#pragma unroll
+        for (int i = tid; i < TOPK_BINS; i += NT) sh.hist[i] = 0;
+        if (tid == 0) sh.cand_n = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < CPT; ++i)
+          if ((uint32_t)(i * NT + tid) < ncand) atomicAdd(&sh.hist[(ck[i] >> nshift) & (uint32_t)(TOPK_BINS - 1)], 1u);
+        __syncthreads();
+        pick_bin<NT>(sh, tid, lane, wave, need);
+        const uint32_t d2 = sh.bcast[0], above2 = sh.bcast[1], inbin2 = sh.bcast[2];
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+          if ((uint32_t)(i * NT + tid) < ncand) {
+            const uint32_t dg = (ck[i] >> nshift) & (uint32_t)(TOPK_BINS - 1);
+            if (dg > d2) {
+              atomicOr(&bm_gt[ci[i] >> 5], 1u << (ci[i] & 31));
+            } else if (dg == d2) {
+              const uint32_t slot = append_slot(&sh.cand_n);
+              sh.cand_key[slot] = ck[i];
+              sh.cand_idx[slot] = ci[i];
+            }
+          }
+        }
+        __syncthreads();  // the new list is complete; bcast may be rewritten
+        need -= above2;
+        ncand = inbin2;
+        cshift = nshift;
+      }
+      if (ncand <= (uint32_t)TOPK_RANK_MAX) {
+        // a short list: exact rank of every candidate by (key desc, index asc)
+#pragma unroll 1
+        for (uint32_t c = (uint32_t)tid; c < ncand; c += NT) {
+          const uint32_t mk = sh.cand_key[c], mi = sh.cand_idx[c];
+          uint32_t rank = 0;
+#pragma unroll 4
+          for (uint32_t u = 0; u < ncand; ++u) {
+            const uint32_t ok = sh.cand_key[u], oi = sh.cand_idx[u];
+            rank += (ok > mk) || (ok == mk && oi < mi);
+          }
+          if (rank < need) atomicOr(&bm_gt[mi >> 5], 1u << (mi & 31));
+        }
+      } else {
+        // every digit used up: the candidates share one key value and tie, lowest index first
+#pragma unroll 1
+        for (uint32_t c = (uint32_t)tid; c < ncand; c += NT) {
+          const uint32_t mi = sh.cand_idx[c];
+          atomicOr(&bm_eq[mi >> 5], 1u << (mi & 31));
+        }
+        need_eq = need;
+      }
+    } else {
+      need_eq = need;  // bin == one key value: admit its first `need` members by index
+    }
+    __syncthreads();
+  } else {
+    // ---- slow path: crowded bin.  More radix digits until the bin is a single key value.
+    uint32_t prefix = d1 << shift, mask = (uint32_t)(TOPK_BINS - 1) << shift;
+    while (shift > 0) {
+      shift = shift > TOPK_DIGIT_BITS ? shift - TOPK_DIGIT_BITS : 0;
+#pragma unroll
+      for (int i = tid; i < TOPK_BINS; i += NT) sh.hist[i] = 0;
+      __syncthreads();
+#pragma unroll 1
+      for (int j = tid; j < N; j += NT) {
+        const uint32_t rel = ordered_key(ld_i32<COH>(sc + j)) - kmin;
+        if ((rel & mask) == prefix) atomicAdd(&sh.hist[(rel >> shift) & (uint32_t)(TOPK_BINS - 1)], 1u);
+      }
+      __syncthreads();
+      pick_bin<NT>(sh, tid, lane, wave, need);
+      prefix |= sh.bcast[0] << shift;
+      mask |= (uint32_t)(TOPK_BINS - 1) << shift;
+      need -= sh.bcast[1];
+      __syncthreads();  // bcast is rewritten by the next round
+    }
+    const uint32_t tau = prefix;
+    need_eq = need;
+#pragma unroll 1
+    for (int j = tid; j < N; j += NT) {
+      const uint32_t rel = ordered_key(ld_i32<COH>(sc + j)) - kmin;
+      if (rel > tau)
+        atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
+      else if (rel == tau)
+        atomicOr(&bm_eq[j >> 5], 1u << (j & 31));
+    }
+    __syncthreads();
+  }
+
+  ABSB_STAMP(p.trace, 15);
+  // ---- 4. bitmaps -> ascending index list
+  uint32_t base_gt = 0, base_eq = 0;
+#pragma unroll 1
+  for (int w0 = 0; w0 < nwords; w0 += NT) {
+    const int w = w0 + tid;
+    const uint32_t g = w < nwords ? bm_gt[w] : 0u;
+    const uint32_t e = (need_eq > 0 && w < nwords) ? bm_eq[w] : 0u;
+    uint32_t tot_gt, tot_eq = 0;
+    uint32_t G = base_gt + block_excl_scan<NT>((uint32_t)__popc(g), sh.wave_a, lane, wave, &tot_gt);
+    uint32_t E = base_eq;
+    if (need_eq > 0) E += block_excl_scan<NT>((uint32_t)__popc(e), sh.wave_b, lane, wave, &tot_eq);
+    uint32_t bitsleft = g | e;
+#pragma unroll 1
+    while (bitsleft) {
+      const int bpos = __builtin_ctz(bitsleft);
+      bitsleft &= bitsleft - 1;
+      const int idx = (w << 5) + bpos;
+      if ((g >> bpos) & 1u) {
+        const uint32_t slot = G + min(E, need_eq);
+        if (slot < (uint32_t)K) st_i32<COH>(out + slot, idx + lo);  // always true for consistent counts; keeps stores in bounds
+        ++G;
+      } else {
+        if (E < need_eq) {
+          const uint32_t slot = G + E;
+          if (slot < (uint32_t)K) st_i32<COH>(out + slot, idx + lo);
+        }
+        ++E;
+      }
+    }
+    base_gt += tot_gt;
+    base_eq += tot_eq;
+    __syncthreads();  // the scan scratch is reused by the next tile of words
+  }
+}
+
+}  // namespace absb

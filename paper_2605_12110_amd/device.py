@@ -75,8 +75,14 @@ class DeviceWorkload:
         self.out = torch.empty((wl.batch, wl.num_q_heads, wl.head_dim), dtype=tdt, device=device)
         self.lse = torch.empty((wl.batch, wl.num_q_heads), dtype=torch.float32, device=device)
         self.tail = torch.empty((nseg, width), dtype=torch.float32, device=device)
-        # poison the workspace: no entry point may depend on its previous contents
-        self.workspace = torch.full((self.plan.workspace_bytes + 256,), 0xA5, dtype=torch.uint8, device=device)
+        self.workspace = torch.empty((self.plan.workspace_bytes + 256,), dtype=torch.uint8, device=device)
+        self.scribble(0xA5)
+
+    def scribble(self, value: int, stream=None):
+        """Poison the workspace (no entry point may depend on its previous contents), then clear its
+        counters the way a caller must before the first fused step on a fresh workspace."""
+        self.workspace.fill_(value)
+        absb.absb_workspace_init(self.layer, self.batch, self.workspace, stream)
 
     # -- entry points, in path order
     def build(self, stream=None):

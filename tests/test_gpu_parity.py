@@ -96,18 +96,32 @@ def run_all_stages(wl, name, block_repr=O.MEAN):
     # the whole step from the GPU-built store
     dw.build()
     dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
-    dw.workspace.fill_(0x5A)
+    dw.scribble(0x5A)
     dw.decode_fused()
     _check_out(dw, ref["out"], ref["lse"], "decode_fused")
     assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
     assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
     # and again without asking for the selection, different workspace poison: same bits out
     first = dw.out.cpu().numpy().copy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy().copy()
-    dw.workspace.fill_(0xC3)
+    dw.scribble(0xC3)
     dw.decode_fused(want_sel=False); _sync()
     second = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
     assert np.array_equal(first, second), "fused output depends on workspace contents or is not deterministic"
-    _say("    fused: selection bit-exact, output within tolerance, deterministic")
+    # the same step as one launch per stage (needs no cleared counters): same selection, same bits out
+    from paper_2605_12110_amd import absb
+    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 3)
+    try:
+        dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+        dw.workspace.fill_(0x3C)
+        dw.decode_fused(); _sync()
+    finally:
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+    third = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
+    assert np.array_equal(first, third), "one launch and three launches disagree"
+    assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
+    dw.scribble(0x99)     # the stand-alone stages do not keep the other counters: clear them again
+    _say("    fused: selection bit-exact, output within tolerance, deterministic, one launch == three launches")
     return dw, st, ref
 
 
@@ -572,7 +586,7 @@ def test_fused_step_replays_from_a_captured_graph():
     _sync()
     for rep in range(4):
         dw.out.fill_(float("nan")); dw.sel_idx.fill_(-7)
-        dw.workspace.fill_(0x11 * (rep + 1))                # eager work between the replays
+        dw.scribble(0x11 * (rep + 1))                       # eager work between the replays
         _sync()
         graph.replay()
         _sync()
