@@ -357,9 +357,9 @@ def main():
     ap.add_argument("--budget", type=int, default=None)
     ap.add_argument("--repr", choices=("mean", "minmax"), default="mean",
                     help="block representation: mean pooling (headline) or channel-wise maxima and minima")
-    ap.add_argument("--launches", type=int, default=1, choices=(1, 3),
-                    help="how absb_decode_fused is enqueued: 1 = the whole step in one launch (default), "
-                         "3 = one launch per stage")
+    ap.add_argument("--launches", type=int, default=0, choices=(0, 1, 3),
+                    help="how absb_decode_fused is enqueued: 0 = the library's choice by shape (default), "
+                         "1 = the whole step in one launch, 3 = one launch per stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also time each entry point on its own")
     ap.add_argument("--matrix", action="store_true", help="run all configurations and the config-5 sweep; markdown out")

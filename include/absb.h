@@ -192,8 +192,11 @@ ABSB_API int absb_workspace_init(const absb_layer* layer, const absb_batch* batc
  * (absb_workspace_init) and are zero again afterwards.
  *   sel_idx_out [Bt*Hkv][plan's sel_stride], sel_cnt_out [Bt*Hkv]: optional copies of the
  *   selection (NULL ok: kept in the workspace).
- * With ABSB_TUNE_STEP_LAUNCHES = 3 (see absb_set_tuning) the three stages are enqueued as three
- * launches instead; that path needs no cleared counters. */
+ * For batches in which a segment is longer than 8192 blocks the three stages are enqueued as
+ * three launches instead (there the selection of the longest segment is the critical path, and
+ * the stand-alone selection kernel, with four times the threads per segment, is worth the two
+ * extra launches); ABSB_TUNE_STEP_LAUNCHES (see absb_set_tuning) forces either form.  The
+ * three-launch form does not need the counters cleared. */
 ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const void* q,
                                const uint8_t* codes, const float* qscale, const void* k_cache,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
@@ -259,8 +262,8 @@ ABSB_API const char* absb_strerror(int status);
  *                            and KV head count on that workspace: the counters sit at its start,
  *                            no other stage writes there, and the attention kernel leaves every
  *                            counter it used at zero.  absb_decode_fused never needs the knob.
- *   ABSB_TUNE_STEP_LAUNCHES: how absb_decode_fused is enqueued: 0 or 1 = one launch (default),
- *                            3 = one launch per stage.
+ *   ABSB_TUNE_STEP_LAUNCHES: how absb_decode_fused is enqueued: 0 = by shape (default; see
+ *                            absb_decode_fused), 1 = one launch, 3 = one launch per stage.
  * Returns ABSB_ERR_BAD_SHAPE for an unknown key or an invalid value. */
 enum {
   ABSB_TUNE_SPLIT_TOKENS = 0,

@@ -116,8 +116,17 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   if (p.max_splits > 65535) return ABSB_ERR_BAD_SHAPE;
   if ((int64_t)p.max_splits * st_tok >= (int64_t(1) << 31)) return ABSB_ERR_BAD_SHAPE;  // positions are 32-bit
 
+  // How absb_decode_fused is enqueued.  Measured on MI355X: the one-launch step wins (2-14 %)
+  // wherever no segment is longer than 8192 blocks; beyond that the selection of the longest
+  // segment, which the one-launch step runs on a 256-thread work-group, is the critical path and
+  // the 1024-thread selection kernel of the per-stage path is worth its two extra launches.
+  const int mode = tuning(ABSB_TUNE_STEP_LAUNCHES);
+  p.one_launch = mode == 1 || (mode == 0 && p.max_blocks <= 8192);
+  // blocks per estimation work-group: 256 (one batch of loads per lane); in the one-launch step,
+  // where estimation work-groups share the CUs with attention work-groups, a large batch does
+  // better with two batches per work-group (the prologue is amortised, half as many work-groups)
   int sc = tuning(ABSB_TUNE_SCORE_CHUNK);
-  p.score_chunk = sc > 0 ? sc : 256;
+  p.score_chunk = sc > 0 ? sc : (p.one_launch && p.total >= 65536 ? 512 : 256);
 
   // workspace: the split counters of the attention kernel come first, at the same place in every
   // carving (nothing else ever writes there); behind them the three users overlap, since they
@@ -274,7 +283,7 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   int32_t* scores = reinterpret_cast<int32_t*>(ws + p.ws_scores);
   int32_t* sel_idx = sel_idx_out ? sel_idx_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_idx);
   int32_t* sel_cnt = sel_cnt_out ? sel_cnt_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_cnt);
-  if (tuning(ABSB_TUNE_STEP_LAUNCHES) != 3 && fused_one_launch_fits(p))
+  if (p.one_launch && fused_one_launch_fits(p))
     return launch_fused(g, p, layer->dtype, resolve_scale(layer), q, codes, qscale, k_cache, v_cache, batch->page_table,
                         batch->seq_lens, batch->cent_off, batch->budget, sel_idx, sel_cnt, out, lse, ws, st);
   rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, batch->seq_lens, scores, nullptr, st);

@@ -43,6 +43,7 @@ struct Plan {
   int64_t sum_tokens;       // sum_s of the same bound
   int32_t split_tokens;     // tokens per split-K work-group
   int32_t max_splits;       // grid.x of the decode kernels
+  int32_t one_launch;       // absb_decode_fused: the whole step as one launch (else one launch per stage)
   int32_t score_chunk;      // centroids per work-group in score
   int32_t build_chunk_tokens;  // tokens per work-group in build (a head's chunk: max(16, that / B_h) blocks)
   int32_t build_max_chunks;    // max_s ceil(N_s / chunk_h)

@@ -107,19 +107,24 @@ def run_all_stages(wl, name, block_repr=O.MEAN):
     dw.decode_fused(want_sel=False); _sync()
     second = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
     assert np.array_equal(first, second), "fused output depends on workspace contents or is not deterministic"
-    # the same step as one launch per stage (needs no cleared counters): same selection, same bits out
+    # both ways of enqueueing the step, forced (the default picks one by shape): the whole step in one
+    # launch, and one launch per stage (which needs no cleared counters): same selection, same bits out
     from paper_2605_12110_amd import absb
-    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 3)
-    try:
-        dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
-        dw.workspace.fill_(0x3C)
-        dw.decode_fused(); _sync()
-    finally:
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
-    third = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
-    assert np.array_equal(first, third), "one launch and three launches disagree"
-    assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
-    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
+    for mode in (1, 3):
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, mode)
+        try:
+            dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+            if mode == 3:
+                dw.workspace.fill_(0x3C)
+            else:
+                dw.scribble(0x3C)
+            dw.decode_fused(); _sync()
+        finally:
+            absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+        again = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
+        assert np.array_equal(first, again), f"enqueue mode {mode} disagrees with the default"
+        assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
     dw.scribble(0x99)     # the stand-alone stages do not keep the other counters: clear them again
     _say("    fused: selection bit-exact, output within tolerance, deterministic, one launch == three launches")
     return dw, st, ref
@@ -477,6 +482,65 @@ def test_forced_blocks_on_a_long_segment_with_many_tiles():
         chosen = set(sel[s, :cnt[s]].tolist())
         want = set(range(-(-128 // B))) | set(range((65536 - 1024) // B, 65536 // B))
         assert (want <= chosen) if len(want) <= cnt[s] else (chosen <= want)
+
+
+# ------------------------------------------------------------------ the one-launch step beyond its default range
+@pytest.mark.parametrize("context,sizes", [(131072, (8, 16)), (163840, (8, 8))])
+def test_one_launch_step_on_segments_longer_than_the_default_allows(context, sizes):
+    """By default a batch with a segment of more than 8192 blocks is enqueued as three launches.  Forced
+    into one launch it must give the same bits: 16384 blocks (the longest register tile of the
+    256-thread selection) and 20480 blocks (keys re-read, no register tile)."""
+    import torch
+    from paper_2605_12110_amd import absb
+    wl = synth.make_workload(3, context=context, budget=4096, block_sizes=sizes)
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    dw = _dev(wl)
+    dw.build()
+    dw.decode_fused()                                            # default: three launches here
+    _check_out(dw, ref["out"], ref["lse"], f"default enqueue, context {context}")
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+    first = dw.out.clone()
+    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 1)
+    try:
+        for rep in range(2):                                     # twice: the counters must come back to zero
+            dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan"))
+            dw.decode_fused(); _sync()
+            assert torch.equal(dw.out, first), f"one launch, call {rep}"
+            assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+            assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+    finally:
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+    head = dw.workspace[:dw.nseg * 3 * 256 + 256].view(torch.int32)
+    assert int(head.abs().sum().item()) == 0, "the step left a counter, a flag or the status word set"
+
+
+def test_one_launch_step_with_constant_keys_takes_the_tie_paths():
+    """All keys of a head equal: every block of it scores the same, the threshold bin holds the whole
+    segment (the crowded path of the selection) and the lowest indices must win, in both enqueue modes."""
+    import torch
+    from paper_2605_12110_amd import absb
+    wl = synth.make_workload(1, context=16384, budget=1024, block_sizes=(8, 16))
+    k = wl.k_cache.reshape(-1, wl.num_kv_heads, wl.page_size, wl.head_dim)
+    k[:, 0] = k[0, 0, 0]                                         # KV head 0 (blocks of 16): one key everywhere
+    k[:, 2] = k[0, 2, 0]                                         # KV head 2 (blocks of 8, 2048 of them): the same
+    k[:, 1, :, 1:] = k[0, 1, 0, 1:]                              # KV head 1: keys differ in one channel only
+    assert wl.block_size[0] == 16 and wl.block_size[2] == 8
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    for h in (0, 2):
+        assert np.array_equal(ref["sel_idx"][h, :ref["sel_cnt"][h]], np.arange(ref["sel_cnt"][h]))
+    for mode in (1, 3):
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, mode)
+        try:
+            dw = _dev(wl)
+            dw.build()
+            dw.decode_fused()
+            _check_out(dw, ref["out"], ref["lse"], f"constant keys, enqueue mode {mode}")
+            assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+            assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+        finally:
+            absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
 
 
 # ------------------------------------------------------------------ growing contexts (store maintenance)
