@@ -64,6 +64,18 @@ typedef enum absb_dtype { ABSB_F16 = 0, ABSB_BF16 = 1 } absb_dtype;
  * R below is the number of vectors per block: 1 for MEAN, 2 for MINMAX (maxima first). */
 typedef enum absb_repr { ABSB_REPR_MEAN = 0, ABSB_REPR_MINMAX = 1 } absb_repr;
 
+/* Who shares a selection (the paper selects "per head" and leaves grouped-query models open):
+ *   ABSB_SELECT_GROUP          : one selection per (request, KV head), shared by its G query heads,
+ *                                ranked by the sum of their scores; K and V rows are read once per
+ *                                KV head.  The default.
+ *   ABSB_SELECT_PER_QUERY_HEAD : one selection per (request, query head), ranked by that head's own
+ *                                score; every query head reads the K and V rows of its own list
+ *                                (G times the traffic).  The centroid store stays one per KV head.
+ * Below, a "selection segment" is t = b*Hsel + hs with Hsel = Hkv (GROUP) or Hq (PER_QUERY_HEAD);
+ * with PER_QUERY_HEAD hs is the query head, its KV head is hs / G, and everything the default mode
+ * does for a KV head and its group is done for the query head alone. */
+typedef enum absb_select { ABSB_SELECT_GROUP = 0, ABSB_SELECT_PER_QUERY_HEAD = 1 } absb_select;
+
 typedef enum absb_status {
   ABSB_OK = 0,
   ABSB_ERR_NULL = -1,           /* a required pointer is NULL                                   */
@@ -95,7 +107,7 @@ typedef struct absb_layer {
      every score (lowest index first among themselves).  Forced blocks count towards K_s.        */
   int32_t sink_tokens;       /* >= 0                                                            */
   int32_t recent_tokens;     /* >= 0                                                            */
-  int32_t reserved1;
+  int32_t selection;         /* absb_select; 0 = one selection per KV head                      */
 } absb_layer;
 
 /* One decode step's batch. */
@@ -152,7 +164,10 @@ ABSB_API int absb_build_centroids(const absb_layer* layer, const absb_batch* bat
  *                       negative q_g[c]: the bound's larger product is the one whose extremum
  *                       matches the sign of q_c, which keeps the group score linear in the codes.
  *   score_exp [Bt*Hkv] i32, optional (NULL ok): e with w ~= wq * 2^e
- * Reads batch->seq_lens and batch->cent_off. */
+ * Reads batch->seq_lens and batch->cent_off.
+ * ABSB_SELECT_PER_QUERY_HEAD: w_c = q_hs[c] * qscale[s][c] for the one query head; scores holds
+ * G*total values, the G selection segments of store segment s side by side: block j of query head
+ * hs at G*off[s] + (hs % G)*(off[s+1]-off[s]) + j; score_exp [Bt*Hq]. */
 ABSB_API int absb_score(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
                         const float* qscale, int32_t* scores, int32_t* score_exp, void* stream);
 
@@ -162,7 +177,9 @@ ABSB_API int absb_score(const absb_layer* layer, const absb_batch* batch, const 
  *   sel_cnt [Bt*Hkv] i32            : K_s
  *   sel_stride >= the value absb_plan reports, else ABSB_ERR_BAD_SHAPE
  * With layer->sink_tokens / recent_tokens set, the blocks holding those tokens are selected first
- * (lowest index first if there are more of them than K_s), the rest of K_s by score. */
+ * (lowest index first if there are more of them than K_s), the rest of K_s by score.
+ * ABSB_SELECT_PER_QUERY_HEAD: one list per selection segment, sel_idx [Bt*Hq][sel_stride],
+ * sel_cnt [Bt*Hq]; scores laid out as absb_score writes them. */
 ABSB_API int absb_topk(const absb_layer* layer, const absb_batch* batch, const int32_t* scores,
                        int32_t* sel_idx, int32_t* sel_cnt, int32_t sel_stride, void* workspace,
                        size_t workspace_bytes, void* stream);
@@ -174,7 +191,8 @@ ABSB_API int absb_topk(const absb_layer* layer, const absb_batch* batch, const i
  *                     sel_stride; when batch->budget_host is non-NULL also sel_cnt[s] <= K_s
  *   out [Bt][Hq][d] : attention output in the K/V dtype
  *   lse [Bt][Hq] f32, optional (NULL ok): natural-log sum of exp of the scaled logits
- * An empty selection yields out = 0 and lse = -inf.  Accumulation is binary32. */
+ * An empty selection yields out = 0 and lse = -inf.  Accumulation is binary32.
+ * ABSB_SELECT_PER_QUERY_HEAD: sel_idx [Bt*Hq][sel_stride], sel_cnt [Bt*Hq], one list per query head. */
 ABSB_API int absb_sparse_decode(const absb_layer* layer, const absb_batch* batch, const void* q,
                                 const void* k_cache, const void* v_cache, const int32_t* sel_idx,
                                 const int32_t* sel_cnt, int32_t sel_stride, void* out, float* lse,
@@ -201,6 +219,11 @@ ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch,
                                const uint8_t* codes, const float* qscale, const void* k_cache,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
                                int32_t* sel_cnt_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* How absb_decode_fused will enqueue the step for this (layer, batch) under the current tuning:
+ * 1 (one launch) or 3 (one launch per stage); a negative absb_status on invalid arguments.  Pure
+ * host helper; reads the host fields only. */
+ABSB_API int absb_step_launches(const absb_layer* layer, const absb_batch* batch);
 
 /* Keeping the store current while decoding, without a rebuild (the paper notes that recomputing
  * every centroid is too expensive, Sec. 1 and 3.2, and leaves the mechanism open; this is the

@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(_HERE, "libabsb.so")
 
 F16, BF16 = 0, 1
 REPR_MEAN, REPR_MINMAX = 0, 1
+SELECT_GROUP, SELECT_PER_QUERY_HEAD = 0, 1
 TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO, TUNE_STEP_LAUNCHES = 0, 1, 2, 3
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
-EXPORTS = ("absb_plan", "absb_workspace_init", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
+EXPORTS = ("absb_plan", "absb_step_launches", "absb_workspace_init", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
            "absb_decode_fused", "absb_tail_init", "absb_append_token", "absb_head_recall", "absb_assign_block_sizes", "absb_stream_read",
            "absb_strerror", "absb_set_tuning")
 
@@ -39,7 +40,7 @@ class _Layer(C.Structure):
                 ("block_size", C.POINTER(C.c_int32)),
                 ("kv_stride_page", C.c_int64), ("kv_stride_head", C.c_int64), ("kv_stride_tok", C.c_int64),
                 ("sm_scale", C.c_float), ("sink_tokens", C.c_int32), ("recent_tokens", C.c_int32),
-                ("reserved1", C.c_int32)]
+                ("selection", C.c_int32)]
 
 
 class _Batch(C.Structure):
@@ -120,6 +121,7 @@ class Layer:
     block_repr: int = REPR_MEAN
     sink_tokens: int = 0
     recent_tokens: int = 0
+    selection: int = SELECT_GROUP
 
     def __setattr__(self, name, value):
         object.__setattr__(self, name, value)
@@ -134,7 +136,7 @@ class Layer:
             self._c = _Layer(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size, self.dtype,
                              int(self.block_repr),
                              bs_p, sp, sh, st, float(self.sm_scale), int(self.sink_tokens),
-                             int(self.recent_tokens), 0)
+                             int(self.recent_tokens), int(self.selection))
         return self._c
 
 
@@ -225,6 +227,14 @@ def absb_decode_fused(layer: Layer, batch: Batch, q, codes, qscale, k_cache, v_c
                                     _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(sel_idx_out), _ptr(sel_cnt_out),
                                     _ptr(workspace), C.c_size_t(_nbytes(workspace)), _stream(stream)),
            "absb_decode_fused")
+
+
+def absb_step_launches(layer: Layer, batch: Batch) -> int:
+    cl, cb = layer.c(), batch.c()
+    n = load().absb_step_launches(C.byref(cl), C.byref(cb))
+    if n < 0:
+        raise AbsbError(n, "absb_step_launches")
+    return int(n)
 
 
 def absb_workspace_init(layer: Layer, batch: Batch, workspace, stream=None) -> None:

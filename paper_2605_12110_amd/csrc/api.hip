@@ -38,14 +38,21 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   if (sp <= 0 || sh <= 0 || st < ABSB_HEAD_DIM || (sp % 8) || (sh % 8) || (st % 8)) return ABSB_ERR_BAD_SHAPE;
   if (!(layer->sm_scale >= 0.0f) || std::isinf(layer->sm_scale)) return ABSB_ERR_BAD_SHAPE;
   if (layer->sink_tokens < 0 || layer->recent_tokens < 0) return ABSB_ERR_BAD_SHAPE;
+  if (layer->selection != ABSB_SELECT_GROUP && layer->selection != ABSB_SELECT_PER_QUERY_HEAD)
+    return ABSB_ERR_UNSUPPORTED;
+  const bool per_q = layer->selection == ABSB_SELECT_PER_QUERY_HEAD;
+  const int Hsel = per_q ? Hq : Hkv;
   const int Bt = batch->batch;
-  if (Bt < 1 || (int64_t)Bt * Hkv > 65535) return ABSB_ERR_BAD_SHAPE;  // segments index grid.y
+  if (Bt < 1 || (int64_t)Bt * Hsel > 65535) return ABSB_ERR_BAD_SHAPE;  // segments index grid.y
 
   Geometry g = {};
   g.Bt = Bt;
   g.Hq = Hq;
   g.Hkv = Hkv;
   g.G = Hq / Hkv;
+  g.Hsel = Hsel;
+  g.Gd = per_q ? 1 : g.G;
+  g.Rk = per_q ? g.G : 1;
   g.log2_page = ilog2(P);
   g.pt_stride = batch->pt_stride;
   g.repr = layer->block_repr;
@@ -63,7 +70,8 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   }
 
   Plan p = {};
-  p.nseg = Bt * Hkv;
+  p.nseg = Bt * Hsel;
+  p.nstore = Bt * Hkv;
   p.build_chunk_tokens = 1024;
   int64_t max_len = 0;
   for (int b = 0; b < Bt; ++b) {
@@ -89,7 +97,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
       if (N > p.max_blocks) p.max_blocks = (int32_t)N;
       const int64_t tok = K * B;
       if (tok > p.max_tokens) p.max_tokens = tok;
-      p.sum_tokens += tok;
+      p.sum_tokens += tok * g.Rk;  // every selection segment of the KV head reads its own tokens
     }
   }
   if (!batch->budget_host) p.sel_stride = p.max_blocks;
@@ -140,16 +148,16 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   p.ws_head_bytes = head;
   size_t o = head;
   p.ws_scores = o;
-  o += align256((size_t)p.total * 4);
+  o += align256((size_t)p.total * g.Rk * 4);
   p.ws_sel_idx = o;
   o += align256((size_t)p.nseg * (size_t)(p.sel_stride > 0 ? p.sel_stride : 1) * 4);
   p.ws_sel_cnt = o;
   o += align256((size_t)p.nseg * 4);
   const size_t fused_head = o;
   p.ws_part_o = o;
-  o += align256((size_t)p.nseg * p.max_splits * g.G * ABSB_HEAD_DIM * 4);
+  o += align256((size_t)p.nseg * p.max_splits * g.Gd * ABSB_HEAD_DIM * 4);
   p.ws_part_ml = o;
-  o += align256((size_t)p.nseg * p.max_splits * g.G * 2 * 4);
+  o += align256((size_t)p.nseg * p.max_splits * g.Gd * 2 * 4);
   p.ws_fused_bytes = o;
   p.ws_decode_bytes = o;  // the stand-alone decode uses the same offsets (the head is left unused)
   (void)fused_head;
@@ -158,9 +166,9 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   const size_t width = (size_t)ABSB_HEAD_DIM * (g.repr + 1);  // values per block
   bo += align256((size_t)p.total * width * 4);
   p.ws_minmax = bo;
-  bo += align256((size_t)p.nseg * p.build_max_chunks * 2 * width * 4);
+  bo += align256((size_t)p.nstore * p.build_max_chunks * 2 * width * 4);
   p.ws_qinv = bo;
-  bo += align256((size_t)p.nseg * width * 4);
+  bo += align256((size_t)p.nstore * width * 4);
   p.ws_build_bytes = bo;
   p.ws_bytes = p.ws_fused_bytes > p.ws_build_bytes ? p.ws_fused_bytes : p.ws_build_bytes;
 
@@ -296,6 +304,14 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
                        batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, true, st);
 }
 
+int absb_step_launches(const absb_layer* layer, const absb_batch* batch) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, true, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  return p.one_launch && fused_one_launch_fits(p) ? 1 : 3;
+}
+
 int absb_workspace_init(const absb_layer* layer, const absb_batch* batch, void* workspace, size_t workspace_bytes,
                         void* stream) {
   Geometry g;
@@ -336,7 +352,7 @@ int absb_head_recall(const absb_layer* layer, const absb_batch* batch, const flo
   int rc = make_plan(layer, batch, false, 0, &g, &p);
   if (rc != ABSB_OK) return rc;
   if (!lse_selected || !lse_dense || !recall) return ABSB_ERR_NULL;
-  return launch_head_recall(lse_selected, lse_dense, recall, p.nseg, g.G, static_cast<hipStream_t>(stream));
+  return launch_head_recall(lse_selected, lse_dense, recall, p.nstore, g.G, static_cast<hipStream_t>(stream));
 }
 
 int absb_assign_block_sizes(int32_t n_samples, int32_t n_heads, int32_t n_cand, const float* recall_host,

@@ -383,7 +383,7 @@ int launch_append(const Geometry& g, const Plan& pl, int dtype, bool append, con
   p.qscale = qscale;
   p.qmin = qmin;
   p.tail = tail;
-  p.nseg = pl.nseg;
+  p.nseg = pl.nstore;
   p.g = g;
   if (dtype == ABSB_F16 && g.repr == ABSB_REPR_MEAN)
     launch_append_kernel<ABSB_F16, 0>(append, p, stream);
@@ -414,7 +414,7 @@ int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cac
   p.max_chunks = pl.build_max_chunks;
   p.g = g;
   const unsigned R = (unsigned)g.repr + 1;
-  const dim3 grid((unsigned)pl.build_max_chunks, (unsigned)pl.nseg), block(BUILD_THREADS);
+  const dim3 grid((unsigned)pl.build_max_chunks, (unsigned)pl.nstore), block(BUILD_THREADS);
   if (dtype == ABSB_F16 && g.repr == ABSB_REPR_MEAN)
     hipLaunchKernelGGL((build_pool_kernel<ABSB_F16, 0>), grid, block, 0, stream, p);
   else if (dtype == ABSB_F16)
@@ -425,7 +425,7 @@ int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cac
     hipLaunchKernelGGL((build_pool_kernel<ABSB_BF16, 1>), grid, block, 0, stream, p);
   int rc = check_launch();
   if (rc != ABSB_OK) return rc;
-  hipLaunchKernelGGL(build_params_kernel, dim3((unsigned)pl.nseg, R), dim3(PARAMS_THREADS), 0, stream, p);
+  hipLaunchKernelGGL(build_params_kernel, dim3((unsigned)pl.nstore, R), dim3(PARAMS_THREADS), 0, stream, p);
   rc = check_launch();
   if (rc != ABSB_OK) return rc;
   hipLaunchKernelGGL(build_codes_kernel, dim3(grid.x, grid.y, R), block, 0, stream, p);

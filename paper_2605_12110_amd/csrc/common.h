@@ -24,6 +24,10 @@ struct HeadTable {
 // Shape of the layer and of the paged cache, passed to kernels by value.
 struct Geometry {
   int32_t Bt, Hq, Hkv, G;
+  // Selection segments.  Group selection (default): one per (request, KV head), whose G query
+  // heads share the list: Hsel = Hkv, Gd = G, Rk = 1.  Per-query-head selection: one per
+  // (request, query head): Hsel = Hq, Gd = 1, Rk = G selection segments read each KV head's store.
+  int32_t Hsel, Gd, Rk;
   int32_t log2_page;  // P = 1 << log2_page
   int32_t pt_stride;
   int32_t repr;       // absb_repr: vectors per block = repr + 1
@@ -35,8 +39,9 @@ struct Geometry {
 
 // Host-side sizes derived from (layer, batch).
 struct Plan {
-  int32_t nseg;
-  int64_t total;            // total centroids
+  int32_t nseg;             // selection segments: Bt * Hsel
+  int32_t nstore;           // store segments: Bt * Hkv
+  int64_t total;            // total centroids (rows of the store)
   int32_t max_blocks;       // max_s N_s
   int32_t sel_stride;       // max_s K_s (0 when no budget was given)
   int64_t max_tokens;       // max_s (upper bound of selected tokens of a segment)
@@ -103,6 +108,23 @@ inline int check_launch() { return hipGetLastError() == hipSuccess ? ABSB_OK : A
 
 // ------------------------------------------------------------------ device helpers
 #ifdef __HIPCC__
+// Selection segment t -> request b, selection head hs (first query head = hs * Gd), KV head hk,
+// store segment s = b * Hkv + hk, and where the segment's scores start in the score array:
+// the Rk selection segments of a store segment lie side by side, Rk * off[s] + (hs % Rk) * rows.
+struct SegMap {
+  int b, hs, hk, s;
+};
+__device__ __forceinline__ SegMap seg_map(int t, int Hsel, int Rk, int Hkv) {
+  SegMap m;
+  m.b = t / Hsel;
+  m.hs = t % Hsel;
+  m.hk = m.hs / Rk;
+  m.s = m.b * Hkv + m.hk;
+  return m;
+}
+__device__ __forceinline__ int64_t score_base(const SegMap& m, int Rk, int off, int rows) {
+  return (int64_t)Rk * off + (int64_t)(m.hs % Rk) * rows;
+}
 // Development aid, compiled in only with -DABSB_TRACE: thread 0 of a work-group stamps the 100 MHz
 // wall clock into slot `k` of its row of a trace buffer.
 #ifdef ABSB_TRACE

@@ -18,7 +18,7 @@ __global__ void decode_clear_tickets_kernel(int32_t* tickets, int n) {
 
 template <int DT>
 static void launch_partial(const DecodeParams& p, dim3 grid, hipStream_t stream) {
-  switch (p.g.G) {
+  switch (p.g.Gd) {
     case 1: hipLaunchKernelGGL((decode_kernel<DT, 1>), grid, dim3(DEC_THREADS), 0, stream, p); break;
     case 2: hipLaunchKernelGGL((decode_kernel<DT, 2>), grid, dim3(DEC_THREADS), 0, stream, p); break;
     case 3: hipLaunchKernelGGL((decode_kernel<DT, 3>), grid, dim3(DEC_THREADS), 0, stream, p); break;

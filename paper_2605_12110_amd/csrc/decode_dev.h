@@ -140,8 +140,11 @@ __device__ __forceinline__ void stage_v_word(char* dst, uint32_t r0, uint32_t r1
 // loads, and the segment's last work-group clears the flag again.  `lds`: DEC_LDS_BYTES.
 template <int DT, int G, bool LISTED>
 __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int split, char* lds) {
-  const int b = s / p.g.Hkv, h = s % p.g.Hkv;
-  const int lb = p.g.heads.log2_block[h];
+  // s is a SELECTION segment: its G (= the template's) query heads start at head hs * G; hk is the
+  // KV head whose rows they read
+  const SegMap sm = seg_map(s, p.g.Hsel, p.g.Rk, p.g.Hkv);
+  const int b = sm.b, hs = sm.hs, hk = sm.hk;
+  const int lb = p.g.heads.log2_block[hk];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, grp = lane >> 4, li = lane & 15;
   const int32_t* sel = p.sel_idx + (size_t)s * p.sel_stride;
   const int pos_begin = split * p.split_tokens;
@@ -158,7 +161,7 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
   // never beyond what the launch covers (a list longer than promised is cut, not overrun)
   int nsel;
   if (LISTED) {
-    const int rows = p.cent_off[s + 1] - p.cent_off[s];
+    const int rows = p.cent_off[sm.s + 1] - p.cent_off[sm.s];
     nsel = budget_blocks(p.budget[b], lb, blocks_in_use(p.g.tight, rows, p.seq_lens, b, lb), p.sel_stride);
   } else {
     nsel = p.sel_cnt[s];
@@ -166,7 +169,7 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
   const int ntok = min(nsel << lb, p.max_splits * p.split_tokens);
   if (ntok == 0 && split == 0) {  // empty selection: the output rows are zero, the log-sum-exp -inf
     for (int i = tid; i < G * ABSB_HEAD_DIM; i += DEC_THREADS) {
-      const size_t row = (size_t)b * p.g.Hq + (size_t)h * G + (i >> 7);
+      const size_t row = (size_t)b * p.g.Hq + (size_t)hs * G + (i >> 7);
       static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + (i & 127)] = 0;
       if (p.lse && (i & 127) == 0) p.lse[row] = -__builtin_inff();
     }
@@ -177,7 +180,7 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
   const int lP = p.g.log2_page;
 
   const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
-  const size_t lane_off = (size_t)h * p.g.s_head + (size_t)li * 8;
+  const size_t lane_off = (size_t)hk * p.g.s_head + (size_t)li * 8;
 
   char* s_stage = lds;  // reused by the epilogue
   float (*s_m)[DEC_WAVES] = reinterpret_cast<float (*)[DEC_WAVES]>(lds + DEC_LDS_STATE);
@@ -194,7 +197,7 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
   for (int ks = 0; ks < 8; ++ks) {
     qb[ks] = make_uint2(0u, 0u);
     if (li < G)
-      qb[ks] = *reinterpret_cast<const uint2*>(p.q + ((size_t)b * p.g.Hq + (size_t)h * G + li) * ABSB_HEAD_DIM + 16 * ks +
+      qb[ks] = *reinterpret_cast<const uint2*>(p.q + ((size_t)b * p.g.Hq + (size_t)hs * G + li) * ABSB_HEAD_DIM + 16 * ks +
                                                4 * grp);
   }
 
@@ -478,7 +481,7 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
 
   // ---- normalise and write the group's output rows
   if (tid < NCOL) {
-    const size_t row = (size_t)b * p.g.Hq + (size_t)h * G + g;
+    const size_t row = (size_t)b * p.g.Hq + (size_t)hs * G + g;
     const bool any = Lsum > 0.0f;
     const float inv = any ? 1.0f / Lsum : 0.0f;
     const uint32_t lo = (uint32_t)Elem<DT>::narrow(O[0] * inv) | ((uint32_t)Elem<DT>::narrow(O[1] * inv) << 16);

@@ -127,7 +127,7 @@ static void launch_fused_rep(const FusedParams& p, int repr, dim3 grid, size_t l
 
 template <int DT>
 static void launch_fused_group(const FusedParams& p, int repr, dim3 grid, size_t lds, hipStream_t stream) {
-  switch (p.dc.g.G) {
+  switch (p.dc.g.Gd) {
     case 1: launch_fused_rep<DT, 1>(p, repr, grid, lds, stream); break;
     case 2: launch_fused_rep<DT, 2>(p, repr, grid, lds, stream); break;
     case 3: launch_fused_rep<DT, 3>(p, repr, grid, lds, stream); break;

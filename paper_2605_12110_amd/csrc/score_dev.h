@@ -34,7 +34,8 @@ struct ScoreParams {
   HeadTable heads;
   int32_t* scores;          // [total]
   int32_t* score_exp;       // [nseg] or null
-  int32_t Hq, Hkv, G, chunk, tight;
+  int32_t Hq, Hkv, G, chunk, tight;  // G: query heads folded into one selection segment (Gd)
+  int32_t Hsel, Rk;
 };
 
 constexpr int SCORE_PLANES = 5;
@@ -54,7 +55,9 @@ inline ScoreParams make_score_params(const Geometry& g, const Plan& pl, const vo
   p.score_exp = score_exp;
   p.Hq = g.Hq;
   p.Hkv = g.Hkv;
-  p.G = g.G;
+  p.G = g.Gd;
+  p.Hsel = g.Hsel;
+  p.Rk = g.Rk;
   p.chunk = pl.score_chunk;
   return p;
 }
@@ -72,15 +75,16 @@ __host__ __device__ constexpr size_t score_lds_bytes() {
   return 16 + (size_t)SCORE_PLANES * (ABSB_HEAD_DIM * (REP + 1) / 8) * sizeof(uint32_t);
 }
 
-// Scores of blocks [chunk_idx*p.chunk, +p.chunk) of segment s by one work-group of 256 threads.
+// Scores of blocks [chunk_idx*p.chunk, +p.chunk) of selection segment t by one work-group of 256 threads.
 // Returns the segment's block count N_s, or 0 (nothing done) when the segment has no such blocks.  COH: the scores are read by
 // another work-group of the same launch.  `lds`: score_lds_bytes<REP>() bytes, 16-byte aligned.
 template <int DT, int REP, bool COH>
-__device__ __forceinline__ int score_chunk(const ScoreParams& p, int s, int chunk_idx, char* lds) {
+__device__ __forceinline__ int score_chunk(const ScoreParams& p, int t, int chunk_idx, char* lds) {
   constexpr int R = REP + 1;                 // vectors per block: the mean, or maxima and minima
   constexpr int W = ABSB_HEAD_DIM * R;       // weights = values per block
   constexpr int ROW_BYTES = W / 2;
-  const int b = s / p.Hkv, h = s % p.Hkv;
+  const SegMap sm = seg_map(t, p.Hsel, p.Rk, p.Hkv);
+  const int b = sm.b, s = sm.s;
   const int tid = threadIdx.x;
   // ---- the group's query values and the scale of this thread's weight go in flight first, all at
   // once: their addresses need nothing from memory, and everything below waits for them
@@ -88,13 +92,15 @@ __device__ __forceinline__ int score_chunk(const ScoreParams& p, int s, int chun
   float scale = 0.0f;
   if (tid < W) {
     const uint16_t* qrow =
-        p.q + ((size_t)b * p.Hq + (size_t)h * p.G) * ABSB_HEAD_DIM + (tid & (ABSB_HEAD_DIM - 1));
+        p.q + ((size_t)b * p.Hq + (size_t)sm.hs * p.G) * ABSB_HEAD_DIM + (tid & (ABSB_HEAD_DIM - 1));
 #pragma unroll
     for (int g = 0; g < ABSB_MAX_GROUP; ++g) qraw[g] = g < p.G ? qrow[(size_t)g * ABSB_HEAD_DIM] : (uint16_t)0;
     scale = p.qscale[(size_t)s * W + tid];
   }
   const int off = p.cent_off[s];
-  const int N = blocks_in_use(p.tight, p.cent_off[s + 1] - off, p.seq_lens, b, p.heads.log2_block[h]);
+  const int rows = p.cent_off[s + 1] - off;
+  const int N = blocks_in_use(p.tight, rows, p.seq_lens, b, p.heads.log2_block[sm.hk]);
+  int32_t* scores_t = p.scores + score_base(sm, p.Rk, off, rows);  // this selection segment's scores
   const int j0 = chunk_idx * p.chunk;
   if (j0 >= N) return 0;
 
@@ -159,7 +165,7 @@ __device__ __forceinline__ int score_chunk(const ScoreParams& p, int s, int chun
       if ((tid & 7) == 0) s_plane[k][tid >> 3] = packed;
     }
   }
-  if (tid == 0 && chunk_idx == 0 && p.score_exp) p.score_exp[s] = ex;
+  if (tid == 0 && chunk_idx == 0 && p.score_exp) p.score_exp[t] = ex;
   __syncthreads();
 
   // ---- each lane: the digit planes of its quarter of each vector (4 words of 8 values)
@@ -200,7 +206,7 @@ __device__ __forceinline__ int score_chunk(const ScoreParams& p, int s, int chun
     for (int u = 0; u < PF; ++u) {
       const int j = jb + u * 64 + (tid >> 2);
       const int32_t sc = dot(pre[u]);
-      if (j < jend && quarter == 0) st_i32<COH>(p.scores + off + j, sc);
+      if (j < jend && quarter == 0) st_i32<COH>(scores_t + j, sc);
     }
     jb += PF * 64;
     if (jb >= jend) break;

@@ -37,6 +37,7 @@ struct TopkParams {
   int32_t* sel_cnt;
   int32_t* tickets;  // [nseg] or null: split counters of the attention kernel that follows, cleared here
   int32_t sel_stride, Hkv, tight;
+  int32_t Hsel, Rk;  // selection segments per request, selection segments per KV head
   HeadTable heads;
   uint64_t* trace;  // development aid (ABSB_TRACE builds), else null
 };
@@ -57,6 +58,8 @@ inline TopkParams make_topk_params(const Geometry& g, const int32_t* scores, con
   p.tickets = tickets;
   p.sel_stride = sel_stride;
   p.Hkv = g.Hkv;
+  p.Hsel = g.Hsel;
+  p.Rk = g.Rk;
   p.heads = g.heads;
   p.trace = nullptr;
   return p;
@@ -152,18 +155,20 @@ __device__ __forceinline__ void pick_bin(TopkShared& sh, int tid, int lane, int 
   __syncthreads();
 }
 
-// The selection of segment s by one work-group of NT threads.
+// The selection of selection segment t by one work-group of NT threads.
 //   KPT > 0: keys of the segment live in registers (competing blocks <= KPT*NT); KPT == 0: re-read.
 //   COH: the scores were written, and the list will be read, by other work-groups of this launch.
 //   sh, bitmap: LDS as sized by topk_lds_bytes().
 // Every thread of the work-group must call it; all of them return together.
 template <int NT, int KPT, bool COH>
-__device__ __forceinline__ void topk_segment(const TopkParams& p, int s, TopkShared& sh, uint32_t* s_bitmap) {
+__device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkShared& sh, uint32_t* s_bitmap) {
   constexpr int WAVES = NT / 64;
-  const int b = s / p.Hkv, h = s % p.Hkv;
-  const int off = p.cent_off[s];
-  const int lb = p.heads.log2_block[h];
-  const int Nall = blocks_in_use(p.tight, p.cent_off[s + 1] - off, p.seq_lens, b, lb);
+  const SegMap sm = seg_map(t, p.Hsel, p.Rk, p.Hkv);
+  const int b = sm.b;
+  const int off = p.cent_off[sm.s];
+  const int rows = p.cent_off[sm.s + 1] - off;
+  const int lb = p.heads.log2_block[sm.hk];
+  const int Nall = blocks_in_use(p.tight, rows, p.seq_lens, b, lb);
   int K = budget_blocks(p.budget[b], lb, Nall, p.sel_stride);
   // Forced blocks are a prefix [0, lo) (they hold the first sink_tokens tokens) and a suffix
   // [hi, Nall) (the last recent_tokens tokens) of the segment; they are selected ahead of every
@@ -174,8 +179,8 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int s, TopkSha
   const int nforced = lo + (Nall - hi);
   const int N = hi - lo;  // competing blocks; the code below indexes them from 0
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int32_t* sc = p.scores + off + (N > 0 ? lo : 0);
-  int32_t* out = p.sel_idx + (size_t)s * p.sel_stride;
+  const int32_t* sc = p.scores + score_base(sm, p.Rk, off, rows) + (N > 0 ? lo : 0);
+  int32_t* out = p.sel_idx + (size_t)t * p.sel_stride;
   constexpr int R = KPT > 0 ? KPT : 1;
   const int ntiles = KPT > 0 ? KPT : (N + NT - 1) / NT;
   const int nwords = (N + 31) >> 5;
@@ -196,8 +201,8 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int s, TopkSha
   };
 
   if (tid == 0) {
-    st_i32<COH>(p.sel_cnt + s, K);
-    if (p.tickets) p.tickets[(size_t)s * ABSB_TICKET_STRIDE] = 0;
+    st_i32<COH>(p.sel_cnt + t, K);
+    if (p.tickets) p.tickets[(size_t)t * ABSB_TICKET_STRIDE] = 0;
   }
 #pragma unroll 1
   for (int i = K + tid; i < p.sel_stride; i += NT) st_i32<COH>(out + i, -1);

@@ -23,7 +23,7 @@ class DeviceWorkload:
     def __init__(self, wl, device: str = "cuda:0", budget: Optional[np.ndarray] = None,
                  block_repr: int = absb.REPR_MEAN, block_size: Optional[np.ndarray] = None,
                  share: Optional["DeviceWorkload"] = None, sink_tokens: int = 0, recent_tokens: int = 0,
-                 cap_lens: Optional[np.ndarray] = None):
+                 cap_lens: Optional[np.ndarray] = None, selection: int = absb.SELECT_GROUP):
         """`block_size` / `budget` override the workload's; `share` reuses another holder's resident
         caches, queries, lengths and page table (same workload under other block sizes or budgets);
         `cap_lens` lays the store out for contexts that grow up to those lengths (set_lens/append)."""
@@ -35,7 +35,7 @@ class DeviceWorkload:
         self.block_size = np.asarray(wl.block_size if block_size is None else block_size, dtype=np.int32)
         self.layer = absb.Layer(wl.num_q_heads, wl.num_kv_heads, wl.head_dim, wl.page_size, wl.dtype,
                                 self.block_size, wl.strides, block_repr=block_repr, sink_tokens=sink_tokens,
-                                recent_tokens=recent_tokens)
+                                recent_tokens=recent_tokens, selection=selection)
         width = wl.head_dim * (2 if block_repr == absb.REPR_MINMAX else 1)      # values per block
         if share is None:
             self.k_cache = _up(wl.k_cache.view(np.int16), tdt, device)
@@ -61,17 +61,21 @@ class DeviceWorkload:
             self.plan = absb.absb_plan(self.layer, self.batch)
         self.cent_off = _up(self.plan.cent_off, None, device)
         self.batch.cent_off = self.cent_off
-        nseg = wl.batch * wl.num_kv_heads
+        nseg = wl.batch * wl.num_kv_heads          # store segments
         self.nseg = nseg
+        per_q = selection == absb.SELECT_PER_QUERY_HEAD
+        nsel = wl.batch * (wl.num_q_heads if per_q else wl.num_kv_heads)      # selection segments
+        self.nsel = nsel
+        rk = wl.num_q_heads // wl.num_kv_heads if per_q else 1
         total = self.plan.total_centroids
         self.codes = torch.empty((total, width // 2), dtype=torch.uint8, device=device)
         self.qscale = torch.empty((nseg, width), dtype=torch.float32, device=device)
         self.qmin = torch.empty((nseg, width), dtype=torch.float32, device=device)
-        self.scores = torch.empty((total,), dtype=torch.int32, device=device)
-        self.score_exp = torch.empty((nseg,), dtype=torch.int32, device=device)
+        self.scores = torch.empty((total * rk,), dtype=torch.int32, device=device)
+        self.score_exp = torch.empty((nsel,), dtype=torch.int32, device=device)
         self.sel_stride = max(self.plan.sel_stride, 1)
-        self.sel_idx = torch.empty((nseg, self.sel_stride), dtype=torch.int32, device=device)
-        self.sel_cnt = torch.empty((nseg,), dtype=torch.int32, device=device)
+        self.sel_idx = torch.empty((nsel, self.sel_stride), dtype=torch.int32, device=device)
+        self.sel_cnt = torch.empty((nsel,), dtype=torch.int32, device=device)
         self.out = torch.empty((wl.batch, wl.num_q_heads, wl.head_dim), dtype=tdt, device=device)
         self.lse = torch.empty((wl.batch, wl.num_q_heads), dtype=torch.float32, device=device)
         self.tail = torch.empty((nseg, width), dtype=torch.float32, device=device)

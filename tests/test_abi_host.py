@@ -173,6 +173,37 @@ def test_tuning_knobs_validate():
     absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
     with pytest.raises(absb.AbsbError):
         absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 64)
+    for ok in (1, 3, 0):
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, ok)
+    with pytest.raises(absb.AbsbError):
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 2)
+
+
+def test_enqueue_mode_of_the_fused_step_follows_the_longest_segment():
+    """One launch while no segment has more than 8192 blocks, one launch per stage beyond; the knob
+    forces either; the workspace always has room for the counters of the one-launch step."""
+    def mode(L, B):
+        layer = absb.Layer(8, 2, 128, 64, absb.F16, [B, 128], (2 * 64 * 128, 64 * 128, 128))
+        batch = absb.Batch(seq_lens_host=[L, 100], budget_host=[64, 64], pt_stride=(L + 63) // 64)
+        return absb.absb_step_launches(layer, batch), absb.absb_plan(layer, batch).workspace_bytes
+    assert mode(8192 * 8, 8)[0] == 1
+    assert mode(8192 * 8 + 1, 8)[0] == 3
+    assert mode(131072, 16)[0] == 1
+    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 3)
+    try:
+        assert mode(4096, 8)[0] == 3
+    finally:
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 1)
+    try:
+        assert mode(131072, 8)[0] == 1
+    finally:
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+    nseg = 2 * 2
+    assert mode(4096, 8)[1] >= 3 * nseg * 256 + 256
+    with pytest.raises(absb.AbsbError):
+        absb.absb_step_launches(absb.Layer(8, 2, 128, 64, absb.F16, [8, 8], (16384, 8192, 128)),
+                                absb.Batch(seq_lens_host=[64], budget_host=None, pt_stride=1))
 
 
 def test_product_package_does_not_reach_the_oracle():

@@ -48,15 +48,24 @@ def _check_out(dw, want_out, want_lse, what):
     assert np.array_equal(np.isneginf(lse), np.isneginf(want_lse))
 
 
-def run_all_stages(wl, name, block_repr=O.MEAN):
+def run_all_stages(wl, name, block_repr=O.MEAN, per_query_head=False):
     """Stage by stage (each GPU stage fed the oracle's inputs), then the fused call end to end."""
     _say(f"[case {name}] repr={block_repr} Bt={wl.batch} Hq={wl.num_q_heads} Hkv={wl.num_kv_heads} P={wl.page_size} "
          f"L={wl.seq_lens.tolist()[:4]}.. B={wl.block_size.tolist()} T={wl.budget.tolist()[:4]}.. dtype={wl.dtype}")
     t0 = time.time()
     st = O.build_centroids(wl, block_repr)
-    ref = O.decode_step(wl, st, sel_stride=None)
-    _say(f"    oracle: build+step {time.time() - t0:.2f}s, centroids={int(st.off[-1])}")
-    dw = _dev(wl, block_repr=block_repr)      # the two enumerations agree: 0 mean, 1 maxima and minima
+    if per_query_head:
+        # the reference is the method on the model in which every query head is its own group; the
+        # library keeps ONE store per KV head (st) and must reproduce that model's scores (same flat
+        # layout: the G copies of a store segment side by side), lists and outputs
+        view = O.per_query_head_view(wl)
+        ref = O.decode_step(view, O.build_centroids(view, block_repr), sel_stride=None)
+    else:
+        ref = O.decode_step(wl, st, sel_stride=None)
+    _say(f"    oracle: build+step {time.time() - t0:.2f}s, centroids={int(st.off[-1])}, per_query_head={per_query_head}")
+    from paper_2605_12110_amd import absb as _absb
+    dw = _dev(wl, block_repr=block_repr,      # the two enumerations agree: 0 mean, 1 maxima and minima
+              selection=_absb.SELECT_PER_QUERY_HEAD if per_query_head else _absb.SELECT_GROUP)
     assert np.array_equal(dw.plan.cent_off.astype(np.int64), st.off)
     K = dw.sel_stride
     assert K == int(ref["sel_cnt"].max())
@@ -482,6 +491,32 @@ def test_forced_blocks_on_a_long_segment_with_many_tiles():
         chosen = set(sel[s, :cnt[s]].tolist())
         want = set(range(-(-128 // B))) | set(range((65536 - 1024) // B, 65536 // B))
         assert (want <= chosen) if len(want) <= cnt[s] else (chosen <= want)
+
+
+# ------------------------------------------------------------------ per-query-head selection
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_per_query_head_selection_ragged_small_batch(dtype):
+    wl = synth.tiny_workload(seed=5, dtype=dtype, Bt=3, Hq=8, Hkv=2, P=16, seq_lens=(37, 700, 1291),
+                             block_size=(8, 32), budget=(64, 200, 96))
+    run_all_stages(wl, f"per-query-head tiny dtype={dtype}", per_query_head=True)
+
+
+@pytest.mark.parametrize("G", [1, 5, 8])
+def test_per_query_head_selection_group_sizes(G):
+    wl = synth.tiny_workload(seed=6, Bt=2, Hq=2 * G, Hkv=2, P=64, seq_lens=(1000, 2500), block_size=(128, 16),
+                             budget=(256, 512))
+    run_all_stages(wl, f"per-query-head G={G}", per_query_head=True)
+
+
+def test_per_query_head_selection_config1_and_max_min_pooling():
+    run_all_stages(synth.make_workload(1), "per-query-head config1", per_query_head=True)
+    run_all_stages(synth.make_workload(1, context=2048, budget=256), "per-query-head config1/2K max-min",
+                   block_repr=O.MINMAX, per_query_head=True)
+
+
+def test_per_query_head_selection_config3_scaled():
+    run_all_stages(synth.make_workload(3, context=32768, budget=2048), "per-query-head config3/32K",
+                   per_query_head=True)
 
 
 # ------------------------------------------------------------------ the one-launch step beyond its default range
