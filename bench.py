@@ -31,29 +31,34 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 METRIC = "decode attention µs/step/layer + achieved HBM GB/s at 128K ctx (8B-shaped GQA)"
 # HBM bytes moved by one launch of the attention kernel on the headline workload, from rocprofv3
-# --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled by a 1 GiB copy in the same run): 17.57 MB read
+# --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled by a 1 GiB copy in the same run): 17.59 MB read
 # (K/V rows, lists, page table, the merging groups' re-read of the partials) + 0.56 MB written.
 # Source: profiles/decode_fused_config3_hbm_counters.md
-HEADLINE_TRAFFIC_BYTES = 18_130_000
+HEADLINE_TRAFFIC_BYTES = 18_150_000
 BASE_SEED = {1: 0, 2: 1, 3: 2, 4: 3, 5: 4}
 
 
-def useful_bytes(wl, plan_off, sel_cnt, vectors=1):
+def useful_bytes(wl, plan_off, sel_cnt, vectors=1, per_query_head=False):
     """Algorithmic bytes of one step: what the method itself must move.
     score : INT4 codes of every block (d/2 bytes per vector: one for mean pooling, two for
             max-min pooling) + per-channel scales + queries
     select: the index list
     decode: K and V rows of the selected tokens + page-table entries touched + queries + outputs
-    Intermediate arrays (int32 scores, split-K partials) are not counted."""
+    Intermediate arrays (int32 scores, split-K partials) are not counted.
+    With per-query-head selection every query head scans its KV head's codes and reads the rows of
+    its own list: the method itself then moves G times the codes and up to G times the rows."""
     d, e = wl.head_dim, 2
-    nseg = wl.batch * wl.num_kv_heads
+    rk = wl.group if per_query_head else 1              # selection segments per KV head
+    hsel = wl.num_kv_heads * rk
+    nseg = wl.batch * hsel
     total = int(plan_off[-1])
-    b_score = vectors * (total * (d // 2) + nseg * d * 4) + wl.batch * wl.num_q_heads * d * e
+    b_score = vectors * rk * (total * (d // 2) + wl.batch * wl.num_kv_heads * d * 4) + wl.batch * wl.num_q_heads * d * e
     b_select = int(sel_cnt.sum()) * 4
     tokens = 0
     pt_entries = 0
     for s in range(nseg):
-        b, h = divmod(s, wl.num_kv_heads)
+        b, hs = divmod(s, hsel)
+        h = hs // rk
         B = int(wl.block_size[h])
         k = int(sel_cnt[s])
         tokens += min(k * B, int(wl.seq_lens[b]))
@@ -95,7 +100,7 @@ def per_step_percentiles(fn, n_steps):
 
 
 def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, uniform_block=None, max_bytes=24 << 30,
-                   block_repr=0):
+                   block_repr=0, selection=0):
     """R independent layer instances of a workload, resident on the GPU, centroid stores built."""
     import torch
     from paper_2605_12110_amd import synth
@@ -106,10 +111,10 @@ def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, u
     if R <= 0:
         R = max(1, min(8, -(-(2 << 30) // wl0.kv_bytes())))
     R = max(1, min(R, max_bytes // max(wl0.kv_bytes(), 1)))
-    insts = [DeviceWorkload(wl0, block_repr=block_repr)]
+    insts = [DeviceWorkload(wl0, block_repr=block_repr, selection=selection)]
     for r in range(1, R):
         wl = synth.make_workload(config, seed=BASE_SEED[config] + 100 * r, **kw)
-        insts.append(DeviceWorkload(wl, block_repr=block_repr))
+        insts.append(DeviceWorkload(wl, block_repr=block_repr, selection=selection))
         wl.k_cache = wl.v_cache = None      # free the host copies of the extra instances
     for dw in insts:
         dw.build()
@@ -124,7 +129,8 @@ def measure(wl0, insts, steps, warmup, stages=False, percentiles=False):
     for dw in insts:        # one untimed step per instance: selection sizes for the byte count
         dw.decode_fused()
         torch.cuda.synchronize()
-        ub.append(useful_bytes(dw.wl, dw.plan.cent_off, dw.sel_cnt.cpu().numpy(), dw.layer.block_repr + 1))
+        ub.append(useful_bytes(dw.wl, dw.plan.cent_off, dw.sel_cnt.cpu().numpy(), dw.layer.block_repr + 1,
+                               dw.layer.selection == 1))
     mean_bytes = {k: float(np.mean([u[k] for u in ub])) for k in ub[0]}
 
     def step(i):
@@ -260,6 +266,29 @@ def run_matrix(args):
         del insts, dw
         torch.cuda.empty_cache()
 
+    print("\nPer-query-head selection (every query head ranks blocks by its own score and reads the rows of its own "
+          "list: G times the code scans and up to G times the K/V rows; one centroid store per KV head), same workloads\n")
+    print("| workload | launches/step | useful MB/step | us/step | GB/s | planted-token recall: per query head / per group |")
+    print("|---|---|---|---|---|---|", flush=True)
+    for cfg in (1, 2, 3, 4):
+        wl0, insts = make_instances(cfg, selection=1)
+        m = measure(wl0, insts, args.steps, args.warmup)
+        dw = insts[0]
+        dw.decode_fused()
+        torch.cuda.synchronize()
+        if wl0.planted:
+            view = O.per_query_head_view(wl0, caches=False)
+            recq = O.planted_recall(view, dw.sel_idx.cpu().numpy(), dw.sel_cnt.cpu().numpy())
+            r1 = O.decode_step(wl0, O.build_centroids(wl0, O.MEAN))
+            recg = O.planted_recall(wl0, r1["sel_idx"], r1["sel_cnt"])
+        else:
+            recq = recg = float("nan")
+        gb = m["bytes"]["total"] / (m["ms"] * 1e-3) / 1e9
+        print(f"| config {cfg} | {m['launches']} | {m['bytes']['total'] / 1e6:.1f} | {m['ms'] * 1e3:.1f} | {gb:.0f} | "
+              f"{recq:.3f} / {recg:.3f} |", flush=True)
+        del insts, dw
+        torch.cuda.empty_cache()
+
     print("\nStore maintenance while decoding (absb_append_token: one new token per request folded into the store, "
           "no rebuild) next to a full rebuild (absb_build_centroids)\n")
     print("| workload | segments | append us/call | rebuild us/call |")
@@ -356,6 +385,8 @@ def main():
     ap.add_argument("--context", type=int, default=None)
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--budget", type=int, default=None)
+    ap.add_argument("--select", choices=("group", "per-query-head"), default="group",
+                    help="who shares a selection: the query heads of a KV head (default), or nobody")
     ap.add_argument("--repr", choices=("mean", "minmax"), default="mean",
                     help="block representation: mean pooling (headline) or channel-wise maxima and minima")
     ap.add_argument("--launches", type=int, default=0, choices=(0, 1, 3),
@@ -400,7 +431,8 @@ def main():
 
     block_repr = 1 if args.repr == "minmax" else 0
     wl0, insts = make_instances(args.config, context=args.context, batch=args.batch, budget=args.budget,
-                                rotate=args.rotate, block_repr=block_repr)
+                                rotate=args.rotate, block_repr=block_repr,
+                                selection=1 if args.select == "per-query-head" else 0)
     m = measure(wl0, insts, args.steps, args.warmup, stages=args.stages, percentiles=True)
     ms, mean_bytes, R = m["ms"], m["bytes"], m["R"]
     gbps = mean_bytes["total"] / (ms * 1e-3) / 1e9
@@ -408,7 +440,7 @@ def main():
     ceiling = stream_read_ceiling()
     wl = wl0
     headline = (args.config == 3 and args.context is None and args.batch is None and args.budget is None
-                and block_repr == 0)
+                and block_repr == 0 and args.select == "group")
     result = {
         "metric": METRIC,
         "value": round(gbps, 2),
@@ -427,7 +459,7 @@ def main():
             "workload": f"config{args.config}: batch {wl.batch}, context {int(wl.seq_lens.max())}, "
                         f"{wl.num_q_heads}q/{wl.num_kv_heads}kv heads, d={wl.head_dim}, page {wl.page_size}, "
                         f"block sizes {wl.block_size.tolist()}, budget {int(wl.budget.max())} tokens, "
-                        f"{args.repr} pooling",
+                        f"{args.repr} pooling, selection per {'query head' if args.select == 'per-query-head' else 'KV head'}",
             "entry_point": "absb_decode_fused",
             "launches_per_step": m["launches"],
             "layer_instances_rotated": R,

@@ -323,20 +323,21 @@ def decode_step(wl, store: CentroidStore, sel_stride: Optional[int] = None, sink
     return dict(scores=scores, score_exp=ex, sel_idx=sel_idx, sel_cnt=sel_cnt, out=out, lse=lse)
 
 
-def per_query_head_view(wl):
+def per_query_head_view(wl, caches: bool = True):
     """Per-query-head selection (every query head ranks and selects blocks by its own score and attends
     over its own list) is, by definition, the method applied to a model in which every query head is a
     group of its own: Hq KV heads, KV head hq holding the keys and values of the original KV head
     hq // G, with that head's block size.  This returns that model as a workload (the caches with
     their heads repeated G times): the oracle's functions applied to it ARE the per-query-head path,
     and a store built from it holds, for every query head, a copy of its KV head's store segment.
-    Heavy-token bookkeeping is carried over per query head."""
+    Heavy-token bookkeeping is carried over per query head.  `caches=False` leaves the caches out (for
+    diagnostics that need the head bookkeeping only)."""
     import copy
     G = wl.group
     v = copy.copy(wl)
     v.num_kv_heads = wl.num_q_heads
     v.block_size = np.repeat(np.asarray(wl.block_size, np.int32), G)
-    v.k_cache = np.repeat(wl.k_cache, G, axis=1)
-    v.v_cache = np.repeat(wl.v_cache, G, axis=1)
+    v.k_cache = np.repeat(wl.k_cache, G, axis=1) if caches else None
+    v.v_cache = np.repeat(wl.v_cache, G, axis=1) if caches else None
     v.planted = {(b, h * G + g): pos for (b, h), pos in wl.planted.items() for g in range(G)}
     return v
