@@ -550,6 +550,39 @@ def test_one_launch_step_on_segments_longer_than_the_default_allows(context, siz
     assert int(head.abs().sum().item()) == 0, "the step left a counter, a flag or the status word set"
 
 
+def test_one_launch_steps_back_to_back_and_on_two_streams():
+    """The one-launch step keeps its hand-off counters in the workspace and leaves them at zero: many
+    steps enqueued without a synchronisation in between must each see clean counters, and two streams
+    working on workspaces of their own must not disturb each other."""
+    import torch
+    from paper_2605_12110_amd import absb
+    wls = [synth.make_workload(2, batch=2, context=8192, budget=1024, seed=s) for s in (41, 42)]
+    refs = []
+    for wl in wls:
+        st = O.build_centroids(wl)
+        refs.append(O.decode_step(wl, st))
+    dws = [_dev(wl) for wl in wls]
+    for dw in dws:
+        dw.build()
+        assert absb.absb_step_launches(dw.layer, dw.batch) == 1
+    _sync()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for st_ in streams:
+        st_.wait_stream(torch.cuda.current_stream())
+    for rep in range(25):                                   # interleaved enqueues, no synchronisation
+        for dw, st_ in zip(dws, streams):
+            with torch.cuda.stream(st_):
+                dw.decode_fused(stream=st_)
+    for st_ in streams:
+        st_.synchronize()
+    for dw, ref in zip(dws, refs):
+        _check_out(dw, ref["out"], ref["lse"], "25 steps back to back, two streams")
+        assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+        head = dw.workspace[:dw.nsel * 3 * 256 + 256].view(torch.int32)
+        assert int(head.abs().sum().item()) == 0
+
+
 def test_one_launch_step_with_constant_keys_takes_the_tie_paths():
     """All keys of a head equal: every block of it scores the same, the threshold bin holds the whole
     segment (the crowded path of the selection) and the lowest indices must win, in both enqueue modes."""
