@@ -289,6 +289,28 @@ def run_matrix(args):
         del insts, dw
         torch.cuda.empty_cache()
 
+    print("\nGroup-maximum score (one selection per KV head, ranked by the maximum over its query heads of q . c^ "
+          "instead of their sum: G integer dots per block and the heads' zero-point terms), same workloads\n")
+    print("| workload | launches/step | useful MB/step | us/step | GB/s | planted-token recall: group maximum / group sum |")
+    print("|---|---|---|---|---|---|", flush=True)
+    for cfg in (1, 2, 3, 4):
+        wl0, insts = make_instances(cfg, selection=2)
+        m = measure(wl0, insts, args.steps, args.warmup)
+        dw = insts[0]
+        dw.decode_fused()
+        torch.cuda.synchronize()
+        if wl0.planted:
+            recm = O.planted_recall(wl0, dw.sel_idx.cpu().numpy(), dw.sel_cnt.cpu().numpy())
+            r1 = O.decode_step(wl0, O.build_centroids(wl0, O.MEAN))
+            recg = O.planted_recall(wl0, r1["sel_idx"], r1["sel_cnt"])
+        else:
+            recm = recg = float("nan")
+        gb = m["bytes"]["total"] / (m["ms"] * 1e-3) / 1e9
+        print(f"| config {cfg} | {m['launches']} | {m['bytes']['total'] / 1e6:.1f} | {m['ms'] * 1e3:.1f} | {gb:.0f} | "
+              f"{recm:.3f} / {recg:.3f} |", flush=True)
+        del insts, dw
+        torch.cuda.empty_cache()
+
     print("\nStore maintenance while decoding (absb_append_token: one new token per request folded into the store, "
           "no rebuild) next to a full rebuild (absb_build_centroids)\n")
     print("| workload | segments | append us/call | rebuild us/call |")
@@ -385,8 +407,9 @@ def main():
     ap.add_argument("--context", type=int, default=None)
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--budget", type=int, default=None)
-    ap.add_argument("--select", choices=("group", "per-query-head"), default="group",
-                    help="who shares a selection: the query heads of a KV head (default), or nobody")
+    ap.add_argument("--select", choices=("group", "per-query-head", "group-max"), default="group",
+                    help="who shares a selection: the query heads of a KV head, ranked by the sum of their scores "
+                         "(default) or by their maximum, or nobody (one selection per query head)")
     ap.add_argument("--repr", choices=("mean", "minmax"), default="mean",
                     help="block representation: mean pooling (headline) or channel-wise maxima and minima")
     ap.add_argument("--launches", type=int, default=0, choices=(0, 1, 3),
@@ -432,7 +455,7 @@ def main():
     block_repr = 1 if args.repr == "minmax" else 0
     wl0, insts = make_instances(args.config, context=args.context, batch=args.batch, budget=args.budget,
                                 rotate=args.rotate, block_repr=block_repr,
-                                selection=1 if args.select == "per-query-head" else 0)
+                                selection={"group": 0, "per-query-head": 1, "group-max": 2}[args.select])
     m = measure(wl0, insts, args.steps, args.warmup, stages=args.stages, percentiles=True)
     ms, mean_bytes, R = m["ms"], m["bytes"], m["R"]
     gbps = mean_bytes["total"] / (ms * 1e-3) / 1e9
@@ -459,7 +482,8 @@ def main():
             "workload": f"config{args.config}: batch {wl.batch}, context {int(wl.seq_lens.max())}, "
                         f"{wl.num_q_heads}q/{wl.num_kv_heads}kv heads, d={wl.head_dim}, page {wl.page_size}, "
                         f"block sizes {wl.block_size.tolist()}, budget {int(wl.budget.max())} tokens, "
-                        f"{args.repr} pooling, selection per {'query head' if args.select == 'per-query-head' else 'KV head'}",
+                        f"{args.repr} pooling, selection per {'query head' if args.select == 'per-query-head' else 'KV head'}"
+                        f"{' (group maximum)' if args.select == 'group-max' else ''}",
             "entry_point": "absb_decode_fused",
             "launches_per_step": m["launches"],
             "layer_instances_rotated": R,

@@ -71,10 +71,18 @@ typedef enum absb_repr { ABSB_REPR_MEAN = 0, ABSB_REPR_MINMAX = 1 } absb_repr;
  *   ABSB_SELECT_PER_QUERY_HEAD : one selection per (request, query head), ranked by that head's own
  *                                score; every query head reads the K and V rows of its own list
  *                                (G times the traffic).  The centroid store stays one per KV head.
+ *   ABSB_SELECT_GROUP_MAX      : as GROUP, but ranked by the maximum over the group's query heads of
+ *                                q_g . c^ (the dequantized centroid) instead of their sum.  Comparing
+ *                                heads needs each head's zero-point term sum_c q_g[c]*qmin[c]: the
+ *                                score stage then reads batch->qmin.  Mean pooling only.
  * Below, a "selection segment" is t = b*Hsel + hs with Hsel = Hkv (GROUP) or Hq (PER_QUERY_HEAD);
  * with PER_QUERY_HEAD hs is the query head, its KV head is hs / G, and everything the default mode
  * does for a KV head and its group is done for the query head alone. */
-typedef enum absb_select { ABSB_SELECT_GROUP = 0, ABSB_SELECT_PER_QUERY_HEAD = 1 } absb_select;
+typedef enum absb_select {
+  ABSB_SELECT_GROUP = 0,
+  ABSB_SELECT_PER_QUERY_HEAD = 1,
+  ABSB_SELECT_GROUP_MAX = 2
+} absb_select;
 
 typedef enum absb_status {
   ABSB_OK = 0,
@@ -126,6 +134,9 @@ typedef struct absb_batch {
                                    ceil(cap_b/B_h) blocks per segment, of which the first
                                    N_s = ceil(L_b/B_h) are in use: contexts can then grow in place
                                    (absb_append_token).  NULL = the tight layout of Sec. 3.4.   */
+  const float* qmin;            /* device [Bt*Hkv][d] or NULL: the store's zero-point offsets as
+                                   written by absb_build_centroids; read by absb_score and
+                                   absb_decode_fused only with ABSB_SELECT_GROUP_MAX            */
 } absb_batch;
 
 /* Sizes derived on the host from a (layer, batch) pair.  Only the host fields of `batch`
@@ -165,6 +176,10 @@ ABSB_API int absb_build_centroids(const absb_layer* layer, const absb_batch* bat
  *                       matches the sign of q_c, which keeps the group score linear in the codes.
  *   score_exp [Bt*Hkv] i32, optional (NULL ok): e with w ~= wq * 2^e
  * Reads batch->seq_lens and batch->cent_off.
+ * ABSB_SELECT_GROUP_MAX (mean pooling): S_j = max_g ( sum_c wq_gc * code_jc + zq_g ) on one exponent
+ * e per group: w_gc = q_g[c] * qscale[s][c], e from the largest |w_gc| of the group, zq_g =
+ * rint(z_g * 2^-e) clamped to +-2^30, z_g = sum_c q_g[c] * qmin[s][c] in binary32 (products summed
+ * pairwise within runs of 16 consecutive channels, the runs then in increasing order).
  * ABSB_SELECT_PER_QUERY_HEAD: w_c = q_hs[c] * qscale[s][c] for the one query head; scores holds
  * G*total values, the G selection segments of store segment s side by side: block j of query head
  * hs at G*off[s] + (hs % G)*(off[s+1]-off[s]) + j; score_exp [Bt*Hq]. */

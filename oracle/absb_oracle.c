@@ -352,6 +352,86 @@ void orc_score_minmax(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t 
     }
 }
 
+/* ---- group score = the MAXIMUM over the group's query heads of r_j = q_g . c^_j (Sec. 2.2), a
+ * second way of sharing one selection among the G query heads of a KV head (the paper selects per
+ * head and leaves grouped-query models open).  Unlike the sum, the maximum compares heads, so the
+ * zero-point term of each head matters:
+ *   q_g . c^_j = sum_c (q_gc * scale_c) * code_jc + z_g,   z_g = sum_c q_gc * min_c.
+ * Fixed point, one exponent for the whole group so that heads are comparable:
+ *   w_gc = q_gc * scale_c (one binary32 multiply);  A = max_{g,c} |w_gc|;  e = ilogb(A) - 14;
+ *   wq_gc = rint(w_gc * 2^-e);
+ *   z_g in binary32: products q_gc * min_c (one multiply each) summed pairwise within each run of 16
+ *   consecutive channels ((p0+p1)+(p2+p3))+... , the 8 run sums then added in increasing order;
+ *   zq_g = rint(z_g * 2^-e) clamped to [-2^30, 2^30] (0 for a NaN);
+ *   S_j = max_g ( sum_c wq_gc * code_jc + zq_g )   (int32; |sum| <= 128*15*2^15 < 2^26).
+ * A < 2^-100, Inf or NaN: every weight and offset is 0, e = 0.  Mean pooling only. */
+static float sum16_pairwise(const float *p) {
+    float a[16];
+    for (int i = 0; i < 16; ++i) a[i] = p[i];
+    for (int n = 16; n > 1; n /= 2)
+        for (int i = 0; i < n / 2; ++i) a[i] = a[2 * i] + a[2 * i + 1];
+    return a[0];
+}
+
+void orc_score_groupmax(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t *q /* [Bt][Hq][d] */,
+                        const uint8_t *codes, const float *qscale, const float *qmin, const int64_t *off,
+                        int32_t *scores /* [total] */, int32_t *score_exp /* [Bt*Hkv] */,
+                        int32_t *wq_out /* [Bt*Hkv][G][d] or NULL */, int32_t *zq_out /* [Bt*Hkv][G] or NULL */) {
+    int G = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < Bt * Hkv; ++s) {
+        int b = s / Hkv, h = s % Hkv;
+        float w[8][256], prod[256];
+        int32_t wq[8][256], zq[8];
+        float z[8];
+        float A = 0.0f;
+        for (int g = 0; g < G; ++g) {
+            const uint16_t *qrow = q + ((int64_t)b * Hq + h * G + g) * d;
+            for (int ch = 0; ch < d; ++ch) {
+                float qv = widen(qrow[ch], dtype);
+                w[g][ch] = qv * qscale[(int64_t)s * d + ch];
+                prod[ch] = qv * qmin[(int64_t)s * d + ch];
+                float a = fabsf(w[g][ch]);
+                if (a > A) A = a;
+            }
+            float acc = sum16_pairwise(prod);
+            for (int k = 1; k < d / 16; ++k) acc = acc + sum16_pairwise(prod + 16 * k);
+            z[g] = acc;
+        }
+        int ex = 0;
+        int live = (A >= 0x1p-100f) && !isinf(A);
+        if (live) ex = ilogbf(A) - 14;
+        for (int g = 0; g < G; ++g) {
+            for (int ch = 0; ch < d; ++ch) wq[g][ch] = live ? (int32_t)rintf(ldexpf(w[g][ch], -ex)) : 0;
+            float zs = live ? rintf(ldexpf(z[g], -ex)) : 0.0f;
+            if (!(zs == zs)) zs = 0.0f;
+            if (zs > 0x1p30f) zs = 0x1p30f;
+            if (zs < -0x1p30f) zs = -0x1p30f;
+            zq[g] = (int32_t)zs;
+        }
+        score_exp[s] = ex;
+        if (wq_out)
+            for (int g = 0; g < G; ++g)
+                for (int ch = 0; ch < d; ++ch) wq_out[((int64_t)s * G + g) * d + ch] = wq[g][ch];
+        if (zq_out)
+            for (int g = 0; g < G; ++g) zq_out[(int64_t)s * G + g] = zq[g];
+        for (int64_t j = off[s]; j < off[s + 1]; ++j) {
+            int32_t best = 0;
+            for (int g = 0; g < G; ++g) {
+                int32_t acc = 0;
+                for (int ch = 0; ch < d; ++ch) {
+                    uint8_t byte = codes[j * (d / 2) + ch / 2];
+                    int32_t code = (ch % 2 == 0) ? (byte & 15) : (byte >> 4);
+                    acc += wq[g][ch] * code;
+                }
+                acc += zq[g];
+                if (g == 0 || acc > best) best = acc;
+            }
+            scores[j] = best;
+        }
+    }
+}
+
 /* ---- O5: Top-K_s per segment, K_s = min(N_s, ceil(T_b / B_h)) ----------------------- */
 typedef struct {
     int32_t score;

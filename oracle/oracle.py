@@ -222,6 +222,22 @@ def score(wl, store: CentroidStore, q: Optional[np.ndarray] = None, want_weights
     return (scores, ex, wq) if want_weights else (scores, ex)
 
 
+def score_groupmax(wl, store: CentroidStore, q: Optional[np.ndarray] = None, want_weights: bool = False):
+    """Group score = maximum over the group's query heads of q_g . c^_j, on one fixed-point scale per
+    group (mean pooling only).  Returns (scores, exponents[, wq [nseg, G, d], zq [nseg, G]])."""
+    assert store.repr == MEAN
+    q = wl.q if q is None else q
+    nseg = wl.batch * wl.num_kv_heads
+    scores = np.empty(int(store.off[-1]), np.int32)
+    ex = np.empty(nseg, np.int32)
+    wq = np.empty((nseg, wl.group, wl.head_dim), np.int32) if want_weights else None
+    zq = np.empty((nseg, wl.group), np.int32) if want_weights else None
+    lib().orc_score_groupmax(C.c_int(wl.dtype), C.c_int(wl.batch), C.c_int(wl.num_q_heads), C.c_int(wl.num_kv_heads),
+                             C.c_int(wl.head_dim), _p(np.ascontiguousarray(q)), _p(store.codes), _p(store.qscale),
+                             _p(store.qmin), _p(store.off), _p(scores), _p(ex), _p(wq), _p(zq))
+    return (scores, ex, wq, zq) if want_weights else (scores, ex)
+
+
 def topk_raw(Bt, Hkv, off, block_size, budget, scores, sel_stride, seq_lens=None, sink_tokens=0, recent_tokens=0):
     nseg = Bt * Hkv
     sel_idx = np.empty((nseg, sel_stride), np.int32)
@@ -315,9 +331,11 @@ def planted_recall(wl, sel_idx, sel_cnt) -> float:
     return hit / max(tot, 1)
 
 
-def decode_step(wl, store: CentroidStore, sel_stride: Optional[int] = None, sink_tokens=0, recent_tokens=0):
-    """O4 -> O5 -> O6 given a prebuilt centroid store: the per-step hot path."""
-    scores, ex = score(wl, store)
+def decode_step(wl, store: CentroidStore, sel_stride: Optional[int] = None, sink_tokens=0, recent_tokens=0,
+                group_max: bool = False):
+    """O4 -> O5 -> O6 given a prebuilt centroid store: the per-step hot path.  `group_max`: the group's
+    shared score is the maximum over its query heads instead of their sum."""
+    scores, ex = score_groupmax(wl, store) if group_max else score(wl, store)
     sel_idx, sel_cnt = topk(wl, store.off, scores, sel_stride, sink_tokens=sink_tokens, recent_tokens=recent_tokens)
     out, lse = sparse_attention(wl, sel_idx, sel_cnt)
     return dict(scores=scores, score_exp=ex, sel_idx=sel_idx, sel_cnt=sel_cnt, out=out, lse=lse)

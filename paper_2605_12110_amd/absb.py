@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libabsb.so")
 
 F16, BF16 = 0, 1
 REPR_MEAN, REPR_MINMAX = 0, 1
-SELECT_GROUP, SELECT_PER_QUERY_HEAD = 0, 1
+SELECT_GROUP, SELECT_PER_QUERY_HEAD, SELECT_GROUP_MAX = 0, 1, 2
 TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO, TUNE_STEP_LAUNCHES = 0, 1, 2, 3
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
@@ -48,7 +48,7 @@ class _Batch(C.Structure):
                 ("seq_lens_host", C.POINTER(C.c_int32)), ("seq_lens", C.c_void_p),
                 ("page_table", C.c_void_p), ("cent_off", C.c_void_p),
                 ("budget_host", C.POINTER(C.c_int32)), ("budget", C.c_void_p),
-                ("cap_lens_host", C.POINTER(C.c_int32))]
+                ("cap_lens_host", C.POINTER(C.c_int32)), ("qmin", C.c_void_p)]
 
 
 _lib = None
@@ -152,6 +152,7 @@ class Batch:
     budget: object = None
     pt_stride: Optional[int] = None
     cap_lens_host: Optional[Sequence[int]] = None
+    qmin: object = None
 
     def __setattr__(self, name, value):
         object.__setattr__(self, name, value)
@@ -168,7 +169,7 @@ class Batch:
                 pts = int(self.page_table.shape[1]) if self.page_table is not None else 0
             self._cl, cl_p = _i32_host(self.cap_lens_host)
             self._c = _Batch(len(self._sl), int(pts), sl_p, _ptr(self.seq_lens), _ptr(self.page_table),
-                             _ptr(self.cent_off), bg_p, _ptr(self.budget), cl_p)
+                             _ptr(self.cent_off), bg_p, _ptr(self.budget), cl_p, _ptr(self.qmin))
         return self._c
 
 

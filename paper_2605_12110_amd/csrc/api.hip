@@ -38,8 +38,10 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   if (sp <= 0 || sh <= 0 || st < ABSB_HEAD_DIM || (sp % 8) || (sh % 8) || (st % 8)) return ABSB_ERR_BAD_SHAPE;
   if (!(layer->sm_scale >= 0.0f) || std::isinf(layer->sm_scale)) return ABSB_ERR_BAD_SHAPE;
   if (layer->sink_tokens < 0 || layer->recent_tokens < 0) return ABSB_ERR_BAD_SHAPE;
-  if (layer->selection != ABSB_SELECT_GROUP && layer->selection != ABSB_SELECT_PER_QUERY_HEAD)
+  if (layer->selection != ABSB_SELECT_GROUP && layer->selection != ABSB_SELECT_PER_QUERY_HEAD &&
+      layer->selection != ABSB_SELECT_GROUP_MAX)
     return ABSB_ERR_UNSUPPORTED;
+  if (layer->selection == ABSB_SELECT_GROUP_MAX && layer->block_repr != ABSB_REPR_MEAN) return ABSB_ERR_UNSUPPORTED;
   const bool per_q = layer->selection == ABSB_SELECT_PER_QUERY_HEAD;
   const int Hsel = per_q ? Hq : Hkv;
   const int Bt = batch->batch;
@@ -53,6 +55,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   g.Hsel = Hsel;
   g.Gd = per_q ? 1 : g.G;
   g.Rk = per_q ? g.G : 1;
+  g.agg_max = layer->selection == ABSB_SELECT_GROUP_MAX;
   g.log2_page = ilog2(P);
   g.pt_stride = batch->pt_stride;
   g.repr = layer->block_repr;
@@ -237,7 +240,8 @@ int absb_score(const absb_layer* layer, const absb_batch* batch, const void* q, 
   int rc = make_plan(layer, batch, false, 0, &g, &p);
   if (rc != ABSB_OK) return rc;
   if (!q || !codes || !qscale || !scores || !batch->cent_off || !batch->seq_lens) return ABSB_ERR_NULL;
-  return launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, batch->seq_lens, scores, score_exp,
+  if (g.agg_max && !batch->qmin) return ABSB_ERR_NULL;
+  return launch_score(g, p, layer->dtype, q, codes, qscale, batch->qmin, batch->cent_off, batch->seq_lens, scores, score_exp,
                       static_cast<hipStream_t>(stream));
 }
 
@@ -284,6 +288,7 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   if (!q || !codes || !qscale || !k_cache || !v_cache || !out || !batch->seq_lens || !batch->page_table ||
       !batch->cent_off || !batch->budget)
     return ABSB_ERR_NULL;
+  if (g.agg_max && !batch->qmin) return ABSB_ERR_NULL;
   rc = check_ws(workspace, workspace_bytes, p.ws_fused_bytes);
   if (rc != ABSB_OK) return rc;
   char* ws = static_cast<char*>(workspace);
@@ -292,9 +297,9 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   int32_t* sel_idx = sel_idx_out ? sel_idx_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_idx);
   int32_t* sel_cnt = sel_cnt_out ? sel_cnt_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_cnt);
   if (p.one_launch && fused_one_launch_fits(p))
-    return launch_fused(g, p, layer->dtype, resolve_scale(layer), q, codes, qscale, k_cache, v_cache, batch->page_table,
+    return launch_fused(g, p, layer->dtype, resolve_scale(layer), q, codes, qscale, batch->qmin, k_cache, v_cache, batch->page_table,
                         batch->seq_lens, batch->cent_off, batch->budget, sel_idx, sel_cnt, out, lse, ws, st);
-  rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->cent_off, batch->seq_lens, scores, nullptr, st);
+  rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->qmin, batch->cent_off, batch->seq_lens, scores, nullptr, st);
   if (rc != ABSB_OK) return rc;
   // the selection kernel also clears the split counters of the attention kernel behind it
   rc = launch_topk(g, p, scores, batch->cent_off, batch->budget, batch->seq_lens, sel_idx, sel_cnt, p.sel_stride,

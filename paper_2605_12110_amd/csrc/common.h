@@ -28,6 +28,7 @@ struct Geometry {
   // heads share the list: Hsel = Hkv, Gd = G, Rk = 1.  Per-query-head selection: one per
   // (request, query head): Hsel = Hq, Gd = 1, Rk = G selection segments read each KV head's store.
   int32_t Hsel, Gd, Rk;
+  int32_t agg_max;    // 1: a group's shared score is the maximum over its query heads (else their sum)
   int32_t log2_page;  // P = 1 << log2_page
   int32_t pt_stride;
   int32_t repr;       // absb_repr: vectors per block = repr + 1
@@ -73,8 +74,8 @@ ABSB_HIDDEN int launch_build(const Geometry& g, const Plan& pl, int dtype, const
                              const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
                              uint8_t* codes, float* qscale, float* qmin, char* ws, hipStream_t stream);
 ABSB_HIDDEN int launch_score(const Geometry& g, const Plan& pl, int dtype, const void* q, const uint8_t* codes,
-                             const float* qscale, const int32_t* cent_off, const int32_t* seq_lens, int32_t* scores,
-                             int32_t* score_exp, hipStream_t stream);
+                             const float* qscale, const float* qmin, const int32_t* cent_off, const int32_t* seq_lens,
+                             int32_t* scores, int32_t* score_exp, hipStream_t stream);
 // append == false: only (re)compute the tail state from the cache
 ABSB_HIDDEN int launch_append(const Geometry& g, const Plan& pl, int dtype, bool append, const void* k_cache,
                               const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
@@ -93,8 +94,8 @@ ABSB_HIDDEN int launch_decode(const Geometry& g, const Plan& pl, int dtype, floa
 // The whole step in one launch (estimation, selection and attention work-groups in one grid).
 ABSB_HIDDEN bool fused_one_launch_fits(const Plan& pl);
 ABSB_HIDDEN int launch_fused(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
-                             const uint8_t* codes, const float* qscale, const void* k_cache, const void* v_cache,
-                             const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
+                             const uint8_t* codes, const float* qscale, const float* qmin, const void* k_cache,
+                             const void* v_cache, const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
                              const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, void* out, float* lse,
                              char* ws, hipStream_t stream);
 ABSB_HIDDEN int launch_workspace_init(const Plan& pl, char* ws, hipStream_t stream);

@@ -147,13 +147,13 @@ bool fused_one_launch_fits(const Plan& pl) {
 }
 
 int launch_fused(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q, const uint8_t* codes,
-                 const float* qscale, const void* k_cache, const void* v_cache, const int32_t* page_table,
+                 const float* qscale, const float* qmin, const void* k_cache, const void* v_cache, const int32_t* page_table,
                  const int32_t* seq_lens, const int32_t* cent_off, const int32_t* budget, int32_t* sel_idx,
                  int32_t* sel_cnt, void* out, float* lse, char* ws, hipStream_t stream) {
   if (!fused_one_launch_fits(pl)) return ABSB_ERR_UNSUPPORTED;
   FusedParams p;
   int32_t* scores = reinterpret_cast<int32_t*>(ws + pl.ws_scores);
-  p.sc = make_score_params(g, pl, q, codes, qscale, cent_off, seq_lens, scores, nullptr);
+  p.sc = make_score_params(g, pl, q, codes, qscale, qmin, cent_off, seq_lens, scores, nullptr);
   p.tk = make_topk_params(g, scores, cent_off, budget, seq_lens, sel_idx, sel_cnt, pl.sel_stride, nullptr);
   p.dc = make_decode_params(g, pl, sm_scale, q, k_cache, v_cache, page_table, seq_lens, sel_idx, sel_cnt,
                             pl.sel_stride, out, lse, ws);

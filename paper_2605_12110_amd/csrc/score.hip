@@ -12,9 +12,9 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreParams p) {
 }
 
 int launch_score(const Geometry& g, const Plan& pl, int dtype, const void* q, const uint8_t* codes,
-                 const float* qscale, const int32_t* cent_off, const int32_t* seq_lens, int32_t* scores,
-                 int32_t* score_exp, hipStream_t stream) {
-  const ScoreParams p = make_score_params(g, pl, q, codes, qscale, cent_off, seq_lens, scores, score_exp);
+                 const float* qscale, const float* qmin, const int32_t* cent_off, const int32_t* seq_lens,
+                 int32_t* scores, int32_t* score_exp, hipStream_t stream) {
+  const ScoreParams p = make_score_params(g, pl, q, codes, qscale, qmin, cent_off, seq_lens, scores, score_exp);
   dim3 grid((unsigned)((pl.max_blocks + pl.score_chunk - 1) / pl.score_chunk), (unsigned)pl.nseg);
   if (dtype == ABSB_F16 && g.repr == ABSB_REPR_MEAN)
     hipLaunchKernelGGL((score_kernel<ABSB_F16, 0>), grid, dim3(256), 0, stream, p);

@@ -29,6 +29,7 @@ struct ScoreParams {
   const uint16_t* q;        // [Bt][Hq][128]
   const uint8_t* codes;     // [total][64 * R], R vectors per block
   const float* qscale;      // [nseg][128 * R]
+  const float* qmin;        // [nseg][128]: read only when agg_max
   const int32_t* cent_off;  // [nseg+1]
   const int32_t* seq_lens;  // [Bt]
   HeadTable heads;
@@ -36,17 +37,20 @@ struct ScoreParams {
   int32_t* score_exp;       // [nseg] or null
   int32_t Hq, Hkv, G, chunk, tight;  // G: query heads folded into one selection segment (Gd)
   int32_t Hsel, Rk;
+  int32_t agg_max;  // the group's score is the maximum over its query heads (mean pooling only)
 };
 
 constexpr int SCORE_PLANES = 5;
 
 inline ScoreParams make_score_params(const Geometry& g, const Plan& pl, const void* q, const uint8_t* codes,
-                                     const float* qscale, const int32_t* cent_off, const int32_t* seq_lens,
-                                     int32_t* scores, int32_t* score_exp) {
+                                     const float* qscale, const float* qmin, const int32_t* cent_off,
+                                     const int32_t* seq_lens, int32_t* scores, int32_t* score_exp) {
   ScoreParams p;
   p.q = static_cast<const uint16_t*>(q);
   p.codes = codes;
   p.qscale = qscale;
+  p.qmin = qmin;
+  p.agg_max = g.agg_max;
   p.cent_off = cent_off;
   p.seq_lens = seq_lens;
   p.heads = g.heads;
@@ -69,10 +73,157 @@ __device__ __forceinline__ uint32_t or8(uint32_t v) {  // OR over aligned groups
   return v;
 }
 
-// LDS of one work-group: the four wave maxima, then the digit planes of the weights.
+// LDS of one work-group: the four wave maxima, then the digit planes of the weights.  The
+// group-maximum score keeps a set of planes per query head, the run sums of the heads' zero-point
+// products and their fixed-point offsets.
+constexpr size_t SCORE_GMAX_PLANES_AT = 16 + ABSB_MAX_GROUP * 8 * 4 + ABSB_MAX_GROUP * 4;
 template <int REP>
 __host__ __device__ constexpr size_t score_lds_bytes() {
-  return 16 + (size_t)SCORE_PLANES * (ABSB_HEAD_DIM * (REP + 1) / 8) * sizeof(uint32_t);
+  const size_t plain = 16 + (size_t)SCORE_PLANES * (ABSB_HEAD_DIM * (REP + 1) / 8) * sizeof(uint32_t);
+  const size_t gmax = SCORE_GMAX_PLANES_AT + (size_t)ABSB_MAX_GROUP * SCORE_PLANES * (ABSB_HEAD_DIM / 8) * sizeof(uint32_t);
+  return REP == 0 && gmax > plain ? gmax : plain;
+}
+
+// Group-maximum score (mean pooling): S_j = max_g ( sum_c wq_gc * code_jc + zq_g ) with one exponent
+// for the group; see absb_score.  Same work split as score_chunk below: four lanes per block, the
+// packed 4-bit dots once per query head against that head's digit planes (read from LDS per head),
+// the sum of the codes shared by all heads.
+template <int DT, bool COH>
+__device__ __forceinline__ int score_chunk_groupmax(const ScoreParams& p, int t, int chunk_idx, char* lds) {
+  constexpr int W = ABSB_HEAD_DIM, ROW_BYTES = W / 2;
+  const SegMap sm = seg_map(t, p.Hsel, p.Rk, p.Hkv);
+  const int b = sm.b, s = sm.s;
+  const int tid = threadIdx.x, G = p.G;
+  uint16_t qraw[ABSB_MAX_GROUP];
+  float scale = 0.0f, zero = 0.0f;
+  if (tid < W) {
+    const uint16_t* qrow = p.q + ((size_t)b * p.Hq + (size_t)sm.hs * G) * ABSB_HEAD_DIM + tid;
+#pragma unroll
+    for (int g = 0; g < ABSB_MAX_GROUP; ++g) qraw[g] = g < G ? qrow[(size_t)g * ABSB_HEAD_DIM] : (uint16_t)0;
+    scale = p.qscale[(size_t)s * W + tid];
+    zero = p.qmin[(size_t)s * W + tid];
+  }
+  const int off = p.cent_off[s];
+  const int rows = p.cent_off[s + 1] - off;
+  const int N = blocks_in_use(p.tight, rows, p.seq_lens, b, p.heads.log2_block[sm.hk]);
+  int32_t* scores_t = p.scores + score_base(sm, p.Rk, off, rows);
+  const int j0 = chunk_idx * p.chunk;
+  if (j0 >= N) return 0;
+
+  float* s_absmax = reinterpret_cast<float*>(lds);                                   // [4]
+  float (*s_zrun)[8] = reinterpret_cast<float (*)[8]>(lds + 16);                     // [G][8 runs of 16 channels]
+  int32_t* s_zq = reinterpret_cast<int32_t*>(lds + 16 + ABSB_MAX_GROUP * 8 * 4);     // [G]
+  uint32_t (*s_plane)[SCORE_PLANES][W / 8] =
+      reinterpret_cast<uint32_t (*)[SCORE_PLANES][W / 8]>(lds + SCORE_GMAX_PLANES_AT);  // [G][planes][16]
+
+  constexpr int PF = 4;
+  const int quarter = tid & 3;
+  const int jend = min(N, j0 + p.chunk);
+  const uint8_t* base = p.codes + (size_t)off * ROW_BYTES + quarter * 16;
+  uint4 pre[PF];
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    const int j = min(j0 + u * 64 + (tid >> 2), jend - 1);
+    pre[u] = *reinterpret_cast<const uint4*>(base + (size_t)j * ROW_BYTES);
+  }
+
+  // ---- prologue (threads 0..127, one channel each): weights of every head, their largest
+  // magnitude, and the heads' zero-point products summed pairwise over each run of 16 channels
+  float w[ABSB_MAX_GROUP];
+  if (tid < W) {
+    float a = 0.0f;
+#pragma unroll
+    for (int g = 0; g < ABSB_MAX_GROUP; ++g) {
+      const float qv = Elem<DT>::widen(qraw[g]);
+      w[g] = qv * scale;
+      float ag = __builtin_fabsf(w[g]);
+      ag = (ag != ag) ? 0.0f : ag;
+      a = fmaxf(a, g < G ? ag : 0.0f);
+      const float run = row16_sum(qv * zero);  // ((p0+p1)+(p2+p3))+... over the row's 16 channels
+      if (g < G && (tid & 15) == 0) s_zrun[g][tid >> 4] = run;
+    }
+    a = wave_max_f32(a);
+    if ((tid & 63) == 0) s_absmax[tid >> 6] = a;
+  }
+  __syncthreads();
+  const float A = fmaxf(s_absmax[0], s_absmax[1]);
+  int ex = 0;
+  const bool live = (A >= 0x1p-100f) && (A <= 3.4028234663852886e38f);
+  if (live) ex = (int)((bitcast<uint32_t>(A) >> 23) & 0xffu) - 127 - 14;
+  if (tid < G) {  // the head's offset on the group's scale: the 8 run sums in order
+    float z = s_zrun[tid][0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) z = z + s_zrun[tid][k];
+    float zs = live ? __builtin_rintf(__builtin_ldexpf(z, -ex)) : 0.0f;
+    zs = (zs != zs) ? 0.0f : zs;
+    zs = fminf(fmaxf(zs, -0x1p30f), 0x1p30f);
+    s_zq[tid] = (int32_t)zs;
+  }
+  if (tid < W) {
+    const int sh = 4 * (tid & 7);
+#pragma unroll
+    for (int g = 0; g < ABSB_MAX_GROUP; ++g) {
+      int32_t wq = 0;
+      if (live) wq = (int32_t)__builtin_rintf(__builtin_ldexpf(w[g], -ex));
+      const uint32_t wo = (uint32_t)(wq + 32768);
+#pragma unroll
+      for (int k = 0; k < SCORE_PLANES; ++k) {
+        const uint32_t packed = or8(((wo >> (4 * k)) & 15u) << sh);
+        if (g < G && (tid & 7) == 0) s_plane[g][k][tid >> 3] = packed;
+      }
+    }
+  }
+  if (tid == 0 && chunk_idx == 0 && p.score_exp) p.score_exp[t] = ex;
+  __syncthreads();
+
+#pragma unroll 1
+  for (int jb = j0;;) {
+    uint32_t ones[PF];
+    int32_t best[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      uint32_t o = __builtin_amdgcn_udot8(pre[u].x, 0x11111111u, 0u, false);
+      o = __builtin_amdgcn_udot8(pre[u].y, 0x11111111u, o, false);
+      o = __builtin_amdgcn_udot8(pre[u].z, 0x11111111u, o, false);
+      ones[u] = __builtin_amdgcn_udot8(pre[u].w, 0x11111111u, o, false);
+      best[u] = 0;
+    }
+#pragma unroll 1
+    for (int g = 0; g < G; ++g) {
+      uint4 wp[SCORE_PLANES];
+#pragma unroll
+      for (int k = 0; k < SCORE_PLANES; ++k) wp[k] = *reinterpret_cast<const uint4*>(&s_plane[g][k][quarter * 4]);
+      const int32_t zq = s_zq[g];
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        uint32_t acc = 0;
+#pragma unroll
+        for (int k = 0; k < SCORE_PLANES; ++k) {
+          uint32_t d = __builtin_amdgcn_udot8(pre[u].x, wp[k].x, 0u, false);
+          d = __builtin_amdgcn_udot8(pre[u].y, wp[k].y, d, false);
+          d = __builtin_amdgcn_udot8(pre[u].z, wp[k].z, d, false);
+          d = __builtin_amdgcn_udot8(pre[u].w, wp[k].w, d, false);
+          acc += d << (4 * k);
+        }
+        acc -= ones[u] << 15;
+        const int32_t sc = quad_sum((int32_t)acc) + zq;
+        best[u] = g == 0 ? sc : max(best[u], sc);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int j = jb + u * 64 + (tid >> 2);
+      if (j < jend && quarter == 0) st_i32<COH>(scores_t + j, best[u]);
+    }
+    jb += PF * 64;
+    if (jb >= jend) break;
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int j = min(jb + u * 64 + (tid >> 2), jend - 1);
+      pre[u] = *reinterpret_cast<const uint4*>(base + (size_t)j * ROW_BYTES);
+    }
+  }
+  return N;
 }
 
 // Scores of blocks [chunk_idx*p.chunk, +p.chunk) of selection segment t by one work-group of 256 threads.
@@ -80,6 +231,7 @@ __host__ __device__ constexpr size_t score_lds_bytes() {
 // another work-group of the same launch.  `lds`: score_lds_bytes<REP>() bytes, 16-byte aligned.
 template <int DT, int REP, bool COH>
 __device__ __forceinline__ int score_chunk(const ScoreParams& p, int t, int chunk_idx, char* lds) {
+  if (REP == 0 && p.agg_max) return score_chunk_groupmax<DT, COH>(p, t, chunk_idx, lds);
   constexpr int R = REP + 1;                 // vectors per block: the mean, or maxima and minima
   constexpr int W = ABSB_HEAD_DIM * R;       // weights = values per block
   constexpr int ROW_BYTES = W / 2;

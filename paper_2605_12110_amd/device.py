@@ -71,6 +71,7 @@ class DeviceWorkload:
         self.codes = torch.empty((total, width // 2), dtype=torch.uint8, device=device)
         self.qscale = torch.empty((nseg, width), dtype=torch.float32, device=device)
         self.qmin = torch.empty((nseg, width), dtype=torch.float32, device=device)
+        self.batch.qmin = self.qmin
         self.scores = torch.empty((total * rk,), dtype=torch.int32, device=device)
         self.score_exp = torch.empty((nsel,), dtype=torch.int32, device=device)
         self.sel_stride = max(self.plan.sel_stride, 1)

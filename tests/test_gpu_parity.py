@@ -48,7 +48,7 @@ def _check_out(dw, want_out, want_lse, what):
     assert np.array_equal(np.isneginf(lse), np.isneginf(want_lse))
 
 
-def run_all_stages(wl, name, block_repr=O.MEAN, per_query_head=False):
+def run_all_stages(wl, name, block_repr=O.MEAN, per_query_head=False, group_max=False):
     """Stage by stage (each GPU stage fed the oracle's inputs), then the fused call end to end."""
     _say(f"[case {name}] repr={block_repr} Bt={wl.batch} Hq={wl.num_q_heads} Hkv={wl.num_kv_heads} P={wl.page_size} "
          f"L={wl.seq_lens.tolist()[:4]}.. B={wl.block_size.tolist()} T={wl.budget.tolist()[:4]}.. dtype={wl.dtype}")
@@ -61,11 +61,12 @@ def run_all_stages(wl, name, block_repr=O.MEAN, per_query_head=False):
         view = O.per_query_head_view(wl)
         ref = O.decode_step(view, O.build_centroids(view, block_repr), sel_stride=None)
     else:
-        ref = O.decode_step(wl, st, sel_stride=None)
+        ref = O.decode_step(wl, st, sel_stride=None, group_max=group_max)
     _say(f"    oracle: build+step {time.time() - t0:.2f}s, centroids={int(st.off[-1])}, per_query_head={per_query_head}")
     from paper_2605_12110_amd import absb as _absb
     dw = _dev(wl, block_repr=block_repr,      # the two enumerations agree: 0 mean, 1 maxima and minima
-              selection=_absb.SELECT_PER_QUERY_HEAD if per_query_head else _absb.SELECT_GROUP)
+              selection=_absb.SELECT_PER_QUERY_HEAD if per_query_head else
+              _absb.SELECT_GROUP_MAX if group_max else _absb.SELECT_GROUP)
     assert np.array_equal(dw.plan.cent_off.astype(np.int64), st.off)
     K = dw.sel_stride
     assert K == int(ref["sel_cnt"].max())
@@ -517,6 +518,43 @@ def test_per_query_head_selection_config1_and_max_min_pooling():
 def test_per_query_head_selection_config3_scaled():
     run_all_stages(synth.make_workload(3, context=32768, budget=2048), "per-query-head config3/32K",
                    per_query_head=True)
+
+
+# ------------------------------------------------------------------ the group's maximum as the shared score
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_group_maximum_selection_ragged_small_batch(dtype):
+    wl = synth.tiny_workload(seed=15, dtype=dtype, Bt=3, Hq=8, Hkv=2, P=16, seq_lens=(37, 700, 1291),
+                             block_size=(8, 32), budget=(64, 200, 96))
+    run_all_stages(wl, f"group-max tiny dtype={dtype}", group_max=True)
+
+
+@pytest.mark.parametrize("G", [1, 3, 5, 8])
+def test_group_maximum_selection_group_sizes(G):
+    wl = synth.tiny_workload(seed=16, Bt=2, Hq=2 * G, Hkv=2, P=64, seq_lens=(1000, 2500), block_size=(128, 16),
+                             budget=(256, 512))
+    run_all_stages(wl, f"group-max G={G}", group_max=True)
+
+
+def test_group_maximum_selection_config1_and_config3_scaled():
+    run_all_stages(synth.make_workload(1), "group-max config1", group_max=True)
+    run_all_stages(synth.make_workload(3, context=32768, budget=2048), "group-max config3/32K", group_max=True)
+
+
+def test_group_maximum_selection_needs_the_offsets_and_mean_pooling():
+    from paper_2605_12110_amd import absb
+    wl = synth.tiny_workload(seed=17)
+    dw = _dev(wl, selection=absb.SELECT_GROUP_MAX)
+    dw.build()
+    dw.batch.qmin = None
+    with pytest.raises(absb.AbsbError) as e:
+        dw.decode_fused()
+    assert e.value.status == absb.ERR_NULL
+    with pytest.raises(absb.AbsbError) as e:
+        dw.score()
+    assert e.value.status == absb.ERR_NULL
+    with pytest.raises(absb.AbsbError) as e:
+        _dev(wl, selection=absb.SELECT_GROUP_MAX, block_repr=absb.REPR_MINMAX)
+    assert e.value.status == absb.ERR_UNSUPPORTED
 
 
 # ------------------------------------------------------------------ the one-launch step beyond its default range
