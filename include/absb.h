@@ -225,11 +225,12 @@ ABSB_API int absb_workspace_init(const absb_layer* layer, const absb_batch* batc
  * (absb_workspace_init) and are zero again afterwards.
  *   sel_idx_out [Bt*Hkv][plan's sel_stride], sel_cnt_out [Bt*Hkv]: optional copies of the
  *   selection (NULL ok: kept in the workspace).
- * For batches in which a segment is longer than 8192 blocks the three stages are enqueued as
- * three launches instead (there the selection of the longest segment is the critical path, and
- * the stand-alone selection kernel, with four times the threads per segment, is worth the two
- * extra launches); ABSB_TUNE_STEP_LAUNCHES (see absb_set_tuning) forces either form.  The
- * three-launch form does not need the counters cleared. */
+ * For batches with very long segments (more than 8192 blocks, or more than 16384 when the batch
+ * has 16 or more selection segments) or very long lists (more than 4096 blocks per segment) the
+ * three stages are enqueued as three launches instead: there the selection of the longest segment
+ * is the critical path, and the stand-alone selection kernel, with four times the threads per
+ * segment, is worth the two extra launches.  ABSB_TUNE_STEP_LAUNCHES (see absb_set_tuning) forces
+ * either form.  The three-launch form does not need the counters cleared. */
 ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const void* q,
                                const uint8_t* codes, const float* qscale, const void* k_cache,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,

@@ -128,11 +128,15 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   if ((int64_t)p.max_splits * st_tok >= (int64_t(1) << 31)) return ABSB_ERR_BAD_SHAPE;  // positions are 32-bit
 
   // How absb_decode_fused is enqueued.  Measured on MI355X: the one-launch step wins (2-14 %)
-  // wherever no segment is longer than 8192 blocks; beyond that the selection of the longest
-  // segment, which the one-launch step runs on a 256-thread work-group, is the critical path and
-  // the 1024-thread selection kernel of the per-stage path is worth its two extra launches.
+  // wherever no segment is longer than 8192 blocks, and up to 16384 blocks when the batch has
+  // other segments to overlap with (16 or more).  Beyond that the selection of the longest
+  // segment, which the one-launch step runs on a 256-thread work-group (register tile up to
+  // 16384 blocks), is the critical path and the 1024-thread selection kernel of the per-stage
+  // path is worth its two extra launches.  Very long lists (budgets near the context) also go to
+  // the per-stage path: its attention kernel reads the lists through the L2.
   const int mode = tuning(ABSB_TUNE_STEP_LAUNCHES);
-  p.one_launch = mode == 1 || (mode == 0 && p.max_blocks <= 8192);
+  const bool by_shape = (p.max_blocks <= 8192 || (p.max_blocks <= 16384 && p.nseg >= 16)) && p.sel_stride <= 4096;
+  p.one_launch = mode == 1 || (mode == 0 && by_shape);
   // blocks per estimation work-group: 256 (one batch of loads per lane); in the one-launch step,
   // where estimation work-groups share the CUs with attention work-groups, a large batch does
   // better with two batches per work-group (the prologue is amortised, half as many work-groups)

@@ -76,7 +76,7 @@ __device__ __forceinline__ uint32_t ordered_key(int32_t score) { return (uint32_
 
 struct TopkShared {
   uint32_t red[2 * TOPK_SLOTS];
-  uint32_t hist[TOPK_BINS];
+  uint32_t hist[TOPK_BINS + 64];  // the bins, then one dump word per lane (slots past a segment's end)
   uint32_t bcast[4];
   uint32_t cand_key[TOPK_MAX_CAND];
   uint32_t cand_idx[TOPK_MAX_CAND];
@@ -126,6 +126,22 @@ __device__ __forceinline__ uint32_t append_slot(uint32_t* counter) {
   uint32_t base = 0;
   if (before == 0) base = atomicAdd(counter, (uint32_t)__popcll(m));
   return (uint32_t)__builtin_amdgcn_readfirstlane((int)base) + before;
+}
+
+// key[i] for an index known only at run time, without leaving the registers: a select tree over
+// the bits of i (R - 1 selects).  Used on the rare paths only.
+template <int R>
+__device__ __forceinline__ uint32_t pick_reg(const uint32_t (&key)[R], int i) {
+  uint32_t t[R];
+#pragma unroll
+  for (int k = 0; k < R; ++k) t[k] = key[k];
+#pragma unroll
+  for (int s = 1, b = 0; s < R; s <<= 1, ++b) {
+    const uint32_t up = 0u - (uint32_t)((i >> b) & 1);  // a bit-mask blend: stays a register operation
+#pragma unroll
+    for (int k = 0; k + s < R; k += 2 * s) t[k] = (t[k + s] & up) | (t[k] & ~up);
+  }
+  return t[0];
 }
 
 // From the histogram of the current digit among the candidates: the bin holding the `need`-th
@@ -267,19 +283,35 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
 
   // ---- 2. histogram of the first digit, threshold bin
   // (slots past the end hold copies of the last key: counting them would pile thousands of LDS
-  // atomics on one bin, so they are skipped, not corrected for afterwards)
+  // atomics on one bin, so they are kept out, not corrected for afterwards)
+  //
+  // With a register tile the passes over the keys are written without branches and without
+  // changes of the execution mask: a 4-wave work-group has one wave per SIMD, which cannot overlap
+  // its own scalar, vector and LDS instructions across such changes (measured: ~14 cycles per
+  // instruction with a predicated body per key, against ~5 for straight-line code).  Which of the
+  // thread's tiles hold a block of the segment (tile i holds block i*NT + tid) is a bit mask; a
+  // slot past the end is counted into a dump word of its lane instead of a bin.
+  const int nvalid = N > tid ? (N - tid + NT - 1) / NT : 0;
+  const uint64_t valid = nvalid >= 64 ? ~0ull : ((1ull << nvalid) - 1ull);
+  if (KPT > 0) {
 #pragma unroll
-  for (int i = 0; i < ntiles; ++i) {
-    if (i * NT + tid < N) atomicAdd(&sh.hist[rel_at(i) >> shift], 1u);
+    for (int i = 0; i < R; ++i) {
+      const uint32_t dg = key[i] >> shift;
+      const uint32_t m = 0u - (uint32_t)((valid >> i) & 1ull);  // all ones for a real block
+      atomicAdd(&sh.hist[(dg & m) | ((uint32_t)(TOPK_BINS + lane) & ~m)], 1u);
+    }
+  } else {
+#pragma unroll 1
+    for (int i = 0; i < ntiles; ++i) {
+      if (i * NT + tid < N) atomicAdd(&sh.hist[rel_at(i) >> shift], 1u);
+    }
   }
   __syncthreads();
   ABSB_STAMP(p.trace, 7);
-  // The next pass over the keys recomputes digits and bounds tests instead of carrying one more
-  // register per key (and one lane mask per key) across the barrier: with a long register tile
-  // that carrying spills.  The empty statements make the values opaque to the optimiser.
-  int Nc = __builtin_amdgcn_readfirstlane(N);
+  // The next pass over the keys recomputes its digits instead of carrying one more register per
+  // key across the barrier: with a long register tile that carrying spills.  The empty statements
+  // make the values opaque to the optimiser.
   if (KPT > 8) {
-    asm volatile("" : "+s"(Nc));
 #pragma unroll
     for (int i = 0; i < R; ++i) asm volatile("" : "+v"(key[i]));
   }
@@ -298,20 +330,63 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
     // ---- 3. keys above the bin are selected; keys inside it become candidates
     // (with shift == 0 the bin is a single key value: its members tie, lowest index first)
     const bool list_cands = ncand <= (uint32_t)TOPK_MAX_CAND;
+    if (KPT > 0) {
+      // straight-line pass: which of the thread's tiles lie above / inside the threshold bin, as two
+      // bit masks built by shifting (tiles taken from the last to the first, so tile i ends up at
+      // bit i of its 32-bit half); the few set bits are then worked off in two short loops
+      constexpr int NW = R > 32 ? 2 : 1;  // 32-bit halves of the masks in use
+      uint32_t above[NW], inside[NW];
 #pragma unroll
-    for (int i = 0; i < ntiles; ++i) {
-      const int j = i * NT + tid;
-      const uint32_t rel = rel_at(i);
-      const uint32_t dg = rel >> shift;
-      if (dg >= d1 && j < Nc) {  // the digit test comes first: it fails for almost every key
-        if (dg > d1) {
+      for (int w = 0; w < NW; ++w) above[w] = inside[w] = 0u;
+#pragma unroll
+      for (int i = R - 1; i >= 0; --i) {
+        const uint32_t dg = key[i] >> shift;
+        const int w = NW == 2 ? (i >> 5) : 0;
+        above[w] = (above[w] << 1) | (uint32_t)(dg > d1);
+        inside[w] = (inside[w] << 1) | (uint32_t)(dg == d1);
+      }
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const uint32_t ok = (uint32_t)(valid >> (32 * w));
+        uint32_t left = above[w] & ok;
+#pragma unroll 1
+        while (left) {
+          const int j = (__builtin_ctz(left) + 32 * w) * NT + tid;
+          left &= left - 1;
           atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
-        } else if (list_cands) {
-          const uint32_t slot = append_slot(&sh.cand_n);
-          sh.cand_key[slot] = rel;
-          sh.cand_idx[slot] = (uint32_t)j;
-        } else {
-          atomicOr(&bm_eq[j >> 5], 1u << (j & 31));
+        }
+        left = inside[w] & ok;
+#pragma unroll 1
+        while (__builtin_expect(left != 0, 0)) {  // rare even per wave
+          const int i = __builtin_ctz(left) + 32 * w;
+          const int j = i * NT + tid;
+          left &= left - 1;
+          if (list_cands) {
+            const uint32_t rel = pick_reg<R>(key, i);
+            const uint32_t slot = append_slot(&sh.cand_n);
+            sh.cand_key[slot] = rel;
+            sh.cand_idx[slot] = (uint32_t)j;
+          } else {
+            atomicOr(&bm_eq[j >> 5], 1u << (j & 31));
+          }
+        }
+      }
+    } else {
+#pragma unroll 1
+      for (int i = 0; i < ntiles; ++i) {
+        const int j = i * NT + tid;
+        const uint32_t rel = rel_at(i);
+        const uint32_t dg = rel >> shift;
+        if (dg >= d1 && j < N) {  // the digit test comes first: it fails for almost every key
+          if (dg > d1) {
+            atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
+          } else if (list_cands) {
+            const uint32_t slot = append_slot(&sh.cand_n);
+            sh.cand_key[slot] = rel;
+            sh.cand_idx[slot] = (uint32_t)j;
+          } else {
+            atomicOr(&bm_eq[j >> 5], 1u << (j & 31));
+          }
         }
       }
     }

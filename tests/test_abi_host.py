@@ -180,15 +180,21 @@ def test_tuning_knobs_validate():
 
 
 def test_enqueue_mode_of_the_fused_step_follows_the_longest_segment():
-    """One launch while no segment has more than 8192 blocks, one launch per stage beyond; the knob
-    forces either; the workspace always has room for the counters of the one-launch step."""
-    def mode(L, B):
+    """One launch while no segment has more than 8192 blocks (16384 in a batch of 16 or more segments)
+    and no list more than 4096 entries, one launch per stage beyond; the knob forces either; the
+    workspace always has room for the counters of the one-launch step."""
+    def mode(L, B, batch_size=2, budget=64):
         layer = absb.Layer(8, 2, 128, 64, absb.F16, [B, 128], (2 * 64 * 128, 64 * 128, 128))
-        batch = absb.Batch(seq_lens_host=[L, 100], budget_host=[64, 64], pt_stride=(L + 63) // 64)
+        batch = absb.Batch(seq_lens_host=[L] + [100] * (batch_size - 1), budget_host=[budget] * batch_size,
+                           pt_stride=(L + 63) // 64)
         return absb.absb_step_launches(layer, batch), absb.absb_plan(layer, batch).workspace_bytes
     assert mode(8192 * 8, 8)[0] == 1
     assert mode(8192 * 8 + 1, 8)[0] == 3
     assert mode(131072, 16)[0] == 1
+    assert mode(16384 * 8, 8, batch_size=8)[0] == 1            # 16 segments: long segments overlap with others
+    assert mode(16384 * 8 + 1, 8, batch_size=8)[0] == 3
+    assert mode(8192 * 8, 8, budget=4096 * 8)[0] == 1
+    assert mode(8192 * 8, 8, budget=4096 * 8 + 1)[0] == 3      # lists of more than 4096 blocks
     absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 3)
     try:
         assert mode(4096, 8)[0] == 3
