@@ -13,7 +13,8 @@
 //      d1 are appended to a candidate list; a long list is cut down by histogram rounds over
 //      further digits of the key, a short one is ranked exactly by (key desc, index asc), and the
 //      best `need` candidates set their bits too;
-//   4. the bitmap is scanned in index order (popcount prefix sums) and the indices written out.
+//   4. the bitmap is scanned in index order (every thread a run of words, one popcount prefix sum over
+//      the work-group) and the indices written out.
 // A crowded bin (more than 1024 candidates, e.g. all scores equal) takes a slow path: further radix
 // digits give the exact threshold tau, and blocks equal to tau are admitted in index order through
 // a second bitmap.  Segments too long for the register tile run the same code with keys re-read.
@@ -496,17 +497,25 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
   }
 
   ABSB_STAMP(p.trace, 15);
-  // ---- 4. bitmaps -> ascending index list
-  uint32_t base_gt = 0, base_eq = 0;
+  // ---- 4. bitmaps -> ascending index list, in one round: every thread owns a run of consecutive
+  // bitmap words, counts their bits, one scan over the work-group places the run, and the thread
+  // writes its blocks out in order
+  const int wpt = (nwords + NT - 1) / NT;  // words per thread
+  const int wa = min(tid * wpt, nwords), wb = min(wa + wpt, nwords);
+  uint32_t cnt_gt = 0, cnt_eq = 0;
 #pragma unroll 1
-  for (int w0 = 0; w0 < nwords; w0 += NT) {
-    const int w = w0 + tid;
-    const uint32_t g = w < nwords ? bm_gt[w] : 0u;
-    const uint32_t e = (need_eq > 0 && w < nwords) ? bm_eq[w] : 0u;
-    uint32_t tot_gt, tot_eq = 0;
-    uint32_t G = base_gt + block_excl_scan<NT>((uint32_t)__popc(g), sh.wave_a, lane, wave, &tot_gt);
-    uint32_t E = base_eq;
-    if (need_eq > 0) E += block_excl_scan<NT>((uint32_t)__popc(e), sh.wave_b, lane, wave, &tot_eq);
+  for (int w = wa; w < wb; ++w) {
+    cnt_gt += (uint32_t)__popc(bm_gt[w]);
+    if (need_eq > 0) cnt_eq += (uint32_t)__popc(bm_eq[w]);
+  }
+  uint32_t tot_gt, tot_eq;
+  uint32_t G = block_excl_scan<NT>(cnt_gt, sh.wave_a, lane, wave, &tot_gt);
+  uint32_t E = 0;
+  if (need_eq > 0) E = block_excl_scan<NT>(cnt_eq, sh.wave_b, lane, wave, &tot_eq);
+#pragma unroll 1
+  for (int w = wa; w < wb; ++w) {
+    const uint32_t g = bm_gt[w];
+    const uint32_t e = need_eq > 0 ? bm_eq[w] : 0u;
     uint32_t bitsleft = g | e;
 #pragma unroll 1
     while (bitsleft) {
@@ -525,9 +534,6 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
         ++E;
       }
     }
-    base_gt += tot_gt;
-    base_eq += tot_eq;
-    __syncthreads();  // the scan scratch is reused by the next tile of words
   }
 }
 
