@@ -494,6 +494,30 @@ def test_forced_blocks_on_a_long_segment_with_many_tiles():
         assert (want <= chosen) if len(want) <= cnt[s] else (chosen <= want)
 
 
+# ------------------------------------------------------------------ randomised shapes
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_shapes_modes_and_enqueue_forms(seed):
+    """Seeded random small workloads over everything that shapes the path: batch, head counts and group
+    size, page size, ragged lengths (down to one token), per-head block sizes on both sides of the page
+    size, budgets from one block to beyond the context, dtype, block representation, who shares a
+    selection, forced blocks.  Every stage against the oracle, the fused step in all its forms."""
+    from paper_2605_12110_amd import absb
+    rng = np.random.default_rng(1000 + seed)
+    Bt = int(rng.integers(1, 5))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.integers(1, 9))
+    P = int(rng.choice([8, 16, 64, 128]))
+    lens = [int(x) for x in rng.choice([1, 7, 64, 65, 300, 1023, 2048, 5000], size=Bt)]
+    bs = [int(x) for x in rng.choice([8, 16, 32, 64, 128], size=Hkv)]
+    budget = [int(x) for x in rng.choice([1, 8, 100, 512, 4096, 100000], size=Bt)]
+    dtype = int(rng.choice([synth.F16, synth.BF16]))
+    mode = int(rng.integers(0, 4))                 # 0 plain, 1 max-min pooling, 2 per query head, 3 group maximum
+    wl = synth.tiny_workload(seed=2000 + seed, dtype=dtype, Bt=Bt, Hq=Hkv * G, Hkv=Hkv, P=P, seq_lens=lens,
+                             block_size=bs, budget=budget)
+    run_all_stages(wl, f"random {seed}: mode {mode}", block_repr=O.MINMAX if mode == 1 else O.MEAN,
+                   per_query_head=mode == 2, group_max=mode == 3)
+
+
 # ------------------------------------------------------------------ per-query-head selection
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
 def test_per_query_head_selection_ragged_small_batch(dtype):
