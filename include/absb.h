@@ -241,6 +241,13 @@ ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch,
  * host helper; reads the host fields only. */
 ABSB_API int absb_step_launches(const absb_layer* layer, const absb_batch* batch);
 
+/* Where the one-launch step reports trouble: byte offset, inside the workspace, of an int32 status
+ * word that absb_workspace_init clears and that stays zero in normal operation.  An attention
+ * work-group that waited 0.25 s for its segment's list without seeing it (the counters were not
+ * cleared, or the device lengths and budgets differ from their host twins) sets it to 1 and leaves;
+ * the outputs of that step are then incomplete.  Pure host helper. */
+ABSB_API int absb_status_offset(const absb_layer* layer, const absb_batch* batch, size_t* offset);
+
 /* Keeping the store current while decoding, without a rebuild (the paper notes that recomputing
  * every centroid is too expensive, Sec. 1 and 3.2, and leaves the mechanism open; this is the
  * reading taken here).  The pooled state of each segment's LAST block is kept in binary32 in

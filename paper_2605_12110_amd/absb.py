@@ -23,7 +23,7 @@ TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO, TUNE_STEP_LAUNCHES = 0,
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 
-EXPORTS = ("absb_plan", "absb_step_launches", "absb_workspace_init", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
+EXPORTS = ("absb_plan", "absb_step_launches", "absb_status_offset", "absb_workspace_init", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
            "absb_decode_fused", "absb_tail_init", "absb_append_token", "absb_head_recall", "absb_assign_block_sizes", "absb_stream_read",
            "absb_strerror", "absb_set_tuning")
 
@@ -236,6 +236,13 @@ def absb_step_launches(layer: Layer, batch: Batch) -> int:
     if n < 0:
         raise AbsbError(n, "absb_step_launches")
     return int(n)
+
+
+def absb_status_offset(layer: Layer, batch: Batch) -> int:
+    cl, cb = layer.c(), batch.c()
+    off = C.c_size_t(0)
+    _check(load().absb_status_offset(C.byref(cl), C.byref(cb), C.byref(off)), "absb_status_offset")
+    return int(off.value)
 
 
 def absb_workspace_init(layer: Layer, batch: Batch, workspace, stream=None) -> None:

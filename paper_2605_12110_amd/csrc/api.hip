@@ -321,6 +321,16 @@ int absb_step_launches(const absb_layer* layer, const absb_batch* batch) {
   return p.one_launch && fused_one_launch_fits(p) ? 1 : 3;
 }
 
+int absb_status_offset(const absb_layer* layer, const absb_batch* batch, size_t* offset) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, false, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (!offset) return ABSB_ERR_NULL;
+  *offset = p.ws_status;
+  return ABSB_OK;
+}
+
 int absb_workspace_init(const absb_layer* layer, const absb_batch* batch, void* workspace, size_t workspace_bytes,
                         void* stream) {
   Geometry g;

@@ -130,6 +130,11 @@ class DeviceWorkload:
                                self.v_cache, self.out, self.lse, self.sel_idx if want_sel else None,
                                self.sel_cnt if want_sel else None, self.workspace, stream)
 
+    def status(self) -> int:
+        """The one-launch step's status word (0 = no wait ran out); synchronises."""
+        off = absb.absb_status_offset(self.layer, self.batch)
+        return int(self.workspace[off:off + 4].view(torch.int32).item())
+
     # -- results back on the host
     def out_f32(self) -> np.ndarray:
         return self.out.float().cpu().numpy()

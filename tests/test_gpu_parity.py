@@ -643,6 +643,46 @@ def test_one_launch_steps_back_to_back_and_on_two_streams():
         assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
         head = dw.workspace[:dw.nsel * 3 * 256 + 256].view(torch.int32)
         assert int(head.abs().sum().item()) == 0
+        assert dw.status() == 0 and absb.absb_status_offset(dw.layer, dw.batch) == dw.nsel * 3 * 256
+
+
+def test_one_launch_step_gives_up_waiting_and_says_so_when_a_counter_was_not_cleared():
+    """The attention work-groups of the one-launch step wait for their segment's list with a time
+    limit.  Forced from the host: one estimation counter starts at a value from which the segment's
+    last ticket is never drawn, so its list never comes.  The launch must end by itself (about a
+    quarter of a second), set the status word, and leave the other segments' lists right; after the
+    counters are cleared again the step works."""
+    import torch
+    from paper_2605_12110_amd import absb
+    wl = synth.make_workload(1, context=4096, budget=256)
+    ref = O.decode_step(wl, O.build_centroids(wl))
+    dw = _dev(wl)
+    dw.build()
+    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 1)
+    try:
+        dw.decode_fused(); _sync()
+        assert dw.status() == 0
+        ctr = dw.workspace.view(torch.int32)
+        stuck = 2
+        ctr[(dw.nsel * 256) // 4 + stuck * 64] = 1000                # estimation tickets follow the attention tickets
+        dw.sel_cnt.fill_(-7)
+        t0 = time.time()
+        dw.decode_fused(); _sync()
+        took = time.time() - t0
+        _say(f"    step with a stuck segment took {took:.2f} s")
+        assert took < 5.0
+        assert dw.status() == 1
+        cnt = dw.sel_cnt.cpu().numpy()
+        assert cnt[stuck] == -7                                       # nobody selected for the stuck segment
+        others = [s for s in range(dw.nsel) if s != stuck]
+        assert np.array_equal(cnt[others], ref["sel_cnt"][others])
+        dw.scribble(0x77)                                             # the contract: clear the counters, go on
+        dw.decode_fused()
+        _check_out(dw, ref["out"], ref["lse"], "after clearing the counters again")
+        assert dw.status() == 0
+        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+    finally:
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
 
 
 def test_one_launch_step_with_constant_keys_takes_the_tie_paths():
