@@ -107,26 +107,6 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   if (p.total >= (int64_t(1) << 31) - 1) return ABSB_ERR_BAD_SHAPE;
   if ((int64_t)batch->pt_stride < ceil_div(max_len, P)) return ABSB_ERR_BAD_SHAPE;
 
-  // split-K shape, in 64-token granules (one work-group step).  Measured on MI355X (256 CUs, three
-  // resident work-groups each): the kernel is fastest with about two work-groups per CU, all
-  // resident at once and each streaming as long as possible; a work-group needs at least two steps
-  // to amortise its set-up; and since one work-group merges a segment's partials, a segment should
-  // not be cut into more than 64.
-  int st_tok = tuning(ABSB_TUNE_SPLIT_TOKENS);
-  if (st_tok <= 0) {
-    const int64_t target_wgs = 640;
-    int64_t t = ceil_div(ceil_div(p.sum_tokens, target_wgs), 64) * 64;
-    if (t < 128) t = p.sum_tokens / 128 >= 128 ? 128 : 64;  // one step only when two would leave the chip idle
-    const int64_t cap_tok = ceil_div(ceil_div(p.max_tokens, 64), 64) * 64;
-    if (t < cap_tok) t = cap_tok;
-    st_tok = (int)t;
-  }
-  p.split_tokens = st_tok;
-  p.max_splits = (int32_t)ceil_div(p.max_tokens, st_tok);
-  if (p.max_splits < 1) p.max_splits = 1;
-  if (p.max_splits > 65535) return ABSB_ERR_BAD_SHAPE;
-  if ((int64_t)p.max_splits * st_tok >= (int64_t(1) << 31)) return ABSB_ERR_BAD_SHAPE;  // positions are 32-bit
-
   // How absb_decode_fused is enqueued.  Measured on MI355X: the one-launch step wins (2-14 %)
   // wherever no segment is longer than 8192 blocks, and up to 16384 blocks when the batch has
   // other segments to overlap with (16 or more).  Beyond that the selection of the longest
@@ -137,6 +117,33 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   const int mode = tuning(ABSB_TUNE_STEP_LAUNCHES);
   const bool by_shape = (p.max_blocks <= 8192 || (p.max_blocks <= 16384 && p.nseg >= 16)) && p.sel_stride <= 4096;
   p.one_launch = mode == 1 || (mode == 0 && by_shape);
+  // split-K shape, in 64-token granules (one work-group step).  Measured on MI355X (256 CUs, three
+  // resident work-groups each): the kernel is fastest with about two work-groups per CU, all
+  // resident at once and each streaming as long as possible; a work-group needs at least two steps
+  // to amortise its set-up; and since one work-group merges a segment's partials, a segment should
+  // not be cut into more than 64.
+  // (the shape follows the batch, not the enqueue knob: every form of the step then cuts the
+  // segments alike and gives the same bits)
+  int st_tok = tuning(ABSB_TUNE_SPLIT_TOKENS);
+  if (st_tok <= 0) {
+    const int64_t target_wgs = 640;
+    int64_t t = ceil_div(ceil_div(p.sum_tokens, target_wgs), 64) * 64;
+    if (t < 128) t = p.sum_tokens / 128 >= 128 ? 128 : 64;  // one step only when two would leave the chip idle
+    // In the one-launch step the attention work-groups of a large batch start segment by segment as
+    // the lists come out, not all at once: sweeps there favour ~1100 work-groups of at least four
+    // steps (config 4 43.5 -> 42.0 us, config 5 at budget 8192 41.4 -> 39.2).
+    if (by_shape && batch->budget_host && p.sum_tokens >= 65536)
+      t = std::max<int64_t>(256, ceil_div(ceil_div(p.sum_tokens, 1100), 64) * 64);
+    const int64_t cap_tok = ceil_div(ceil_div(p.max_tokens, 64), 64) * 64;
+    if (t < cap_tok) t = cap_tok;
+    st_tok = (int)t;
+  }
+  p.split_tokens = st_tok;
+  p.max_splits = (int32_t)ceil_div(p.max_tokens, st_tok);
+  if (p.max_splits < 1) p.max_splits = 1;
+  if (p.max_splits > 65535) return ABSB_ERR_BAD_SHAPE;
+  if ((int64_t)p.max_splits * st_tok >= (int64_t(1) << 31)) return ABSB_ERR_BAD_SHAPE;  // positions are 32-bit
+
   // blocks per estimation work-group: 256 (one batch of loads per lane); in the one-launch step,
   // where estimation work-groups share the CUs with attention work-groups, a large batch does
   // better with two batches per work-group (the prologue is amortised, half as many work-groups)
