@@ -206,7 +206,9 @@ ABSB_API int absb_topk(const absb_layer* layer, const absb_batch* batch, const i
  *                     sel_stride; when batch->budget_host is non-NULL also sel_cnt[s] <= K_s
  *   out [Bt][Hq][d] : attention output in the K/V dtype
  *   lse [Bt][Hq] f32, optional (NULL ok): natural-log sum of exp of the scaled logits
- * An empty selection yields out = 0 and lse = -inf.  Accumulation is binary32.
+ * An empty selection yields out = 0 and lse = -inf.  Accumulation is binary32; the softmax weights
+ * enter the P V product rounded to the K/V dtype and out is normalised by the sum of the rounded
+ * weights, lse is taken from the weights before rounding.
  * ABSB_SELECT_PER_QUERY_HEAD: sel_idx [Bt*Hq][sel_stride], sel_cnt [Bt*Hq], one list per query head. */
 ABSB_API int absb_sparse_decode(const absb_layer* layer, const absb_batch* batch, const void* q,
                                 const void* k_cache, const void* v_cache, const int32_t* sel_idx,

@@ -171,7 +171,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   p.ws_part_o = o;
   o += align256((size_t)p.nseg * p.max_splits * g.Gd * ABSB_HEAD_DIM * 4);
   p.ws_part_ml = o;
-  o += align256((size_t)p.nseg * p.max_splits * g.Gd * 2 * 4);
+  o += align256((size_t)p.nseg * p.max_splits * g.Gd * 4 * 4);  // (max, rounded sum, exact sum, -) per split and head
   p.ws_fused_bytes = o;
   p.ws_decode_bytes = o;  // the stand-alone decode uses the same offsets (the head is left unused)
   (void)fused_head;

@@ -41,7 +41,7 @@ struct DecodeParams {
   const int32_t* sel_idx;
   const int32_t* sel_cnt;
   float* part_o;   // [nseg][max_splits][G][128]
-  float* part_ml;  // [nseg][max_splits][G][2]  (running max in log2 units, sum)
+  float* part_ml;  // [nseg][max_splits][G][4]  (running max in log2 units, sum of the rounded weights, exact sum, -)
   int32_t* tickets;  // [nseg], zero when the kernel starts
   // one-launch step only: the list is produced by another work-group of the same launch
   const int32_t* budget;    // [Bt]
@@ -96,9 +96,9 @@ constexpr int V_TILE_BYTES = 8 * 512;         // [channel % 8][channel / 8][16 r
 constexpr int STAGE_BYTES = K_TILE_BYTES + V_TILE_BYTES;
 constexpr int MRG_UNROLL = 16;                // splits a thread merges per memory round trip
 // LDS of one work-group: the waves' staging areas (reused by the epilogue), per-wave maxima and
-// sums per head, two words for work-group broadcasts
+// the two sums per head, two words for work-group broadcasts
 constexpr int DEC_LDS_STATE = DEC_WAVES * STAGE_BYTES;
-constexpr int DEC_LDS_BYTES = DEC_LDS_STATE + 2 * ABSB_MAX_GROUP * DEC_WAVES * 4 + 16;
+constexpr int DEC_LDS_BYTES = DEC_LDS_STATE + 3 * ABSB_MAX_GROUP * DEC_WAVES * 4 + 16;
 // a work-group that waits for its segment's list gives up after this long (100 MHz ticks): the
 // wait cannot outlast the launch whatever the rest of the grid does
 constexpr uint64_t DEC_WAIT_LIMIT_TICKS = 25u * 1000u * 1000u;
@@ -185,7 +185,8 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
   char* s_stage = lds;  // reused by the epilogue
   float (*s_m)[DEC_WAVES] = reinterpret_cast<float (*)[DEC_WAVES]>(lds + DEC_LDS_STATE);
   float (*s_l)[DEC_WAVES] = s_m + ABSB_MAX_GROUP;
-  int* s_bcast = reinterpret_cast<int*>(lds + DEC_LDS_STATE + 2 * ABSB_MAX_GROUP * DEC_WAVES * 4);
+  float (*s_lx)[DEC_WAVES] = s_l + ABSB_MAX_GROUP;
+  int* s_bcast = reinterpret_cast<int*>(lds + DEC_LDS_STATE + 3 * ABSB_MAX_GROUP * DEC_WAVES * 4);
   const int nsplit = (ntok + p.split_tokens - 1) / p.split_tokens;
   char* kt = s_stage + wave * STAGE_BYTES;
   char* vt = kt + K_TILE_BYTES;
@@ -225,7 +226,11 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     sj = ld_i32<true>(sel + (min(pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4, maxpos) >> lb));
   }
 
-  float m = M_INIT, l = 0.0f;  // per head (= li), common to the four groups / partial over the lane's rows
+  // per head (= li): running maximum, common to the four groups; partial sums over the lane's rows of
+  // the weights as rounded for the P V product (the output's normaliser: the output stays a convex
+  // combination of value rows) and of the weights before rounding (the log-sum-exp: rounding to
+  // bf16 would bias it by up to 2^-8 when all weights round the same way)
+  float m = M_INIT, l = 0.0f, lx = 0.0f;
   float4_t oacc[8];            // O[head = 4*grp + i][channel = 8*li + j], j = 0..7
 #pragma unroll
   for (int j = 0; j < 8; ++j) oacc[j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
@@ -313,14 +318,17 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     const float alpha = fast_exp2(m - mn);
     m = mn;
     uint32_t pb[4];
-    float psum = 0.0f;
+    float psum = 0.0f, esum = 0.0f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint16_t ph = Elem<DT>::narrow(fast_exp2(sc[i] - mn));  // the weight as the product will see it
+      const float e = fast_exp2(sc[i] - mn);
+      const uint16_t ph = Elem<DT>::narrow(e);  // the weight as the product will see it
       psum += Elem<DT>::widen(ph);
+      esum += e;
       pb[i] = ph;
     }
     l = __builtin_fmaf(l, alpha, psum);
+    lx = __builtin_fmaf(lx, alpha, esum);
     const uint2 pa = make_uint2(pb[0] | (pb[1] << 16), pb[2] | (pb[3] << 16));
     // ---- rescale O when some head's maximum moved (rare once the maxima have settled)
     if (__any(alpha != 1.0f)) {
@@ -352,13 +360,17 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
   // ---- the wave's state: m per head (lane li), l summed over the four groups, O in groups 0 (and 1)
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
+  lx += __shfl_xor(lx, 16);
+  lx += __shfl_xor(lx, 32);
   if (grp == 0 && li < G) s_m[li][wave] = m;
   __syncthreads();  // also: every wave is done with its staging area, which the merge reuses below
   // work-group maximum per head; own state rescaled to it, so that the four states simply add up
   float* s_o = reinterpret_cast<float*>(s_stage);  // [DEC_WAVES][G][128]
   if (grp == 0 && li < G) {
     const float M = fmaxf(fmaxf(s_m[li][0], s_m[li][1]), fmaxf(s_m[li][2], s_m[li][3]));
-    s_l[li][wave] = l * fast_exp2(m - M);
+    const float a = fast_exp2(m - M);
+    s_l[li][wave] = l * a;
+    s_lx[li][wave] = lx * a;
   }
   if (grp * 4 < G) {
 #pragma unroll
@@ -386,6 +398,7 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     O += *reinterpret_cast<const float4_t*>(s_o + ((size_t)w * G + g) * ABSB_HEAD_DIM + c4 * 4);
   float M = fmaxf(fmaxf(s_m[g][0], s_m[g][1]), fmaxf(s_m[g][2], s_m[g][3]));
   float Lsum = (s_l[g][0] + s_l[g][1]) + (s_l[g][2] + s_l[g][3]);
+  float Lx = (s_lx[g][0] + s_lx[g][1]) + (s_lx[g][2] + s_lx[g][3]);
 
   if (nsplit > 1) {
     // Publish the partial, take a ticket; the work-group that draws the segment's last ticket merges.
@@ -399,13 +412,13 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     const __amdgpu_buffer_rsrc_t part_o = __builtin_amdgcn_make_buffer_rsrc(
         p.part_o + slot0 * G * ABSB_HEAD_DIM, 0, p.max_splits * G * ABSB_HEAD_DIM * 4, 0x00020000);
     const __amdgpu_buffer_rsrc_t part_ml =
-        __builtin_amdgcn_make_buffer_rsrc(p.part_ml + slot0 * G * 2, 0, p.max_splits * G * 8, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc(p.part_ml + slot0 * G * 4, 0, p.max_splits * G * 16, 0x00020000);
     if (tid < NCOL) {
       __builtin_amdgcn_raw_buffer_store_b128(bitcast<u32x4>(O), part_o, ((split * G + g) * ABSB_HEAD_DIM + c4 * 4) * 4,
                                              0, COHERENT);
       if (c4 == 0)
-        __builtin_amdgcn_raw_buffer_store_b64(bitcast<u32x2>(float2_t{M, Lsum}), part_ml, (split * G + g) * 8, 0,
-                                              COHERENT);
+        __builtin_amdgcn_raw_buffer_store_b128(bitcast<u32x4>(float4_t{M, Lsum, Lx, 0.0f}), part_ml,
+                                               (split * G + g) * 16, 0, COHERENT);
     }
     int& s_last = s_bcast[0];
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's stores have been acknowledged
@@ -426,14 +439,15 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     // them per memory round trip, folded into a running (M, Lsum, O)
     M = M_INIT;
     Lsum = 0.0f;
+    Lx = 0.0f;
     O = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
     for (int i0 = sl; i0 < nsplit; i0 += SL * MRG_UNROLL) {
-      float2_t mlv[MRG_UNROLL];
+      float4_t mlv[MRG_UNROLL];
       float4_t ov[MRG_UNROLL];
 #pragma unroll
       for (int u = 0; u < MRG_UNROLL; ++u) {
         const int i = min(i0 + u * SL, nsplit - 1);  // the tail repeats the last slot, with weight 0
-        mlv[u] = bitcast<float2_t>(__builtin_amdgcn_raw_buffer_load_b64(part_ml, (i * G + g) * 8, 0, COHERENT));
+        mlv[u] = bitcast<float4_t>(__builtin_amdgcn_raw_buffer_load_b128(part_ml, (i * G + g) * 16, 0, COHERENT));
         ov[u] = bitcast<float4_t>(
             __builtin_amdgcn_raw_buffer_load_b128(part_o, ((i * G + g) * ABSB_HEAD_DIM + c4 * 4) * 4, 0, COHERENT));
       }
@@ -443,37 +457,40 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
       const float a = fast_exp2(M - bm);
       O *= a;
       Lsum *= a;
+      Lx *= a;
       M = bm;
 #pragma unroll
       for (int u = 0; u < MRG_UNROLL; ++u) {
         const float w = i0 + u * SL < nsplit ? fast_exp2(mlv[u].x - bm) : 0.0f;
         O += ov[u] * w;
         Lsum = __builtin_fmaf(mlv[u].y, w, Lsum);
+        Lx = __builtin_fmaf(mlv[u].z, w, Lx);
       }
     }
     if (SL > 1) {  // fold the split lanes of a column (the staging area is free again)
-      float* s_red = reinterpret_cast<float*>(s_stage);  // [SL][CP][6]
+      float* s_red = reinterpret_cast<float*>(s_stage);  // [SL][CP][8]
       __syncthreads();
-      float* mine = s_red + ((size_t)sl * CP + col) * 6;
-      *reinterpret_cast<float2_t*>(mine) = float2_t{M, Lsum};
-      *reinterpret_cast<float2_t*>(mine + 2) = float2_t{O[0], O[1]};
-      *reinterpret_cast<float2_t*>(mine + 4) = float2_t{O[2], O[3]};
+      float* mine = s_red + ((size_t)sl * CP + col) * 8;
+      *reinterpret_cast<float4_t*>(mine) = float4_t{M, Lsum, Lx, 0.0f};
+      *reinterpret_cast<float4_t*>(mine + 4) = O;
       __syncthreads();
       if (sl == 0) {
         float bm = M;
 #pragma unroll
-        for (int k = 1; k < SL; ++k) bm = fmaxf(bm, s_red[((size_t)k * CP + col) * 6]);
+        for (int k = 1; k < SL; ++k) bm = fmaxf(bm, s_red[((size_t)k * CP + col) * 8]);
         const float a = fast_exp2(M - bm);
         O *= a;
         Lsum *= a;
+        Lx *= a;
         M = bm;
 #pragma unroll
         for (int k = 1; k < SL; ++k) {
-          const float* st = s_red + ((size_t)k * CP + col) * 6;
+          const float* st = s_red + ((size_t)k * CP + col) * 8;
           const float w = fast_exp2(st[0] - bm);
           Lsum = __builtin_fmaf(st[1], w, Lsum);
+          Lx = __builtin_fmaf(st[2], w, Lx);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) O[j] = __builtin_fmaf(st[2 + j], w, O[j]);
+          for (int j = 0; j < 4; ++j) O[j] = __builtin_fmaf(st[4 + j], w, O[j]);
         }
       }
     }
@@ -487,7 +504,7 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     const uint32_t lo = (uint32_t)Elem<DT>::narrow(O[0] * inv) | ((uint32_t)Elem<DT>::narrow(O[1] * inv) << 16);
     const uint32_t hi = (uint32_t)Elem<DT>::narrow(O[2] * inv) | ((uint32_t)Elem<DT>::narrow(O[3] * inv) << 16);
     *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + row * ABSB_HEAD_DIM + c4 * 4) = make_uint2(lo, hi);
-    if (p.lse && c4 == 0) p.lse[row] = any ? (M + __builtin_log2f(Lsum)) * 0.6931471805599453f : -__builtin_inff();
+    if (p.lse && c4 == 0) p.lse[row] = any ? (M + __builtin_log2f(Lx)) * 0.6931471805599453f : -__builtin_inff();
   }
   ABSB_STAMP(p.trace, 13);
 }

@@ -14,7 +14,7 @@ from paper_2605_12110_amd import synth
 pytestmark = pytest.mark.gpu
 
 TOL = {synth.F16: 2e-3, synth.BF16: 1e-2}
-LSE_TOL = 2e-3
+LSE_TOL = 1e-4      # binary32 sums of the unrounded weights: measured <= 2e-6
 
 
 def _say(msg):
@@ -711,6 +711,28 @@ def test_one_launch_step_with_constant_keys_takes_the_tie_paths():
             assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
         finally:
             absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+
+
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_log_sum_exp_does_not_carry_the_rounding_of_the_weights(dtype):
+    """Few distinct keys per head: every softmax weight of a kind rounds the same way when it is
+    narrowed to the K/V type for the P V product (bf16: up to 2^-8 relative).  The output is
+    normalised by the rounded weights (it stays a convex combination of value rows); the
+    log-sum-exp must come from the weights before rounding and stay far inside its tolerance."""
+    rng = np.random.default_rng(77)
+    wl = synth.tiny_workload(seed=78, dtype=dtype, Bt=4, Hq=14, Hkv=2, P=8, seq_lens=(9, 65, 1000, 4097),
+                             block_size=(16, 128), budget=(8, 2048, 100, 100000))
+    pal = synth.f32_to_bits(rng.standard_normal((2, wl.head_dim)).astype(np.float32), dtype)
+    pick = rng.integers(0, 2, size=wl.k_cache.shape[:2])
+    wl.k_cache[:] = pal[pick][:, :, None, :]                     # two keys in all, one per page slab
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    dw = _dev(wl)
+    dw.build()
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "two distinct keys")
+    lse = dw.lse.cpu().numpy().astype(np.float64)
+    assert np.abs(lse - ref["lse"]).max() <= 2e-5
 
 
 # ------------------------------------------------------------------ growing contexts (store maintenance)
