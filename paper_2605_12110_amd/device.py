@@ -75,13 +75,16 @@ class DeviceWorkload:
         self.scores = torch.empty((total * rk,), dtype=torch.int32, device=device)
         self.score_exp = torch.empty((nsel,), dtype=torch.int32, device=device)
         self.sel_stride = max(self.plan.sel_stride, 1)
-        self.sel_idx = torch.empty((nsel, self.sel_stride), dtype=torch.int32, device=device)
+        self._sel_buf = torch.empty((nsel * self.sel_stride,), dtype=torch.int32, device=device)
+        self.sel_idx = self._sel_buf.view(nsel, self.sel_stride)
         self.sel_cnt = torch.empty((nsel,), dtype=torch.int32, device=device)
         self.out = torch.empty((wl.batch, wl.num_q_heads, wl.head_dim), dtype=tdt, device=device)
         self.lse = torch.empty((wl.batch, wl.num_q_heads), dtype=torch.float32, device=device)
         self.tail = torch.empty((nseg, width), dtype=torch.float32, device=device)
         self.workspace = torch.empty((self.plan.workspace_bytes + 256,), dtype=torch.uint8, device=device)
         self.scribble(0xA5)
+        if cap_lens is not None:
+            self.set_lens(wl.seq_lens)             # the lists are as wide as the current lengths make them
 
     def scribble(self, value: int, stream=None):
         """Poison the workspace (no entry point may depend on its previous contents), then clear its
@@ -100,6 +103,10 @@ class DeviceWorkload:
         lens = np.asarray(lens, dtype=np.int32)
         self.seq_lens.copy_(torch.from_numpy(lens))
         self.batch.seq_lens_host = lens
+        # the list width follows the lengths (budgets beyond a context select all of its blocks):
+        # the lists of the current lengths are [segments][sel_stride] at the start of the buffer
+        self.sel_stride = max(absb.absb_plan(self.layer, self.batch).sel_stride, 1)
+        self.sel_idx = self._sel_buf[:self.nsel * self.sel_stride].view(self.nsel, self.sel_stride)
 
     def tail_init(self, stream=None):
         absb.absb_tail_init(self.layer, self.batch, self.k_cache, self.tail, stream)

@@ -796,6 +796,38 @@ def test_appending_tokens_keeps_the_store_and_the_step_in_parity(repr_, dtype):
             assert np.array_equal(got[:, :kk], ref["sel_idx"][:, :kk]) and np.all(got[:, kk:] == -1)
 
 
+def test_lists_widen_with_the_context_when_the_budget_exceeds_it():
+    """A budget beyond the context selects every block, so K_s and the list width that absb_plan
+    reports grow with the lengths: the fused step writes [segments][that width] for the lengths
+    of the call, inside a buffer sized for the longest contexts."""
+    full = synth.tiny_workload(seed=73, dtype=synth.F16, Bt=3, Hq=15, Hkv=3, P=8, seq_lens=(3020, 85, 148),
+                               block_size=(64, 16, 128), budget=(8, 4096, 8))
+    start = full.seq_lens - 20
+    view = _view_at(full, start)
+    dw = _dev(view, cap_lens=full.seq_lens)
+    dw.build(); dw.tail_init(); _sync()
+    store = O.build_centroids(view)
+    tail = O.tail_state(view)
+    widths = set()
+    for step in range(1, 21):
+        lens = start + step
+        view = _view_at(full, lens)
+        dw.wl = view
+        dw.set_lens(lens)
+        dw.append_token()
+        store, _ = O.append_token(view, store, tail)
+        ref = O.decode_step(view, store)
+        dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7)
+        dw.decode_fused()
+        _check_out(dw, ref["out"], ref["lse"], f"after {step} tokens")
+        K = dw.sel_stride
+        widths.add(K)
+        assert K == int(ref["sel_cnt"].max())
+        assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
+    assert len(widths) > 1
+
+
 def test_stages_ignore_the_unused_rows_of_a_layout_sized_for_longer_contexts():
     """A store laid out for longer contexts than the current ones: build, score, selection and the
     step give the same results as the tight layout (the unused rows hold garbage)."""
