@@ -518,6 +518,48 @@ def test_random_shapes_modes_and_enqueue_forms(seed):
                    per_query_head=mode == 2, group_max=mode == 3)
 
 
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_shapes_with_few_distinct_keys_and_forced_blocks(seed):
+    """As above on caches that hold 1, 2 or 17 distinct keys (one per page and head): whole runs of
+    blocks score the same, so the selection lives on its tie paths and the softmax weights take few
+    values; in the default mode also with forced first / last blocks through the fused step."""
+    from paper_2605_12110_amd import absb
+    rng = np.random.default_rng(3000 + seed)
+    Bt = int(rng.integers(1, 5))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.integers(1, 9))
+    P = int(rng.choice([8, 16, 32, 64, 128, 256]))
+    lens = [int(x) for x in rng.choice([1, 2, 9, 63, 65, 129, 300, 1024, 2049, 4097, 7000], size=Bt)]
+    bs = [int(x) for x in rng.choice([8, 16, 32, 64, 128], size=Hkv)]
+    budget = [int(x) for x in rng.choice([1, 7, 64, 500, 2048, 9000, 100000], size=Bt)]
+    dtype = int(rng.choice([synth.F16, synth.BF16]))
+    mode = int(rng.integers(0, 4))
+    wl = synth.tiny_workload(seed=4000 + seed, dtype=dtype, Bt=Bt, Hq=Hkv * G, Hkv=Hkv, P=P, seq_lens=lens,
+                             block_size=bs, budget=budget)
+    m = int(rng.choice([1, 2, 17]))
+    pal = synth.f32_to_bits(rng.standard_normal((m, wl.head_dim)).astype(np.float32), dtype)
+    wl.k_cache[:] = pal[rng.integers(0, m, size=wl.k_cache.shape[:2])][:, :, None, :]
+    run_all_stages(wl, f"few keys {seed}: mode {mode}, {m} keys", block_repr=O.MINMAX if mode == 1 else O.MEAN,
+                   per_query_head=mode == 2, group_max=mode == 3)
+    if mode == 0:
+        sink, recent = int(rng.choice([0, 1, 9, 200, 5000])), int(rng.choice([0, 1, 65, 700, 5000]))
+        st = O.build_centroids(wl)
+        ref = O.decode_step(wl, st, sink_tokens=sink, recent_tokens=recent)
+        dw = _dev(wl, sink_tokens=sink, recent_tokens=recent)
+        dw.build()
+        for launches in (1, 3):
+            absb.set_tuning(absb.TUNE_STEP_LAUNCHES, launches)
+            try:
+                dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7)
+                dw.decode_fused()
+                _check_out(dw, ref["out"], ref["lse"], f"forced sink={sink} recent={recent}, {launches} launch(es)")
+            finally:
+                absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+            assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+            assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+            assert dw.status() == 0
+
+
 # ------------------------------------------------------------------ per-query-head selection
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
 def test_per_query_head_selection_ragged_small_batch(dtype):
