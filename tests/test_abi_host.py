@@ -255,6 +255,20 @@ def test_block_size_assignment_rule_matches_the_oracle_on_the_host():
     assert e.value.status == absb.ERR_BAD_SHAPE
 
 
+def test_plan_accepts_65535_selection_segments_and_no_more():
+    # selection segments index the second grid dimension of the per-stage kernels
+    lens, T = [64] * 65535, [8] * 65535
+    one = _layer(num_q_heads=3, num_kv_heads=1, block_size=[16])
+    assert absb.absb_plan(one, _batch(lens, T)).total_centroids == 4 * 65535
+    with pytest.raises(absb.AbsbError) as e:
+        absb.absb_plan(one, _batch(lens + [64], T + [8]))
+    assert e.value.status == absb.ERR_BAD_SHAPE
+    per_q = _layer(num_q_heads=3, num_kv_heads=1, block_size=[16], selection=absb.SELECT_PER_QUERY_HEAD)
+    assert absb.absb_plan(per_q, _batch(lens[:21845], T[:21845])).total_centroids == 4 * 21845
+    with pytest.raises(absb.AbsbError):
+        absb.absb_plan(per_q, _batch(lens[:21846], T[:21846]))
+
+
 def test_plan_lays_the_store_out_for_the_capacity_lengths_when_given():
     layer = _layer()
     tight = absb.absb_plan(layer, _batch((1000,), (64,)))

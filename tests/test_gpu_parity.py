@@ -494,6 +494,27 @@ def test_forced_blocks_on_a_long_segment_with_many_tiles():
         assert (want <= chosen) if len(want) <= cnt[s] else (chosen <= want)
 
 
+@pytest.mark.parametrize("Hkv,G", [(33, 2), (64, 1), (64, 8)])
+def test_many_kv_heads(Hkv, G):
+    """Head counts beyond the benchmark shapes, up to the 64 KV heads the head table holds."""
+    rng = np.random.default_rng(Hkv * 10 + G)
+    wl = synth.tiny_workload(seed=Hkv, dtype=synth.BF16 if G == 1 else synth.F16, Bt=2, Hq=Hkv * G, Hkv=Hkv, P=32,
+                             seq_lens=(700, 65), block_size=rng.choice([8, 16, 32, 64, 128], size=Hkv).tolist(),
+                             budget=(96, 2048))
+    run_all_stages(wl, f"{Hkv} KV heads x {G}", group_max=G == 8)
+
+
+def test_the_largest_number_of_segments():
+    """65535 selection segments (the limit of the plan), each a short context: every stage and the
+    fused step in all its forms."""
+    rng = np.random.default_rng(65535)
+    Bt = 13107
+    lens = rng.integers(1, 200, size=Bt).tolist()
+    wl = synth.tiny_workload(seed=65535, dtype=synth.F16, Bt=Bt, Hq=5, Hkv=5, P=16, seq_lens=lens,
+                             block_size=(16, 16, 64, 8, 128), budget=rng.choice([1, 8, 64, 1000], size=Bt).tolist())
+    run_all_stages(wl, "65535 segments")
+
+
 # ------------------------------------------------------------------ randomised shapes
 @pytest.mark.parametrize("seed", list(range(24)))
 def test_random_shapes_modes_and_enqueue_forms(seed):
