@@ -504,6 +504,15 @@ def test_many_kv_heads(Hkv, G):
     run_all_stages(wl, f"{Hkv} KV heads x {G}", group_max=G == 8)
 
 
+@pytest.mark.parametrize("L,sizes,G,budget", [(1 << 20, (8, 128), 4, 8192), ((1 << 20) - 3, (8,), 1, 1 << 20)])
+def test_one_million_token_context(L, sizes, G, budget):
+    """The longest segment the selection holds (2^17 blocks of 8 tokens) through every stage and the
+    fused step; the second case selects all of it (a dense read through a 131072-entry list)."""
+    wl = synth.tiny_workload(seed=L % 1000, dtype=synth.F16, Bt=1, Hq=len(sizes) * G, Hkv=len(sizes), P=64,
+                             seq_lens=(L,), block_size=sizes, budget=(budget,))
+    run_all_stages(wl, f"context {L}, blocks {sizes}, budget {budget}")
+
+
 def test_the_largest_number_of_segments():
     """65535 selection segments (the limit of the plan), each a short context: every stage and the
     fused step in all its forms."""
