@@ -37,6 +37,9 @@
  *     count); a workspace allocated zero-filled needs no call), and every entry point leaves
  *     them zero.  Nothing else in the workspace needs initialisation or survives a call.  Calls
  *     that share a workspace must be ordered on one stream.
+ *   - Limits: at most 65535 selection segments per batch (ABSB_ERR_BAD_SHAPE beyond); the selection
+ *     (absb_topk, absb_decode_fused) holds at most 2^17 blocks per segment (ABSB_ERR_UNSUPPORTED
+ *     beyond: 1 Mi tokens at B_h = 8, 16 Mi at B_h = 128); fewer than 2^31 blocks in all.
  */
 #ifndef ABSB_H
 #define ABSB_H

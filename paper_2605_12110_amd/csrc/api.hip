@@ -104,6 +104,9 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
     }
   }
   if (!batch->budget_host) p.sel_stride = p.max_blocks;
+  // entry points that select (they are the ones that need the budgets) refuse on the host what the
+  // selection cannot hold, before anything is enqueued
+  if (need_budget && p.max_blocks > ABSB_MAX_SEL_BLOCKS) return ABSB_ERR_UNSUPPORTED;
   if (p.total >= (int64_t(1) << 31) - 1) return ABSB_ERR_BAD_SHAPE;
   if ((int64_t)batch->pt_stride < ceil_div(max_len, P)) return ABSB_ERR_BAD_SHAPE;
 

@@ -9,6 +9,7 @@
 #define ABSB_HEAD_DIM 128
 #define ABSB_MAX_KV_HEADS 64
 #define ABSB_MAX_GROUP 8
+#define ABSB_MAX_SEL_BLOCKS (1 << 17)  // blocks per segment the selection holds (its LDS bitmap)
 #define ABSB_HIDDEN __attribute__((visibility("hidden")))
 // Split counters sit 256 bytes apart: counters that share a memory line serialise each other's
 // atomic updates (measured: 8 segments x 32 arrivals on one line cost 2.7 us, apart 0.x us).

@@ -68,7 +68,7 @@ inline TopkParams make_topk_params(const Geometry& g, const int32_t* scores, con
 
 constexpr int TOPK_MAX_CAND = 1024;       // longest candidate list
 constexpr int TOPK_RANK_MAX = 128;        // candidates ranked against each other (quadratic work)
-constexpr int TOPK_MAX_BLOCKS = 1 << 17;  // bitmap capacity (2 x 16 KiB of LDS)
+constexpr int TOPK_MAX_BLOCKS = ABSB_MAX_SEL_BLOCKS;  // bitmap capacity (2 x 16 KiB of LDS)
 constexpr int TOPK_DIGIT_BITS = 11;
 constexpr int TOPK_BINS = 1 << TOPK_DIGIT_BITS;
 constexpr int TOPK_SLOTS = 16;            // per-wave scratch words: up to 16 waves per work-group

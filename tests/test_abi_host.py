@@ -234,6 +234,12 @@ def test_selection_rejects_segments_beyond_its_capacity_before_any_launch():
     with pytest.raises(absb.AbsbError) as e:
         absb.absb_topk(layer, batch, fake, fake, fake, 8, stream=0)
     assert e.value.status == absb.ERR_UNSUPPORTED
+    with pytest.raises(absb.AbsbError) as e:                 # the whole step: refused before its first stage is enqueued
+        absb.absb_decode_fused(layer, batch, fake, fake, fake, fake, fake, fake, None, None, None, fake, stream=0)
+    assert e.value.status == absb.ERR_UNSUPPORTED
+    with pytest.raises(absb.AbsbError) as e:
+        absb.absb_step_launches(layer, batch)
+    assert e.value.status == absb.ERR_UNSUPPORTED
 
 
 def test_block_size_assignment_rule_matches_the_oracle_on_the_host():
