@@ -313,20 +313,30 @@ def run_matrix(args):
 
     print("\nStore maintenance while decoding (absb_append_token: one new token per request folded into the store, "
           "no rebuild) next to a full rebuild (absb_build_centroids)\n")
-    print("| workload | segments | append us/call | rebuild us/call |")
-    print("|---|---|---|---|", flush=True)
+    print("| workload | segments | append us/call (back-to-back calls from Python: the host's call rate, the kernel "
+          "itself takes ~3 us) | rebuild us/call | after 256 appended tokens: values of completed "
+          "blocks outside the frozen ranges (the re-ranging signal) |")
+    print("|---|---|---|---|---|", flush=True)
     from paper_2605_12110_amd.device import DeviceWorkload
     for cfg in (3, 4):
         import copy
         full = synth_workload(cfg)
-        wl0 = copy.copy(full)                       # the same caches, 64 tokens before their final lengths
-        wl0.seq_lens = full.seq_lens - 64
+        grow = 256
+        wl0 = copy.copy(full)                       # the same caches, `grow` tokens before their final lengths
+        wl0.seq_lens = full.seq_lens - grow
         dw = DeviceWorkload(wl0, cap_lens=full.seq_lens)
         dw.build()
         dw.tail_init()
+        for t in range(1, grow + 1):                # real growth: ranges frozen at the build above
+            dw.set_lens(wl0.seq_lens + t)
+            dw.append_token()
+        outside = int(dw.clamped.sum().item())
+        bs = np.asarray(dw.block_size, dtype=np.int64)[None, :]
+        closed = int((full.seq_lens.astype(np.int64)[:, None] // bs - wl0.seq_lens.astype(np.int64)[:, None] // bs).sum())
         ms_app, _ = time_loop(lambda i: dw.append_token(), 10, 100)      # the same token again and again: timing only
         ms_bld, _ = time_loop(lambda i: dw.build(), 2, 10)
-        print(f"| config {cfg} | {dw.nseg} | {ms_app * 1e3:.1f} | {ms_bld * 1e3:.1f} |", flush=True)
+        print(f"| config {cfg} | {dw.nseg} | {ms_app * 1e3:.1f} | {ms_bld * 1e3:.1f} | {outside} of {closed * 128} "
+              f"({100.0 * outside / max(closed * 128, 1):.2f} %) in {closed} blocks |", flush=True)
         del dw
         torch.cuda.empty_cache()
 

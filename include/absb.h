@@ -269,12 +269,18 @@ ABSB_API int absb_status_offset(const absb_layer* layer, const absb_batch* batch
  * qscale/qmin: code = clamp(rint((value - qmin) * (1/qscale)), 0, 15), 0 where qscale is 0.  Rows
  * of closed blocks never change; qscale/qmin are only refreshed by absb_build_centroids.  When the
  * token opens a new block the row off[s] + N_s - 1 is written for the first time: the layout must
- * have room for it (batch->cap_lens_host). */
+ * have room for it (batch->cap_lens_host).
+ *   clamped [Bt*Hkv] i32, optional (NULL ok): the signal for a re-ranging policy.  When the token
+ *   completes its block (L_b % B_h == 0; the row is final from then on), the number of the row's R*d
+ *   values that the frozen range does not hold is ADDED to clamped[s]: values whose unclamped code
+ *   falls outside [0, 15], and values that differ from qmin where qscale is 0.  The caller zeroes
+ *   the array after absb_build_centroids and rebuilds when the counts (at most R*d per completed
+ *   block) exceed what it tolerates. */
 ABSB_API int absb_tail_init(const absb_layer* layer, const absb_batch* batch, const void* k_cache, float* tail,
                             void* stream);
 ABSB_API int absb_append_token(const absb_layer* layer, const absb_batch* batch, const void* k_cache,
                                uint8_t* codes, const float* qscale, const float* qmin, float* tail,
-                               void* stream);
+                               int32_t* clamped, void* stream);
 
 /* Offline calibration of the per-head block sizes (Sec. 3.2).  Two pieces; the loop over
  * calibration samples and candidate sizes around them uses the entry points above.

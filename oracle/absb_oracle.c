@@ -684,11 +684,14 @@ void orc_tail_state(int dtype, int repr, int Bt, int Hkv, int d, int P, int64_t 
 /* orc_append_token: the token at position L_b - 1 (lengths already include it) joins the store.
  * tail: in/out state as above.  row_out [nseg][R*d/2]: the re-emitted 4-bit row of the block that
  * holds the token; value_out [nseg][R*d] (may be NULL): that block's pooled value (mean, or
- * maxima and minima). */
+ * maxima and minima).  clamped [nseg] (may be NULL): when the token completes its block (the row is
+ * final from then on), the number of the row's values that the frozen range does not hold is ADDED:
+ * values whose unclamped code rint((value - min) / scale) falls outside [0, 15], and values that
+ * differ from min where the scale is 0. */
 void orc_append_token(int dtype, int repr, int Bt, int Hkv, int d, int P, int64_t s_page, int64_t s_head,
                       int64_t s_tok, const uint16_t *k_cache, const int32_t *page_table, int pt_stride,
                       const int32_t *seq_lens, const int32_t *block_size, const float *qscale,
-                      const float *qmin, float *tail, uint8_t *row_out, float *value_out) {
+                      const float *qmin, float *tail, uint8_t *row_out, float *value_out, int32_t *clamped) {
     paged_t kc = {k_cache, page_table, pt_stride, P, s_page, s_head, s_tok};
     int W = d * (repr + 1);
     for (int s = 0; s < Bt * Hkv; ++s) {
@@ -699,6 +702,7 @@ void orc_append_token(int dtype, int repr, int Bt, int Hkv, int d, int P, int64_
         float *st = tail + (int64_t)s * W;
         float n = (float)(t - t0 + 1);
         uint8_t *codes = row_out + (int64_t)s * (W / 2);
+        int outside = 0;
         for (int c = 0; c < W; ++c) {
             int ch = c % d;
             float v = widen(row[ch], dtype);
@@ -716,8 +720,11 @@ void orc_append_token(int dtype, int repr, int Bt, int Hkv, int d, int P, int64_
                 float inv = 1.0f / sc;
                 float x = value - qmin[(int64_t)s * W + c];
                 r = rintf(x * inv);
+                if (!(r >= 0.0f && r <= 15.0f)) ++outside;
                 if (!(r >= 0.0f)) r = 0.0f;
                 if (r > 15.0f) r = 15.0f;
+            } else if (value != qmin[(int64_t)s * W + c]) {
+                ++outside;
             }
             uint8_t code = (uint8_t)r;
             if (c % 2 == 0)
@@ -725,6 +732,7 @@ void orc_append_token(int dtype, int repr, int Bt, int Hkv, int d, int P, int64_
             else
                 codes[c / 2] = (uint8_t)(codes[c / 2] | (code << 4));
         }
+        if (clamped && L % B == 0) clamped[s] += outside;
     }
 }
 

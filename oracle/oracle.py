@@ -178,10 +178,12 @@ def tail_state(wl, repr: int = MEAN) -> np.ndarray:
     return tail
 
 
-def append_token(wl, store: CentroidStore, tail: np.ndarray):
+def append_token(wl, store: CentroidStore, tail: np.ndarray, clamped: Optional[np.ndarray] = None):
     """The token at position L_b - 1 of every request (wl.seq_lens already counts it, the key is in
     wl.k_cache) joins the store under its frozen ranges.  Returns (new store in the tight layout of
-    the new lengths, block values [nseg, W]); `tail` is updated in place."""
+    the new lengths, block values [nseg, W]); `tail` is updated in place, and so is `clamped`
+    (int32 [nseg], optional): per segment the running count of values in completed blocks that the
+    frozen ranges did not hold."""
     dt, Bt, _, Hkv, d, P, sp, sh, st = _geom(wl)
     nseg = wl.batch * wl.num_kv_heads
     W = wl.head_dim * (store.repr + 1)
@@ -190,7 +192,7 @@ def append_token(wl, store: CentroidStore, tail: np.ndarray):
     pt = _i32(wl.page_table)
     lib().orc_append_token(dt, C.c_int(store.repr), Bt, Hkv, d, P, sp, sh, st, _p(wl.k_cache), _p(pt),
                            C.c_int(pt.shape[1]), _p(_i32(wl.seq_lens)), _p(_i32(wl.block_size)), _p(store.qscale),
-                           _p(store.qmin), _p(tail), _p(rows), _p(values))
+                           _p(store.qmin), _p(tail), _p(rows), _p(values), _p(clamped))
     new_off = offsets(wl)
     codes = np.zeros((int(new_off[-1]), W // 2), np.uint8)
     cent = None if store.cent is None else np.zeros((int(new_off[-1]), W), np.float32)

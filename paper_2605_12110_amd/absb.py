@@ -257,10 +257,11 @@ def absb_tail_init(layer: Layer, batch: Batch, k_cache, tail, stream=None) -> No
            "absb_tail_init")
 
 
-def absb_append_token(layer: Layer, batch: Batch, k_cache, codes, qscale, qmin, tail, stream=None) -> None:
+def absb_append_token(layer: Layer, batch: Batch, k_cache, codes, qscale, qmin, tail, clamped=None,
+                      stream=None) -> None:
     cl, cb = layer.c(), batch.c()
     _check(load().absb_append_token(C.byref(cl), C.byref(cb), _ptr(k_cache), _ptr(codes), _ptr(qscale), _ptr(qmin),
-                                    _ptr(tail), _stream(stream)), "absb_append_token")
+                                    _ptr(tail), _ptr(clamped), _stream(stream)), "absb_append_token")
 
 
 def absb_head_recall(layer: Layer, batch: Batch, lse_selected, lse_dense, recall, stream=None) -> None:

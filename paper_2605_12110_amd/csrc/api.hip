@@ -359,11 +359,11 @@ int absb_tail_init(const absb_layer* layer, const absb_batch* batch, const void*
   if (rc != ABSB_OK) return rc;
   if (!k_cache || !tail || !batch->seq_lens || !batch->page_table) return ABSB_ERR_NULL;
   return launch_append(g, p, layer->dtype, false, k_cache, batch->page_table, batch->seq_lens, nullptr, nullptr,
-                       nullptr, nullptr, tail, static_cast<hipStream_t>(stream));
+                       nullptr, nullptr, tail, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int absb_append_token(const absb_layer* layer, const absb_batch* batch, const void* k_cache, uint8_t* codes,
-                      const float* qscale, const float* qmin, float* tail, void* stream) {
+                      const float* qscale, const float* qmin, float* tail, int32_t* clamped, void* stream) {
   Geometry g;
   Plan p;
   int rc = make_plan(layer, batch, false, 0, &g, &p);
@@ -371,7 +371,7 @@ int absb_append_token(const absb_layer* layer, const absb_batch* batch, const vo
   if (!k_cache || !codes || !qscale || !qmin || !tail || !batch->seq_lens || !batch->page_table || !batch->cent_off)
     return ABSB_ERR_NULL;
   return launch_append(g, p, layer->dtype, true, k_cache, batch->page_table, batch->seq_lens, batch->cent_off, codes,
-                       qscale, qmin, tail, static_cast<hipStream_t>(stream));
+                       qscale, qmin, tail, clamped, static_cast<hipStream_t>(stream));
 }
 
 int absb_head_recall(const absb_layer* layer, const absb_batch* batch, const float* lse_selected,

@@ -273,7 +273,9 @@ __global__ __launch_bounds__(BUILD_THREADS) void build_codes_kernel(BuildParams 
 // Decode-time maintenance.  A 16-lane row-group per segment (each lane 8 channels): folds the key
 // of the newest token (position L - 1) into the pooled state of the segment's last block and
 // re-emits that block's 4-bit row under the store's frozen ranges; with APPEND == false it only
-// recomputes the state from the cache (the tokens of the last block, in order).
+// recomputes the state from the cache (the tokens of the last block, in order).  When the new token
+// completes its block the row is final: the number of its values that the frozen range does not
+// hold is then added to the segment's counter (the signal for a re-ranging policy).
 struct AppendParams {
   const uint16_t* k;
   const int32_t* page_table;
@@ -283,6 +285,7 @@ struct AppendParams {
   const float* qscale;
   const float* qmin;
   float* tail;  // [nseg][W]
+  int32_t* clamped;  // [nseg] or null
   int32_t nseg;
   Geometry g;
 };
@@ -341,6 +344,7 @@ __global__ __launch_bounds__(BUILD_THREADS) void append_kernel(AppendParams p) {
 
   const float fn = (float)(t_new - t0 + 1);
   const size_t row_at = ((size_t)p.cent_off[s] + j) * (W / 2);
+  int outside = 0;
 #pragma unroll
   for (int v = 0; v <= REP; ++v) {
     const int col = v * ABSB_HEAD_DIM + li * 8;
@@ -354,11 +358,23 @@ __global__ __launch_bounds__(BUILD_THREADS) void append_kernel(AppendParams p) {
         const float inv = 1.0f / sc;
         const float x = value - p.qmin[(size_t)s * W + col + c];
         r = __builtin_rintf(x * inv);
+        outside += !(r >= 0.0f && r <= 15.0f);
         r = fminf(fmaxf(r, 0.0f), 15.0f);  // a NaN ends up at 0
+      } else {
+        outside += value != p.qmin[(size_t)s * W + col + c];  // a channel that was constant at build time
       }
       packed |= (uint32_t)r << (4 * c);
     }
     *reinterpret_cast<uint32_t*>(p.codes + row_at + col / 2) = packed;
+  }
+  if (p.clamped && ((t_new + 1) & ((1 << lb) - 1)) == 0) {  // the block is complete (wave-uniform per row-group)
+    outside += __shfl_xor(outside, 1);
+    outside += __shfl_xor(outside, 2);
+    outside += __shfl_xor(outside, 4);
+    outside += __shfl_xor(outside, 8);
+    // this row-group is the segment's only writer; an add without return value, so that nothing waits for it
+    if (li == 0 && outside)
+      __hip_atomic_fetch_add(p.clamped + s, outside, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -373,7 +389,7 @@ static void launch_append_kernel(bool append, const AppendParams& p, hipStream_t
 
 int launch_append(const Geometry& g, const Plan& pl, int dtype, bool append, const void* k_cache,
                   const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off, uint8_t* codes,
-                  const float* qscale, const float* qmin, float* tail, hipStream_t stream) {
+                  const float* qscale, const float* qmin, float* tail, int32_t* clamped, hipStream_t stream) {
   AppendParams p;
   p.k = static_cast<const uint16_t*>(k_cache);
   p.page_table = page_table;
@@ -383,6 +399,7 @@ int launch_append(const Geometry& g, const Plan& pl, int dtype, bool append, con
   p.qscale = qscale;
   p.qmin = qmin;
   p.tail = tail;
+  p.clamped = clamped;
   p.nseg = pl.nstore;
   p.g = g;
   if (dtype == ABSB_F16 && g.repr == ABSB_REPR_MEAN)

@@ -81,7 +81,7 @@ ABSB_HIDDEN int launch_score(const Geometry& g, const Plan& pl, int dtype, const
 ABSB_HIDDEN int launch_append(const Geometry& g, const Plan& pl, int dtype, bool append, const void* k_cache,
                               const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
                               uint8_t* codes, const float* qscale, const float* qmin, float* tail,
-                              hipStream_t stream);
+                              int32_t* clamped, hipStream_t stream);
 ABSB_HIDDEN int launch_topk(const Geometry& g, const Plan& pl, const int32_t* scores, const int32_t* cent_off,
                             const int32_t* budget, const int32_t* seq_lens, int32_t* sel_idx, int32_t* sel_cnt,
                             int32_t sel_stride,

@@ -81,6 +81,7 @@ class DeviceWorkload:
         self.out = torch.empty((wl.batch, wl.num_q_heads, wl.head_dim), dtype=tdt, device=device)
         self.lse = torch.empty((wl.batch, wl.num_q_heads), dtype=torch.float32, device=device)
         self.tail = torch.empty((nseg, width), dtype=torch.float32, device=device)
+        self.clamped = torch.zeros((nseg,), dtype=torch.int32, device=device)   # values outside the frozen ranges
         self.workspace = torch.empty((self.plan.workspace_bytes + 256,), dtype=torch.uint8, device=device)
         self.scribble(0xA5)
         if cap_lens is not None:
@@ -113,7 +114,7 @@ class DeviceWorkload:
 
     def append_token(self, stream=None):
         absb.absb_append_token(self.layer, self.batch, self.k_cache, self.codes, self.qscale, self.qmin,
-                               self.tail, stream)
+                               self.tail, self.clamped, stream)
 
     def load_store(self, codes: np.ndarray, qscale: np.ndarray, qmin: np.ndarray):
         """Install a centroid store computed elsewhere (e.g. by the oracle, for stage-isolated tests)."""

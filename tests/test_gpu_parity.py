@@ -846,16 +846,18 @@ def test_appending_tokens_keeps_the_store_and_the_step_in_parity(repr_, dtype):
     tail = O.tail_state(view, repr_)
     assert np.array_equal(_tight(dw, start), store.codes) and np.array_equal(dw.qscale.cpu().numpy(), store.qscale)
     assert np.array_equal(dw.tail.cpu().numpy(), tail)
+    clamped = np.zeros(dw.nseg, np.int32)              # values of completed blocks outside the frozen ranges
     for step in range(1, grow + 1):
         lens = start + step
         view = _view_at(full, lens)
         dw.wl = view
         dw.set_lens(lens)
         dw.append_token()
-        store, _ = O.append_token(view, store, tail)
+        store, _ = O.append_token(view, store, tail, clamped)
         _sync()
         assert np.array_equal(dw.tail.cpu().numpy(), tail), f"tail state after {step} tokens"
         assert np.array_equal(_tight(dw, lens), store.codes), f"code rows after {step} tokens"
+        assert np.array_equal(dw.clamped.cpu().numpy(), clamped), f"re-ranging counters after {step} tokens"
         if step in (1, 7, 8, 9, 32, grow):
             ref = O.decode_step(view, store)
             dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
@@ -866,6 +868,7 @@ def test_appending_tokens_keeps_the_store_and_the_step_in_parity(repr_, dtype):
             got = dw.sel_idx.cpu().numpy()
             kk = min(K, ref["sel_idx"].shape[1])
             assert np.array_equal(got[:, :kk], ref["sel_idx"][:, :kk]) and np.all(got[:, kk:] == -1)
+    assert clamped.sum() > 0                           # the counters were exercised
 
 
 def test_lists_widen_with_the_context_when_the_budget_exceeds_it():

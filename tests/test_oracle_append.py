@@ -133,3 +133,80 @@ def test_constant_keys_keep_their_code_and_zero_scale_channels_stay_zero():
         cu_new, cu_old = _unpack(grown.codes[2:3])[0], _unpack(row[None])[0]
         # a mean of equal fp16 keys is the key itself up to the rounding of sum/n: at most one level off
         assert np.all(np.abs(cu_new - cu_old) <= 1) and cu_new[5] == 0
+
+
+# ------------------------------------------------------------------ the re-ranging signal
+def _outside(values, scale, mn):
+    """Independent count (numpy, exact rational thresholds in float64): a value is held by a frozen
+    range [mn, mn + 15*scale] iff its code rint((v - mn) * (1/scale)) lies in [0, 15]; with the
+    binary32 steps of the emitter that is decided here from the binary32 product itself."""
+    inv = (np.float32(1.0) / np.where(scale > 0, scale, np.float32(1))).astype(np.float32)
+    r = np.rint(((values - mn).astype(np.float32) * inv).astype(np.float32))
+    return np.where(scale > 0, (r < 0) | (r > 15), values != mn)
+
+
+@pytest.mark.parametrize("repr_", [O.MEAN, O.MINMAX])
+def test_clamp_counter_counts_completed_blocks_only_and_matches_an_independent_count(repr_):
+    full = synth.tiny_workload(seed=66, dtype=synth.BF16, Bt=2, Hq=4, Hkv=2, P=16, seq_lens=(150, 97),
+                               block_size=(8, 32), budget=(8, 8))
+    # outliers among the tokens to come, so that some completed blocks leave the ranges
+    rng = np.random.default_rng(5)
+    k32 = synth.bits_to_f32(full.k_cache, full.dtype)
+    k32 *= np.where(rng.random(k32.shape) < 0.02, 6.0, 1.0).astype(np.float32)
+    full.k_cache[:] = synth.f32_to_bits(k32, full.dtype)
+    start = np.array([150 - 70, 97 - 70], np.int32)
+    wl = _at(full, start)
+    store = O.build_centroids(wl, repr_)
+    tail = O.tail_state(wl, repr_)
+    clamped = np.zeros(4, np.int32)
+    want = np.zeros(4, np.int64)
+    for step in range(1, 71):
+        wl = _at(full, start + step)
+        before = clamped.copy()
+        store, values = O.append_token(wl, store, tail, clamped)
+        for s in range(4):
+            b, h = divmod(s, 2)
+            if int(wl.seq_lens[b]) % int(wl.block_size[h]) == 0:          # the token completed its block
+                want[s] += int(_outside(values[s], store.qscale[s], store.qmin[s]).sum())
+            else:
+                assert clamped[s] == before[s]
+        assert np.array_equal(clamped, want)
+    assert clamped.sum() > 0 and np.all(clamped[[0, 2]] > 0)              # blocks of 8: several completed, some outside
+
+
+def test_clamp_counter_hand_case_boundaries_and_zero_scale_channels():
+    full = synth.tiny_workload(seed=67, Bt=1, Hq=2, Hkv=1, P=8, seq_lens=(24,), block_size=(8,), budget=(8,))
+    # blocks 0 and 1 fix the ranges: channel c spans [0, 1.5] (step 0.1), channel 5 is constant 0.25
+    k = np.zeros((24, 128), np.float32)
+    k[8:16] = 1.5
+    k[:16, 5] = 0.25
+    # block 2 (one key repeated, so its mean is the key): inside, on both ends, half a step beyond, far out
+    last = np.full(128, 0.75, np.float32)
+    last[0], last[1] = 0.0, 1.5                       # the ends: codes 0 and 15, held
+    last[2] = 1.5390625                               # (v - 0) / 0.1 = 15.39 -> 15, held
+    last[3] = 1.5625                                  # 15.625 -> 16: outside
+    last[4] = -0.0625                                 # -0.625 -> -1: outside
+    last[5] = 0.25                                    # constant channel, same value: held
+    last[6] = 100.0                                   # far outside
+    k[16:24] = last
+    for t in range(24):
+        full.k_cache[full.page_table[0, t // 8], 0, t % 8] = synth.f32_to_bits(k[t], full.dtype)
+    wl = _at(full, [16])
+    store = O.build_centroids(wl)
+    assert store.qscale[0, 5] == 0 and store.qmin[0, 5] == np.float32(0.25)
+    assert np.all(store.qmin[0, [0, 1, 2, 3, 4, 6]] == 0) and np.allclose(store.qscale[0, :5], 0.1)
+    tail = O.tail_state(wl)
+    clamped = np.array([7], np.int32)                 # the count is added to what is there
+    for L in range(17, 25):
+        store, _ = O.append_token(_at(full, [L]), store, tail, clamped)
+        assert clamped[0] == (7 if L < 24 else 7 + 3)
+    # the same block with the constant channel moved: one more value outside
+    k[16:24, 5] = 0.5
+    for t in range(16, 24):
+        full.k_cache[full.page_table[0, t // 8], 0, t % 8] = synth.f32_to_bits(k[t], full.dtype)
+    store = O.build_centroids(wl)
+    tail = O.tail_state(wl)
+    clamped = np.zeros(1, np.int32)
+    for L in range(17, 25):
+        store, _ = O.append_token(_at(full, [L]), store, tail, clamped)
+    assert clamped[0] == 4
