@@ -275,7 +275,11 @@ ABSB_API int absb_status_offset(const absb_layer* layer, const absb_batch* batch
  *   values that the frozen range does not hold is ADDED to clamped[s]: values whose unclamped code
  *   falls outside [0, 15], and values that differ from qmin where qscale is 0.  The caller zeroes
  *   the array after absb_build_centroids and rebuilds when the counts (at most R*d per completed
- *   block) exceed what it tolerates. */
+ *   block) exceed what it tolerates.  One request is re-ranged without touching the others by
+ *   absb_build_centroids on a batch of one: that request's length, capacity, page-table row and its
+ *   own prefix sums (those of the batch minus off[b*Hkv]), with codes + off[b*Hkv]*(R*d/2),
+ *   qscale + b*Hkv*R*d and qmin + b*Hkv*R*d as outputs, and a workspace of its own (the counters at
+ *   the start of a workspace belong to one batch shape). */
 ABSB_API int absb_tail_init(const absb_layer* layer, const absb_batch* batch, const void* k_cache, float* tail,
                             void* stream);
 ABSB_API int absb_append_token(const absb_layer* layer, const absb_batch* batch, const void* k_cache,

@@ -903,6 +903,72 @@ def test_lists_widen_with_the_context_when_the_budget_exceeds_it():
     assert len(widths) > 1
 
 
+def test_one_request_of_a_batch_is_re_ranged_in_place():
+    """Re-ranging one request without touching the others: a batch of one (that request's lengths,
+    page-table row and capacity) whose code, scale and offset pointers point into the batch's arrays
+    at the request's first segment.  Its rows and ranges become those of a fresh build at the new
+    length; every other request's stay bit for bit; the step on the mixed store matches the oracle."""
+    import torch
+    from paper_2605_12110_amd import absb
+    full = synth.tiny_workload(seed=74, dtype=synth.F16, Bt=3, Hq=8, Hkv=2, P=16, seq_lens=(400, 333, 900),
+                               block_size=(8, 32), budget=(64, 64, 128))
+    start = full.seq_lens - 60
+    view = _view_at(full, start)
+    dw = _dev(view, cap_lens=full.seq_lens)
+    dw.build(); dw.tail_init(); _sync()
+    store = O.build_centroids(view)
+    tail = O.tail_state(view)
+    for step in range(1, 61):                                # grow all three requests under frozen ranges
+        lens = start + step
+        view = _view_at(full, lens)
+        dw.wl = view
+        dw.set_lens(lens)
+        dw.append_token()
+        store, _ = O.append_token(view, store, tail)
+    _sync()
+    before_codes, before_scale, before_min = dw.codes.cpu().numpy(), dw.qscale.cpu().numpy(), dw.qmin.cpu().numpy()
+    assert np.array_equal(_tight(dw, lens), store.codes)
+
+    b, Hkv = 1, full.num_kv_heads
+    one_lens = full.seq_lens[b:b + 1].copy()
+    sub = absb.Batch(seq_lens_host=one_lens, budget_host=full.budget[b:b + 1].copy(), seq_lens=dw.seq_lens[b:b + 1],
+                     page_table=dw.page_table[b:b + 1], budget=dw.budget[b:b + 1], pt_stride=dw.page_table.shape[1])
+    sub.cap_lens_host = one_lens
+    sub_plan = absb.absb_plan(dw.layer, sub)
+    sub_off = sub_plan.cent_off
+    base = int(dw.plan.cent_off[b * Hkv])
+    assert np.array_equal(sub_off, dw.plan.cent_off[b * Hkv:(b + 1) * Hkv + 1] - base)   # same layout, shifted
+    sub.cent_off = torch.from_numpy(sub_off).to(dw.device)
+    # a workspace of its own: the counters at the start of a workspace belong to one batch shape
+    ws = torch.empty((sub_plan.workspace_bytes,), dtype=torch.uint8, device=dw.device)
+    absb.absb_build_centroids(dw.layer, sub, dw.k_cache, dw.codes[base:], dw.qscale[b * Hkv:], dw.qmin[b * Hkv:], ws)
+    _sync()
+    fresh = O.build_centroids(view)                          # every request rebuilt: request b must match this one
+    codes, scale, mn = dw.codes.cpu().numpy(), dw.qscale.cpu().numpy(), dw.qmin.cpu().numpy()
+    off = dw.plan.cent_off
+    for s in range(dw.nseg):
+        n = -(-int(lens[s // Hkv]) // int(dw.block_size[s % Hkv]))
+        rows = slice(int(off[s]), int(off[s]) + n)
+        if s // Hkv == b:
+            assert np.array_equal(codes[rows], fresh.codes[fresh.off[s]:fresh.off[s + 1]])
+            assert np.array_equal(scale[s], fresh.qscale[s]) and np.array_equal(mn[s], fresh.qmin[s])
+        else:
+            assert np.array_equal(codes[rows], before_codes[rows])
+            assert np.array_equal(scale[s], before_scale[s]) and np.array_equal(mn[s], before_min[s])
+    assert not np.array_equal(scale[b * Hkv], before_scale[b * Hkv])      # the ranges did move
+    # the step on the mixed store: the oracle's store with request b's segments replaced
+    import copy
+    mixed = copy.copy(store)
+    mixed.codes, mixed.qscale, mixed.qmin = store.codes.copy(), store.qscale.copy(), store.qmin.copy()
+    for s in range(b * Hkv, (b + 1) * Hkv):
+        mixed.codes[mixed.off[s]:mixed.off[s + 1]] = fresh.codes[fresh.off[s]:fresh.off[s + 1]]
+        mixed.qscale[s], mixed.qmin[s] = fresh.qscale[s], fresh.qmin[s]
+    ref = O.decode_step(view, mixed)
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "step after re-ranging one request")
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+
+
 def test_stages_ignore_the_unused_rows_of_a_layout_sized_for_longer_contexts():
     """A store laid out for longer contexts than the current ones: build, score, selection and the
     step give the same results as the tight layout (the unused rows hold garbage)."""
