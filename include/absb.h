@@ -33,10 +33,13 @@
  *   - Workspace: `absb_plan` reports the size that suffices for every entry point on that
  *     (layer, batch); 256-byte aligned.  Its first bytes hold the counters through which the
  *     work-groups of absb_decode_fused hand work to each other: they must be zero when that
- *     call starts.  absb_workspace_init clears them (once per workspace and (batch, KV head
- *     count); a workspace allocated zero-filled needs no call), and every entry point leaves
- *     them zero.  Nothing else in the workspace needs initialisation or survives a call.  Calls
- *     that share a workspace must be ordered on one stream.
+ *     call starts.  absb_workspace_init clears them (a workspace allocated zero-filled needs no
+ *     call), and every entry point leaves them zero.  Where they sit depends on the number of
+ *     selection segments of the batch, and the other stages' data lies right behind them: when a
+ *     workspace is reused for a batch with a different number of segments (requests joining or
+ *     leaving), call absb_workspace_init again (one small launch), or keep a workspace per batch
+ *     shape.  Nothing else in the workspace needs initialisation or survives a call.  Calls that
+ *     share a workspace must be ordered on one stream.
  *   - Limits: at most 65535 selection segments per batch (ABSB_ERR_BAD_SHAPE beyond); the selection
  *     (absb_topk, absb_decode_fused) holds at most 2^17 blocks per segment (ABSB_ERR_UNSUPPORTED
  *     beyond: 1 Mi tokens at B_h = 8, 16 Mi at B_h = 128); fewer than 2^31 blocks in all.
