@@ -718,6 +718,35 @@ def test_one_launch_steps_back_to_back_and_on_two_streams():
         assert dw.status() == 0 and absb.absb_status_offset(dw.layer, dw.batch) == dw.nsel * 3 * 256
 
 
+def test_one_workspace_serves_batches_of_different_shapes_when_cleared_in_between():
+    """Requests join and leave: the same workspace runs a batch of three, of one, of five; its counters
+    move with the number of segments, so absb_workspace_init runs whenever the shape changes."""
+    from paper_2605_12110_amd import absb
+    shapes = [((700, 65, 2049), (64, 2048, 100)), ((1500,), (256,)), ((9, 300, 4097, 64, 1023), (8, 64, 512, 4096, 100))]
+    cases = []
+    for i, (lens, budget) in enumerate(shapes):
+        wl = synth.tiny_workload(seed=90 + i, dtype=synth.F16, Bt=len(lens), Hq=8, Hkv=2, P=16, seq_lens=lens,
+                                 block_size=(8, 64), budget=budget)
+        st = O.build_centroids(wl)
+        cases.append((wl, O.decode_step(wl, st), _dev(wl)))
+    shared = max((c[2].workspace for c in cases), key=lambda t: t.numel())
+    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 1)
+    try:
+        for rnd in range(2):
+            for wl, ref, dw in cases:
+                dw.workspace = shared
+                dw.build()                                   # leaves its scratch data where the next shape's counters sit
+                dw.scribble(0xB7 + rnd)                      # = fill + absb_workspace_init for this shape
+                for rep in range(2):                         # and no clearing between steps of one shape
+                    dw.sel_idx.fill_(-7); dw.out.fill_(float("nan"))
+                    dw.decode_fused()
+                    _check_out(dw, ref["out"], ref["lse"], f"shared workspace, batch of {wl.batch}, round {rnd}, step {rep}")
+                    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+                    assert dw.status() == 0
+    finally:
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+
+
 def test_one_launch_step_gives_up_waiting_and_says_so_when_a_counter_was_not_cleared():
     """The attention work-groups of the one-launch step wait for their segment's list with a time
     limit.  Forced from the host: one estimation counter starts at a value from which the segment's
