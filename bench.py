@@ -184,12 +184,39 @@ def _time_oracle(fn, seconds, max_n=2000):
             return el / n, n, el
 
 
-def cpu_baseline(wl0, bytes0, seconds=10.0, block_repr=0):
+def verify_against_oracle(dw, ref):
+    """One more step of instance `dw`, checked against the oracle's step on the same inputs: the
+    number above is only worth reporting if the timed path computes the right thing."""
+    import torch
+    dw.sel_idx.fill_(-7)
+    dw.out.fill_(float("nan"))
+    dw.decode_fused()
+    torch.cuda.synchronize()
+    K = dw.sel_stride
+    sel_ok = bool(np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"]) and
+                  np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K]))
+    err = float(np.abs(dw.out_f32().astype(np.float64) - ref["out"]).max())
+    tol = 2e-3 if dw.wl.dtype == 0 else 1e-2
+    ok = sel_ok and err <= tol and dw.status() == 0
+    if not ok:
+        raise SystemExit(f"bench.py: the timed path disagrees with the oracle (selection bit-exact: {sel_ok}, "
+                         f"max |out - oracle| = {err:.3e}, tolerance {tol:.0e}, status word {dw.status()})")
+    return {"selection_bit_exact": sel_ok, "max_abs_err_out": float(f"{err:.3e}"), "tolerance": tol,
+            "what": "one fused step of instance 0 after the timed loop against the oracle's step"}
+
+
+def cpu_baseline(wl0, bytes0, seconds=10.0, block_repr=0, check=None, selection=0):
     from oracle import oracle as O
     t0 = time.perf_counter()
     st = O.build_centroids(wl0, block_repr)
     build_s = time.perf_counter() - t0
-    O.decode_step(wl0, st)                       # warm
+    ref = O.decode_step(wl0, st, group_max=selection == 2)        # warm
+    verified = None
+    if check is not None:
+        if selection == 1:     # every query head its own group: the oracle runs the method on that model
+            view = O.per_query_head_view(wl0)
+            ref = O.decode_step(view, O.build_centroids(view, block_repr))
+        verified = verify_against_oracle(check, ref)
     cpu_s, n, el = _time_oracle(lambda: O.decode_step(wl0, st), seconds)
     threads = O.num_threads()
     O.set_threads(1)
@@ -208,6 +235,7 @@ def cpu_baseline(wl0, bytes0, seconds=10.0, block_repr=0):
         "single_thread_us_per_step": round(one_s * 1e6, 1),
         "single_thread_sample": f"{n1} steps, {el1:.1f} s",
         "oracle_build_seconds_once": round(build_s, 3),
+        "verified": verified,
     }
 
 
@@ -538,7 +566,10 @@ def main():
             "frac_of_stream_read_ceiling": round(dec_gbps / ceiling, 4),
         }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl0, m["bytes0"], block_repr=block_repr)
+        cb = cpu_baseline(wl0, m["bytes0"], block_repr=block_repr, check=insts[0],
+                          selection={"group": 0, "per-query-head": 1, "group-max": 2}[args.select])
+        result["verified"] = cb.pop("verified")
+        result["cpu_baseline"] = cb
     print(json.dumps(result))
 
 
