@@ -524,6 +524,47 @@ def test_the_largest_number_of_segments():
     run_all_stages(wl, "65535 segments")
 
 
+def test_non_finite_values_in_one_request_do_not_disturb_the_others_or_stall_anything():
+    """Inputs are finite by contract; NaN and infinities must still not fault, hang or leak into other
+    requests.  Request 0 gets a NaN and an infinity in its queries, keys and values: every call
+    completes, no wait runs out, its lists are well formed (K_s ascending indices in range), and
+    request 1 comes out exactly as the oracle has it."""
+    from paper_2605_12110_amd import absb
+    wl = synth.tiny_workload(seed=95, dtype=synth.F16, Bt=2, Hq=8, Hkv=2, P=16, seq_lens=(700, 500),
+                             block_size=(8, 32), budget=(96, 128))
+    nan, inf, ninf = np.uint16(0x7E00), np.uint16(0x7C00), np.uint16(0xFC00)
+    wl.q[0, 1, 5] = nan
+    wl.q[0, 6, 7] = inf
+    pages0 = wl.page_table[0, :(700 + 15) // 16]
+    wl.k_cache[pages0[3], 0, 2, 9] = nan
+    wl.k_cache[pages0[5], 1, 1, 0] = inf
+    wl.k_cache[pages0[7], 1, 4, 3] = ninf
+    wl.v_cache[pages0[2], 0, 0, 1] = nan
+    ref = O.decode_step(wl, O.build_centroids(wl))          # request 1 of it is untouched by all this
+    dw = _dev(wl)
+    K = dw.sel_stride
+    for mode in (1, 3):
+        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, mode)
+        try:
+            dw.build()
+            dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(0); dw.lse.fill_(0)
+            dw.decode_fused(); _sync()
+        finally:
+            absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+        assert dw.status() == 0
+        cnt, sel = dw.sel_cnt.cpu().numpy(), dw.sel_idx.cpu().numpy()
+        assert np.array_equal(cnt, ref["sel_cnt"])                       # K_s does not depend on the data
+        for s in range(4):
+            b, h = divmod(s, 2)
+            n = -(-int(wl.seq_lens[b]) // int(wl.block_size[h]))
+            row = sel[s, :cnt[s]]
+            assert np.all(row >= 0) and np.all(row < n) and np.all(np.diff(row) > 0) and np.all(sel[s, cnt[s]:] == -1)
+        assert np.array_equal(sel[2:], ref["sel_idx"][2:, :K])           # request 1: bit-exact selection
+        got = dw.out_f32().astype(np.float64)
+        assert np.abs(got[1] - ref["out"][1]).max() <= TOL[wl.dtype]
+        assert np.abs(dw.lse.cpu().numpy()[1].astype(np.float64) - ref["lse"][1]).max() <= LSE_TOL
+
+
 # ------------------------------------------------------------------ randomised shapes
 @pytest.mark.parametrize("seed", list(range(24)))
 def test_random_shapes_modes_and_enqueue_forms(seed):
