@@ -524,6 +524,31 @@ def test_the_largest_number_of_segments():
     run_all_stages(wl, "65535 segments")
 
 
+@pytest.mark.parametrize("scale", [0.02, 0.25, 1.0])
+def test_caller_given_softmax_scale(scale):
+    """absb_layer.sm_scale other than 1/sqrt(d): flat and very peaked softmax, stand-alone and fused."""
+    import torch
+    wl = synth.tiny_workload(seed=96, dtype=synth.BF16, Bt=2, Hq=10, Hkv=2, P=16, seq_lens=(900, 130),
+                             block_size=(16, 64), budget=(256, 4096))
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)                               # the selection does not depend on the scale
+    want, want_lse = O.sparse_attention(wl, ref["sel_idx"], ref["sel_cnt"], sm_scale=scale)
+    dw = _dev(wl)
+    dw.layer.sm_scale = scale
+    K = dw.sel_stride
+    dw.sel_idx.copy_(torch.from_numpy(np.ascontiguousarray(ref["sel_idx"][:, :K])))
+    dw.sel_cnt.copy_(torch.from_numpy(ref["sel_cnt"]))
+    dw.sparse_decode()
+    _check_out(dw, want, want_lse, f"sm_scale = {scale}, stand-alone")
+    dw.build()
+    dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+    dw.decode_fused()
+    _check_out(dw, want, want_lse, f"sm_scale = {scale}, fused")
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
+    base = O.sparse_attention(wl, ref["sel_idx"], ref["sel_cnt"])[0]
+    assert np.abs(base - want).max() > 1e-2                   # the scale does change the answer here
+
+
 def test_non_finite_values_in_one_request_do_not_disturb_the_others_or_stall_anything():
     """Inputs are finite by contract; NaN and infinities must still not fault, hang or leak into other
     requests.  Request 0 gets a NaN and an infinity in its queries, keys and values: every call
