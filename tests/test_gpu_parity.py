@@ -524,6 +524,40 @@ def test_the_largest_number_of_segments():
     run_all_stages(wl, "65535 segments")
 
 
+def test_optional_outputs_may_be_left_out_and_lists_may_be_wider_than_needed():
+    """lse, score_exp and the copies of the selection are optional (NULL); a list buffer wider than
+    absb_plan's sel_stride is padded with -1 to its full width."""
+    import torch
+    from paper_2605_12110_amd import absb
+    wl = synth.tiny_workload(seed=97, dtype=synth.F16, Bt=3, Hq=8, Hkv=2, P=16, seq_lens=(333, 2100, 64),
+                             block_size=(8, 64), budget=(100, 512, 64))
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    dw = _dev(wl)
+    dw.build()
+    absb.absb_score(dw.layer, dw.batch, dw.q, dw.codes, dw.qscale, dw.scores, None)
+    wide = dw.sel_stride + 19
+    sel = torch.full((dw.nsel, wide), -7, dtype=torch.int32, device=dw.device)
+    cnt = torch.full((dw.nsel,), -7, dtype=torch.int32, device=dw.device)
+    absb.absb_topk(dw.layer, dw.batch, dw.scores, sel, cnt, wide)
+    _sync()
+    assert np.array_equal(dw.scores.cpu().numpy(), ref["scores"])
+    got = sel.cpu().numpy()
+    assert np.array_equal(cnt.cpu().numpy(), ref["sel_cnt"])
+    assert np.array_equal(got[:, :dw.sel_stride], ref["sel_idx"][:, :dw.sel_stride]) and np.all(got[:, dw.sel_stride:] == -1)
+    dw.out.fill_(float("nan"))
+    absb.absb_sparse_decode(dw.layer, dw.batch, dw.q, dw.k_cache, dw.v_cache, sel, cnt, wide, dw.out, None, dw.workspace)
+    _sync()
+    assert np.abs(dw.out_f32().astype(np.float64) - ref["out"]).max() <= TOL[wl.dtype]
+    dw.scribble(0x21)
+    dw.out.fill_(float("nan"))
+    absb.absb_decode_fused(dw.layer, dw.batch, dw.q, dw.codes, dw.qscale, dw.k_cache, dw.v_cache, dw.out, None, None, None,
+                           dw.workspace)
+    _sync()
+    assert np.abs(dw.out_f32().astype(np.float64) - ref["out"]).max() <= TOL[wl.dtype]
+    assert dw.status() == 0
+
+
 @pytest.mark.parametrize("scale", [0.02, 0.25, 1.0])
 def test_caller_given_softmax_scale(scale):
     """absb_layer.sm_scale other than 1/sqrt(d): flat and very peaked softmax, stand-alone and fused."""
