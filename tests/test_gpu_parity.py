@@ -513,6 +513,14 @@ def test_one_million_token_context(L, sizes, G, budget):
     run_all_stages(wl, f"context {L}, blocks {sizes}, budget {budget}")
 
 
+@pytest.mark.parametrize("P", [2048, 65536])
+def test_pages_much_larger_than_blocks(P):
+    """Up to the largest page the plan accepts (65536 tokens): hundreds of blocks per page."""
+    wl = synth.tiny_workload(seed=P, dtype=synth.BF16, Bt=2, Hq=6, Hkv=2, P=P, seq_lens=(P + 37, 700),
+                             block_size=(8, 128), budget=(200, 1000), extra_pages=1)
+    run_all_stages(wl, f"page size {P}")
+
+
 def test_the_largest_number_of_segments():
     """65535 selection segments (the limit of the plan), each a short context: every stage and the
     fused step in all its forms."""
