@@ -633,7 +633,7 @@ def test_non_finite_values_in_one_request_do_not_disturb_the_others_or_stall_any
 
 
 # ------------------------------------------------------------------ randomised shapes
-@pytest.mark.parametrize("seed", list(range(24)))
+@pytest.mark.parametrize("seed", list(range(64)))
 def test_random_shapes_modes_and_enqueue_forms(seed):
     """Seeded random small workloads over everything that shapes the path: batch, head counts and group
     size, page size, ragged lengths (down to one token), per-head block sizes on both sides of the page
@@ -656,7 +656,7 @@ def test_random_shapes_modes_and_enqueue_forms(seed):
                    per_query_head=mode == 2, group_max=mode == 3)
 
 
-@pytest.mark.parametrize("seed", list(range(24)))
+@pytest.mark.parametrize("seed", list(range(64)))
 def test_random_shapes_with_few_distinct_keys_and_forced_blocks(seed):
     """As above on caches that hold 1, 2 or 17 distinct keys (one per page and head): whole runs of
     blocks score the same, so the selection lives on its tie paths and the softmax weights take few
