@@ -98,7 +98,9 @@ typedef enum absb_status {
                                    the page size                                                */
   ABSB_ERR_UNSUPPORTED = -4,    /* head_dim != 128, group size > 8, more than 64 KV heads, dtype */
   ABSB_ERR_WORKSPACE = -5,      /* workspace NULL, misaligned or smaller than absb_plan reports  */
-  ABSB_ERR_HIP = -6             /* a HIP launch failed (see hipGetLastError)                     */
+  ABSB_ERR_HIP = -6,            /* a HIP launch failed (see hipGetLastError)                     */
+  ABSB_ERR_STATIC_WORKSPACE = -7 /* absb_decode_fused_static: the batch needs more scratch memory
+                                   than the library's built-in array (ABSB_STATIC_WORKSPACE_BYTES) */
 } absb_status;
 
 /* Static description of one attention layer.  Host memory. */
@@ -243,6 +245,27 @@ ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch,
                                const uint8_t* codes, const float* qscale, const void* k_cache,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
                                int32_t* sel_cnt_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): absb_decode_fused without a workspace argument.  The
+ * scratch memory (counters, scores, lists, split-K partials) is a fixed array of
+ * ABSB_STATIC_WORKSPACE_BYTES inside the library's code object: every GPU the library runs on holds
+ * its own copy from the first use until the process ends.  The call allocates and frees nothing and
+ * calls no runtime routine that does; inputs and outputs are still the caller's.  Same results as
+ * absb_decode_fused with a cleared workspace of the caller's.
+ *   - A (layer, batch) whose absb_plan workspace_bytes exceeds ABSB_STATIC_WORKSPACE_BYTES is refused
+ *     with ABSB_ERR_STATIC_WORKSPACE before anything is enqueued.
+ *   - The array keeps what the last call left; the call clears what must start at zero itself (a
+ *     small fill kernel on `stream` whenever the batch shape's counter area differs from the last
+ *     call's on that GPU), so no absb_workspace_init is needed.
+ *   - All calls on one GPU share that GPU's array: calls whose device work can overlap (different
+ *     streams, or threads that do not order their streams) race.  Order them on one stream.
+ *   - The device is the one current at the call (hipGetDevice); `stream` must belong to it. */
+#define ABSB_STATIC_WORKSPACE_BYTES (16u << 20)
+ABSB_API int absb_decode_fused_static(const absb_layer* layer, const absb_batch* batch, const void* q,
+                                      const uint8_t* codes, const float* qscale, const void* k_cache,
+                                      const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
+                                      int32_t* sel_cnt_out, void* stream);
 
 /* How absb_decode_fused will enqueue the step for this (layer, batch) under the current tuning:
  * 1 (one launch) or 3 (one launch per stage); a negative absb_status on invalid arguments.  Pure

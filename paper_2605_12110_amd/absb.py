@@ -22,10 +22,12 @@ SELECT_GROUP, SELECT_PER_QUERY_HEAD, SELECT_GROUP_MAX = 0, 1, 2
 TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO, TUNE_STEP_LAUNCHES = 0, 1, 2, 3
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+ERR_STATIC_WORKSPACE = -7
+STATIC_WORKSPACE_BYTES = 16 << 20
 
 EXPORTS = ("absb_plan", "absb_step_launches", "absb_status_offset", "absb_workspace_init", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
            "absb_decode_fused", "absb_tail_init", "absb_append_token", "absb_head_recall", "absb_assign_block_sizes", "absb_stream_read",
-           "absb_strerror", "absb_set_tuning")
+           "absb_strerror", "absb_set_tuning", "absb_decode_fused_static")
 
 
 class AbsbError(RuntimeError):
@@ -228,6 +230,15 @@ def absb_decode_fused(layer: Layer, batch: Batch, q, codes, qscale, k_cache, v_c
                                     _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(sel_idx_out), _ptr(sel_cnt_out),
                                     _ptr(workspace), C.c_size_t(_nbytes(workspace)), _stream(stream)),
            "absb_decode_fused")
+
+
+def absb_decode_fused_static(layer: Layer, batch: Batch, q, codes, qscale, k_cache, v_cache, out, lse=None,
+                             sel_idx_out=None, sel_cnt_out=None, stream=None) -> None:
+    """The step on the library's built-in scratch array: no workspace argument, nothing allocated."""
+    cl, cb = layer.c(), batch.c()
+    _check(load().absb_decode_fused_static(C.byref(cl), C.byref(cb), _ptr(q), _ptr(codes), _ptr(qscale),
+                                           _ptr(k_cache), _ptr(v_cache), _ptr(out), _ptr(lse), _ptr(sel_idx_out),
+                                           _ptr(sel_cnt_out), _stream(stream)), "absb_decode_fused_static")
 
 
 def absb_step_launches(layer: Layer, batch: Batch) -> int:

@@ -3,6 +3,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cmath>
+#include <mutex>
 
 #include "common.h"
 
@@ -427,6 +428,9 @@ const char* absb_strerror(int status) {
     case ABSB_ERR_UNSUPPORTED: return "unsupported configuration (head_dim, group size, head count or dtype)";
     case ABSB_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case ABSB_ERR_HIP: return "HIP launch failed";
+    case ABSB_ERR_STATIC_WORKSPACE:
+      return "the batch needs more scratch memory than the library's built-in array holds (ABSB_STATIC_WORKSPACE_BYTES); "
+             "use absb_decode_fused with a workspace of the caller's";
     default: return "unknown status";
   }
 }
@@ -442,6 +446,72 @@ int absb_set_tuning(int key, int value) {
   }
   g_tuning[key].store(value, std::memory_order_relaxed);
   return ABSB_OK;
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------ the step for callers that cannot allocate
+//
+// absb_decode_fused with the workspace taken from device memory that the library's code object
+// holds: a file-scope array, one copy per GPU, there from the moment the library is loaded on that
+// GPU until the process ends.  Nothing is allocated or freed by the call, by the library or by any
+// runtime routine it uses.
+namespace absb {
+
+static __device__ __align__(256) unsigned char scratch[ABSB_STATIC_WORKSPACE_BYTES];
+
+constexpr int kMaxDevices = 64;
+struct StaticWorkspace {
+  char* ptr = nullptr;        // this device's copy of `scratch` (a device address; the array's name is not one)
+  size_t head_bytes = 0;      // counters cleared for a batch shape whose counters take this many bytes
+};
+static StaticWorkspace g_static_ws[kMaxDevices];
+static std::mutex g_static_ws_lock;
+
+// Device address of the current device's scratch array, resolved once per device.
+static int static_workspace(int* dev_out, StaticWorkspace** slot) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ABSB_ERR_HIP;
+  StaticWorkspace& w = g_static_ws[dev];
+  if (!w.ptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ABSB_ERR_HIP;
+    w.ptr = static_cast<char*>(p);
+    w.head_bytes = 0;
+  }
+  *dev_out = dev;
+  *slot = &w;
+  return ABSB_OK;
+}
+
+}  // namespace absb
+
+extern "C" {
+
+int absb_decode_fused_static(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
+                             const float* qscale, const void* k_cache, const void* v_cache, void* out, float* lse,
+                             int32_t* sel_idx_out, int32_t* sel_cnt_out, void* stream) {
+  Geometry g;
+  Plan p;
+  int rc = make_plan(layer, batch, true, 0, &g, &p);
+  if (rc != ABSB_OK) return rc;
+  if (p.ws_fused_bytes > (size_t)ABSB_STATIC_WORKSPACE_BYTES) return ABSB_ERR_STATIC_WORKSPACE;
+  std::lock_guard<std::mutex> hold(g_static_ws_lock);
+  int dev = 0;
+  StaticWorkspace* w = nullptr;
+  rc = static_workspace(&dev, &w);
+  if (rc != ABSB_OK) return rc;
+  // The array keeps what the last call left.  The counters at its start are zero after every
+  // completed step, but where they sit follows the batch shape: a first call on this device, or a
+  // call whose counters take a different number of bytes than the last one's, clears them first
+  // (a small fill kernel on the caller's stream, ordered before the step).
+  if (w->head_bytes != p.ws_head_bytes) {
+    rc = launch_workspace_init(p, w->ptr, static_cast<hipStream_t>(stream));
+    if (rc != ABSB_OK) return rc;
+    w->head_bytes = p.ws_head_bytes;
+  }
+  return absb_decode_fused(layer, batch, q, codes, qscale, k_cache, v_cache, out, lse, sel_idx_out, sel_cnt_out, w->ptr,
+                           (size_t)ABSB_STATIC_WORKSPACE_BYTES, stream);
 }
 
 }  // extern "C"
