@@ -100,7 +100,7 @@ def per_step_percentiles(fn, n_steps):
 
 
 def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, uniform_block=None, max_bytes=24 << 30,
-                   block_repr=0, selection=0):
+                   block_repr=0, selection=0, opts=None):
     """R independent layer instances of a workload, resident on the GPU, centroid stores built."""
     import torch
     from paper_2605_12110_amd import synth
@@ -111,10 +111,10 @@ def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, u
     if R <= 0:
         R = max(1, min(8, -(-(2 << 30) // wl0.kv_bytes())))
     R = max(1, min(R, max_bytes // max(wl0.kv_bytes(), 1)))
-    insts = [DeviceWorkload(wl0, block_repr=block_repr, selection=selection)]
+    insts = [DeviceWorkload(wl0, block_repr=block_repr, selection=selection, opts=opts)]
     for r in range(1, R):
         wl = synth.make_workload(config, seed=BASE_SEED[config] + 100 * r, **kw)
-        insts.append(DeviceWorkload(wl, block_repr=block_repr, selection=selection))
+        insts.append(DeviceWorkload(wl, block_repr=block_repr, selection=selection, opts=opts))
         wl.k_cache = wl.v_cache = None      # free the host copies of the extra instances
     for dw in insts:
         dw.build()
@@ -139,16 +139,19 @@ def measure(wl0, insts, steps, warmup, stages=False, percentiles=False):
     ms, wall_ms = time_loop(step, warmup, steps)
     from paper_2605_12110_amd import absb
     out = dict(ms=ms, wall_ms=wall_ms, bytes=mean_bytes, bytes0=ub[0], R=R,
-               launches=absb.absb_step_launches(insts[0].layer, insts[0].batch))
+               form=absb.absb_step_form_used(insts[0].layer, insts[0].batch))
+    out["launches"] = 3 if out["form"] == absb.STEP_PER_STAGE else 1
     # dominant kernel on its own: attention over the fused step's selection (split-K partials and
     # their merge happen inside the one kernel)
     # (every instance has completed a fused step on its workspace, so its split counters are zero and
     # the stage is the attention kernel alone, as in the fused step)
-    absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 1)
+    for dw in insts:
+        dw.batch.opts.counters_zero = 1
     try:
         ms_dec, _ = time_loop(lambda i: insts[i % R].sparse_decode(), warmup, steps)
     finally:
-        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
+        for dw in insts:
+            dw.batch.opts.counters_zero = 0
     out["ms_decode"] = ms_dec
     st = {"sparse_decode_us": ms_dec * 1e3}
     if stages:
@@ -450,7 +453,7 @@ def main():
                          "(default) or by their maximum, or nobody (one selection per query head)")
     ap.add_argument("--repr", choices=("mean", "minmax"), default="mean",
                     help="block representation: mean pooling (headline) or channel-wise maxima and minima")
-    ap.add_argument("--launches", type=int, default=0, choices=(0, 1, 3),
+    ap.add_argument("--launches", type=int, default=0, choices=(0, 1, 2, 3),
                     help="how absb_decode_fused is enqueued: 0 = the library's choice by shape (default), "
                          "1 = the whole step in one launch, 3 = one launch per stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -473,7 +476,6 @@ def main():
         sys.exit(2)
     absb.load()
     torch.cuda.set_device(0)
-    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, args.launches)
 
     if args.copy_calibration > 0:
         src = torch.full((args.copy_calibration << 20,), 7, dtype=torch.uint8, device="cuda")
@@ -493,7 +495,8 @@ def main():
     block_repr = 1 if args.repr == "minmax" else 0
     wl0, insts = make_instances(args.config, context=args.context, batch=args.batch, budget=args.budget,
                                 rotate=args.rotate, block_repr=block_repr,
-                                selection={"group": 0, "per-query-head": 1, "group-max": 2}[args.select])
+                                selection={"group": 0, "per-query-head": 1, "group-max": 2}[args.select],
+                                opts=dict(step_form=args.launches))
     m = measure(wl0, insts, args.steps, args.warmup, stages=args.stages, percentiles=True)
     ms, mean_bytes, R = m["ms"], m["bytes"], m["R"]
     gbps = mean_bytes["total"] / (ms * 1e-3) / 1e9

@@ -126,6 +126,33 @@ typedef struct absb_layer {
   int32_t selection;         /* absb_select; 0 = one selection per KV head                      */
 } absb_layer;
 
+/* How a call is enqueued: launch shapes that never change what is computed (selections stay
+ * bit-identical, outputs stay within rounding).  All zero = the library's choices, which is what
+ * correct use needs; the fields exist for measurements and for callers that know their shapes.  They
+ * are read from the batch of the call they are passed with and from nowhere else: nothing
+ * process-wide, two callers cannot change each other's launches.  An invalid value makes the entry
+ * point return ABSB_ERR_BAD_SHAPE before anything is enqueued. */
+typedef enum absb_step_form {
+  ABSB_STEP_AUTO = 0,       /* by shape (see absb_decode_fused)                                    */
+  ABSB_STEP_PIPELINED = 1,  /* one launch: estimation work-groups, a segment's last one selects, then
+                               attention work-groups that start on the segment's flag              */
+  ABSB_STEP_UNITS = 2,      /* one launch: every work-group scores, selects and attends for its own
+                               stretch of a segment's blocks                                       */
+  ABSB_STEP_PER_STAGE = 3   /* one launch per stage: score, top-k, sparse decode                   */
+} absb_step_form;
+typedef struct absb_launch_opts {
+  int32_t step_form;     /* absb_step_form; read by absb_decode_fused(_static), absb_step_form_used */
+  int32_t split_tokens;  /* tokens per split-K work-group of the attention kernel; multiple of 64    */
+  int32_t score_chunk;   /* blocks per estimation work-group; multiple of 64                        */
+  int32_t unit_tokens;   /* ABSB_STEP_UNITS: selected tokens a work-group should get; multiple of 64 */
+  int32_t counters_zero; /* absb_sparse_decode only: 1 = the split counters at the start of the
+                            workspace are known to be zero, the kernel that clears them is skipped.
+                            That holds after any completed absb_sparse_decode / absb_decode_fused call
+                            for the same number of segments on that workspace (the counters sit at its
+                            start, no other stage writes there, every kernel leaves the ones it used
+                            at zero).  0 = clear them (default).                                    */
+} absb_launch_opts;
+
 /* One decode step's batch. */
 typedef struct absb_batch {
   int32_t batch;                /* Bt >= 1                                                      */
@@ -145,6 +172,7 @@ typedef struct absb_batch {
   const float* qmin;            /* device [Bt*Hkv][d] or NULL: the store's zero-point offsets as
                                    written by absb_build_centroids; read by absb_score and
                                    absb_decode_fused only with ABSB_SELECT_GROUP_MAX            */
+  absb_launch_opts opts;        /* all zero = the library's choices                             */
 } absb_batch;
 
 /* Sizes derived on the host from a (layer, batch) pair.  Only the host fields of `batch`
@@ -227,20 +255,37 @@ ABSB_API int absb_sparse_decode(const absb_layer* layer, const absb_batch* batch
 ABSB_API int absb_workspace_init(const absb_layer* layer, const absb_batch* batch, void* workspace,
                                  size_t workspace_bytes, void* stream);
 
-/* The whole step: score -> topk -> sparse decode (Sec. 3.4, kernels 1-3) in ONE launch: the grid
- * holds the estimation work-groups, then the attention work-groups; a segment's last estimation
- * work-group runs its selection and raises a flag, and the segment's attention work-groups start
- * on that flag.  Produces exactly the selection of absb_score + absb_topk and the output of
- * absb_sparse_decode on it.  The counters at the start of the workspace must be zero
- * (absb_workspace_init) and are zero again afterwards.
+/* The whole step: score -> topk -> sparse decode (Sec. 3.4, kernels 1-3) through one call, with the
+ * fewest launches that are fastest for the shape.  Produces exactly the selection of absb_score +
+ * absb_topk, and the output of absb_sparse_decode on it up to the rounding of a different summation
+ * order (same tolerance against exact arithmetic).  Three ways to enqueue it (batch->opts.step_form;
+ * ABSB_STEP_AUTO picks by shape):
+ *   ABSB_STEP_PIPELINED  one launch.  The grid holds the estimation work-groups, then the attention
+ *                        work-groups; a segment's last estimation work-group runs its selection and
+ *                        raises a flag, the segment's attention work-groups start on that flag.
+ *                        Chosen while no segment exceeds 8192 blocks (16384 in batches of 16 or more
+ *                        selection segments) and no list 4096 blocks.
+ *   ABSB_STEP_UNITS      one launch.  Every segment is cut into units of consecutive blocks; a unit's
+ *                        work-group scores its blocks, publishes a histogram row of its scores,
+ *                        derives the segment's threshold from all rows, and attends over its own
+ *                        selected blocks; blocks inside the threshold bin are settled by an exact
+ *                        ranking among the segment's candidates.  No work-group ever passes over a
+ *                        whole segment, so the cost hardly grows with the context.  Chosen for
+ *                        segments beyond 16384 blocks when the chip holds all units at once.
+ *   ABSB_STEP_PER_STAGE  three launches (score, top-k, sparse decode).  Otherwise.
+ * The one-launch forms hand work between work-groups through the counters at the start of the
+ * workspace: they must be zero when the call starts (absb_workspace_init) and are zero again when its
+ * work has finished.  ABSB_STEP_PER_STAGE does not need them cleared.
  *   sel_idx_out [Bt*Hkv][plan's sel_stride], sel_cnt_out [Bt*Hkv]: optional copies of the
- *   selection (NULL ok: kept in the workspace).
- * For batches with very long segments (more than 8192 blocks, or more than 16384 when the batch
- * has 16 or more selection segments) or very long lists (more than 4096 blocks per segment) the
- * three stages are enqueued as three launches instead: there the selection of the longest segment
- * is the critical path, and the stand-alone selection kernel, with four times the threads per
- * segment, is worth the two extra launches.  ABSB_TUNE_STEP_LAUNCHES (see absb_set_tuning) forces
- * either form.  The three-launch form does not need the counters cleared. */
+ *   selection (NULL ok).
+ * Status word (one-launch forms): every wait of a work-group for another is bounded in time (0.25 s).
+ * A wait that runs out can only mean that the contract was broken (counters not zero at the start,
+ * device lengths or budgets that differ from their host twins) or that the device was taken away
+ * from the launch for that long; the work-group then sets the int32 at absb_status_offset() to 1,
+ * writes NaN into its segment's rows of `out` (and `lse`) and leaves, so the launch always ends.  The
+ * call itself has long returned ABSB_OK by then: a caller that cannot rule those causes out reads
+ * the status word after synchronising with the stream (or looks for NaN in `out`), and when it is
+ * set calls absb_workspace_init before the workspace is used again and repeats the step. */
 ABSB_API int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const void* q,
                                const uint8_t* codes, const float* qscale, const void* k_cache,
                                const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
@@ -267,16 +312,16 @@ ABSB_API int absb_decode_fused_static(const absb_layer* layer, const absb_batch*
                                       const void* v_cache, void* out, float* lse, int32_t* sel_idx_out,
                                       int32_t* sel_cnt_out, void* stream);
 
-/* How absb_decode_fused will enqueue the step for this (layer, batch) under the current tuning:
- * 1 (one launch) or 3 (one launch per stage); a negative absb_status on invalid arguments.  Pure
- * host helper; reads the host fields only. */
-ABSB_API int absb_step_launches(const absb_layer* layer, const absb_batch* batch);
+/* How absb_decode_fused will enqueue the step for this (layer, batch, batch->opts): the absb_step_form
+ * it will use (ABSB_STEP_PIPELINED, ABSB_STEP_UNITS: one launch; ABSB_STEP_PER_STAGE: three), never
+ * ABSB_STEP_AUTO; a negative absb_status on invalid arguments.  A form asked for in batch->opts that
+ * cannot hold the shape falls back to ABSB_STEP_PER_STAGE.  Pure host helper; reads the host fields
+ * only. */
+ABSB_API int absb_step_form_used(const absb_layer* layer, const absb_batch* batch);
 
-/* Where the one-launch step reports trouble: byte offset, inside the workspace, of an int32 status
- * word that absb_workspace_init clears and that stays zero in normal operation.  An attention
- * work-group that waited 0.25 s for its segment's list without seeing it (the counters were not
- * cleared, or the device lengths and budgets differ from their host twins) sets it to 1 and leaves;
- * the outputs of that step are then incomplete.  Pure host helper. */
+/* Where the one-launch forms report a wait that ran out (see absb_decode_fused): byte offset, inside
+ * the workspace, of an int32 status word that absb_workspace_init clears and that stays zero in
+ * normal operation.  Pure host helper. */
 ABSB_API int absb_status_offset(const absb_layer* layer, const absb_batch* batch, size_t* offset);
 
 /* Keeping the store current while decoding, without a rebuild (the paper notes that recomputing
@@ -338,28 +383,6 @@ ABSB_API int absb_stream_read(const void* src, size_t bytes, void* sink, void* s
 
 /* Static string for a status code. */
 ABSB_API const char* absb_strerror(int status);
-
-/* Launch-shape knobs for benchmarking sweeps (process-wide; not needed for correct use).
- *   ABSB_TUNE_SPLIT_TOKENS : tokens per split-K work-group in decode (multiple of 64; 0 = auto)
- *   ABSB_TUNE_SCORE_CHUNK  : centroids per work-group in score (multiple of 64; 0 = auto)
- *   ABSB_TUNE_COUNTERS_ZERO: 1 = absb_sparse_decode may assume that the split counters in the
- *                            workspace are zero and skips the kernel that clears them; 0 (default)
- *                            = it clears them.  The assumption holds after any completed
- *                            absb_sparse_decode / absb_decode_fused call for the same batch size
- *                            and KV head count on that workspace: the counters sit at its start,
- *                            no other stage writes there, and the attention kernel leaves every
- *                            counter it used at zero.  absb_decode_fused never needs the knob.
- *   ABSB_TUNE_STEP_LAUNCHES: how absb_decode_fused is enqueued: 0 = by shape (default; see
- *                            absb_decode_fused), 1 = one launch, 3 = one launch per stage.
- * Returns ABSB_ERR_BAD_SHAPE for an unknown key or an invalid value. */
-enum {
-  ABSB_TUNE_SPLIT_TOKENS = 0,
-  ABSB_TUNE_SCORE_CHUNK = 1,
-  ABSB_TUNE_COUNTERS_ZERO = 2,
-  ABSB_TUNE_STEP_LAUNCHES = 3,
-  ABSB_TUNE_COUNT_ = 4
-};
-ABSB_API int absb_set_tuning(int key, int value);
 
 #ifdef __cplusplus
 }

@@ -19,15 +19,15 @@ LIB_PATH = os.path.join(_HERE, "libabsb.so")
 F16, BF16 = 0, 1
 REPR_MEAN, REPR_MINMAX = 0, 1
 SELECT_GROUP, SELECT_PER_QUERY_HEAD, SELECT_GROUP_MAX = 0, 1, 2
-TUNE_SPLIT_TOKENS, TUNE_SCORE_CHUNK, TUNE_COUNTERS_ZERO, TUNE_STEP_LAUNCHES = 0, 1, 2, 3
+STEP_AUTO, STEP_PIPELINED, STEP_UNITS, STEP_PER_STAGE = 0, 1, 2, 3
 
 OK, ERR_NULL, ERR_BAD_SHAPE, ERR_BAD_BLOCK_SIZE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
 ERR_STATIC_WORKSPACE = -7
 STATIC_WORKSPACE_BYTES = 16 << 20
 
-EXPORTS = ("absb_plan", "absb_step_launches", "absb_status_offset", "absb_workspace_init", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
+EXPORTS = ("absb_plan", "absb_step_form_used", "absb_status_offset", "absb_workspace_init", "absb_build_centroids", "absb_score", "absb_topk", "absb_sparse_decode",
            "absb_decode_fused", "absb_tail_init", "absb_append_token", "absb_head_recall", "absb_assign_block_sizes", "absb_stream_read",
-           "absb_strerror", "absb_set_tuning", "absb_decode_fused_static")
+           "absb_strerror", "absb_decode_fused_static")
 
 
 class AbsbError(RuntimeError):
@@ -45,12 +45,17 @@ class _Layer(C.Structure):
                 ("selection", C.c_int32)]
 
 
+class _Opts(C.Structure):
+    _fields_ = [("step_form", C.c_int32), ("split_tokens", C.c_int32), ("score_chunk", C.c_int32),
+                ("unit_tokens", C.c_int32), ("counters_zero", C.c_int32)]
+
+
 class _Batch(C.Structure):
     _fields_ = [("batch", C.c_int32), ("pt_stride", C.c_int32),
                 ("seq_lens_host", C.POINTER(C.c_int32)), ("seq_lens", C.c_void_p),
                 ("page_table", C.c_void_p), ("cent_off", C.c_void_p),
                 ("budget_host", C.POINTER(C.c_int32)), ("budget", C.c_void_p),
-                ("cap_lens_host", C.POINTER(C.c_int32)), ("qmin", C.c_void_p)]
+                ("cap_lens_host", C.POINTER(C.c_int32)), ("qmin", C.c_void_p), ("opts", _Opts)]
 
 
 _lib = None
@@ -74,10 +79,6 @@ def load() -> C.CDLL:
 
 def strerror(status: int) -> str:
     return load().absb_strerror(int(status)).decode()
-
-
-def set_tuning(key: int, value: int) -> None:
-    _check(load().absb_set_tuning(C.c_int(key), C.c_int(value)), "absb_set_tuning")
 
 
 def _check(status: int, where: str) -> None:
@@ -143,6 +144,16 @@ class Layer:
 
 
 @dataclass
+class LaunchOpts:
+    """How a call is enqueued (mirrors absb_launch_opts): all zero = the library's choices."""
+    step_form: int = STEP_AUTO
+    split_tokens: int = 0
+    score_chunk: int = 0
+    unit_tokens: int = 0
+    counters_zero: int = 0
+
+
+@dataclass
 class Batch:
     """One decode step's batch (mirrors absb_batch).  Host arrays are numpy/sequences, device
     arrays are int32 torch tensors on the GPU (or None where an entry point does not need them)."""
@@ -155,6 +166,11 @@ class Batch:
     pt_stride: Optional[int] = None
     cap_lens_host: Optional[Sequence[int]] = None
     qmin: object = None
+    opts: LaunchOpts = None
+
+    def __post_init__(self):
+        if self.opts is None:
+            self.opts = LaunchOpts()
 
     def __setattr__(self, name, value):
         object.__setattr__(self, name, value)
@@ -171,7 +187,10 @@ class Batch:
                 pts = int(self.page_table.shape[1]) if self.page_table is not None else 0
             self._cl, cl_p = _i32_host(self.cap_lens_host)
             self._c = _Batch(len(self._sl), int(pts), sl_p, _ptr(self.seq_lens), _ptr(self.page_table),
-                             _ptr(self.cent_off), bg_p, _ptr(self.budget), cl_p, _ptr(self.qmin))
+                             _ptr(self.cent_off), bg_p, _ptr(self.budget), cl_p, _ptr(self.qmin), _Opts())
+        o = self.opts                   # the options object may have been changed in place: copied every time
+        self._c.opts = _Opts(int(o.step_form), int(o.split_tokens), int(o.score_chunk), int(o.unit_tokens),
+                             int(o.counters_zero))
         return self._c
 
 
@@ -241,11 +260,12 @@ def absb_decode_fused_static(layer: Layer, batch: Batch, q, codes, qscale, k_cac
                                            _ptr(sel_cnt_out), _stream(stream)), "absb_decode_fused_static")
 
 
-def absb_step_launches(layer: Layer, batch: Batch) -> int:
+def absb_step_form_used(layer: Layer, batch: Batch) -> int:
+    """The absb_step_form absb_decode_fused will use for this (layer, batch, batch.opts): 1, 2 or 3."""
     cl, cb = layer.c(), batch.c()
-    n = load().absb_step_launches(C.byref(cl), C.byref(cb))
+    n = load().absb_step_form_used(C.byref(cl), C.byref(cb))
     if n < 0:
-        raise AbsbError(n, "absb_step_launches")
+        raise AbsbError(n, "absb_step_form_used")
     return int(n)
 
 

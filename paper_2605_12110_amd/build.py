@@ -25,6 +25,7 @@ _SOURCES = {
     "topk.hip": [],
     "decode.hip": ["-ffp-contract=off"],   # FMAs are written explicitly there
     "fused.hip": ["-ffp-contract=off"],    # holds the estimation stage too
+    "step.hip": ["-ffp-contract=off"],     # likewise
     "util.hip": [],
 }
 
@@ -48,7 +49,7 @@ def _compile(name: str, extra) -> str:
     return obj
 
 
-def build_library(force: bool = True, jobs: int = 5) -> str:
+def build_library(force: bool = True, jobs: int = 8) -> str:
     """Compile every HIP source and link libabsb.so.  `force=False` skips when up to date."""
     srcs = [os.path.join(_CSRC, n) for n in os.listdir(_CSRC)] + [os.path.join(_INCLUDE, "absb.h")]
     if not force and os.path.exists(LIB_PATH) and all(os.path.getmtime(LIB_PATH) >= os.path.getmtime(s) for s in srcs):

@@ -1,17 +1,12 @@
 // Host side of libabsb.so: argument validation, size planning, workspace carving and the
 // extern "C" entry points.  Nothing here touches the device except through the launchers.
 #include <algorithm>
-#include <atomic>
 #include <cmath>
 #include <mutex>
 
 #include "common.h"
 
 namespace absb {
-
-static std::atomic<int> g_tuning[ABSB_TUNE_COUNT_] = {};
-
-int tuning(int key) { return g_tuning[key].load(std::memory_order_relaxed); }
 
 static inline bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 static inline int ilog2(int64_t v) {
@@ -74,6 +69,20 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   }
 
   Plan p = {};
+  // selected tokens a unit of the one-launch step should get: two attention steps at batch 1; large
+  // batches, whose work-groups queue for the compute units anyway, do better with longer units
+  int64_t budget_tokens = 0;
+  if (batch->budget_host)
+    for (int b = 0; b < Bt; ++b) budget_tokens += (int64_t)std::min(batch->budget_host[b], batch->seq_lens_host[b]) * Hsel;
+  const absb_launch_opts& opts = batch->opts;
+  if (opts.step_form < ABSB_STEP_AUTO || opts.step_form > ABSB_STEP_PER_STAGE) return ABSB_ERR_BAD_SHAPE;
+  if (opts.split_tokens < 0 || opts.split_tokens % 64 || opts.score_chunk < 0 || opts.score_chunk % 64 ||
+      opts.unit_tokens < 0 || opts.unit_tokens % 64 || opts.counters_zero < 0 || opts.counters_zero > 1)
+    return ABSB_ERR_BAD_SHAPE;
+  int unit_tokens = opts.unit_tokens;
+  if (unit_tokens <= 0) unit_tokens = budget_tokens >= 131072 ? 256 : 128;
+  p.unit_tokens = unit_tokens;
+  p.units_max = 1;
   p.nseg = Bt * Hsel;
   p.nstore = Bt * Hkv;
   p.build_chunk_tokens = 1024;
@@ -100,6 +109,11 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
       if (ceil_div(N, cb) > p.build_max_chunks) p.build_max_chunks = (int32_t)ceil_div(N, cb);
       if (N > p.max_blocks) p.max_blocks = (int32_t)N;
       const int64_t tok = K * B;
+      {
+        int su = 1, sb = 32;
+        step_units((int)K, g.heads.log2_block[h], (int)N, unit_tokens, &su, &sb);
+        if (su > p.units_max) p.units_max = su;
+      }
       if (tok > p.max_tokens) p.max_tokens = tok;
       p.sum_tokens += tok * g.Rk;  // every selection segment of the KV head reads its own tokens
     }
@@ -118,9 +132,16 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   // 16384 blocks), is the critical path and the 1024-thread selection kernel of the per-stage
   // path is worth its two extra launches.  Very long lists (budgets near the context) also go to
   // the per-stage path: its attention kernel reads the lists through the L2.
-  const int mode = tuning(ABSB_TUNE_STEP_LAUNCHES);
   const bool by_shape = (p.max_blocks <= 8192 || (p.max_blocks <= 16384 && p.nseg >= 16)) && p.sel_stride <= 4096;
-  p.one_launch = mode == 1 || (mode == 0 && by_shape);
+  // Segments beyond 16384 blocks: there the selection by one work-group costs more than everything
+  // else together (measured at 256K / 512K context: 33.5 / 48.0 us per stage against 29.4 / 33.8 us),
+  // and the step runs as units that select among themselves, as long as the chip holds all of a
+  // batch's units at once (two work-groups per compute unit).
+  const bool by_units = !by_shape && p.max_blocks > 16384 && (int64_t)p.nseg * (p.units_max + 1) <= 480;
+  p.step_form = opts.step_form != ABSB_STEP_AUTO ? opts.step_form
+                : by_shape ? ABSB_STEP_PIPELINED : by_units ? ABSB_STEP_UNITS : ABSB_STEP_PER_STAGE;
+  p.one_launch = p.step_form != ABSB_STEP_PER_STAGE;
+  p.bitmap_words = (p.max_blocks + 31) / 32;
   // split-K shape, in 64-token granules (one work-group step).  Measured on MI355X (256 CUs, three
   // resident work-groups each): the kernel is fastest with about two work-groups per CU, all
   // resident at once and each streaming as long as possible; a work-group needs at least two steps
@@ -128,7 +149,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   // not be cut into more than 64.
   // (the shape follows the batch, not the enqueue knob: every form of the step then cuts the
   // segments alike and gives the same bits)
-  int st_tok = tuning(ABSB_TUNE_SPLIT_TOKENS);
+  int st_tok = opts.split_tokens;
   if (st_tok <= 0) {
     const int64_t target_wgs = 640;
     int64_t t = ceil_div(ceil_div(p.sum_tokens, target_wgs), 64) * 64;
@@ -151,7 +172,7 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   // blocks per estimation work-group: 256 (one batch of loads per lane); in the one-launch step,
   // where estimation work-groups share the CUs with attention work-groups, a large batch does
   // better with two batches per work-group (the prologue is amortised, half as many work-groups)
-  int sc = tuning(ABSB_TUNE_SCORE_CHUNK);
+  int sc = opts.score_chunk;
   p.score_chunk = sc > 0 ? sc : (p.one_launch && p.total >= 65536 ? 512 : 256);
 
   // workspace: the split counters of the attention kernel come first, at the same place in every
@@ -162,7 +183,10 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   p.ws_score_tickets = ctr;
   p.ws_flags = 2 * ctr;
   p.ws_status = 3 * ctr;
-  const size_t head = 3 * ctr + 256;
+  p.ws_cand_done = 3 * ctr + 256;
+  p.ws_listed = 4 * ctr + 256;
+  p.ws_cutoff = 5 * ctr + 256;
+  const size_t head = 6 * ctr + 256;
   p.ws_head_bytes = head;
   size_t o = head;
   p.ws_scores = o;
@@ -176,8 +200,19 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   o += align256((size_t)p.nseg * p.max_splits * g.Gd * ABSB_HEAD_DIM * 4);
   p.ws_part_ml = o;
   o += align256((size_t)p.nseg * p.max_splits * g.Gd * 4 * 4);  // (max, rounded sum, exact sum, -) per split and head
-  p.ws_fused_bytes = o;
   p.ws_decode_bytes = o;  // the stand-alone decode uses the same offsets (the head is left unused)
+  // the unit form of the one-launch step: histogram rows, candidates, bitmaps, one partial per unit
+  p.ws_rows = o;
+  o += align256((size_t)p.nseg * p.units_max * 256 * 2);
+  p.ws_cand = o;
+  o += align256((size_t)p.total * g.Rk * 8);
+  p.ws_bitmap = o;
+  o += align256((size_t)p.nseg * p.bitmap_words * 4);
+  p.ws_unit_o = o;
+  o += align256((size_t)p.nseg * p.units_max * g.Gd * ABSB_HEAD_DIM * 4);
+  p.ws_unit_ml = o;
+  o += align256((size_t)p.nseg * p.units_max * g.Gd * 4 * 4);
+  p.ws_fused_bytes = o;
   (void)fused_head;
   size_t bo = head;
   p.ws_cent = bo;
@@ -289,7 +324,7 @@ int absb_sparse_decode(const absb_layer* layer, const absb_batch* batch, const v
   if (rc != ABSB_OK) return rc;
   return launch_decode(g, p, layer->dtype, resolve_scale(layer), q, k_cache, v_cache, batch->page_table,
                        batch->seq_lens, sel_idx, sel_cnt, sel_stride, out, lse, static_cast<char*>(workspace),
-                       tuning(ABSB_TUNE_COUNTERS_ZERO) == 1, static_cast<hipStream_t>(stream));
+                       batch->opts.counters_zero == 1, static_cast<hipStream_t>(stream));
 }
 
 int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const void* q, const uint8_t* codes,
@@ -311,7 +346,11 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
   int32_t* scores = reinterpret_cast<int32_t*>(ws + p.ws_scores);
   int32_t* sel_idx = sel_idx_out ? sel_idx_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_idx);
   int32_t* sel_cnt = sel_cnt_out ? sel_cnt_out : reinterpret_cast<int32_t*>(ws + p.ws_sel_cnt);
-  if (p.one_launch && fused_one_launch_fits(p))
+  if (p.step_form == ABSB_STEP_UNITS && step_fits(p))
+    return launch_step(g, p, layer->dtype, resolve_scale(layer), q, codes, qscale, batch->qmin, k_cache, v_cache,
+                       batch->page_table, batch->seq_lens, batch->cent_off, batch->budget, sel_idx, sel_cnt,
+                       sel_idx_out != nullptr, out, lse, ws, st);
+  if (p.step_form == ABSB_STEP_PIPELINED && fused_one_launch_fits(p))
     return launch_fused(g, p, layer->dtype, resolve_scale(layer), q, codes, qscale, batch->qmin, k_cache, v_cache, batch->page_table,
                         batch->seq_lens, batch->cent_off, batch->budget, sel_idx, sel_cnt, out, lse, ws, st);
   rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->qmin, batch->cent_off, batch->seq_lens, scores, nullptr, st);
@@ -324,12 +363,14 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
                        batch->seq_lens, sel_idx, sel_cnt, p.sel_stride, out, lse, ws, true, st);
 }
 
-int absb_step_launches(const absb_layer* layer, const absb_batch* batch) {
+int absb_step_form_used(const absb_layer* layer, const absb_batch* batch) {
   Geometry g;
   Plan p;
   int rc = make_plan(layer, batch, true, 0, &g, &p);
   if (rc != ABSB_OK) return rc;
-  return p.one_launch && fused_one_launch_fits(p) ? 1 : 3;
+  if (p.step_form == ABSB_STEP_UNITS && step_fits(p)) return ABSB_STEP_UNITS;
+  if (p.step_form == ABSB_STEP_PIPELINED && fused_one_launch_fits(p)) return ABSB_STEP_PIPELINED;
+  return ABSB_STEP_PER_STAGE;
 }
 
 int absb_status_offset(const absb_layer* layer, const absb_batch* batch, size_t* offset) {
@@ -433,19 +474,6 @@ const char* absb_strerror(int status) {
              "use absb_decode_fused with a workspace of the caller's";
     default: return "unknown status";
   }
-}
-
-int absb_set_tuning(int key, int value) {
-  if (key < 0 || key >= ABSB_TUNE_COUNT_ || value < 0) return ABSB_ERR_BAD_SHAPE;
-  if (key == ABSB_TUNE_COUNTERS_ZERO) {
-    if (value > 1) return ABSB_ERR_BAD_SHAPE;
-  } else if (key == ABSB_TUNE_STEP_LAUNCHES) {
-    if (value != 0 && value != 1 && value != 3) return ABSB_ERR_BAD_SHAPE;
-  } else if (value % 64 != 0) {
-    return ABSB_ERR_BAD_SHAPE;
-  }
-  g_tuning[key].store(value, std::memory_order_relaxed);
-  return ABSB_OK;
 }
 
 }  // extern "C"

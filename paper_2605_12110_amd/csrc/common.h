@@ -14,6 +14,7 @@
 // Split counters sit 256 bytes apart: counters that share a memory line serialise each other's
 // atomic updates (measured: 8 segments x 32 arrivals on one line cost 2.7 us, apart 0.x us).
 #define ABSB_TICKET_STRIDE 64
+#define ABSB_STEP_MAX_UNITS 64   // work-groups that share a segment in the one-launch step
 
 namespace absb {
 
@@ -51,12 +52,18 @@ struct Plan {
   int32_t split_tokens;     // tokens per split-K work-group
   int32_t max_splits;       // grid.x of the decode kernels
   int32_t one_launch;       // absb_decode_fused: the whole step as one launch (else one launch per stage)
+  int32_t step_form;        // absb_step_form actually used (never ABSB_STEP_AUTO)
+  int32_t unit_tokens;      // one-launch step: selected tokens a unit should get
+  int32_t units_max;        // max_s units of a segment
+  int32_t bitmap_words;     // words of a segment's selection bitmap
   int32_t score_chunk;      // centroids per work-group in score
   int32_t build_chunk_tokens;  // tokens per work-group in build (a head's chunk: max(16, that / B_h) blocks)
   int32_t build_max_chunks;    // max_s ceil(N_s / chunk_h)
   // workspace carving (byte offsets, 256-aligned)
   size_t ws_part_o, ws_part_ml, ws_tickets;       // decode partials, per-segment split counters
   size_t ws_score_tickets, ws_flags, ws_status;   // more counters of the one-launch step
+  size_t ws_cand_done, ws_listed, ws_cutoff;      // ... and of its unit form
+  size_t ws_rows, ws_cand, ws_bitmap, ws_unit_o, ws_unit_ml;
   size_t ws_head_bytes;                           // all counters: the part absb_workspace_init clears
   size_t ws_scores, ws_sel_idx, ws_sel_cnt;       // fused step intermediates
   size_t ws_cent, ws_minmax, ws_qinv;             // build intermediates
@@ -68,7 +75,6 @@ struct Plan {
 // the selected-token estimate for the stand-alone decode.
 ABSB_HIDDEN int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget,
                           int32_t sel_stride_in, Geometry* geo, Plan* plan);
-ABSB_HIDDEN int tuning(int key);
 
 // Launchers (one per stage); all enqueue on `stream` and return an absb_status.
 ABSB_HIDDEN int launch_build(const Geometry& g, const Plan& pl, int dtype, const void* k_cache,
@@ -100,6 +106,30 @@ ABSB_HIDDEN int launch_fused(const Geometry& g, const Plan& pl, int dtype, float
                              const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, void* out, float* lse,
                              char* ws, hipStream_t stream);
 ABSB_HIDDEN int launch_workspace_init(const Plan& pl, char* ws, hipStream_t stream);
+// The whole step in one launch, units of a segment doing score, selection and attention for their own blocks.
+ABSB_HIDDEN bool step_fits(const Plan& pl);
+ABSB_HIDDEN int launch_step(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
+                            const uint8_t* codes, const float* qscale, const float* qmin, const void* k_cache,
+                            const void* v_cache, const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
+                            const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, bool want_list, void* out, float* lse,
+                            char* ws, hipStream_t stream);
+
+// How a segment of N blocks in use, K of them to be selected, is cut into units of the one-launch step:
+// enough units that each gets about `unit_tokens` selected tokens and scores at most 512 blocks, at
+// most ABSB_STEP_MAX_UNITS; a unit's blocks start at a multiple of 32.  Host and device agree on it.
+__host__ __device__ inline void step_units(int K, int log2_block, int N, int unit_tokens, int* units, int* unit_blocks) {
+  const long long tok = (long long)K << log2_block;
+  long long u = (tok + unit_tokens - 1) / unit_tokens;
+  const long long by_blocks = ((long long)N + 511) / 512;
+  if (u < by_blocks) u = by_blocks;
+  if (u < 1) u = 1;
+  if (u > ABSB_STEP_MAX_UNITS) u = ABSB_STEP_MAX_UNITS;
+  int cb = (int)(((long long)N + u - 1) / u);
+  cb = (cb + 31) & ~31;
+  if (cb < 32) cb = 32;
+  *unit_blocks = cb;
+  *units = N > 0 ? (N + cb - 1) / cb : 1;
+}
 
 ABSB_HIDDEN int launch_stream_read(const void* src, size_t bytes, uint32_t* sink, int num_cus, hipStream_t stream);
 
@@ -127,25 +157,6 @@ __device__ __forceinline__ SegMap seg_map(int t, int Hsel, int Rk, int Hkv) {
 __device__ __forceinline__ int64_t score_base(const SegMap& m, int Rk, int off, int rows) {
   return (int64_t)Rk * off + (int64_t)(m.hs % Rk) * rows;
 }
-// Development aid, compiled in only with -DABSB_TRACE: thread 0 of a work-group stamps the 100 MHz
-// wall clock into slot `k` of its row of a trace buffer.
-#ifdef ABSB_TRACE
-#define ABSB_STAMP(trace, k)                                                                   \
-  do {                                                                                         \
-    if ((trace) && threadIdx.x == 0) (trace)[(size_t)blockIdx.x * 32 + (k)] = wall_clock64();  \
-  } while (0)
-#define ABSB_NOTE(trace, k, v)                                                                 \
-  do {                                                                                         \
-    if ((trace) && threadIdx.x == 0) (trace)[(size_t)blockIdx.x * 32 + (k)] = (uint64_t)(v);   \
-  } while (0)
-#else
-#define ABSB_STAMP(trace, k) \
-  do {                       \
-  } while (0)
-#define ABSB_NOTE(trace, k, v) \
-  do {                         \
-  } while (0)
-#endif
 // Device-coherent 32-bit accesses for data handed from one work-group to another inside a launch
 // (relaxed, agent scope: served past the caches that are not coherent across the chip).  The
 // hand-off protocol around them: the writer waits until its stores are acknowledged

@@ -48,7 +48,6 @@ struct DecodeParams {
   const int32_t* cent_off;  // [nseg+1]
   int32_t* flags;    // [nseg] (ABSB_TICKET_STRIDE apart): non-zero once the segment's list is complete
   int32_t* status;   // one word: set non-zero when a wait ran into its time limit
-  uint64_t* trace;   // development aid (ABSB_TRACE builds), else null
   void* out;       // [Bt][Hq][128]
   float* lse;      // [Bt][Hq] or null
   int32_t sel_stride, split_tokens, max_splits;
@@ -75,7 +74,6 @@ inline DecodeParams make_decode_params(const Geometry& g, const Plan& pl, float 
   p.cent_off = nullptr;
   p.flags = nullptr;
   p.status = nullptr;
-  p.trace = nullptr;
   p.out = out;
   p.lse = lse;
   p.sel_stride = sel_stride;
@@ -132,68 +130,70 @@ __device__ __forceinline__ void stage_v_word(char* dst, uint32_t r0, uint32_t r1
   *reinterpret_cast<uint2*>(dst + 512) = make_uint2(o01, o23);
 }
 
-// Partial (and, for the last arriver, merged) attention of split `split` of segment s by one
-// work-group of DEC_THREADS threads.  LISTED == false: the block list was complete before the
-// launch.  LISTED == true (one-launch step): the list is being produced by another work-group of
-// this launch with a lower index; its length K_s is recomputed here from the budget, the
-// work-group waits (bounded) for the segment's flag before it reads the list with device-coherent
-// loads, and the segment's last work-group clears the flag again.  `lds`: DEC_LDS_BYTES.
-template <int DT, int G, bool LISTED>
-__device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int split, char* lds) {
-  // s is a SELECTION segment: its G (= the template's) query heads start at head hs * G; hk is the
-  // KV head whose rows they read
-  const SegMap sm = seg_map(s, p.g.Hsel, p.g.Rk, p.g.Hkv);
-  const int b = sm.b, hs = sm.hs, hk = sm.hk;
-  const int lb = p.g.heads.log2_block[hk];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, grp = lane >> 4, li = lane & 15;
-  const int32_t* sel = p.sel_idx + (size_t)s * p.sel_stride;
-  const int pos_begin = split * p.split_tokens;
+// Where the attention loop takes a segment's block list from.
+enum : int {
+  LIST_PLAIN = 0,     // device memory, complete before the launch
+  LIST_COHERENT = 1,  // device memory, written by another work-group of this launch: device-coherent loads
+  LIST_LOCAL = 2      // this work-group's LDS
+};
 
-  // A lane's four rows of a step are four consecutive positions starting at a multiple of four:
-  // they lie in one block (B >= 8) and one page (P >= 8), so one list entry and one page-table
-  // entry serve all four.  The first step's list entry is fetched before the list length is known
-  // (the address is clamped to the list's storage, so the read is always legal); this takes one
-  // memory round trip off the dependent chain count -> entry -> page -> row.
-  const int maxpos = (p.sel_stride << lb) - 1;
-  int sj = 0;
-  if (!LISTED) sj = sel[min(pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4, maxpos) >> lb];
-
-  // never beyond what the launch covers (a list longer than promised is cut, not overrun)
-  int nsel;
-  if (LISTED) {
-    const int rows = p.cent_off[sm.s + 1] - p.cent_off[sm.s];
-    nsel = budget_blocks(p.budget[b], lb, blocks_in_use(p.g.tight, rows, p.seq_lens, b, lb), p.sel_stride);
-  } else {
-    nsel = p.sel_cnt[s];
+// A block list: entry i is a block index of the segment.  Indices beyond `last` read entry `last`
+// (the loop prefetches ahead of the range it works on; the clamp keeps every read inside the storage).
+template <int SRC>
+struct ListRef {
+  const int32_t* ptr;
+  int last;
+  __device__ __forceinline__ int at(int i) const {
+    i = min(i, last);
+    if (SRC == LIST_COHERENT) return ld_i32<true>(ptr + i);
+    return ptr[i];
   }
-  const int ntok = min(nsel << lb, p.max_splits * p.split_tokens);
-  if (ntok == 0 && split == 0) {  // empty selection: the output rows are zero, the log-sum-exp -inf
-    for (int i = tid; i < G * ABSB_HEAD_DIM; i += DEC_THREADS) {
-      const size_t row = (size_t)b * p.g.Hq + (size_t)hs * G + (i >> 7);
-      static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + (i & 127)] = 0;
-      if (p.lse && (i & 127) == 0) p.lse[row] = -__builtin_inff();
-    }
+};
+
+// Logical page -> physical page of one request: the page table row in device memory, or a copy of the
+// entries [first, first + count) that the work-group holds in LDS.
+typedef __attribute__((address_space(3))) const int32_t lds_const_i32;
+struct PageRef {
+  const int32_t* row;    // device memory
+  lds_const_i32* local;  // LDS copy, or null (typed as LDS: a generic pointer would make these reads wait
+                         // for every row load in flight)
+  int first, count;
+  __device__ __forceinline__ int at(int page) const {
+    if (local) return local[min(max(page - first, 0), count - 1)];
+    return row[page];
   }
-  if (pos_begin >= ntok) return;
-  const int pos_end = min(ntok, pos_begin + p.split_tokens);
-  const int L = p.seq_lens[b];
-  const int lP = p.g.log2_page;
+};
 
-  const int32_t* pt = p.page_table + (size_t)b * p.g.pt_stride;
-  const size_t lane_off = (size_t)hk * p.g.s_head + (size_t)li * 8;
+// Running state of the online softmax of one wave: per head (= lane % 16) the running maximum, common
+// to the wave's four row groups; partial sums over the lane's rows of the weights as rounded for the
+// P V product (the output's normaliser: the output stays a convex combination of value rows) and of
+// the weights before rounding (the log-sum-exp: rounding to bf16 would bias it by up to 2^-8 when all
+// weights round the same way); O[head = 4*grp + i][channel = 8*li + j], j = 0..7.
+struct AttnState {
+  float m, l, lx;
+  float4_t oacc[8];
+  __device__ __forceinline__ void reset() {
+    m = M_INIT;
+    l = 0.0f;
+    lx = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) oacc[j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+  }
+};
 
-  char* s_stage = lds;  // reused by the epilogue
-  float (*s_m)[DEC_WAVES] = reinterpret_cast<float (*)[DEC_WAVES]>(lds + DEC_LDS_STATE);
-  float (*s_l)[DEC_WAVES] = s_m + ABSB_MAX_GROUP;
-  float (*s_lx)[DEC_WAVES] = s_l + ABSB_MAX_GROUP;
-  int* s_bcast = reinterpret_cast<int*>(lds + DEC_LDS_STATE + 3 * ABSB_MAX_GROUP * DEC_WAVES * 4);
-  const int nsplit = (ntok + p.split_tokens - 1) / p.split_tokens;
-  char* kt = s_stage + wave * STAGE_BYTES;
-  char* vt = kt + K_TILE_BYTES;
+// What a work-group needs to know about its segment and its place in LDS.
+struct SplitCtx {
+  int b, hs, hk, lb, L, lP;
+  size_t lane_off;
+  char* kt;  // this wave's staging areas
+  char* vt;
+};
 
-  // Q as the B operand of S = K Q^T: lane (head = li, k-group = grp) holds Q[head][16*ks + 4*grp + i];
-  // heads beyond G are zero rows of the tile
-  uint2 qb[8];
+// Q as the B operand of S = K Q^T: lane (head = li, k-group = grp) holds Q[head][16*ks + 4*grp + i];
+// heads beyond G are zero rows of the tile.
+template <int G>
+__device__ __forceinline__ void load_q(const DecodeParams& p, int b, int hs, uint2 (&qb)[8]) {
+  const int lane = threadIdx.x & 63, grp = lane >> 4, li = lane & 15;
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
     qb[ks] = make_uint2(0u, 0u);
@@ -201,40 +201,32 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
       qb[ks] = *reinterpret_cast<const uint2*>(p.q + ((size_t)b * p.g.Hq + (size_t)hs * G + li) * ABSB_HEAD_DIM + 16 * ks +
                                                4 * grp);
   }
+}
 
-  ABSB_STAMP(p.trace, 8);
-  if (LISTED) {
-    // The list comes from a work-group with a lower index, which never waits for anything and was
-    // dispatched before this one: the wait ends.  The time limit only makes that unconditional.
-    if (tid == 0) {
-      int32_t* flag = p.flags + (size_t)s * ABSB_TICKET_STRIDE;
-      int ready = ld_i32<true>(flag);
-      if (!ready) {
-        const uint64_t t0 = wall_clock64();
-        do {
-          __builtin_amdgcn_s_sleep(8);
-          ready = ld_i32<true>(flag);
-        } while (!ready && wall_clock64() - t0 < DEC_WAIT_LIMIT_TICKS);
-      }
-      s_bcast[1] = ready;
-      if (ready && nsplit == 1) st_i32<true>(flag, 0);  // the segment's only reader
-      if (!ready) st_i32<true>(p.status, 1);
-    }
-    __syncthreads();
-    if (!s_bcast[1]) return;
-    ABSB_STAMP(p.trace, 9);
-    sj = ld_i32<true>(sel + (min(pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4, maxpos) >> lb));
-  }
-
-  // per head (= li): running maximum, common to the four groups; partial sums over the lane's rows of
-  // the weights as rounded for the P V product (the output's normaliser: the output stays a convex
-  // combination of value rows) and of the weights before rounding (the log-sum-exp: rounding to
-  // bf16 would bias it by up to 2^-8 when all weights round the same way)
-  float m = M_INIT, l = 0.0f, lx = 0.0f;
-  float4_t oacc[8];            // O[head = 4*grp + i][channel = 8*li + j], j = 0..7
-#pragma unroll
-  for (int j = 0; j < 8; ++j) oacc[j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
-
+// Attention of this wave over positions [pos_begin, pos_end) of the virtual token sequence of a block
+// list (position -> list entry pos >> lb -> token -> page/slot), folded into `st`.  A work-group step
+// covers DEC_WAVES * 16 consecutive positions, 16 per wave; pos_begin must be a multiple of 4.  `sj`:
+// the list entry of this lane's first rows, fetched by the caller (so that the load is in flight early).
+//
+// `after_first_issue()` runs once the first step's row loads are in flight (work that has to wait for
+// memory anyway can hide behind them; it may contain barriers: every wave of the work-group calls this
+// function).  `live(entry)`: false for list entries whose rows were requested but must not count
+// (evaluated when a step is computed, after after_first_issue()).
+struct NoHook {
+  __device__ __forceinline__ void operator()() const {}
+};
+struct AllLive {
+  __device__ __forceinline__ bool operator()(int) const { return true; }
+};
+template <int DT, int G, int SRC, class Hook = NoHook, class Live = AllLive>
+__device__ __forceinline__ void attend_positions(const DecodeParams& p, const SplitCtx& c, const ListRef<SRC>& list,
+                                                 const PageRef& pages, int pos_begin, int pos_end, int sj,
+                                                 const uint2 (&qb)[8], AttnState& st, Hook&& after_first_issue = Hook(),
+                                                 Live&& live = Live()) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, grp = lane >> 4, li = lane & 15;
+  const int lb = c.lb, L = c.L, lP = c.lP;
+  char* kt = c.kt;
+  char* vt = c.vt;
   constexpr int STEP = DEC_WAVES * ROWS_PER_WAVE_STEP;  // positions per work-group step
   u32x4 k0, k1, k2, k3, v0, v1, v2, v3;
 
@@ -252,12 +244,12 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     _Pragma("unroll") for (int r = 0; r < 4; ++r)                                                     \
         vb |= (uint32_t)(pos + r < pos_end && t + r < L) << r; /* a selected last block may be partial */ \
     tcb = max(0, min(t, L - 1)) & ~3;                                                                 \
-    pg = pt[tcb >> lP];                                                                               \
+    pg = pages.at(tcb >> lP);                                                                         \
   }
 #define ABSB_ISSUE(base_expr)                                                                         \
   {                                                                                                   \
     const int base_ = (base_expr);                                                                    \
-    const size_t row0 = (size_t)pg * p.g.s_page + lane_off;                                           \
+    const size_t row0 = (size_t)pg * p.g.s_page + c.lane_off;                                         \
     const size_t off0 = row0 + (size_t)(min(tcb + 0, L - 1) & ((1 << lP) - 1)) * p.g.s_tok;           \
     const size_t off1 = row0 + (size_t)(min(tcb + 1, L - 1) & ((1 << lP) - 1)) * p.g.s_tok;           \
     const size_t off2 = row0 + (size_t)(min(tcb + 2, L - 1) & ((1 << lP) - 1)) * p.g.s_tok;           \
@@ -272,19 +264,20 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     v2 = *reinterpret_cast<const u32x4*>(p.v + off2);                                                 \
     v3 = *reinterpret_cast<const u32x4*>(p.v + off3);                                                 \
     ABSB_GROUP_TOKEN(base_ + STEP)                                                                    \
-    sj = ld_i32<LISTED>(sel + (min(base_ + 2 * STEP + grp * 4, maxpos) >> lb));                       \
+    sj = list.at((base_ + 2 * STEP + grp * 4) >> lb);                                                 \
   }
 
   int base = pos_begin + wave * ROWS_PER_WAVE_STEP;
   uint32_t valid_next = 0, vb;
   int tcb, pg;
-  ABSB_GROUP_TOKEN(base)                                     // first step: entry -> page, in order
-  sj = ld_i32<LISTED>(sel + (min(base + STEP + grp * 4, maxpos) >> lb));  // second step's entry
+  ABSB_GROUP_TOKEN(base)                           // first step: entry -> page, in order
+  sj = list.at((base + STEP + grp * 4) >> lb);     // second step's entry
   if (base < pos_end) ABSB_ISSUE(base)
-  ABSB_STAMP(p.trace, 10);
+  after_first_issue();
+  float m = st.m, l = st.l, lx = st.lx;
   while (base < pos_end) {  // trip count depends on the wave only: every branch here is wave-uniform
     // ---- stage the step's rows in LDS
-    const uint32_t valid = valid_next;
+    const uint32_t valid = live((base + grp * 4) >> lb) ? valid_next : 0u;
     *reinterpret_cast<u32x4*>(kt + (grp * 4 + 0) * K_PITCH + li * 16) = k0;
     *reinterpret_cast<u32x4*>(kt + (grp * 4 + 1) * K_PITCH + li * 16) = k1;
     *reinterpret_cast<u32x4*>(kt + (grp * 4 + 2) * K_PITCH + li * 16) = k2;
@@ -342,21 +335,53 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) oacc[j][i] *= ah[i];
+        for (int i = 0; i < 4; ++i) st.oacc[j][i] *= ah[i];
       }
     }
     // ---- O[head][channel] += P V: B operand = four rows of one channel, one LDS word
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const uint2 bv = *reinterpret_cast<const uint2*>(vt + j * 512 + li * 32 + grp * 8);
-      oacc[j] = mma16<DT>(pa, bv, oacc[j]);
+      st.oacc[j] = mma16<DT>(pa, bv, st.oacc[j]);
     }
     base = next;
   }
 #undef ABSB_ISSUE
 #undef ABSB_GROUP_TOKEN
+  st.m = m;
+  st.l = l;
+  st.lx = lx;
+}
 
-  ABSB_STAMP(p.trace, 11);
+// An empty selection: the output rows are zero, the log-sum-exp -inf.
+template <int G>
+__device__ __forceinline__ void write_empty_rows(const DecodeParams& p, int b, int hs) {
+  for (int i = threadIdx.x; i < G * ABSB_HEAD_DIM; i += DEC_THREADS) {
+    const size_t row = (size_t)b * p.g.Hq + (size_t)hs * G + (i >> 7);
+    static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + (i & 127)] = 0;
+    if (p.lse && (i & 127) == 0) p.lse[row] = -__builtin_inff();
+  }
+}
+
+// The end of a work-group's attention: the four wave states are folded into the work-group's partial;
+// with one split per segment it is normalised and written out; otherwise it goes to slot `split` of
+// the segment's partials, the work-group draws a ticket, and the one that draws ticket nsplit - 1
+// merges the segment's `nsplit` partials with the log-sum-exp rule and writes the output rows.
+// `slots`: partial slots per segment (the stride of the partial arrays).  `on_last`: called by thread 0
+// of the segment's last work-group (the merging one, or the only one), for flags of the segment that
+// have to go back to zero: every other work-group of the segment has drawn its ticket by then.  Every
+// thread of the work-group must call.
+template <int DT, int G, class OnLast>
+__device__ __forceinline__ void finish_split(const DecodeParams& p, int s, int b, int hs, int split, int nsplit, int slots,
+                                             AttnState& st, char* lds, OnLast&& on_last) {
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, grp = lane >> 4, li = lane & 15;
+  char* s_stage = lds;
+  float (*s_m)[DEC_WAVES] = reinterpret_cast<float (*)[DEC_WAVES]>(lds + DEC_LDS_STATE);
+  float (*s_l)[DEC_WAVES] = s_m + ABSB_MAX_GROUP;
+  float (*s_lx)[DEC_WAVES] = s_l + ABSB_MAX_GROUP;
+  int* s_bcast = reinterpret_cast<int*>(lds + DEC_LDS_STATE + 3 * ABSB_MAX_GROUP * DEC_WAVES * 4);
+  float m = st.m, l = st.l, lx = st.lx;
+
   // ---- the wave's state: m per head (lane li), l summed over the four groups, O in groups 0 (and 1)
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
@@ -380,8 +405,8 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
         const float M = fmaxf(fmaxf(s_m[hd][0], s_m[hd][1]), fmaxf(s_m[hd][2], s_m[hd][3]));
         const float a = fast_exp2(s_m[hd][wave] - M);
         float4* dst = reinterpret_cast<float4*>(s_o + ((size_t)wave * G + hd) * ABSB_HEAD_DIM + li * 8);
-        dst[0] = make_float4(oacc[0][i] * a, oacc[1][i] * a, oacc[2][i] * a, oacc[3][i] * a);
-        dst[1] = make_float4(oacc[4][i] * a, oacc[5][i] * a, oacc[6][i] * a, oacc[7][i] * a);
+        dst[0] = make_float4(st.oacc[0][i] * a, st.oacc[1][i] * a, st.oacc[2][i] * a, st.oacc[3][i] * a);
+        dst[1] = make_float4(st.oacc[4][i] * a, st.oacc[5][i] * a, st.oacc[6][i] * a, st.oacc[7][i] * a);
       }
     }
   }
@@ -408,11 +433,11 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     // and the merging group issues its reads only after its ticket has come back.  Nobody waits
     // for anybody.
     constexpr int COHERENT = 16;  // cache-policy operand of the buffer instructions: sc1
-    const size_t slot0 = (size_t)s * p.max_splits;
+    const size_t slot0 = (size_t)s * slots;
     const __amdgpu_buffer_rsrc_t part_o = __builtin_amdgcn_make_buffer_rsrc(
-        p.part_o + slot0 * G * ABSB_HEAD_DIM, 0, p.max_splits * G * ABSB_HEAD_DIM * 4, 0x00020000);
+        p.part_o + slot0 * G * ABSB_HEAD_DIM, 0, slots * G * ABSB_HEAD_DIM * 4, 0x00020000);
     const __amdgpu_buffer_rsrc_t part_ml =
-        __builtin_amdgcn_make_buffer_rsrc(p.part_ml + slot0 * G * 4, 0, p.max_splits * G * 16, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc(p.part_ml + slot0 * G * 4, 0, slots * G * 16, 0x00020000);
     if (tid < NCOL) {
       __builtin_amdgcn_raw_buffer_store_b128(bitcast<u32x4>(O), part_o, ((split * G + g) * ABSB_HEAD_DIM + c4 * 4) * 4,
                                              0, COHERENT);
@@ -427,12 +452,11 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
       s_last = __hip_atomic_fetch_add(p.tickets + (size_t)s * ABSB_TICKET_STRIDE, 1, __ATOMIC_RELAXED,
                                       __HIP_MEMORY_SCOPE_AGENT) == nsplit - 1;
     __syncthreads();
-    ABSB_STAMP(p.trace, 12);
     if (!s_last) return;
     // every counter a launch touches is back at zero when the launch ends
     if (tid == 0) {
       __hip_atomic_store(p.tickets + (size_t)s * ABSB_TICKET_STRIDE, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (LISTED) st_i32<true>(p.flags + (size_t)s * ABSB_TICKET_STRIDE, 0);  // every reader has drawn its ticket
+      on_last();
     }
 
     // log-sum-exp merge: split lane `sl` of a column takes splits sl, sl + SL, ...; MRG_UNROLL of
@@ -485,16 +509,18 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
         M = bm;
 #pragma unroll
         for (int k = 1; k < SL; ++k) {
-          const float* st = s_red + ((size_t)k * CP + col) * 8;
-          const float w = fast_exp2(st[0] - bm);
-          Lsum = __builtin_fmaf(st[1], w, Lsum);
-          Lx = __builtin_fmaf(st[2], w, Lx);
+          const float* sr = s_red + ((size_t)k * CP + col) * 8;
+          const float w = fast_exp2(sr[0] - bm);
+          Lsum = __builtin_fmaf(sr[1], w, Lsum);
+          Lx = __builtin_fmaf(sr[2], w, Lx);
 #pragma unroll
-          for (int j = 0; j < 4; ++j) O[j] = __builtin_fmaf(st[4 + j], w, O[j]);
+          for (int j = 0; j < 4; ++j) O[j] = __builtin_fmaf(sr[4 + j], w, O[j]);
         }
       }
     }
   }
+
+  if (nsplit <= 1 && tid == 0) on_last();
 
   // ---- normalise and write the group's output rows
   if (tid < NCOL) {
@@ -506,7 +532,100 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
     *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.out) + row * ABSB_HEAD_DIM + c4 * 4) = make_uint2(lo, hi);
     if (p.lse && c4 == 0) p.lse[row] = any ? (M + __builtin_log2f(Lx)) * 0.6931471805599453f : -__builtin_inff();
   }
-  ABSB_STAMP(p.trace, 13);
+}
+
+// Waits (thread 0, bounded in time) until the 32-bit word at `flag` is non-zero; every thread of the
+// work-group returns the value seen (0: the wait ran into its limit; *status is then set).  Two
+// barriers inside.  `s_word`: one word of LDS.
+__device__ __forceinline__ int wait_for_flag(const int32_t* flag, int32_t* status, int* s_word) {
+  if (threadIdx.x == 0) {
+    int v = ld_i32<true>(flag);
+    if (!v) {
+      const uint64_t t0 = wall_clock64();
+      do {
+        __builtin_amdgcn_s_sleep(8);
+        v = ld_i32<true>(flag);
+      } while (!v && wall_clock64() - t0 < DEC_WAIT_LIMIT_TICKS);
+    }
+    if (!v) st_i32<true>(status, 1);
+    *s_word = v;
+  }
+  __syncthreads();
+  const int v = *s_word;
+  __syncthreads();  // the word may be reused
+  return v;
+}
+
+// Partial (and, for the last arriver, merged) attention of split `split` of segment s by one
+// work-group of DEC_THREADS threads.  LISTED == false: the block list was complete before the
+// launch.  LISTED == true (the pipelined one-launch step): the list is being produced by another work-group of
+// this launch with a lower index; its length K_s is recomputed here from the budget, the
+// work-group waits (bounded) for the segment's flag before it reads the list with device-coherent
+// loads, and the segment's last work-group clears the flag again.  `lds`: DEC_LDS_BYTES.
+template <int DT, int G, bool LISTED>
+__device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int split, char* lds) {
+  // s is a SELECTION segment: its G (= the template's) query heads start at head hs * G; hk is the
+  // KV head whose rows they read
+  const SegMap sm = seg_map(s, p.g.Hsel, p.g.Rk, p.g.Hkv);
+  const int b = sm.b, hs = sm.hs, hk = sm.hk;
+  const int lb = p.g.heads.log2_block[hk];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, grp = lane >> 4, li = lane & 15;
+  constexpr int SRC = LISTED ? LIST_COHERENT : LIST_PLAIN;
+  const ListRef<SRC> list{p.sel_idx + (size_t)s * p.sel_stride, p.sel_stride - 1};
+  const int pos_begin = split * p.split_tokens;
+
+  // A lane's four rows of a step are four consecutive positions starting at a multiple of four:
+  // they lie in one block (B >= 8) and one page (P >= 8), so one list entry and one page-table
+  // entry serve all four.  The first step's list entry is fetched before the list length is known
+  // (the index is clamped to the list's storage, so the read is always legal); this takes one
+  // memory round trip off the dependent chain count -> entry -> page -> row.
+  int sj = 0;
+  if (!LISTED) sj = list.at((pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4) >> lb);
+
+  // never beyond what the launch covers (a list longer than promised is cut, not overrun)
+  int nsel;
+  if (LISTED) {
+    const int rows = p.cent_off[sm.s + 1] - p.cent_off[sm.s];
+    nsel = budget_blocks(p.budget[b], lb, blocks_in_use(p.g.tight, rows, p.seq_lens, b, lb), p.sel_stride);
+  } else {
+    nsel = p.sel_cnt[s];
+  }
+  const int ntok = min(nsel << lb, p.max_splits * p.split_tokens);
+  if (ntok == 0 && split == 0) write_empty_rows<G>(p, b, hs);
+  if (pos_begin >= ntok) return;
+  const int pos_end = min(ntok, pos_begin + p.split_tokens);
+
+  SplitCtx c;
+  c.b = b;
+  c.hs = hs;
+  c.hk = hk;
+  c.lb = lb;
+  c.L = p.seq_lens[b];
+  c.lP = p.g.log2_page;
+  c.lane_off = (size_t)hk * p.g.s_head + (size_t)li * 8;
+  c.kt = lds + wave * STAGE_BYTES;
+  c.vt = c.kt + K_TILE_BYTES;
+  const PageRef pages{p.page_table + (size_t)b * p.g.pt_stride, nullptr, 0, 0};
+  int* s_bcast = reinterpret_cast<int*>(lds + DEC_LDS_STATE + 3 * ABSB_MAX_GROUP * DEC_WAVES * 4);
+  const int nsplit = (ntok + p.split_tokens - 1) / p.split_tokens;
+
+  uint2 qb[8];
+  load_q<G>(p, b, hs, qb);
+
+  int32_t* flag = LISTED ? p.flags + (size_t)s * ABSB_TICKET_STRIDE : nullptr;
+  if (LISTED) {
+    // The list comes from a work-group with a lower index, which never waits for anything and was
+    // dispatched before this one: the wait ends.  The time limit only makes that unconditional.
+    if (!wait_for_flag(flag, p.status, s_bcast + 1)) return;
+    sj = list.at((pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4) >> lb);
+  }
+
+  AttnState st;
+  st.reset();
+  attend_positions<DT, G, SRC>(p, c, list, pages, pos_begin, pos_end, sj, qb, st);
+  finish_split<DT, G>(p, s, b, hs, split, nsplit, p.max_splits, st, lds, [&]() {
+    if (LISTED) st_i32<true>(flag, 0);  // every reader of the list has drawn its ticket
+  });
 }
 
 }  // namespace absb

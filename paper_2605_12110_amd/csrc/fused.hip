@@ -48,7 +48,6 @@ template <int DT, int G, int REP>
 __global__ __launch_bounds__(FUSED_THREADS, 3) void fused_step_kernel(FusedParams p) {
   extern __shared__ __align__(16) char lds[];
   const int bid = blockIdx.x, tid = threadIdx.x;
-  ABSB_STAMP(p.dc.trace, 0);
   if (bid >= p.n_score) {
     const int id = bid - p.n_score;
     decode_split<DT, G, true>(p.dc, id / p.dc.max_splits, id % p.dc.max_splits, lds);
@@ -59,10 +58,8 @@ __global__ __launch_bounds__(FUSED_THREADS, 3) void fused_step_kernel(FusedParam
   if (N == 0) return;
 
   // ---- hand the chunk's scores over; the segment's last chunk goes on to select
-  ABSB_STAMP(p.dc.trace, 1);
   wait_stores_acknowledged();
   __syncthreads();  // every thread's scores are visible device-wide; the estimation's LDS is free
-  ABSB_STAMP(p.dc.trace, 2);
   int* s_last = reinterpret_cast<int*>(lds);
   if (tid == 0) {
     int32_t* ticket = p.score_tickets + (size_t)s * ABSB_TICKET_STRIDE;
@@ -73,7 +70,6 @@ __global__ __launch_bounds__(FUSED_THREADS, 3) void fused_step_kernel(FusedParam
     *s_last = last;
   }
   __syncthreads();
-  ABSB_STAMP(p.dc.trace, 3);
   if (!*s_last) return;
   __syncthreads();  // everybody has read the word before the selection reuses the memory
 
@@ -92,17 +88,10 @@ __global__ __launch_bounds__(FUSED_THREADS, 3) void fused_step_kernel(FusedParam
     topk_segment<FUSED_THREADS, 0, true>(p.tk, s, sh, bitmap);
 
   // ---- publish the list
-  ABSB_STAMP(p.dc.trace, 4);
   wait_stores_acknowledged();
   __syncthreads();
   if (tid == 0) st_i32<true>(p.dc.flags + (size_t)s * ABSB_TICKET_STRIDE, 1);
-  ABSB_STAMP(p.dc.trace, 5);
 }
-
-#ifdef ABSB_TRACE
-static uint64_t* g_trace = nullptr;
-extern "C" ABSB_API void absb_debug_set_trace(void* buf) { g_trace = static_cast<uint64_t*>(buf); }
-#endif
 
 // Clears the counters at the start of a workspace (all three kinds, and the status word).
 __global__ void clear_counters_kernel(int32_t* head, int nwords) {
@@ -161,10 +150,6 @@ int launch_fused(const Geometry& g, const Plan& pl, int dtype, float sm_scale, c
   p.dc.cent_off = cent_off;
   p.dc.flags = reinterpret_cast<int32_t*>(ws + pl.ws_flags);
   p.dc.status = reinterpret_cast<int32_t*>(ws + pl.ws_status);
-#ifdef ABSB_TRACE
-  p.dc.trace = g_trace;
-  p.tk.trace = g_trace;
-#endif
   p.score_tickets = reinterpret_cast<int32_t*>(ws + pl.ws_score_tickets);
   p.chunks_per_seg = (pl.max_blocks + pl.score_chunk - 1) / pl.score_chunk;
   p.n_score = p.chunks_per_seg * pl.nseg;

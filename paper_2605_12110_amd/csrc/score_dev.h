@@ -77,19 +77,36 @@ __device__ __forceinline__ uint32_t or8(uint32_t v) {  // OR over aligned groups
 // group-maximum score keeps a set of planes per query head, the run sums of the heads' zero-point
 // products and their fixed-point offsets.
 constexpr size_t SCORE_GMAX_PLANES_AT = 16 + ABSB_MAX_GROUP * 8 * 4 + ABSB_MAX_GROUP * 4;
+constexpr size_t SCORE_GMAX_RANGE_AT =
+    SCORE_GMAX_PLANES_AT + (size_t)ABSB_MAX_GROUP * SCORE_PLANES * (ABSB_HEAD_DIM / 8) * sizeof(uint32_t);
+template <int REP>
+__host__ __device__ constexpr size_t score_range_at() {  // per-wave sums of the negative / positive weights
+  return 16 + (size_t)SCORE_PLANES * (ABSB_HEAD_DIM * (REP + 1) / 8) * sizeof(uint32_t);
+}
 template <int REP>
 __host__ __device__ constexpr size_t score_lds_bytes() {
-  const size_t plain = 16 + (size_t)SCORE_PLANES * (ABSB_HEAD_DIM * (REP + 1) / 8) * sizeof(uint32_t);
-  const size_t gmax = SCORE_GMAX_PLANES_AT + (size_t)ABSB_MAX_GROUP * SCORE_PLANES * (ABSB_HEAD_DIM / 8) * sizeof(uint32_t);
+  const size_t plain = score_range_at<REP>() + 4 * 2 * sizeof(int32_t);
+  const size_t gmax = SCORE_GMAX_RANGE_AT + 2 * ABSB_MAX_GROUP * 2 * sizeof(int32_t);
   return REP == 0 && gmax > plain ? gmax : plain;
 }
+
+// Bounds of a segment's scores that follow from the weights alone (every code lies in [0, 15]):
+// lo = 15 * sum_c min(wq_c, 0) <= S_j <= 15 * sum_c max(wq_c, 0) = hi.  The same for every work-group
+// that scores a part of the segment, before any code has been read.
+struct ScoreRange {
+  int32_t lo, hi;
+};
+struct IAdd {
+  __device__ __forceinline__ uint32_t operator()(uint32_t a, uint32_t b) const { return a + b; }
+};
 
 // Group-maximum score (mean pooling): S_j = max_g ( sum_c wq_gc * code_jc + zq_g ) with one exponent
 // for the group; see absb_score.  Same work split as score_chunk below: four lanes per block, the
 // packed 4-bit dots once per query head against that head's digit planes (read from LDS per head),
 // the sum of the codes shared by all heads.
-template <int DT, bool COH>
-__device__ __forceinline__ int score_chunk_groupmax(const ScoreParams& p, int t, int chunk_idx, char* lds) {
+template <int DT, bool RANGE, int PF, class Sink>
+__device__ __forceinline__ int score_blocks_groupmax(const ScoreParams& p, int t, int j0, int jcount, char* lds,
+                                                     Sink&& sink, ScoreRange* range) {
   constexpr int W = ABSB_HEAD_DIM, ROW_BYTES = W / 2;
   const SegMap sm = seg_map(t, p.Hsel, p.Rk, p.Hkv);
   const int b = sm.b, s = sm.s;
@@ -106,8 +123,6 @@ __device__ __forceinline__ int score_chunk_groupmax(const ScoreParams& p, int t,
   const int off = p.cent_off[s];
   const int rows = p.cent_off[s + 1] - off;
   const int N = blocks_in_use(p.tight, rows, p.seq_lens, b, p.heads.log2_block[sm.hk]);
-  int32_t* scores_t = p.scores + score_base(sm, p.Rk, off, rows);
-  const int j0 = chunk_idx * p.chunk;
   if (j0 >= N) return 0;
 
   float* s_absmax = reinterpret_cast<float*>(lds);                                   // [4]
@@ -116,9 +131,11 @@ __device__ __forceinline__ int score_chunk_groupmax(const ScoreParams& p, int t,
   uint32_t (*s_plane)[SCORE_PLANES][W / 8] =
       reinterpret_cast<uint32_t (*)[SCORE_PLANES][W / 8]>(lds + SCORE_GMAX_PLANES_AT);  // [G][planes][16]
 
-  constexpr int PF = 4;
+  int32_t (*s_rng)[ABSB_MAX_GROUP][2] =
+      reinterpret_cast<int32_t (*)[ABSB_MAX_GROUP][2]>(lds + SCORE_GMAX_RANGE_AT);     // [2 waves][G][neg, pos]
+
   const int quarter = tid & 3;
-  const int jend = min(N, j0 + p.chunk);
+  const int jend = min(N, j0 + jcount);
   const uint8_t* base = p.codes + (size_t)off * ROW_BYTES + quarter * 16;
   uint4 pre[PF];
 #pragma unroll
@@ -171,10 +188,26 @@ __device__ __forceinline__ int score_chunk_groupmax(const ScoreParams& p, int t,
         const uint32_t packed = or8(((wo >> (4 * k)) & 15u) << sh);
         if (g < G && (tid & 7) == 0) s_plane[g][k][tid >> 3] = packed;
       }
+      if (RANGE) {  // per head: sums of its negative and of its positive weights (exact, order-free)
+        const uint32_t neg = wave_reduce_u32((uint32_t)min(wq, 0), IAdd()), pos = wave_reduce_u32((uint32_t)max(wq, 0), IAdd());
+        if (g < G && (tid & 63) == 0) {
+          s_rng[tid >> 6][g][0] = (int32_t)neg;
+          s_rng[tid >> 6][g][1] = (int32_t)pos;
+        }
+      }
     }
   }
-  if (tid == 0 && chunk_idx == 0 && p.score_exp) p.score_exp[t] = ex;
+  if (tid == 0 && j0 == 0 && p.score_exp) p.score_exp[t] = ex;
   __syncthreads();
+  if (RANGE) {  // S_j = max_g (dot_g + zq_g), and dot_g lies in 15 * [sum of negative, sum of positive weights]
+    int32_t lo = INT32_MIN, hi = INT32_MIN;
+    for (int g = 0; g < G; ++g) {
+      lo = max(lo, 15 * (s_rng[0][g][0] + s_rng[1][g][0]) + s_zq[g]);
+      hi = max(hi, 15 * (s_rng[0][g][1] + s_rng[1][g][1]) + s_zq[g]);
+    }
+    range->lo = lo;
+    range->hi = hi;
+  }
 
 #pragma unroll 1
   for (int jb = j0;;) {
@@ -213,7 +246,7 @@ __device__ __forceinline__ int score_chunk_groupmax(const ScoreParams& p, int t,
 #pragma unroll
     for (int u = 0; u < PF; ++u) {
       const int j = jb + u * 64 + (tid >> 2);
-      if (j < jend && quarter == 0) st_i32<COH>(scores_t + j, best[u]);
+      if (j < jend && quarter == 0) sink(j, best[u]);
     }
     jb += PF * 64;
     if (jb >= jend) break;
@@ -226,12 +259,15 @@ __device__ __forceinline__ int score_chunk_groupmax(const ScoreParams& p, int t,
   return N;
 }
 
-// Scores of blocks [chunk_idx*p.chunk, +p.chunk) of selection segment t by one work-group of 256 threads.
-// Returns the segment's block count N_s, or 0 (nothing done) when the segment has no such blocks.  COH: the scores are read by
-// another work-group of the same launch.  `lds`: score_lds_bytes<REP>() bytes, 16-byte aligned.
-template <int DT, int REP, bool COH>
-__device__ __forceinline__ int score_chunk(const ScoreParams& p, int t, int chunk_idx, char* lds) {
-  if (REP == 0 && p.agg_max) return score_chunk_groupmax<DT, COH>(p, t, chunk_idx, lds);
+// Scores of blocks [j0, j0 + jcount) of selection segment t by one work-group of 256 threads; every score is
+// handed to sink(block index, score) by one lane.  Returns the segment's block count N_s, or 0 (nothing
+// done, *range untouched) when the segment has no such blocks.  RANGE: *range receives the bounds of the
+// segment's scores.  PF: steps of 64 blocks whose codes are requested at once (a batch).
+// `lds`: score_lds_bytes<REP>() bytes, 16-byte aligned.
+template <int DT, int REP, bool RANGE, int PF, class Sink>
+__device__ __forceinline__ int score_blocks(const ScoreParams& p, int t, int j0, int jcount, char* lds, Sink&& sink,
+                                            ScoreRange* range) {
+  if (REP == 0 && p.agg_max) return score_blocks_groupmax<DT, RANGE, PF>(p, t, j0, jcount, lds, sink, range);
   constexpr int R = REP + 1;                 // vectors per block: the mean, or maxima and minima
   constexpr int W = ABSB_HEAD_DIM * R;       // weights = values per block
   constexpr int ROW_BYTES = W / 2;
@@ -252,18 +288,17 @@ __device__ __forceinline__ int score_chunk(const ScoreParams& p, int t, int chun
   const int off = p.cent_off[s];
   const int rows = p.cent_off[s + 1] - off;
   const int N = blocks_in_use(p.tight, rows, p.seq_lens, b, p.heads.log2_block[sm.hk]);
-  int32_t* scores_t = p.scores + score_base(sm, p.Rk, off, rows);  // this selection segment's scores
-  const int j0 = chunk_idx * p.chunk;
   if (j0 >= N) return 0;
 
   float* s_absmax = reinterpret_cast<float*>(lds);
   uint32_t (*s_plane)[W / 8] = reinterpret_cast<uint32_t (*)[W / 8]>(lds + 16);
+  int32_t (*s_rng)[2] = reinterpret_cast<int32_t (*)[2]>(lds + score_range_at<REP>());  // [wave][neg, pos]
 
   // ---- the work-group's first batch of codes goes in flight before anything else: the loads do
   // not depend on the query, so their latency overlaps the prologue below
-  constexpr int PF = 4;  // 64 blocks per work-group step, PF steps per batch
+  // 64 blocks per work-group step, PF steps per batch
   const int quarter = tid & 3;
-  const int jend = min(N, j0 + p.chunk);
+  const int jend = min(N, j0 + jcount);
   const uint8_t* base = p.codes + (size_t)off * ROW_BYTES + quarter * 16;
   uint4 pre[PF][R];
 #pragma unroll
@@ -316,9 +351,25 @@ __device__ __forceinline__ int score_chunk(const ScoreParams& p, int t, int chun
       const uint32_t packed = or8(((wo >> (4 * k)) & 15u) << sh);
       if ((tid & 7) == 0) s_plane[k][tid >> 3] = packed;
     }
+    if (RANGE) {  // sums of the negative and of the positive weights (exact, order-free)
+      const uint32_t neg = wave_reduce_u32((uint32_t)min(wq, 0), IAdd()), pos = wave_reduce_u32((uint32_t)max(wq, 0), IAdd());
+      if ((tid & 63) == 0) {
+        s_rng[tid >> 6][0] = (int32_t)neg;
+        s_rng[tid >> 6][1] = (int32_t)pos;
+      }
+    }
   }
-  if (tid == 0 && chunk_idx == 0 && p.score_exp) p.score_exp[t] = ex;
+  if (tid == 0 && j0 == 0 && p.score_exp) p.score_exp[t] = ex;
   __syncthreads();
+  if (RANGE) {
+    int32_t neg = s_rng[0][0] + s_rng[1][0], pos = s_rng[0][1] + s_rng[1][1];
+    if (REP) {
+      neg += s_rng[2][0] + s_rng[3][0];
+      pos += s_rng[2][1] + s_rng[3][1];
+    }
+    range->lo = 15 * neg;
+    range->hi = 15 * pos;
+  }
 
   // ---- each lane: the digit planes of its quarter of each vector (4 words of 8 values)
   uint4 wp[R][SCORE_PLANES];
@@ -358,7 +409,7 @@ __device__ __forceinline__ int score_chunk(const ScoreParams& p, int t, int chun
     for (int u = 0; u < PF; ++u) {
       const int j = jb + u * 64 + (tid >> 2);
       const int32_t sc = dot(pre[u]);
-      if (j < jend && quarter == 0) st_i32<COH>(scores_t + j, sc);
+      if (j < jend && quarter == 0) sink(j, sc);
     }
     jb += PF * 64;
     if (jb >= jend) break;
@@ -372,5 +423,20 @@ __device__ __forceinline__ int score_chunk(const ScoreParams& p, int t, int chun
   return N;
 }
 
+// Where selection segment t's scores start in the score array.
+__device__ __forceinline__ int32_t* scores_of(const ScoreParams& p, int t) {
+  const SegMap sm = seg_map(t, p.Hsel, p.Rk, p.Hkv);
+  const int off = p.cent_off[sm.s];
+  return p.scores + score_base(sm, p.Rk, off, p.cent_off[sm.s + 1] - off);
+}
+
+// The stand-alone form: blocks [chunk_idx * p.chunk, + p.chunk), scores stored to the score array.
+// COH: they are read by another work-group of the same launch.
+template <int DT, int REP, bool COH>
+__device__ __forceinline__ int score_chunk(const ScoreParams& p, int t, int chunk_idx, char* lds) {
+  int32_t* scores_t = scores_of(p, t);
+  return score_blocks<DT, REP, false, 4>(
+      p, t, chunk_idx * p.chunk, p.chunk, lds, [&](int j, int32_t sc) { st_i32<COH>(scores_t + j, sc); }, nullptr);
+}
 
 }  // namespace absb

@@ -40,7 +40,6 @@ struct TopkParams {
   int32_t sel_stride, Hkv, tight;
   int32_t Hsel, Rk;  // selection segments per request, selection segments per KV head
   HeadTable heads;
-  uint64_t* trace;  // development aid (ABSB_TRACE builds), else null
 };
 
 inline TopkParams make_topk_params(const Geometry& g, const int32_t* scores, const int32_t* cent_off,
@@ -62,7 +61,6 @@ inline TopkParams make_topk_params(const Geometry& g, const int32_t* scores, con
   p.Hsel = g.Hsel;
   p.Rk = g.Rk;
   p.heads = g.heads;
-  p.trace = nullptr;
   return p;
 }
 
@@ -256,7 +254,6 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
     kmin = min(kmin, k);
     kmax = max(kmax, k);
   }
-  ABSB_STAMP(p.trace, 6);
   kmin = wave_reduce_u32(kmin, UMin());
   kmax = wave_reduce_u32(kmax, UMax());
   if (lane == 0) {
@@ -308,7 +305,6 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
     }
   }
   __syncthreads();
-  ABSB_STAMP(p.trace, 7);
   // The next pass over the keys recomputes its digits instead of carrying one more register per
   // key across the barrier: with a long register tile that carrying spills.  The empty statements
   // make the values opaque to the optimiser.
@@ -317,14 +313,9 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
     for (int i = 0; i < R; ++i) asm volatile("" : "+v"(key[i]));
   }
   pick_bin<NT>(sh, tid, lane, wave, (uint32_t)K);
-  ABSB_STAMP(p.trace, 14);
   const uint32_t d1 = sh.bcast[0];
   uint32_t need = (uint32_t)K - sh.bcast[1];
   uint32_t ncand = sh.bcast[2];
-  ABSB_NOTE(p.trace, 16, ncand);
-  ABSB_NOTE(p.trace, 17, shift);
-  ABSB_NOTE(p.trace, 18, N);
-  ABSB_NOTE(p.trace, 19, K);
   uint32_t need_eq = 0;
 
   if (shift == 0 || ncand <= (uint32_t)TOPK_MAX_CAND) {
@@ -392,7 +383,6 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
       }
     }
     __syncthreads();
-    ABSB_STAMP(p.trace, 20);
     if (list_cands) {
       // A long candidate list (a range stretched by a few outliers packs the bulk of the keys into
       // few bins) is cut down by further digits of the key, a histogram round per digit over the
@@ -495,8 +485,6 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
     }
     __syncthreads();
   }
-
-  ABSB_STAMP(p.trace, 15);
   // ---- 4. bitmaps -> ascending index list, in one round: every thread owns a run of consecutive
   // bitmap words, counts their bits, one scan over the work-group places the run, and the thread
   // writes its blocks out in order

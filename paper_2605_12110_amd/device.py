@@ -23,10 +23,12 @@ class DeviceWorkload:
     def __init__(self, wl, device: str = "cuda:0", budget: Optional[np.ndarray] = None,
                  block_repr: int = absb.REPR_MEAN, block_size: Optional[np.ndarray] = None,
                  share: Optional["DeviceWorkload"] = None, sink_tokens: int = 0, recent_tokens: int = 0,
-                 cap_lens: Optional[np.ndarray] = None, selection: int = absb.SELECT_GROUP):
+                 cap_lens: Optional[np.ndarray] = None, selection: int = absb.SELECT_GROUP,
+                 opts: Optional[dict] = None):
         """`block_size` / `budget` override the workload's; `share` reuses another holder's resident
         caches, queries, lengths and page table (same workload under other block sizes or budgets);
-        `cap_lens` lays the store out for contexts that grow up to those lengths (set_lens/append)."""
+        `cap_lens` lays the store out for contexts that grow up to those lengths (set_lens/append);
+        `opts`: fields of absb_launch_opts that shape buffers (split_tokens, unit_tokens, ...)."""
         self.wl = wl
         self.device = device
         tdt = torch.float16 if wl.dtype == absb.F16 else torch.bfloat16
@@ -49,7 +51,7 @@ class DeviceWorkload:
             self.seq_lens, self.page_table = share.seq_lens, share.page_table
         self.budget = _up(budget.astype(np.int32), None, device)
         self.batch = absb.Batch(seq_lens_host=wl.seq_lens, budget_host=budget, seq_lens=self.seq_lens,
-                                page_table=self.page_table, budget=self.budget)
+                                page_table=self.page_table, budget=self.budget, opts=absb.LaunchOpts(**(opts or {})))
         if cap_lens is not None:
             # buffers are sized for the longest contexts; the layout (offsets) stays that of cap_lens
             cap = np.asarray(cap_lens, dtype=np.int32)

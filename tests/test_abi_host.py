@@ -162,54 +162,58 @@ def test_workspace_and_list_width_checks_come_before_any_launch():
     assert rc == absb.ERR_BAD_SHAPE
 
 
-def test_tuning_knobs_validate():
-    absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 128)
-    absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 0)
-    with pytest.raises(absb.AbsbError):
-        absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 100)
-    with pytest.raises(absb.AbsbError):
-        absb.set_tuning(99, 64)
-    absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 1)
-    absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
-    with pytest.raises(absb.AbsbError):
-        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 64)
-    for ok in (1, 3, 0):
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, ok)
-    with pytest.raises(absb.AbsbError):
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 2)
+def test_launch_options_are_per_call_and_validated():
+    """absb_launch_opts travels with the batch of a call: invalid values are refused before anything
+    is enqueued, valid ones change the plan of that batch only (another batch object keeps the
+    library's choices), and the library exports no process-wide knob."""
+    layer = absb.Layer(8, 2, 128, 64, absb.F16, [8, 128], (2 * 64 * 128, 64 * 128, 128))
+
+    def batch(**opts):
+        return absb.Batch(seq_lens_host=[4096, 100], budget_host=[512, 64], pt_stride=64, opts=absb.LaunchOpts(**opts))
+    base = absb.absb_plan(layer, batch()).workspace_bytes
+    assert absb.absb_plan(layer, batch(split_tokens=64)).workspace_bytes >= base      # more splits, more partials
+    assert absb.absb_plan(layer, batch()).workspace_bytes == base                     # ... for that batch only
+    for bad in (dict(split_tokens=100), dict(split_tokens=-64), dict(score_chunk=65), dict(unit_tokens=32),
+                dict(counters_zero=2), dict(counters_zero=-1), dict(step_form=4), dict(step_form=-1)):
+        with pytest.raises(absb.AbsbError) as e:
+            absb.absb_plan(layer, batch(**bad))
+        assert e.value.status == absb.ERR_BAD_SHAPE, bad
+        with pytest.raises(absb.AbsbError) as e:
+            absb.absb_step_form_used(layer, batch(**bad))
+        assert e.value.status == absb.ERR_BAD_SHAPE, bad
+    for ok in (dict(split_tokens=128), dict(score_chunk=512), dict(unit_tokens=256), dict(counters_zero=1),
+               dict(step_form=1), dict(step_form=2), dict(step_form=3)):
+        absb.absb_plan(layer, batch(**ok))
+    assert not hasattr(absb.load(), "absb_set_tuning")
 
 
-def test_enqueue_mode_of_the_fused_step_follows_the_longest_segment():
-    """One launch while no segment has more than 8192 blocks (16384 in a batch of 16 or more segments)
-    and no list more than 4096 entries, one launch per stage beyond; the knob forces either; the
-    workspace always has room for the counters of the one-launch step."""
-    def mode(L, B, batch_size=2, budget=64):
+def test_enqueue_form_of_the_fused_step_follows_the_longest_segment():
+    """Pipelined one-launch step while no segment has more than 8192 blocks (16384 in a batch of 16 or
+    more segments) and no list more than 4096 entries; beyond 16384 blocks the unit form, as long as
+    the chip holds all units at once; one launch per stage otherwise; the option forces any of them; the
+    workspace always has room for the counters of the one-launch forms."""
+    def form(L, B, batch_size=2, budget=64, **opts):
         layer = absb.Layer(8, 2, 128, 64, absb.F16, [B, 128], (2 * 64 * 128, 64 * 128, 128))
         batch = absb.Batch(seq_lens_host=[L] + [100] * (batch_size - 1), budget_host=[budget] * batch_size,
-                           pt_stride=(L + 63) // 64)
-        return absb.absb_step_launches(layer, batch), absb.absb_plan(layer, batch).workspace_bytes
-    assert mode(8192 * 8, 8)[0] == 1
-    assert mode(8192 * 8 + 1, 8)[0] == 3
-    assert mode(131072, 16)[0] == 1
-    assert mode(16384 * 8, 8, batch_size=8)[0] == 1            # 16 segments: long segments overlap with others
-    assert mode(16384 * 8 + 1, 8, batch_size=8)[0] == 3
-    assert mode(8192 * 8, 8, budget=4096 * 8)[0] == 1
-    assert mode(8192 * 8, 8, budget=4096 * 8 + 1)[0] == 3      # lists of more than 4096 blocks
-    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 3)
-    try:
-        assert mode(4096, 8)[0] == 3
-    finally:
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
-    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 1)
-    try:
-        assert mode(131072, 8)[0] == 1
-    finally:
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+                           pt_stride=(L + 63) // 64, opts=absb.LaunchOpts(**opts))
+        return absb.absb_step_form_used(layer, batch), absb.absb_plan(layer, batch).workspace_bytes
+    P, U, S = absb.STEP_PIPELINED, absb.STEP_UNITS, absb.STEP_PER_STAGE
+    assert form(8192 * 8, 8)[0] == P
+    assert form(8192 * 8 + 1, 8)[0] == S
+    assert form(131072, 16)[0] == P
+    assert form(16384 * 8, 8, batch_size=8)[0] == P            # 16 segments: long segments overlap with others
+    assert form(16384 * 8 + 1, 8, batch_size=4)[0] == U        # beyond: units select among themselves
+    assert form(16384 * 8 + 1, 8, batch_size=8)[0] == S        # ... unless there are more units than the chip holds
+    assert form(8192 * 8, 8, budget=4096 * 8)[0] == P
+    assert form(8192 * 8, 8, budget=4096 * 8 + 1)[0] == S      # lists of more than 4096 blocks
+    assert form(4096, 8, step_form=S)[0] == S
+    assert form(4096, 8, step_form=U)[0] == U
+    assert form(131072, 8, step_form=P)[0] == P
     nseg = 2 * 2
-    assert mode(4096, 8)[1] >= 3 * nseg * 256 + 256
+    assert form(4096, 8)[1] >= 6 * nseg * 256 + 256
     with pytest.raises(absb.AbsbError):
-        absb.absb_step_launches(absb.Layer(8, 2, 128, 64, absb.F16, [8, 8], (16384, 8192, 128)),
-                                absb.Batch(seq_lens_host=[64], budget_host=None, pt_stride=1))
+        absb.absb_step_form_used(absb.Layer(8, 2, 128, 64, absb.F16, [8, 8], (16384, 8192, 128)),
+                                 absb.Batch(seq_lens_host=[64], budget_host=None, pt_stride=1))
 
 
 def test_product_package_does_not_reach_the_oracle():
@@ -238,7 +242,7 @@ def test_selection_rejects_segments_beyond_its_capacity_before_any_launch():
         absb.absb_decode_fused(layer, batch, fake, fake, fake, fake, fake, fake, None, None, None, fake, stream=0)
     assert e.value.status == absb.ERR_UNSUPPORTED
     with pytest.raises(absb.AbsbError) as e:
-        absb.absb_step_launches(layer, batch)
+        absb.absb_step_form_used(layer, batch)
     assert e.value.status == absb.ERR_UNSUPPORTED
 
 

@@ -34,6 +34,25 @@ def _sync():
     torch.cuda.synchronize()
 
 
+from contextlib import contextmanager
+
+
+@contextmanager
+def _opts(dw, **kw):
+    """Launch options of the holder's batch (absb_launch_opts) for the calls inside the block."""
+    old = {k: getattr(dw.batch.opts, k) for k in kw}
+    for k, v in kw.items():
+        setattr(dw.batch.opts, k, v)
+    try:
+        yield
+    finally:
+        for k, v in old.items():
+            setattr(dw.batch.opts, k, v)
+
+
+FORMS = {1: "pipelined", 2: "units", 3: "per stage"}      # absb_step_form
+
+
 def _check_out(dw, want_out, want_lse, what):
     _sync()
     got = dw.out_f32().astype(np.float64)
@@ -117,26 +136,36 @@ def run_all_stages(wl, name, block_repr=O.MEAN, per_query_head=False, group_max=
     dw.decode_fused(want_sel=False); _sync()
     second = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
     assert np.array_equal(first, second), "fused output depends on workspace contents or is not deterministic"
-    # both ways of enqueueing the step, forced (the default picks one by shape): the whole step in one
-    # launch, and one launch per stage (which needs no cleared counters): same selection, same bits out
+    # every way of enqueueing the step, forced (the default picks one by shape): two one-launch forms
+    # and one launch per stage (which needs no cleared counters).  Same selection from all; outputs
+    # within tolerance of the oracle; the pipelined and the per-stage form cut the lists alike and give
+    # the same bits, the unit form sums in another order
     from paper_2605_12110_amd import absb
-    for mode in (1, 3):
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, mode)
-        try:
+    outs = {}
+    for mode in (1, 2, 3):
+        with _opts(dw, step_form=mode):
             dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
             if mode == 3:
                 dw.workspace.fill_(0x3C)
             else:
                 dw.scribble(0x3C)
-            dw.decode_fused(); _sync()
-        finally:
-            absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
-        again = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
-        assert np.array_equal(first, again), f"enqueue mode {mode} disagrees with the default"
-        assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
-        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K])
+            dw.decode_fused()
+            _check_out(dw, ref["out"], ref["lse"], f"decode_fused, {FORMS[mode]}")
+        outs[mode] = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
+        assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"]), FORMS[mode]
+        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K]), FORMS[mode]
+        if mode != 3:
+            assert dw.status() == 0, FORMS[mode]
+            # and once more without asking for the list: same bits (nothing depends on the workspace's contents)
+            with _opts(dw, step_form=mode):
+                dw.scribble(0xC5)
+                dw.decode_fused(want_sel=False); _sync()
+            again = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
+            assert np.array_equal(outs[mode], again), f"{FORMS[mode]}: not deterministic, or the list request changes the output"
+    assert np.array_equal(outs[1], outs[3]), "pipelined and per-stage forms disagree"
+    assert np.array_equal(first, outs[absb.absb_step_form_used(dw.layer, dw.batch)]), "default form"
     dw.scribble(0x99)     # the stand-alone stages do not keep the other counters: clear them again
-    _say("    fused: selection bit-exact, output within tolerance, deterministic, one launch == three launches")
+    _say("    fused: selection bit-exact in every enqueue form, outputs within tolerance, deterministic")
     return dw, st, ref
 
 
@@ -268,27 +297,28 @@ def test_decode_accepts_any_list_order_partial_last_block_and_empty_lists():
 
 
 def test_split_shapes_do_not_change_the_selection_and_stay_within_tolerance():
-    from paper_2605_12110_amd import absb
     wl = synth.make_workload(1, context=8192, budget=2048)
     st = O.build_centroids(wl)
     ref = O.decode_step(wl, st)
-    try:
-        for split in (64, 128, 512, 1024):
-            absb.set_tuning(absb.TUNE_SPLIT_TOKENS, split)
-            dw = _dev(wl)
+    for split in (64, 128, 512, 1024):
+        for form in (1, 3):
+            dw = _dev(wl, opts=dict(split_tokens=split, step_form=form))
             dw.build()
             dw.decode_fused()
-            _check_out(dw, ref["out"], ref["lse"], f"split_tokens={split}")
+            _check_out(dw, ref["out"], ref["lse"], f"split_tokens={split}, {FORMS[form]}")
             assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
-        for chunk in (64, 1024):
-            absb.set_tuning(absb.TUNE_SCORE_CHUNK, chunk)
-            dw = _dev(wl)
-            dw.load_store(st.codes, st.qscale, st.qmin)
-            dw.score(); _sync()
-            assert np.array_equal(dw.scores.cpu().numpy(), ref["scores"])
-    finally:
-        absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 0)
-        absb.set_tuning(absb.TUNE_SCORE_CHUNK, 0)
+    for unit in (64, 256, 1024):
+        dw = _dev(wl, opts=dict(unit_tokens=unit, step_form=2))
+        dw.build()
+        dw.decode_fused()
+        _check_out(dw, ref["out"], ref["lse"], f"unit_tokens={unit}, units")
+        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+        assert dw.status() == 0
+    for chunk in (64, 1024):
+        dw = _dev(wl, opts=dict(score_chunk=chunk))
+        dw.load_store(st.codes, st.qscale, st.qmin)
+        dw.score(); _sync()
+        assert np.array_equal(dw.scores.cpu().numpy(), ref["scores"])
 
 
 def test_nonstandard_cache_strides_nhd_layout():
@@ -320,26 +350,20 @@ def test_many_splits_per_segment_and_split_counters_left_at_zero():
     wl = synth.make_workload(1, context=8192, budget=8192)       # every block selected: 8192 tokens per segment
     st = O.build_centroids(wl)
     ref = O.decode_step(wl, st)
-    try:
-        absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 64)              # 128 splits per segment
-        dw = _dev(wl)
-        dw.build()
-        dw.decode_fused()
-        _check_out(dw, ref["out"], ref["lse"], "128 splits, fused")
-        dw.build()
-        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 1)
+    dw = _dev(wl, opts=dict(split_tokens=64, step_form=1))       # 128 splits per segment
+    dw.build()
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "128 splits, fused")
+    dw.build()
+    with _opts(dw, counters_zero=1):
         for rep in range(3):
             dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
             dw.sparse_decode()
             _check_out(dw, ref["out"], ref["lse"], f"128 splits, stand-alone call {rep}, counters promised zero")
-        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
-        dw.workspace.fill_(0x5A)                                 # garbage counters: the default path clears them
-        dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
-        dw.sparse_decode()
-        _check_out(dw, ref["out"], ref["lse"], "128 splits, stand-alone call on a scribbled workspace")
-    finally:
-        absb.set_tuning(absb.TUNE_SPLIT_TOKENS, 0)
-        absb.set_tuning(absb.TUNE_COUNTERS_ZERO, 0)
+    dw.workspace.fill_(0x5A)                                 # garbage counters: the default path clears them
+    dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+    dw.sparse_decode()
+    _check_out(dw, ref["out"], ref["lse"], "128 splits, stand-alone call on a scribbled workspace")
 
 
 def test_stream_read_helper_runs_and_leaves_its_sink_alone():
@@ -610,14 +634,11 @@ def test_non_finite_values_in_one_request_do_not_disturb_the_others_or_stall_any
     ref = O.decode_step(wl, O.build_centroids(wl))          # request 1 of it is untouched by all this
     dw = _dev(wl)
     K = dw.sel_stride
-    for mode in (1, 3):
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, mode)
-        try:
+    for mode in (1, 2, 3):
+        with _opts(dw, step_form=mode):
             dw.build()
             dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(0); dw.lse.fill_(0)
             dw.decode_fused(); _sync()
-        finally:
-            absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
         assert dw.status() == 0
         cnt, sel = dw.sel_cnt.cpu().numpy(), dw.sel_idx.cpu().numpy()
         assert np.array_equal(cnt, ref["sel_cnt"])                       # K_s does not depend on the data
@@ -685,14 +706,11 @@ def test_random_shapes_with_few_distinct_keys_and_forced_blocks(seed):
         ref = O.decode_step(wl, st, sink_tokens=sink, recent_tokens=recent)
         dw = _dev(wl, sink_tokens=sink, recent_tokens=recent)
         dw.build()
-        for launches in (1, 3):
-            absb.set_tuning(absb.TUNE_STEP_LAUNCHES, launches)
-            try:
+        for form in (1, 2, 3):
+            with _opts(dw, step_form=form):
                 dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7)
                 dw.decode_fused()
-                _check_out(dw, ref["out"], ref["lse"], f"forced sink={sink} recent={recent}, {launches} launch(es)")
-            finally:
-                absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+                _check_out(dw, ref["out"], ref["lse"], f"forced sink={sink} recent={recent}, {FORMS[form]}")
             assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
             assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
             assert dw.status() == 0
@@ -764,9 +782,10 @@ def test_group_maximum_selection_needs_the_offsets_and_mean_pooling():
 # ------------------------------------------------------------------ the one-launch step beyond its default range
 @pytest.mark.parametrize("context,sizes", [(131072, (8, 16)), (163840, (8, 8))])
 def test_one_launch_step_on_segments_longer_than_the_default_allows(context, sizes):
-    """By default a batch with a segment of more than 8192 blocks is enqueued as three launches.  Forced
-    into one launch it must give the same bits: 16384 blocks (the longest register tile of the
-    256-thread selection) and 20480 blocks (keys re-read, no register tile)."""
+    """By default a batch with a segment of more than 8192 blocks does not run as the pipelined
+    one-launch step.  Forced into it, it must give the bits of the per-stage form: 16384 blocks (the
+    longest register tile of the 256-thread selection) and 20480 blocks (keys re-read, no register
+    tile).  The unit form, the default beyond 16384 blocks, selects the same blocks."""
     import torch
     from paper_2605_12110_amd import absb
     wl = synth.make_workload(3, context=context, budget=4096, block_sizes=sizes)
@@ -774,26 +793,30 @@ def test_one_launch_step_on_segments_longer_than_the_default_allows(context, siz
     ref = O.decode_step(wl, st)
     dw = _dev(wl)
     dw.build()
-    dw.decode_fused()                                            # default: three launches here
-    _check_out(dw, ref["out"], ref["lse"], f"default enqueue, context {context}")
+    assert absb.absb_step_form_used(dw.layer, dw.batch) == (absb.STEP_UNITS if context > 131072 else absb.STEP_PER_STAGE)
+    with _opts(dw, step_form=3):
+        dw.decode_fused()
+        _check_out(dw, ref["out"], ref["lse"], f"per stage, context {context}")
     assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
     first = dw.out.clone()
-    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 1)
-    try:
-        for rep in range(2):                                     # twice: the counters must come back to zero
-            dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan"))
-            dw.decode_fused(); _sync()
-            assert torch.equal(dw.out, first), f"one launch, call {rep}"
-            assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
-            assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
-    finally:
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
-    head = dw.workspace[:dw.nseg * 3 * 256 + 256].view(torch.int32)
+    for form in (1, 2, 0):
+        with _opts(dw, step_form=form):
+            for rep in range(2):                                     # twice: the counters must come back to zero
+                dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7); dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
+                dw.decode_fused()
+                _check_out(dw, ref["out"], ref["lse"], f"form {form}, call {rep}, context {context}")
+                if form == 1:
+                    assert torch.equal(dw.out, first), f"pipelined, call {rep}"
+                assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+                assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+                assert dw.status() == 0
+    head = dw.workspace[:dw.nseg * 6 * 256 + 256].view(torch.int32)
     assert int(head.abs().sum().item()) == 0, "the step left a counter, a flag or the status word set"
 
 
-def test_one_launch_steps_back_to_back_and_on_two_streams():
-    """The one-launch step keeps its hand-off counters in the workspace and leaves them at zero: many
+@pytest.mark.parametrize("form", [1, 2])
+def test_one_launch_steps_back_to_back_and_on_two_streams(form):
+    """The one-launch forms keep their hand-off counters in the workspace and leave them at zero: many
     steps enqueued without a synchronisation in between must each see clean counters, and two streams
     working on workspaces of their own must not disturb each other."""
     import torch
@@ -803,10 +826,10 @@ def test_one_launch_steps_back_to_back_and_on_two_streams():
     for wl in wls:
         st = O.build_centroids(wl)
         refs.append(O.decode_step(wl, st))
-    dws = [_dev(wl) for wl in wls]
+    dws = [_dev(wl, opts=dict(step_form=form)) for wl in wls]
     for dw in dws:
         dw.build()
-        assert absb.absb_step_launches(dw.layer, dw.batch) == 1
+        assert absb.absb_step_form_used(dw.layer, dw.batch) == form
     _sync()
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     for st_ in streams:
@@ -821,7 +844,7 @@ def test_one_launch_steps_back_to_back_and_on_two_streams():
         _check_out(dw, ref["out"], ref["lse"], "25 steps back to back, two streams")
         assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
         assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
-        head = dw.workspace[:dw.nsel * 3 * 256 + 256].view(torch.int32)
+        head = dw.workspace[:dw.nsel * 6 * 256 + 256].view(torch.int32)
         assert int(head.abs().sum().item()) == 0
         assert dw.status() == 0 and absb.absb_status_offset(dw.layer, dw.batch) == dw.nsel * 3 * 256
 
@@ -838,60 +861,60 @@ def test_one_workspace_serves_batches_of_different_shapes_when_cleared_in_betwee
         st = O.build_centroids(wl)
         cases.append((wl, O.decode_step(wl, st), _dev(wl)))
     shared = max((c[2].workspace for c in cases), key=lambda t: t.numel())
-    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 1)
-    try:
-        for rnd in range(2):
-            for wl, ref, dw in cases:
-                dw.workspace = shared
-                dw.build()                                   # leaves its scratch data where the next shape's counters sit
-                dw.scribble(0xB7 + rnd)                      # = fill + absb_workspace_init for this shape
-                for rep in range(2):                         # and no clearing between steps of one shape
+    for rnd in range(2):
+        for wl, ref, dw in cases:
+            dw.workspace = shared
+            dw.build()                                   # leaves its scratch data where the next shape's counters sit
+            dw.scribble(0xB7 + rnd)                      # = fill + absb_workspace_init for this shape
+            for rep in range(4):                         # and no clearing between steps of one shape, whatever their form
+                with _opts(dw, step_form=1 + rep % 2):
                     dw.sel_idx.fill_(-7); dw.out.fill_(float("nan"))
                     dw.decode_fused()
                     _check_out(dw, ref["out"], ref["lse"], f"shared workspace, batch of {wl.batch}, round {rnd}, step {rep}")
-                    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
-                    assert dw.status() == 0
-    finally:
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+                assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+                assert dw.status() == 0
 
 
-def test_one_launch_step_gives_up_waiting_and_says_so_when_a_counter_was_not_cleared():
-    """The attention work-groups of the one-launch step wait for their segment's list with a time
-    limit.  Forced from the host: one estimation counter starts at a value from which the segment's
-    last ticket is never drawn, so its list never comes.  The launch must end by itself (about a
-    quarter of a second), set the status word, and leave the other segments' lists right; after the
-    counters are cleared again the step works."""
+@pytest.mark.parametrize("form", [1, 2])
+def test_one_launch_step_gives_up_waiting_and_says_so_when_a_counter_was_not_cleared(form):
+    """Work-groups of the one-launch forms wait for each other with a time limit.  Forced from the host:
+    one segment's arrival counter starts at a value from which the count its work-groups wait for is
+    never reached, so its list (pipelined form) or its threshold (unit form) never comes.  The launch
+    must end by itself (about a quarter of a second per wait), set the status word, leave the other
+    segments right, and (unit form) write NaN into the stuck segment's output rows; after the counters
+    are cleared again the step works."""
     import torch
-    from paper_2605_12110_amd import absb
     wl = synth.make_workload(1, context=4096, budget=256)
     ref = O.decode_step(wl, O.build_centroids(wl))
-    dw = _dev(wl)
+    dw = _dev(wl, opts=dict(step_form=form))
     dw.build()
-    absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 1)
-    try:
-        dw.decode_fused(); _sync()
-        assert dw.status() == 0
-        ctr = dw.workspace.view(torch.int32)
-        stuck = 2
-        ctr[(dw.nsel * 256) // 4 + stuck * 64] = 1000                # estimation tickets follow the attention tickets
-        dw.sel_cnt.fill_(-7)
-        t0 = time.time()
-        dw.decode_fused(); _sync()
-        took = time.time() - t0
-        _say(f"    step with a stuck segment took {took:.2f} s")
-        assert took < 5.0
-        assert dw.status() == 1
-        cnt = dw.sel_cnt.cpu().numpy()
-        assert cnt[stuck] == -7                                       # nobody selected for the stuck segment
-        others = [s for s in range(dw.nsel) if s != stuck]
-        assert np.array_equal(cnt[others], ref["sel_cnt"][others])
-        dw.scribble(0x77)                                             # the contract: clear the counters, go on
-        dw.decode_fused()
-        _check_out(dw, ref["out"], ref["lse"], "after clearing the counters again")
-        assert dw.status() == 0
-        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
-    finally:
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+    dw.decode_fused(); _sync()
+    assert dw.status() == 0
+    ctr = dw.workspace.view(torch.int32)
+    stuck = 2
+    ctr[(dw.nsel * 256) // 4 + stuck * 64] = 1000                # the arrival counters follow the attention tickets
+    dw.sel_cnt.fill_(-7)
+    t0 = time.time()
+    dw.decode_fused(); _sync()
+    took = time.time() - t0
+    _say(f"    step with a stuck segment took {took:.2f} s")
+    assert took < 5.0
+    assert dw.status() == 1
+    cnt = dw.sel_cnt.cpu().numpy()
+    assert cnt[stuck] == -7                                       # nobody selected for the stuck segment
+    others = [s for s in range(dw.nsel) if s != stuck]
+    assert np.array_equal(cnt[others], ref["sel_cnt"][others])
+    got = dw.out_f32().astype(np.float64)
+    G = wl.group
+    for s in others:
+        assert np.abs(got[0, s * G:(s + 1) * G] - ref["out"][0, s * G:(s + 1) * G]).max() <= TOL[wl.dtype]
+    if form == 2:
+        assert np.isnan(got[0, stuck * G:(stuck + 1) * G]).all()
+    dw.scribble(0x77)                                             # the contract: clear the counters, go on
+    dw.decode_fused()
+    _check_out(dw, ref["out"], ref["lse"], "after clearing the counters again")
+    assert dw.status() == 0
+    assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
 
 
 def test_one_launch_step_with_constant_keys_takes_the_tie_paths():
@@ -909,17 +932,14 @@ def test_one_launch_step_with_constant_keys_takes_the_tie_paths():
     ref = O.decode_step(wl, st)
     for h in (0, 2):
         assert np.array_equal(ref["sel_idx"][h, :ref["sel_cnt"][h]], np.arange(ref["sel_cnt"][h]))
-    for mode in (1, 3):
-        absb.set_tuning(absb.TUNE_STEP_LAUNCHES, mode)
-        try:
-            dw = _dev(wl)
-            dw.build()
-            dw.decode_fused()
-            _check_out(dw, ref["out"], ref["lse"], f"constant keys, enqueue mode {mode}")
-            assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
-            assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
-        finally:
-            absb.set_tuning(absb.TUNE_STEP_LAUNCHES, 0)
+    for mode in (1, 2, 3):
+        dw = _dev(wl, opts=dict(step_form=mode))
+        dw.build()
+        dw.decode_fused()
+        _check_out(dw, ref["out"], ref["lse"], f"constant keys, {FORMS[mode]}")
+        assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+        assert dw.status() == 0
 
 
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
