@@ -222,6 +222,14 @@ void orc_dequantize(int nseg, int d, const int64_t *off, const uint8_t *codes, c
  * The min term is the same for every block of the segment, so the ranking is that of
  * sum_c (u_c * scale_c) * code_jc.  w_c = u_c*scale_c is imaged on integers wq_c with the
  * largest |w_c| placed in [2^14, 2^15]; S_j = sum_c wq_c * code_jc is exact in int32. */
+/* Fixed-point image of one weight on the scale 2^ex: rint(w * 2^-ex) as an integer.  Inputs are
+ * finite by contract; a NaN weight next to finite ones (its magnitude never enters the maximum the
+ * scale comes from) images to 0 instead of reaching a float-to-integer conversion. */
+static int32_t fixed_image(float w, int ex) {
+    if (w != w) return 0;
+    return (int32_t)rintf(ldexpf(w, -ex));
+}
+
 void orc_score(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t *q /* [Bt][Hq][d] */,
                const uint8_t *codes, const float *qscale, const int64_t *off, int32_t *scores /* [total] */,
                int32_t *score_exp /* [Bt*Hkv] */, int32_t *wq_out /* [Bt*Hkv][d] or NULL */) {
@@ -244,7 +252,7 @@ void orc_score(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t *q /* [
             for (int ch = 0; ch < d; ++ch) wq[ch] = 0;
         } else {
             ex = ilogbf(A) - 14;
-            for (int ch = 0; ch < d; ++ch) wq[ch] = (int32_t)rintf(ldexpf(w[ch], -ex));
+            for (int ch = 0; ch < d; ++ch) wq[ch] = fixed_image(w[ch], ex);
         }
         score_exp[s] = ex;
         if (wq_out)
@@ -335,7 +343,7 @@ void orc_score_minmax(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t 
             for (int c = 0; c < d2; ++c) wq[c] = 0;
         } else {
             ex = ilogbf(A) - 14;
-            for (int c = 0; c < d2; ++c) wq[c] = (int32_t)rintf(ldexpf(w[c], -ex));
+            for (int c = 0; c < d2; ++c) wq[c] = fixed_image(w[c], ex);
         }
         score_exp[s] = ex;
         if (wq_out)
@@ -402,7 +410,7 @@ void orc_score_groupmax(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_
         int live = (A >= 0x1p-100f) && !isinf(A);
         if (live) ex = ilogbf(A) - 14;
         for (int g = 0; g < G; ++g) {
-            for (int ch = 0; ch < d; ++ch) wq[g][ch] = live ? (int32_t)rintf(ldexpf(w[g][ch], -ex)) : 0;
+            for (int ch = 0; ch < d; ++ch) wq[g][ch] = live ? fixed_image(w[g][ch], ex) : 0;
             float zs = live ? rintf(ldexpf(z[g], -ex)) : 0.0f;
             if (!(zs == zs)) zs = 0.0f;
             if (zs > 0x1p30f) zs = 0x1p30f;
@@ -806,7 +814,7 @@ void orc_score_variant(int dtype, int Bt, int Hq, int Hkv, int d, const uint16_t
             for (int ch = 0; ch < d; ++ch) wq[ch] = 0;
         } else {
             ex = ilogbf(A) - 14;
-            for (int ch = 0; ch < d; ++ch) wq[ch] = (int32_t)rintf(ldexpf(w[ch], -ex));
+            for (int ch = 0; ch < d; ++ch) wq[ch] = fixed_image(w[ch], ex);
         }
         score_exp[s] = ex;
         for (int64_t j = off[s]; j < off[s + 1]; ++j) {

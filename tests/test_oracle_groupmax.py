@@ -55,6 +55,39 @@ def test_offsets_are_the_pairwise_binary32_sums_on_the_groups_scale():
             assert int(zq[seg, g]) == want
 
 
+def test_offsets_equal_exact_rational_arithmetic_where_no_summation_order_can_matter():
+    """The binary32 sum of the zero-point products has a stated order (a reading, for reproducibility),
+    which the test above restates.  This one does not: queries and zero points are small dyadic
+    numbers, so every product and every partial sum in ANY order is exact in binary32, and z_g must
+    equal the sum in exact rational arithmetic; scaled by the group's exponent and rounded half to even
+    it must give the reported offsets.  A dropped channel, a wrong sign or head, or the scale of another
+    head fails here whatever the order."""
+    from fractions import Fraction
+    wl = _wl(seed=21)
+    rng = np.random.default_rng(22)
+    q = rng.integers(-8, 9, size=wl.q.shape).astype(np.float32) / 4.0            # multiples of 1/4 in [-2, 2]
+    wl.q = synth.f32_to_bits(q, wl.dtype)
+    st = O.build_centroids(wl)
+    st.qmin[:] = (rng.integers(-64, 65, size=st.qmin.shape) / 8.0).astype(np.float32)   # multiples of 1/8 in [-8, 8]
+    st.qscale[:] = (2.0 ** rng.integers(-6, -2, size=st.qscale.shape)).astype(np.float32)
+    s, ex, wq, zq = O.score_groupmax(wl, st, want_weights=True)
+    G, d = wl.group, wl.head_dim
+    for seg in range(wl.batch * wl.num_kv_heads):
+        b, h = divmod(seg, wl.num_kv_heads)
+        for g in range(G):
+            z = sum(Fraction(float(q[b, h * G + g, c])) * Fraction(float(st.qmin[seg, c])) for c in range(d))
+            scaled = z / Fraction(2) ** int(ex[seg])
+            lo = scaled.numerator // scaled.denominator                          # floor
+            frac = scaled - lo
+            want = lo + (1 if frac > Fraction(1, 2) or (frac == Fraction(1, 2) and lo % 2 == 1) else 0)
+            want = max(-2 ** 30, min(2 ** 30, want))
+            assert int(zq[seg, g]) == want, (seg, g)
+            # and the weights on the same scale, exactly
+            for c in range(0, d, 17):
+                w = Fraction(float(q[b, h * G + g, c])) * Fraction(float(st.qscale[seg, c])) / Fraction(2) ** int(ex[seg])
+                assert w.denominator == 1 and int(wq[seg, g, c]) == w.numerator
+
+
 def test_score_is_within_the_rounding_bound_of_the_fp64_maximum_over_dequantized_centroids():
     wl = _wl(seed=21)
     st = O.build_centroids(wl)
