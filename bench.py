@@ -415,7 +415,7 @@ def run_calibration(args):
           f"sit in runs of {list(roles)} consecutive positions in every sample (head roles are a property of the "
           f"'model'); 8 calibration samples (seeds 300-307), 4 held-out samples (seeds 400-403).\n")
     t0 = time.perf_counter()
-    per_sample = np.stack([calibrate.measure_recall(sample(300 + i), cand) for i in range(8)])
+    per_sample = np.concatenate([calibrate.measure_recall(sample(300 + i), cand) for i in range(8)])
     torch.cuda.synchronize()
     print(f"Recall(h, B), mean over the calibration samples ({time.perf_counter() - t0:.1f} s for 8 samples x "
           f"{len(cand)} candidates, generation included):\n")
@@ -424,7 +424,8 @@ def run_calibration(args):
     print("|---|" + "---|" * len(cand))
     for h in range(8):
         print(f"| {h} ({roles[h]}) | " + " | ".join(f"{mean[h, k]:.3f}" for k in range(len(cand))) + " |")
-    held = np.stack([calibrate.measure_recall(sample(400 + i), cand) for i in range(4)]).mean(axis=0)   # [Hkv, cand]
+    _, held = absb.absb_assign_block_sizes(np.concatenate([calibrate.measure_recall(sample(400 + i), cand) for i in range(4)]),
+                                           cand, 1.0)                 # the library's means over the held-out samples: [Hkv, cand]
     print("\nEq. (2) assignments and their recall on the held-out samples (mean over heads), against uniform sizes:\n")
     print("| assignment | block sizes | mean block size | blocks per 1K tokens (mean over heads) | held-out recall |")
     print("|---|---|---|---|---|")

@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libabsb.so")
+# ABSB_LIB names another build of the same library (the host-sanitizer build of tests/sanitized.py)
+LIB_PATH = os.environ.get("ABSB_LIB") or os.path.join(_HERE, "libabsb.so")
 
 F16, BF16 = 0, 1
 REPR_MEAN, REPR_MINMAX = 0, 1

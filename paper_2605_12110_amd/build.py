@@ -37,6 +37,11 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# host-side sanitizers (the device pass is left alone: -Xarch_host applies each flag to the host compile only)
+_HOST_SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+                  "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
 def _compile(name: str, extra) -> str:
     obj = os.path.join(_OBJ, name.replace(".hip", ".o"))
     cmd = [_hipcc(), *_COMMON, *extra, "-c", os.path.join(_CSRC, name), "-o", obj]
@@ -47,6 +52,24 @@ def _compile(name: str, extra) -> str:
     if out.strip():
         sys.stderr.write(out + "\n")
     return obj
+
+
+def build_sanitized(jobs: int = 8) -> str:
+    """libabsb_san.so: the same sources with AddressSanitizer + UndefinedBehaviorSanitizer on the HOST
+    code (argument validation, planning, workspace carving, Eq. (2)), for CPU-only test runs under the
+    clang sanitizer runtime.  Returns its path."""
+    global _OBJ, LIB_PATH
+    keep = (_OBJ, LIB_PATH)
+    _OBJ, LIB_PATH = os.path.join(_HERE, "_build_san"), os.path.join(_HERE, "libabsb_san.so")
+    try:
+        os.makedirs(_OBJ, exist_ok=True)
+        with ThreadPoolExecutor(max_workers=jobs) as ex:
+            objs = list(ex.map(lambda kv: _compile(kv[0], [*kv[1], *_HOST_SANITIZE]), _SOURCES.items()))
+        subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-Xarch_host", "-fsanitize=address",
+                               "-Xarch_host", "-fsanitize=undefined", "-shared-libsan", *objs, "-o", LIB_PATH])
+        return LIB_PATH
+    finally:
+        _OBJ, LIB_PATH = keep
 
 
 def build_library(force: bool = True, jobs: int = 8) -> str:

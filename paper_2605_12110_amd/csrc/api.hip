@@ -429,23 +429,33 @@ int absb_head_recall(const absb_layer* layer, const absb_batch* batch, const flo
 int absb_assign_block_sizes(int32_t n_samples, int32_t n_heads, int32_t n_cand, const float* recall_host,
                             const int32_t* cand, double tau, int32_t* block_size_out, double* mean_out) {
   if (!recall_host || !cand || !block_size_out) return ABSB_ERR_NULL;
-  if (n_samples < 1 || n_heads < 1 || n_cand < 1 || !(tau >= 0.0)) return ABSB_ERR_BAD_SHAPE;
-  for (int k = 0; k < n_cand; ++k) {
-    if (!is_pow2(cand[k]) || cand[k] < 8 || cand[k] > 128) return ABSB_ERR_BAD_BLOCK_SIZE;
-    if (k > 0 && cand[k] <= cand[k - 1]) return ABSB_ERR_BAD_SHAPE;
+  if (n_samples < 1 || n_heads < 1 || n_cand < 1 || n_cand > 64 || !(tau >= 0.0)) return ABSB_ERR_BAD_SHAPE;
+  if (!is_pow2(cand[0]) || cand[0] < 8 || cand[0] > 128) return ABSB_ERR_BAD_BLOCK_SIZE;
+  for (int k = 1; k < n_cand; ++k) {
+    if (!is_pow2(cand[k]) || cand[k] > 128) return ABSB_ERR_BAD_BLOCK_SIZE;
+    if (cand[k] <= cand[k - 1]) return ABSB_ERR_BAD_SHAPE;
   }
+  // Eq. (2), head by head.  First Recall(h, B) for every candidate: the mean over the samples (which
+  // are whatever the caller measured recall on: one row per request of every calibration input),
+  // accumulated in binary64 in sample order.  Then the candidates are tried from the largest down:
+  // the set {B : Recall(h, B) >= tau * Recall(h, B_min)} is read as written, so the first one that
+  // passes is its maximum, whatever the candidates below it do; B_min is in the set for tau <= 1 and
+  // is the answer when nothing passes.
+  const size_t row = (size_t)n_heads * n_cand;
   for (int h = 0; h < n_heads; ++h) {
-    double base = 0.0;
-    int best = 0;
+    double recall_of[64];
+    for (int k = 0; k < n_cand; ++k) recall_of[k] = 0.0;
+    const float* sample = recall_host + (size_t)h * n_cand;
+    for (int i = 0; i < n_samples; ++i, sample += row)
+      for (int k = 0; k < n_cand; ++k) recall_of[k] += (double)sample[k];
     for (int k = 0; k < n_cand; ++k) {
-      double acc = 0.0;
-      for (int i = 0; i < n_samples; ++i) acc += (double)recall_host[((size_t)i * n_heads + h) * n_cand + k];
-      const double mean = acc / (double)n_samples;
-      if (mean_out) mean_out[(size_t)h * n_cand + k] = mean;
-      if (k == 0) base = mean;
-      if (mean >= tau * base) best = k;  // the smallest candidate always qualifies for tau <= 1
+      recall_of[k] /= (double)n_samples;
+      if (mean_out) mean_out[(size_t)h * n_cand + k] = recall_of[k];
     }
-    block_size_out[h] = cand[best];
+    const double floor_of_head = tau * recall_of[0];
+    int chosen = n_cand - 1;
+    while (chosen > 0 && !(recall_of[chosen] >= floor_of_head)) --chosen;
+    block_size_out[h] = cand[chosen];
   }
   return ABSB_OK;
 }

@@ -181,7 +181,7 @@ __device__ __forceinline__ int score_blocks_groupmax(const ScoreParams& p, int t
 #pragma unroll
     for (int g = 0; g < ABSB_MAX_GROUP; ++g) {
       int32_t wq = 0;
-      if (live) wq = (int32_t)__builtin_rintf(__builtin_ldexpf(w[g], -ex));
+      if (live && w[g] == w[g]) wq = (int32_t)__builtin_rintf(__builtin_ldexpf(w[g], -ex));  // a NaN weight images to 0
       const uint32_t wo = (uint32_t)(wq + 32768);
 #pragma unroll
       for (int k = 0; k < SCORE_PLANES; ++k) {
@@ -342,7 +342,7 @@ __device__ __forceinline__ int score_blocks(const ScoreParams& p, int t, int j0,
   if (live) ex = (int)((bitcast<uint32_t>(A) >> 23) & 0xffu) - 127 - 14;
   if (tid < W) {
     int32_t wq = 0;
-    if (live) wq = (int32_t)__builtin_rintf(__builtin_ldexpf(w, -ex));
+    if (live && w == w) wq = (int32_t)__builtin_rintf(__builtin_ldexpf(w, -ex));  // a NaN weight images to 0
     // biased weight in [0, 2^16]; its five 4-bit digits, packed over 8 consecutive values
     const uint32_t wo = (uint32_t)(wq + 32768);
     const int sh = 4 * (tid & 7);

@@ -145,6 +145,36 @@ class DeviceWorkload:
         off = absb.absb_status_offset(self.layer, self.batch)
         return int(self.workspace[off:off + 4].view(torch.int32).item())
 
+    def check_device_contents(self, lists: bool = False) -> None:
+        """Debug aid: the library trusts what device arrays hold (a page index out of range is undefined
+        behaviour there).  This copies the index arrays back and checks them on the host: lengths and
+        budgets equal to their host twins, offsets equal to the plan's, every page-table entry a context
+        reaches inside the caches, and (`lists`) every list well formed: counts within the list width,
+        indices ascending and inside their segments, -1 behind them.  Raises AssertionError naming the
+        first violation.  Synchronises; not for timed code."""
+        wl = self.wl
+        lens = np.asarray(self.batch.seq_lens_host, dtype=np.int64)
+        assert np.array_equal(self.seq_lens.cpu().numpy(), lens), "seq_lens differs from seq_lens_host"
+        assert np.array_equal(self.budget.cpu().numpy(), np.asarray(self.batch.budget_host)), "budget differs from budget_host"
+        assert np.array_equal(self.cent_off.cpu().numpy(), self.plan.cent_off), "cent_off differs from absb_plan's"
+        pt = self.page_table.cpu().numpy()
+        npages = int(self.k_cache.shape[0])
+        for b, L in enumerate(lens):
+            used = pt[b, :-(-int(L) // wl.page_size)]
+            assert used.size == 0 or (used.min() >= 0 and used.max() < npages), f"page table of request {b} leaves the cache"
+        if lists:
+            cnt, idx = self.sel_cnt.cpu().numpy(), self.sel_idx.cpu().numpy()
+            rk = self.nsel // self.nseg
+            for t in range(self.nsel):
+                s = (t // (wl.num_kv_heads * rk)) * wl.num_kv_heads + (t % (wl.num_kv_heads * rk)) // rk
+                b, h = divmod(s, wl.num_kv_heads)
+                n = -(-int(lens[b]) // int(self.block_size[h]))
+                k = int(cnt[t])
+                assert 0 <= k <= min(n, self.sel_stride), f"sel_cnt[{t}] = {k}"
+                row = idx[t, :k]
+                assert k == 0 or (row.min() >= 0 and row.max() < n and np.all(np.diff(row) > 0)), f"sel_idx[{t}] malformed"
+                assert np.all(idx[t, k:] == -1), f"sel_idx[{t}] not padded"
+
     # -- results back on the host
     def out_f32(self) -> np.ndarray:
         return self.out.float().cpu().numpy()

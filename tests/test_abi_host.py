@@ -260,6 +260,23 @@ def test_block_size_assignment_rule_matches_the_oracle_on_the_host():
     with pytest.raises(absb.AbsbError) as e:
         absb.absb_assign_block_sizes(rec, [8, 16, 32, 64, 96], 0.9)
     assert e.value.status == absb.ERR_BAD_BLOCK_SIZE
+
+
+def test_block_size_assignment_rule_on_cases_worked_by_hand():
+    """Eq. (2) on tables small enough to do in the head (two samples, exact binary fractions).  Head 0
+    falls off at 32; head 1 dips at 16 and recovers at 32 (the set is read as written: its maximum wins);
+    head 2 never keeps the share, so B_min it is; head 3 keeps it everywhere."""
+    cand = [8, 16, 32, 64]
+    sample0 = [[1.0, 1.0, 0.5, 0.25], [0.5, 0.25, 0.5, 0.125], [1.0, 0.5, 0.5, 0.5], [0.5, 0.5, 0.5, 0.5]]
+    sample1 = [[0.5, 0.5, 0.5, 0.25], [1.0, 0.25, 0.75, 0.125], [1.0, 0.5, 0.25, 0.5], [1.0, 1.0, 1.0, 1.0]]
+    rec = np.array([sample0, sample1], np.float32)
+    sizes, mean = absb.absb_assign_block_sizes(rec, cand, 0.75)
+    assert np.array_equal(mean, [[0.75, 0.75, 0.5, 0.25], [0.75, 0.25, 0.625, 0.125], [1.0, 0.5, 0.375, 0.5],
+                                 [0.75, 0.75, 0.75, 0.75]])
+    assert sizes.tolist() == [16, 32, 8, 64]
+    # tau = 1: only candidates that lose nothing; tau = 0: the largest candidate, always
+    assert absb.absb_assign_block_sizes(rec, cand, 1.0)[0].tolist() == [16, 8, 8, 64]
+    assert absb.absb_assign_block_sizes(rec, cand, 0.0)[0].tolist() == [64, 64, 64, 64]
     with pytest.raises(absb.AbsbError) as e:
         absb.absb_assign_block_sizes(rec, [8, 32, 16, 64, 128], 0.9)
     assert e.value.status == absb.ERR_BAD_SHAPE

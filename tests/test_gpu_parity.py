@@ -164,6 +164,7 @@ def run_all_stages(wl, name, block_repr=O.MEAN, per_query_head=False, group_max=
             assert np.array_equal(outs[mode], again), f"{FORMS[mode]}: not deterministic, or the list request changes the output"
     assert np.array_equal(outs[1], outs[3]), "pipelined and per-stage forms disagree"
     assert np.array_equal(first, outs[absb.absb_step_form_used(dw.layer, dw.batch)]), "default form"
+    dw.check_device_contents(lists=True)      # the holder's host-side bounds checks agree with all of that
     dw.scribble(0x99)     # the stand-alone stages do not keep the other counters: clear them again
     _say("    fused: selection bit-exact in every enqueue form, outputs within tolerance, deterministic")
     return dw, st, ref
@@ -364,6 +365,26 @@ def test_many_splits_per_segment_and_split_counters_left_at_zero():
     dw.out.fill_(float("nan")); dw.lse.fill_(float("nan"))
     dw.sparse_decode()
     _check_out(dw, ref["out"], ref["lse"], "128 splits, stand-alone call on a scribbled workspace")
+
+
+def test_host_side_bounds_checks_of_the_holder_catch_bad_device_contents():
+    """The debug aid that stands in for device-side asserts: planted violations are named on the host."""
+    import torch
+    wl = synth.tiny_workload(seed=61, Bt=2, Hq=8, Hkv=2, P=16, seq_lens=(100, 50), block_size=(8, 32), budget=(32, 32))
+    dw = _dev(wl)
+    dw.build(); dw.decode_fused(); _sync()
+    dw.check_device_contents(lists=True)
+    keep = dw.page_table.clone()
+    dw.page_table[1, 2] = int(dw.k_cache.shape[0])               # one page past the cache
+    with pytest.raises(AssertionError, match="page table of request 1"):
+        dw.check_device_contents()
+    dw.page_table.copy_(keep)
+    dw.sel_idx[3, 0] = 10 ** 6
+    with pytest.raises(AssertionError, match="sel_idx"):
+        dw.check_device_contents(lists=True)
+    dw.seq_lens[0] += 1
+    with pytest.raises(AssertionError, match="seq_lens"):
+        dw.check_device_contents()
 
 
 def test_stream_read_helper_runs_and_leaves_its_sink_alone():
