@@ -7,8 +7,16 @@ batch of synthetic input that is already resident in HBM.  The default workload 
 one: batch 1, 128K context, Llama-3.1-8B-shaped layer (32 query / 8 KV heads, d = 128, fp16),
 per-head block sizes from {8,...,128}, budget 4096 tokens.
 
-Cold-cache discipline: the step cycles over R independent layer instances (own KV pages, codes,
-query) so that no step re-reads lines the previous ones left in L2 / Infinity Cache.
+Cold-cache discipline: the step cycles over R resident copies of the layer (own KV pages, codes,
+query, workspace: same contents at other addresses), with R sized by the bytes a step TOUCHES:
+R x useful bytes >= 2 x the 256 MB last-level cache, so that no step finds lines that an earlier
+visit of the same copy left in L2 or in the Infinity Cache.  All copies hold the same data, so one
+block-size table, one selection and one byte count describe every step; copy 0 is checked against
+the oracle after the timed loop and every other copy against copy 0.
+
+Timing: the K timed steps are captured into a HIP graph (kernels only) and replayed between two
+events on the launch stream, so the figure is the GPU's step time, not the Python loop's call
+rate; the eager loop is timed too and reported next to it.
 
 Default run: prints ONE JSON line.  `value` = useful (algorithmic) bytes per step / step time, GB/s.
 `--matrix`: runs every benchmark configuration (and the config-5 budget sweep with selection
@@ -30,12 +38,34 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 METRIC = "decode attention µs/step/layer + achieved HBM GB/s at 128K ctx (8B-shaped GQA)"
-# HBM bytes moved by one launch of the attention kernel on the headline workload, from rocprofv3
-# --pmc (FETCH_SIZE, then WRITE_SIZE, each scaled by a 1 GiB copy in the same run): 17.59 MB read
-# (K/V rows, lists, page table, the merging groups' re-read of the partials) + 0.56 MB written.
-# Source: profiles/decode_fused_config3_hbm_counters.md
-HEADLINE_TRAFFIC_BYTES = 18_150_000
+LAST_LEVEL_CACHE_BYTES = 256 << 20   # Infinity Cache; the L2s (8 x 4 MB) are smaller
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "decode_fused_config3_hbm_counters.md")
 BASE_SEED = {1: 0, 2: 1, 3: 2, 4: 3, 5: 4}
+
+
+def kernel_sources_sha16():
+    """Hash of the library's sources: ties a counter measurement under profiles/ to the kernels it was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_2605_12110_amd", "csrc")
+    for name in sorted(os.listdir(src)):
+        h.update(open(os.path.join(src, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` on the headline workload as rocprofv3 --pmc counted them
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size), from the committed profile summary,
+    or None when that summary was taken on other kernel sources than the ones in this tree."""
+    import re
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch\[" + re.escape(kernel) + r"\]\s*=\s*(\d+)\s+kernel_sources_sha16\s*=\s*([0-9a-f]{16})", text)
+    if not m or m.group(2) != kernel_sources_sha16():
+        return None
+    return int(m.group(1))
 
 
 def useful_bytes(wl, plan_off, sel_cnt, vectors=1, per_query_head=False):
@@ -69,7 +99,8 @@ def useful_bytes(wl, plan_off, sel_cnt, vectors=1, per_query_head=False):
 
 
 def time_loop(fn, n_warm, n_steps):
-    """Average milliseconds per call of fn(i), timed with events on the launch stream."""
+    """Average milliseconds per call of fn(i) in an eager loop, timed with events on the launch stream;
+    also the host's wall time per call."""
     import torch
     for i in range(n_warm):
         fn(i)
@@ -85,8 +116,48 @@ def time_loop(fn, n_warm, n_steps):
     return ev0.elapsed_time(ev1) / n_steps, wall
 
 
+def time_graph(fn, period, n_warm, n_steps):
+    """Average milliseconds per call of fn(i), i = 0 .. n_steps-1 (fn only depends on i % period), with
+    the calls captured into HIP graphs and replayed between two events on the launch stream: exactly
+    n_steps calls are timed, as floor(n_steps / period) replays of a graph of `period` calls plus one
+    graph holding the remainder.  The calls enqueue kernels only (no memset, allocation or
+    synchronisation), which is what a captured graph may hold."""
+    import torch
+    for i in range(n_warm):
+        fn(i)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+
+    def capture(count, first):
+        g = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for i in range(count):
+                    fn(first + i)
+        torch.cuda.current_stream().wait_stream(side)
+        return g
+    full, rem = divmod(n_steps, period)
+    g_full = capture(period, 0) if full else None
+    g_rem = capture(rem, full * period) if rem else None
+    for g in (g_full, g_rem):                     # first replay uploads the graph: not timed
+        if g is not None:
+            g.replay()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(full):
+        g_full.replay()
+    if g_rem is not None:
+        g_rem.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / n_steps
+
+
 def per_step_percentiles(fn, n_steps):
-    """Per-step durations from an event between consecutive steps: (p10, median, p90) in us."""
+    """Per-step durations from an event between consecutive eager steps: (p10, median, p90) in us
+    (each includes the event's own cost, about 2-3 us)."""
     import torch
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_steps + 1)]
     torch.cuda.synchronize()
@@ -99,65 +170,63 @@ def per_step_percentiles(fn, n_steps):
     return float(np.percentile(d, 10)), float(np.median(d)), float(np.percentile(d, 90))
 
 
-def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, uniform_block=None, max_bytes=24 << 30,
-                   block_repr=0, selection=0, opts=None):
-    """R independent layer instances of a workload, resident on the GPU, centroid stores built."""
+def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, uniform_block=None, max_bytes=64 << 30,
+                   block_repr=0, selection=0, opts=None, block_sizes=None):
+    """R resident copies of one workload (the same data at R places in HBM), the centroid store built
+    once and copied.  R (`rotate`, 0 = auto) is sized by what a step touches: R x useful bytes of a
+    step >= 2 x the last-level cache, at most 256 copies and `max_bytes` of device memory."""
     import torch
     from paper_2605_12110_amd import synth
     from paper_2605_12110_amd.device import DeviceWorkload
     kw = dict(context=context, batch=batch, budget=budget, uniform_block=uniform_block)
+    if block_sizes is not None:
+        kw["block_sizes"] = block_sizes
     wl0 = synth.make_workload(config, **kw)
+    first = DeviceWorkload(wl0, block_repr=block_repr, selection=selection, opts=opts)
+    first.build()
+    first.decode_fused()
+    torch.cuda.synchronize()
+    ub = useful_bytes(wl0, first.plan.cent_off, first.sel_cnt.cpu().numpy(), block_repr + 1, selection == 1)
     R = rotate
     if R <= 0:
-        R = max(1, min(8, -(-(2 << 30) // wl0.kv_bytes())))
-    R = max(1, min(R, max_bytes // max(wl0.kv_bytes(), 1)))
-    insts = [DeviceWorkload(wl0, block_repr=block_repr, selection=selection, opts=opts)]
-    for r in range(1, R):
-        wl = synth.make_workload(config, seed=BASE_SEED[config] + 100 * r, **kw)
-        insts.append(DeviceWorkload(wl, block_repr=block_repr, selection=selection, opts=opts))
-        wl.k_cache = wl.v_cache = None      # free the host copies of the extra instances
-    for dw in insts:
-        dw.build()
+        R = -(-2 * LAST_LEVEL_CACHE_BYTES // max(ub["total"], 1)) + 1
+    per_copy = 2 * first.k_cache.numel() * 2 + first.workspace.numel() + first.codes.numel()
+    R = max(1, min(R, 256, max_bytes // max(per_copy, 1)))
+    insts = [first] + [first.clone() for _ in range(R - 1)]
     torch.cuda.synchronize()
-    return wl0, insts
+    return wl0, insts, ub
 
 
-def measure(wl0, insts, steps, warmup, stages=False, percentiles=False):
+def measure(wl0, insts, ub, steps, warmup, stages=True, percentiles=False):
+    """Times the fused step (graph replay and eager) and, with `stages`, every entry point on its own."""
     import torch
+    from paper_2605_12110_amd import absb
     R = len(insts)
-    ub = []
-    for dw in insts:        # one untimed step per instance: selection sizes for the byte count
-        dw.decode_fused()
-        torch.cuda.synchronize()
-        ub.append(useful_bytes(dw.wl, dw.plan.cent_off, dw.sel_cnt.cpu().numpy(), dw.layer.block_repr + 1,
-                               dw.layer.selection == 1))
-    mean_bytes = {k: float(np.mean([u[k] for u in ub])) for k in ub[0]}
 
     def step(i):
         insts[i % R].decode_fused(want_sel=False)
 
-    ms, wall_ms = time_loop(step, warmup, steps)
-    from paper_2605_12110_amd import absb
-    out = dict(ms=ms, wall_ms=wall_ms, bytes=mean_bytes, bytes0=ub[0], R=R,
-               form=absb.absb_step_form_used(insts[0].layer, insts[0].batch))
-    out["launches"] = 3 if out["form"] == absb.STEP_PER_STAGE else 1
-    # dominant kernel on its own: attention over the fused step's selection (split-K partials and
-    # their merge happen inside the one kernel)
-    # (every instance has completed a fused step on its workspace, so its split counters are zero and
-    # the stage is the attention kernel alone, as in the fused step)
+    ms = time_graph(step, R, warmup, steps)
+    ms_eager, wall_ms = time_loop(step, min(warmup, 10), steps)
+    form = absb.absb_step_form_used(insts[0].layer, insts[0].batch)
+    out = dict(ms=ms, ms_eager=ms_eager, wall_ms=wall_ms, bytes=ub, R=R, form=form,
+               launches=3 if form == absb.STEP_PER_STAGE else 1)
+    # every instance has completed a fused step on its workspace, so its split counters are zero and
+    # absb_sparse_decode with that promise is exactly one launch of the attention kernel, on the
+    # fused step's own selection
     for dw in insts:
+        dw.decode_fused()
         dw.batch.opts.counters_zero = 1
+    torch.cuda.synchronize()
     try:
-        ms_dec, _ = time_loop(lambda i: insts[i % R].sparse_decode(), warmup, steps)
+        st = {"sparse_decode_us": time_graph(lambda i: insts[i % R].sparse_decode(), R, warmup, steps) * 1e3}
     finally:
         for dw in insts:
             dw.batch.opts.counters_zero = 0
-    out["ms_decode"] = ms_dec
-    st = {"sparse_decode_us": ms_dec * 1e3}
     if stages:
-        ms_sc, _ = time_loop(lambda i: insts[i % R].score(), warmup, steps)
-        ms_tk, _ = time_loop(lambda i: insts[i % R].topk(), warmup, steps)
-        st.update(score_us=ms_sc * 1e3, topk_us=ms_tk * 1e3)
+        st["score_us"] = time_graph(lambda i: insts[i % R].score(), R, warmup, steps) * 1e3
+        st["topk_us"] = time_graph(lambda i: insts[i % R].topk(), R, warmup, steps) * 1e3
+    out["ms_decode"] = st["sparse_decode_us"] * 1e-3
     out["stages"] = st
     if percentiles:
         out["p10_med_p90_us"] = per_step_percentiles(step, min(steps, 200))
@@ -187,25 +256,34 @@ def _time_oracle(fn, seconds, max_n=2000):
             return el / n, n, el
 
 
-def verify_against_oracle(dw, ref):
-    """One more step of instance `dw`, checked against the oracle's step on the same inputs: the
-    number above is only worth reporting if the timed path computes the right thing."""
+def verify_against_oracle(insts, ref):
+    """One more step of every resident copy: copy 0 against the oracle's step on the same inputs
+    (selection bit for bit, output within tolerance), every other copy against copy 0 (same inputs,
+    so the same bits).  The number above is only worth reporting if the timed path computes the right
+    thing, on every copy it was timed on."""
     import torch
-    dw.sel_idx.fill_(-7)
-    dw.out.fill_(float("nan"))
-    dw.decode_fused()
+    for dw in insts:
+        dw.sel_idx.fill_(-7)
+        dw.out.fill_(float("nan"))
+        dw.decode_fused()
     torch.cuda.synchronize()
+    dw = insts[0]
     K = dw.sel_stride
     sel_ok = bool(np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"]) and
                   np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :K]))
     err = float(np.abs(dw.out_f32().astype(np.float64) - ref["out"]).max())
     tol = 2e-3 if dw.wl.dtype == 0 else 1e-2
-    ok = sel_ok and err <= tol and dw.status() == 0
-    if not ok:
+    status = max(d.status() for d in insts)
+    same = all(torch.equal(d.sel_idx, dw.sel_idx) and torch.equal(d.sel_cnt, dw.sel_cnt) and torch.equal(d.out, dw.out)
+               for d in insts[1:])
+    if not (sel_ok and err <= tol and status == 0 and same):
         raise SystemExit(f"bench.py: the timed path disagrees with the oracle (selection bit-exact: {sel_ok}, "
-                         f"max |out - oracle| = {err:.3e}, tolerance {tol:.0e}, status word {dw.status()})")
+                         f"max |out - oracle| = {err:.3e}, tolerance {tol:.0e}, status word {status}, "
+                         f"all {len(insts)} copies agree: {same})")
     return {"selection_bit_exact": sel_ok, "max_abs_err_out": float(f"{err:.3e}"), "tolerance": tol,
-            "what": "one fused step of instance 0 after the timed loop against the oracle's step"}
+            "copies_checked": len(insts),
+            "what": "one fused step of every resident copy after the timed loops: copy 0 against the oracle's step, "
+                    "the others bit for bit against copy 0"}
 
 
 def cpu_baseline(wl0, bytes0, seconds=10.0, block_repr=0, check=None, selection=0):
@@ -256,9 +334,9 @@ def run_matrix(args):
           "decode stage us | decode GB/s | oracle us/step (cores) |")
     print("|---|---|---|---|---|---|---|---|---|---|---|", flush=True)
     for cfg in (1, 2, 3, 4):
-        wl0, insts = make_instances(cfg)
-        m = measure(wl0, insts, args.steps, args.warmup, percentiles=True)
-        cb = cpu_baseline(wl0, m["bytes0"], seconds=3.0)
+        wl0, insts, ub = make_instances(cfg)
+        m = measure(wl0, insts, ub, args.steps, args.warmup, stages=False, percentiles=True)
+        cb = cpu_baseline(wl0, m["bytes"], seconds=3.0)
         gb = m["bytes"]["total"] / (m["ms"] * 1e-3) / 1e9
         dgb = m["bytes"]["decode"] / (m["ms_decode"] * 1e-3) / 1e9
         p = m["p10_med_p90_us"]
@@ -269,8 +347,8 @@ def run_matrix(args):
         del insts
         torch.cuda.empty_cache()
     # dense reference through the same kernels: budget >= context on the headline cache
-    wl0, insts = make_instances(3, budget=131072, rotate=2)
-    m = measure(wl0, insts, 50, 5)
+    wl0, insts, ub = make_instances(3, budget=131072, rotate=2)
+    m = measure(wl0, insts, ub, 50, 5, stages=False)
     dgb = m["bytes"]["decode"] / (m["ms_decode"] * 1e-3) / 1e9
     print(f"| config 3, budget = context (dense read of 512 MiB) | 1 | f16 | {m['launches']} | {m['bytes']['total'] / 1e6:.1f} | "
           f"{m['ms'] * 1e3:.1f} | {m['bytes']['total'] / (m['ms'] * 1e-3) / 1e9:.0f} | "
@@ -283,8 +361,8 @@ def run_matrix(args):
     print("| workload | useful MB/step | us/step | GB/s | planted-token recall: max-min / mean |")
     print("|---|---|---|---|---|", flush=True)
     for cfg in (1, 2, 3, 4):
-        wl0, insts = make_instances(cfg, block_repr=1)
-        m = measure(wl0, insts, args.steps, args.warmup)
+        wl0, insts, ub = make_instances(cfg, block_repr=1)
+        m = measure(wl0, insts, ub, args.steps, args.warmup, stages=False)
         dw = insts[0]
         dw.decode_fused()
         torch.cuda.synchronize()
@@ -302,8 +380,8 @@ def run_matrix(args):
     print("| workload | launches/step | useful MB/step | us/step | GB/s | planted-token recall: per query head / per group |")
     print("|---|---|---|---|---|---|", flush=True)
     for cfg in (1, 2, 3, 4):
-        wl0, insts = make_instances(cfg, selection=1)
-        m = measure(wl0, insts, args.steps, args.warmup)
+        wl0, insts, ub = make_instances(cfg, selection=1)
+        m = measure(wl0, insts, ub, args.steps, args.warmup, stages=False)
         dw = insts[0]
         dw.decode_fused()
         torch.cuda.synchronize()
@@ -325,8 +403,8 @@ def run_matrix(args):
     print("| workload | launches/step | useful MB/step | us/step | GB/s | planted-token recall: group maximum / group sum |")
     print("|---|---|---|---|---|---|", flush=True)
     for cfg in (1, 2, 3, 4):
-        wl0, insts = make_instances(cfg, selection=2)
-        m = measure(wl0, insts, args.steps, args.warmup)
+        wl0, insts, ub = make_instances(cfg, selection=2)
+        m = measure(wl0, insts, ub, args.steps, args.warmup, stages=False)
         dw = insts[0]
         dw.decode_fused()
         torch.cuda.synchronize()
@@ -377,10 +455,10 @@ def run_matrix(args):
     print("| blocks | budget | us/step | GB/s | planted-token recall | attention recall (mean) | max abs err vs dense | "
           "rel L2 err vs dense |")
     print("|---|---|---|---|---|---|---|---|", flush=True)
-    for label, ub in (("uniform 16", 16), ("adaptive", None)):
+    for label, ublock in (("uniform 16", 16), ("adaptive", None)):
         for T in (1024, 2048, 4096, 8192):
-            wl0, insts = make_instances(5, budget=T, uniform_block=ub, rotate=2)
-            m = measure(wl0, insts, args.steps, args.warmup)
+            wl0, insts, ub = make_instances(5, budget=T, uniform_block=ublock, rotate=0)
+            m = measure(wl0, insts, ub, args.steps, args.warmup, stages=False)
             dw = insts[0]
             dw.decode_fused()
             torch.cuda.synchronize()
@@ -445,7 +523,8 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", type=int, default=3, help="workload recipe 1..5 (3 = headline)")
-    ap.add_argument("--rotate", type=int, default=0, help="layer instances cycled through (0 = auto: >= 2 GiB of KV)")
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="resident copies cycled through (0 = auto: enough that a rotation touches 2 x the last-level cache)")
     ap.add_argument("--context", type=int, default=None)
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--budget", type=int, default=None)
@@ -454,11 +533,12 @@ def main():
                          "(default) or by their maximum, or nobody (one selection per query head)")
     ap.add_argument("--repr", choices=("mean", "minmax"), default="mean",
                     help="block representation: mean pooling (headline) or channel-wise maxima and minima")
-    ap.add_argument("--launches", type=int, default=0, choices=(0, 1, 2, 3),
-                    help="how absb_decode_fused is enqueued: 0 = the library's choice by shape (default), "
-                         "1 = the whole step in one launch, 3 = one launch per stage")
+    ap.add_argument("--form", type=int, default=0, choices=(0, 1, 2, 3),
+                    help="how absb_decode_fused is enqueued (absb_step_form): 0 = the library's choice by shape "
+                         "(default), 1 = pipelined one-launch step, 2 = one-launch step of units, 3 = one launch per stage")
+    ap.add_argument("--split-tokens", type=int, default=0, help="absb_launch_opts.split_tokens (0 = the library's choice)")
+    ap.add_argument("--unit-tokens", type=int, default=0, help="absb_launch_opts.unit_tokens (0 = the library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--stages", action="store_true", help="also time each entry point on its own")
     ap.add_argument("--matrix", action="store_true", help="run all configurations and the config-5 sweep; markdown out")
     ap.add_argument("--calibrate", action="store_true",
                     help="per-head block-size calibration (Eq. 2) on synthetic samples, with held-out validation; markdown out")
@@ -494,18 +574,31 @@ def main():
         return
 
     block_repr = 1 if args.repr == "minmax" else 0
-    wl0, insts = make_instances(args.config, context=args.context, batch=args.batch, budget=args.budget,
-                                rotate=args.rotate, block_repr=block_repr,
-                                selection={"group": 0, "per-query-head": 1, "group-max": 2}[args.select],
-                                opts=dict(step_form=args.launches))
-    m = measure(wl0, insts, args.steps, args.warmup, stages=args.stages, percentiles=True)
-    ms, mean_bytes, R = m["ms"], m["bytes"], m["R"]
-    gbps = mean_bytes["total"] / (ms * 1e-3) / 1e9
-    dec_gbps = mean_bytes["decode"] / (m["ms_decode"] * 1e-3) / 1e9
+    selection = {"group": 0, "per-query-head": 1, "group-max": 2}[args.select]
+    wl0, insts, ub = make_instances(args.config, context=args.context, batch=args.batch, budget=args.budget,
+                                    rotate=args.rotate, block_repr=block_repr, selection=selection,
+                                    opts=dict(step_form=args.form, split_tokens=args.split_tokens, unit_tokens=args.unit_tokens))
+    m = measure(wl0, insts, ub, args.steps, args.warmup, stages=True, percentiles=True)
+    ms, R = m["ms"], m["R"]
+    gbps = ub["total"] / (ms * 1e-3) / 1e9
+    dec_gbps = ub["decode"] / (m["ms_decode"] * 1e-3) / 1e9
     ceiling = stream_read_ceiling()
     wl = wl0
     headline = (args.config == 3 and args.context is None and args.batch is None and args.budget is None
                 and block_repr == 0 and args.select == "group")
+    form_name = {absb.STEP_PIPELINED: "pipelined (one launch)", absb.STEP_UNITS: "units (one launch)",
+                 absb.STEP_PER_STAGE: "per stage (three launches)"}[m["form"]]
+    stages = {k: round(v, 3) for k, v in m["stages"].items()}
+    if headline:
+        # the same attention kernel on a budget that covers the context: a dense read of the layer's 512 MiB
+        d_wl, d_insts, d_ub = make_instances(3, budget=int(wl.seq_lens.max()), rotate=2)
+        for dw in d_insts:
+            dw.batch.opts.counters_zero = 1
+        d_ms = time_graph(lambda i: d_insts[i % 2].sparse_decode(), 2, 4, 20)
+        stages["dense_read_us"] = round(d_ms * 1e3, 2)
+        stages["dense_read_gbps"] = round(d_ub["decode"] / (d_ms * 1e-3) / 1e9, 1)
+        del d_insts
+        torch.cuda.empty_cache()
     result = {
         "metric": METRIC,
         "value": round(gbps, 2),
@@ -527,51 +620,58 @@ def main():
                         f"{args.repr} pooling, selection per {'query head' if args.select == 'per-query-head' else 'KV head'}"
                         f"{' (group maximum)' if args.select == 'group-max' else ''}",
             "entry_point": "absb_decode_fused",
+            "step_form": form_name,
             "launches_per_step": m["launches"],
-            "layer_instances_rotated": R,
+            "timing": "the timed steps captured into HIP graphs and replayed between two events on the launch stream",
+            "resident_copies_rotated": R,
+            "bytes_touched_per_rotation": int(R * ub["total"]),
+            "cache_state": f"cold: {R} copies x {ub['total'] / 1e6:.1f} MB touched per step = "
+                           f"{R * ub['total'] / LAST_LEVEL_CACHE_BYTES:.1f} x the 256 MB last-level cache between two visits of a copy",
             "resident_kv_bytes": int(sum(i.k_cache.numel() * 2 * 2 for i in insts)),
-            "useful_bytes_per_step": {k: int(v) for k, v in mean_bytes.items()},
+            "useful_bytes_per_step": {k: int(v) for k, v in ub.items()},
             "fraction_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-            "host_wall_us_per_step": round(m["wall_ms"] * 1e3, 2),
-            "us_per_step_p10_median_p90": [round(x, 2) for x in m["p10_med_p90_us"]],
-            "stages": {k: round(v, 3) for k, v in m["stages"].items()},
+            "eager_us_per_step": round(m["ms_eager"] * 1e3, 3),
+            "host_wall_us_per_step_eager": round(m["wall_ms"] * 1e3, 2),
+            "eager_us_per_step_p10_median_p90": [round(x, 2) for x in m["p10_med_p90_us"]],
+            "stages": stages,
         },
     }
     if m["launches"] == 1:
-        # the step is one launch of fused_step_kernel: the dominant kernel is the step itself
+        # the step is one launch: the dominant kernel is the step itself
+        kern = "fused_step_kernel" if m["form"] == absb.STEP_PIPELINED else "step_kernel"
         result["roofline"] = {
             "bound": "hbm",
-            "kernel": "fused_step_kernel (one absb_decode_fused call = one launch: estimation, selection, attention)",
+            "kernel": f"{kern} (one absb_decode_fused call = one launch: estimation, selection, attention)",
             "achieved": round(gbps, 2),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(gbps / HBM_PEAK_GBPS, 4),
-            "algorithmic_bytes_per_launch": int(mean_bytes["total"]),
+            "algorithmic_bytes_per_launch": int(ub["total"]),
             "us_per_launch": round(ms * 1e3, 3),
-            "traffic": None,
+            "traffic": measured_traffic(kern) if headline else None,
             "stream_read_ceiling": round(ceiling, 1),
             "frac_of_stream_read_ceiling": round(gbps / ceiling, 4),
         }
     else:
         result["roofline"] = {
             "bound": "hbm",
-            # the event-timed unit is the entry point absb_sparse_decode with the split counters
-            # known to be zero: exactly one launch of the attention kernel per call
+            # the timed unit is the entry point absb_sparse_decode with the split counters known to
+            # be zero: exactly one launch of the attention kernel per call, on the fused step's selection
             "kernel": "decode_kernel (one absb_sparse_decode call = one launch)",
             "achieved": round(dec_gbps, 2),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
-            "algorithmic_bytes_per_launch": int(mean_bytes["decode"]),
+            "algorithmic_bytes_per_launch": int(ub["decode"]),
             "us_per_launch": round(m["ms_decode"] * 1e3, 3),
-            "traffic": HEADLINE_TRAFFIC_BYTES if headline and args.launches == 0 else None,
+            # counted by rocprofv3 --pmc on these very kernel sources (else null): see profiles/
+            "traffic": measured_traffic("decode_kernel") if headline else None,
             # practical ceiling measured in this run: a plain 128-bit-load read of 2 GiB
             "stream_read_ceiling": round(ceiling, 1),
             "frac_of_stream_read_ceiling": round(dec_gbps / ceiling, 4),
         }
     if not args.no_cpu_baseline:
-        cb = cpu_baseline(wl0, m["bytes0"], block_repr=block_repr, check=insts[0],
-                          selection={"group": 0, "per-query-head": 1, "group-max": 2}[args.select])
+        cb = cpu_baseline(wl0, ub, block_repr=block_repr, check=insts, selection=selection)
         result["verified"] = cb.pop("verified")
         result["cpu_baseline"] = cb
     print(json.dumps(result))

@@ -263,8 +263,7 @@ ABSB_API int absb_workspace_init(const absb_layer* layer, const absb_batch* batc
  *   ABSB_STEP_PIPELINED  one launch.  The grid holds the estimation work-groups, then the attention
  *                        work-groups; a segment's last estimation work-group runs its selection and
  *                        raises a flag, the segment's attention work-groups start on that flag.
- *                        Chosen while no segment exceeds 8192 blocks (16384 in batches of 16 or more
- *                        selection segments) and no list 4096 blocks.
+ *                        Chosen while no segment exceeds 16384 blocks and no list 4096 blocks.
  *   ABSB_STEP_UNITS      one launch.  Every segment is cut into units of consecutive blocks; a unit's
  *                        work-group scores its blocks, publishes a histogram row of its scores,
  *                        derives the segment's threshold from all rows, and attends over its own

@@ -125,16 +125,16 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
   if (p.total >= (int64_t(1) << 31) - 1) return ABSB_ERR_BAD_SHAPE;
   if ((int64_t)batch->pt_stride < ceil_div(max_len, P)) return ABSB_ERR_BAD_SHAPE;
 
-  // How absb_decode_fused is enqueued.  Measured on MI355X: the one-launch step wins (2-14 %)
-  // wherever no segment is longer than 8192 blocks, and up to 16384 blocks when the batch has
-  // other segments to overlap with (16 or more).  Beyond that the selection of the longest
-  // segment, which the one-launch step runs on a 256-thread work-group (register tile up to
-  // 16384 blocks), is the critical path and the 1024-thread selection kernel of the per-stage
-  // path is worth its two extra launches.  Very long lists (budgets near the context) also go to
-  // the per-stage path: its attention kernel reads the lists through the L2.
-  const bool by_shape = (p.max_blocks <= 8192 || (p.max_blocks <= 16384 && p.nseg >= 16)) && p.sel_stride <= 4096;
+  // How absb_decode_fused is enqueued.  Measured on MI355X with cold caches (every step on a copy
+  // of the layer that the last-level cache has forgotten): the pipelined one-launch step wins by
+  // 3-7 % (config 1: 16.9 against 17.9 us, config 2: 31.1 / 32.7, config 3: 23.7 / 24.7, config 4:
+  // 53.2 / 56.8) wherever no segment is longer than 16384 blocks, the longest register tile of its
+  // 256-thread selection; beyond (keys re-read) that selection takes several times longer (69 against
+  // 36 us at 256K context).  Very long lists (budgets near the context) go to the per-stage path: its
+  // attention kernel reads the lists through the L2.
+  const bool by_shape = p.max_blocks <= 16384 && p.sel_stride <= 4096;
   // Segments beyond 16384 blocks: there the selection by one work-group costs more than everything
-  // else together (measured at 256K / 512K context: 33.5 / 48.0 us per stage against 29.4 / 33.8 us),
+  // else together (measured at 256K context: 35.9 us per stage against 31.4 us),
   // and the step runs as units that select among themselves, as long as the chip holds all of a
   // batch's units at once (two work-groups per compute unit).
   const bool by_units = !by_shape && p.max_blocks > 16384 && (int64_t)p.nseg * (p.units_max + 1) <= 480;

@@ -89,6 +89,24 @@ class DeviceWorkload:
         if cap_lens is not None:
             self.set_lens(wl.seq_lens)             # the lists are as wide as the current lengths make them
 
+    def clone(self) -> "DeviceWorkload":
+        """A second resident copy of everything a step reads or writes, at other addresses: same
+        workload, same block sizes and budgets, the centroid store copied as it stands.  Stepping
+        through several clones in turn keeps a benchmark from re-reading lines that an earlier step left
+        in a cache."""
+        c = DeviceWorkload.__new__(DeviceWorkload)
+        c.__dict__.update(self.__dict__)
+        for name in ("k_cache", "v_cache", "q", "seq_lens", "page_table", "budget", "cent_off", "codes", "qscale", "qmin",
+                     "scores", "score_exp", "_sel_buf", "sel_cnt", "out", "lse", "tail", "clamped", "workspace"):
+            setattr(c, name, getattr(self, name).clone())
+        c.sel_idx = c._sel_buf[:c.nsel * c.sel_stride].view(c.nsel, c.sel_stride)
+        c.batch = absb.Batch(seq_lens_host=self.batch.seq_lens_host, budget_host=self.batch.budget_host,
+                             seq_lens=c.seq_lens, page_table=c.page_table, cent_off=c.cent_off, budget=c.budget,
+                             cap_lens_host=self.batch.cap_lens_host, qmin=c.qmin,
+                             opts=absb.LaunchOpts(**vars(self.batch.opts)))
+        absb.absb_workspace_init(c.layer, c.batch, c.workspace)
+        return c
+
     def scribble(self, value: int, stream=None):
         """Poison the workspace (no entry point may depend on its previous contents), then clear its
         counters the way a caller must before the first fused step on a fresh workspace."""

@@ -188,8 +188,8 @@ def test_launch_options_are_per_call_and_validated():
 
 
 def test_enqueue_form_of_the_fused_step_follows_the_longest_segment():
-    """Pipelined one-launch step while no segment has more than 8192 blocks (16384 in a batch of 16 or
-    more segments) and no list more than 4096 entries; beyond 16384 blocks the unit form, as long as
+    """Pipelined one-launch step while no segment has more than 16384 blocks and no list more than
+    4096 entries; beyond 16384 blocks the unit form, as long as
     the chip holds all units at once; one launch per stage otherwise; the option forces any of them; the
     workspace always has room for the counters of the one-launch forms."""
     def form(L, B, batch_size=2, budget=64, **opts):
@@ -199,9 +199,8 @@ def test_enqueue_form_of_the_fused_step_follows_the_longest_segment():
         return absb.absb_step_form_used(layer, batch), absb.absb_plan(layer, batch).workspace_bytes
     P, U, S = absb.STEP_PIPELINED, absb.STEP_UNITS, absb.STEP_PER_STAGE
     assert form(8192 * 8, 8)[0] == P
-    assert form(8192 * 8 + 1, 8)[0] == S
+    assert form(16384 * 8, 8)[0] == P
     assert form(131072, 16)[0] == P
-    assert form(16384 * 8, 8, batch_size=8)[0] == P            # 16 segments: long segments overlap with others
     assert form(16384 * 8 + 1, 8, batch_size=4)[0] == U        # beyond: units select among themselves
     assert form(16384 * 8 + 1, 8, batch_size=8)[0] == S        # ... unless there are more units than the chip holds
     assert form(8192 * 8, 8, budget=4096 * 8)[0] == P

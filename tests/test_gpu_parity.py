@@ -814,7 +814,7 @@ def test_one_launch_step_on_segments_longer_than_the_default_allows(context, siz
     ref = O.decode_step(wl, st)
     dw = _dev(wl)
     dw.build()
-    assert absb.absb_step_form_used(dw.layer, dw.batch) == (absb.STEP_UNITS if context > 131072 else absb.STEP_PER_STAGE)
+    assert absb.absb_step_form_used(dw.layer, dw.batch) == (absb.STEP_UNITS if context > 131072 else absb.STEP_PIPELINED)
     with _opts(dw, step_form=3):
         dw.decode_fused()
         _check_out(dw, ref["out"], ref["lse"], f"per stage, context {context}")
