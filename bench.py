@@ -171,7 +171,7 @@ def per_step_percentiles(fn, n_steps):
 
 
 def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, uniform_block=None, max_bytes=64 << 30,
-                   block_repr=0, selection=0, opts=None, block_sizes=None):
+                   block_repr=0, selection=0, opts=None, block_sizes=None, **synth_kw):
     """R resident copies of one workload (the same data at R places in HBM), the centroid store built
     once and copied.  R (`rotate`, 0 = auto) is sized by what a step touches: R x useful bytes of a
     step >= 2 x the last-level cache, at most 256 copies and `max_bytes` of device memory."""
@@ -181,6 +181,7 @@ def make_instances(config, *, context=None, batch=None, budget=None, rotate=0, u
     kw = dict(context=context, batch=batch, budget=budget, uniform_block=uniform_block)
     if block_sizes is not None:
         kw["block_sizes"] = block_sizes
+    kw.update(synth_kw)
     wl0 = synth.make_workload(config, **kw)
     first = DeviceWorkload(wl0, block_repr=block_repr, selection=selection, opts=opts)
     first.build()
@@ -455,7 +456,7 @@ def run_matrix(args):
     print("| blocks | budget | us/step | GB/s | planted-token recall | attention recall (mean) | max abs err vs dense | "
           "rel L2 err vs dense |")
     print("|---|---|---|---|---|---|---|---|", flush=True)
-    for label, ublock in (("uniform 16", 16), ("adaptive", None)):
+    for label, ublock in (("uniform 16", 16), ("seeded random draw per head", None)):
         for T in (1024, 2048, 4096, 8192):
             wl0, insts, ub = make_instances(5, budget=T, uniform_block=ublock, rotate=0)
             m = measure(wl0, insts, ub, args.steps, args.warmup, stages=False)
@@ -515,6 +516,38 @@ def run_calibration(args):
         rec = float(np.mean([held[h, idx[h]] for h in range(8)]))
         print(f"| Eq. (2), tau = {tau} | {sizes.tolist()} | {float(np.mean(sizes)):.1f} | "
               f"{float(np.mean(1024 / sizes)):.1f} | {rec:.3f} |", flush=True)
+
+    # the same assignments timed: config-5 shape (batch 4, context 65536) with the head roles above, a
+    # held-out seed, cold caches; quality against dense attention over the whole context from the oracle
+    from oracle import oracle as O
+    print("\nTimed A/B on the config-5 shape (batch 4, context 65536, fp16, head roles as above, seed 500): the step with "
+          "calibrated sizes against uniform sizes, same budget; recall and error against dense attention\n")
+    print("| assignment | block sizes | budget | us/step | useful MB/step | planted-token recall | attention recall (mean) | "
+          "rel L2 err vs dense |")
+    print("|---|---|---|---|---|---|---|---|", flush=True)
+    assignments = [("uniform 16", [16] * 8), ("uniform 32", [32] * 8)]
+    for tau in (0.9, 0.8, 0.7, 0.6):
+        sizes, _ = absb.absb_assign_block_sizes(per_sample, cand, tau)
+        if [int(x) for x in sizes] not in [a[1] for a in assignments]:
+            assignments.append((f"Eq. (2), tau = {tau}", [int(x) for x in sizes]))
+    for Tb in (1024, 4096):
+        dense = None
+        for label, sizes in assignments:
+            wl0, insts, ub = make_instances(5, budget=Tb, seed=500, run_lengths=roles, head_block_sizes=sizes)
+            m = measure(wl0, insts, ub, args.steps, args.warmup, stages=False)
+            dw = insts[0]
+            dw.decode_fused()
+            torch.cuda.synchronize()
+            sel, cnt = dw.sel_idx.cpu().numpy(), dw.sel_cnt.cpu().numpy()
+            got = dw.out_f32().astype(np.float64)
+            if dense is None:
+                dense, _ = O.dense_attention(wl0)
+            rel = float(np.linalg.norm(got - dense) / np.linalg.norm(dense))
+            print(f"| {label} | {sizes} | {Tb} | {m['ms'] * 1e3:.1f} | {m['bytes']['total'] / 1e6:.1f} | "
+                  f"{O.planted_recall(wl0, sel, cnt):.3f} | {float(O.attention_recall(wl0, sel, cnt).mean()):.3f} | "
+                  f"{rel:.3e} |", flush=True)
+            del insts, dw
+            torch.cuda.empty_cache()
 
 
 def main():

@@ -219,7 +219,8 @@ def make_workload(config: int, *, seed: Optional[int] = None, context: Optional[
                   block_sizes: Optional[Sequence[int]] = None, uniform_block: Optional[int] = None,
                   shuffle_pages: bool = True, plant_unit: str = "rms",
                   seq_lens: Optional[Sequence[int]] = None,
-                  run_lengths: Optional[Sequence[int]] = None) -> Workload:
+                  run_lengths: Optional[Sequence[int]] = None,
+                  head_block_sizes: Optional[Sequence[int]] = None) -> Workload:
     """Build one of the five benchmark-shaped workloads (1-based `config`), optionally
     scaled down (context / batch / budget overrides) for quick tests.
 
@@ -246,6 +247,8 @@ def make_workload(config: int, *, seed: Optional[int] = None, context: Optional[
     bs = r_bs.choice(np.asarray(sizes), size=Hkv).astype(np.int32)
     if uniform_block is not None:
         bs[:] = uniform_block
+    if head_block_sizes is not None:           # an explicit assignment (a calibration's result), one size per KV head
+        bs = np.asarray(head_block_sizes, dtype=np.int32).reshape(Hkv).copy()
 
     if seq_lens is not None:
         lens = np.asarray(seq_lens, dtype=np.int32)
