@@ -363,6 +363,18 @@ __device__ __forceinline__ void write_empty_rows(const DecodeParams& p, int b, i
   }
 }
 
+// A wait ran out: the segment's output cannot be completed.  Its rows are set to NaN so that nobody
+// takes stale values for results.
+template <int DT, int G>
+__device__ __forceinline__ void poison_rows(const DecodeParams& p, int b, int hs) {
+  const uint16_t nan16 = DT == ABSB_F16 ? (uint16_t)0x7e00 : (uint16_t)0x7fc0;
+  for (int i = threadIdx.x; i < G * ABSB_HEAD_DIM; i += DEC_THREADS) {
+    const size_t row = (size_t)b * p.g.Hq + (size_t)hs * G + (i >> 7);
+    static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + (i & 127)] = nan16;
+    if (p.lse && (i & 127) == 0) p.lse[row] = __builtin_nanf("");
+  }
+}
+
 // The end of a work-group's attention: the four wave states are folded into the work-group's partial;
 // with one split per segment it is normalised and written out; otherwise it goes to slot `split` of
 // the segment's partials, the work-group draws a ticket, and the one that draws ticket nsplit - 1
@@ -561,7 +573,8 @@ __device__ __forceinline__ int wait_for_flag(const int32_t* flag, int32_t* statu
 // launch.  LISTED == true (the pipelined one-launch step): the list is being produced by another work-group of
 // this launch with a lower index; its length K_s is recomputed here from the budget, the
 // work-group waits (bounded) for the segment's flag before it reads the list with device-coherent
-// loads, and the segment's last work-group clears the flag again.  `lds`: DEC_LDS_BYTES.
+// loads, and the segment's last work-group clears the flag again; a wait that ran out leaves NaN in
+// the segment's rows.  `lds`: DEC_LDS_BYTES.
 template <int DT, int G, bool LISTED>
 __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int split, char* lds) {
   // s is a SELECTION segment: its G (= the template's) query heads start at head hs * G; hk is the
@@ -616,7 +629,10 @@ __device__ __forceinline__ void decode_split(const DecodeParams& p, int s, int s
   if (LISTED) {
     // The list comes from a work-group with a lower index, which never waits for anything and was
     // dispatched before this one: the wait ends.  The time limit only makes that unconditional.
-    if (!wait_for_flag(flag, p.status, s_bcast + 1)) return;
+    if (!wait_for_flag(flag, p.status, s_bcast + 1)) {
+      if (split == 0) poison_rows<DT, G>(p, b, hs);  // nobody will complete this segment's rows
+      return;
+    }
     sj = list.at((pos_begin + wave * ROWS_PER_WAVE_STEP + grp * 4) >> lb);
   }
 

@@ -20,7 +20,7 @@
 // only for work-groups with lower indices; the hardware starts work-groups in index order, so
 // every work-group waited for is already running or done.  The wait is also bounded in time, so
 // the launch ends whatever happens (a wait that ran out sets the status word; its segment's
-// output is then not written).
+// output rows are then set to NaN).
 //
 // Counters (estimation tickets, flags, attention tickets; 256 bytes apart) must be zero when the
 // launch starts and are zero again when it ends: absb_workspace_init clears them once.

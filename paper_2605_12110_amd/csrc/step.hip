@@ -157,18 +157,6 @@ __device__ __forceinline__ int wait_for_count(const int32_t* ctr, int target, in
   return ok;
 }
 
-// A wait ran out: the segment's output cannot be completed.  Its rows are set to NaN so that nobody
-// takes stale values for results.
-template <int DT, int G>
-__device__ __forceinline__ void poison_rows(const DecodeParams& p, int b, int hs) {
-  const uint16_t nan16 = DT == ABSB_F16 ? (uint16_t)0x7e00 : (uint16_t)0x7fc0;
-  for (int i = threadIdx.x; i < G * ABSB_HEAD_DIM; i += STEP_THREADS) {
-    const size_t row = (size_t)b * p.g.Hq + (size_t)hs * G + (i >> 7);
-    static_cast<uint16_t*>(p.out)[row * ABSB_HEAD_DIM + (i & 127)] = nan16;
-    if (p.lse && (i & 127) == 0) p.lse[row] = __builtin_nanf("");
-  }
-}
-
 // Ascending index list of the set bits of an LDS bitmap of `nwords` words: every thread owns a run of
 // consecutive words, one scan over the work-group places the runs.  Writes at most `K` entries.
 __device__ __forceinline__ void emit_bitmap_list(const uint32_t* bm, int nwords, int32_t* out, int K, uint32_t* slot) {

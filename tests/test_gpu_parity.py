@@ -902,7 +902,7 @@ def test_one_launch_step_gives_up_waiting_and_says_so_when_a_counter_was_not_cle
     one segment's arrival counter starts at a value from which the count its work-groups wait for is
     never reached, so its list (pipelined form) or its threshold (unit form) never comes.  The launch
     must end by itself (about a quarter of a second per wait), set the status word, leave the other
-    segments right, and (unit form) write NaN into the stuck segment's output rows; after the counters
+    segments right, and write NaN into the stuck segment's output rows; after the counters
     are cleared again the step works."""
     import torch
     wl = synth.make_workload(1, context=4096, budget=256)
@@ -929,8 +929,7 @@ def test_one_launch_step_gives_up_waiting_and_says_so_when_a_counter_was_not_cle
     G = wl.group
     for s in others:
         assert np.abs(got[0, s * G:(s + 1) * G] - ref["out"][0, s * G:(s + 1) * G]).max() <= TOL[wl.dtype]
-    if form == 2:
-        assert np.isnan(got[0, stuck * G:(stuck + 1) * G]).all()
+    assert np.isnan(got[0, stuck * G:(stuck + 1) * G]).all()
     dw.scribble(0x77)                                             # the contract: clear the counters, go on
     dw.decode_fused()
     _check_out(dw, ref["out"], ref["lse"], "after clearing the counters again")
