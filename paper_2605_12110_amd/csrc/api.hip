@@ -352,7 +352,7 @@ int absb_decode_fused(const absb_layer* layer, const absb_batch* batch, const vo
                        sel_idx_out != nullptr, out, lse, ws, st);
   if (p.step_form == ABSB_STEP_PIPELINED && fused_one_launch_fits(p))
     return launch_fused(g, p, layer->dtype, resolve_scale(layer), q, codes, qscale, batch->qmin, k_cache, v_cache, batch->page_table,
-                        batch->seq_lens, batch->cent_off, batch->budget, sel_idx, sel_cnt, out, lse, ws, st);
+                        batch->seq_lens, batch->cent_off, batch->budget, sel_idx_out, sel_cnt, out, lse, ws, st);
   rc = launch_score(g, p, layer->dtype, q, codes, qscale, batch->qmin, batch->cent_off, batch->seq_lens, scores, nullptr, st);
   if (rc != ABSB_OK) return rc;
   // the selection kernel also clears the split counters of the attention kernel behind it

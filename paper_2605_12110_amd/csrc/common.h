@@ -103,7 +103,7 @@ ABSB_HIDDEN bool fused_one_launch_fits(const Plan& pl);
 ABSB_HIDDEN int launch_fused(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q,
                              const uint8_t* codes, const float* qscale, const float* qmin, const void* k_cache,
                              const void* v_cache, const int32_t* page_table, const int32_t* seq_lens, const int32_t* cent_off,
-                             const int32_t* budget, int32_t* sel_idx, int32_t* sel_cnt, void* out, float* lse,
+                             const int32_t* budget, int32_t* sel_idx_out, int32_t* sel_cnt, void* out, float* lse,
                              char* ws, hipStream_t stream);
 ABSB_HIDDEN int launch_workspace_init(const Plan& pl, char* ws, hipStream_t stream);
 // The whole step in one launch, units of a segment doing score, selection and attention for their own blocks.

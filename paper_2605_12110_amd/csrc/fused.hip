@@ -9,12 +9,14 @@
 //   [0, n_score)        estimation of one chunk of one segment's blocks (score_dev.h).  Scores are
 //                       stored device-coherently; the work-group then draws a ticket from the
 //                       segment's counter, and the one that draws the last ticket runs the
-//                       segment's selection (topk_dev.h), stores the list device-coherently and
-//                       raises the segment's flag.
+//                       segment's selection (topk_dev.h): it stores the selected blocks
+//                       device-coherently in the order it finds them, raises the segment's flag,
+//                       and only then writes the ascending list if the caller asked for one.
 //   [n_score, grid)     attention over one split of one segment's selection (decode_dev.h): the
 //                       work-group loads its queries, waits for the segment's flag, reads the
-//                       list with device-coherent loads and proceeds as in the stand-alone
-//                       kernel (partials, ticket, the last arriver merges).
+//                       blocks with device-coherent loads (attention does not depend on their
+//                       order beyond rounding) and proceeds as in the stand-alone kernel
+//                       (partials, ticket, the last arriver merges).
 //
 // Progress: estimation/selection work-groups never wait for anything.  Attention work-groups wait
 // only for work-groups with lower indices; the hardware starts work-groups in index order, so
@@ -77,20 +79,16 @@ __global__ __launch_bounds__(FUSED_THREADS, 3) void fused_step_kernel(FusedParam
   uint32_t* bitmap = reinterpret_cast<uint32_t*>(lds + ((sizeof(TopkShared) + 15) & ~size_t(15)));
   const int tiles = (N + FUSED_THREADS - 1) / FUSED_THREADS;
   if (tiles <= 8)
-    topk_segment<FUSED_THREADS, 8, true>(p.tk, s, sh, bitmap);
+    topk_segment<FUSED_THREADS, 8, true, true>(p.tk, s, sh, bitmap);
   else if (tiles <= 16)
-    topk_segment<FUSED_THREADS, 16, true>(p.tk, s, sh, bitmap);
+    topk_segment<FUSED_THREADS, 16, true, true>(p.tk, s, sh, bitmap);
   else if (tiles <= 32)
-    topk_segment<FUSED_THREADS, 32, true>(p.tk, s, sh, bitmap);
+    topk_segment<FUSED_THREADS, 32, true, true>(p.tk, s, sh, bitmap);
   else if (tiles <= 64)
-    topk_segment<FUSED_THREADS, 64, true>(p.tk, s, sh, bitmap);
+    topk_segment<FUSED_THREADS, 64, true, true>(p.tk, s, sh, bitmap);
   else
-    topk_segment<FUSED_THREADS, 0, true>(p.tk, s, sh, bitmap);
-
-  // ---- publish the list
-  wait_stores_acknowledged();
-  __syncthreads();
-  if (tid == 0) st_i32<true>(p.dc.flags + (size_t)s * ABSB_TICKET_STRIDE, 1);
+    topk_segment<FUSED_THREADS, 0, true, true>(p.tk, s, sh, bitmap);
+  // (the selection raises the segment's flag itself, as soon as its members are known)
 }
 
 // Clears the counters at the start of a workspace (all three kinds, and the status word).
@@ -137,14 +135,18 @@ bool fused_one_launch_fits(const Plan& pl) {
 
 int launch_fused(const Geometry& g, const Plan& pl, int dtype, float sm_scale, const void* q, const uint8_t* codes,
                  const float* qscale, const float* qmin, const void* k_cache, const void* v_cache, const int32_t* page_table,
-                 const int32_t* seq_lens, const int32_t* cent_off, const int32_t* budget, int32_t* sel_idx,
+                 const int32_t* seq_lens, const int32_t* cent_off, const int32_t* budget, int32_t* sel_idx_out,
                  int32_t* sel_cnt, void* out, float* lse, char* ws, hipStream_t stream) {
   if (!fused_one_launch_fits(pl)) return ABSB_ERR_UNSUPPORTED;
   FusedParams p;
   int32_t* scores = reinterpret_cast<int32_t*>(ws + pl.ws_scores);
   p.sc = make_score_params(g, pl, q, codes, qscale, qmin, cent_off, seq_lens, scores, nullptr);
-  p.tk = make_topk_params(g, scores, cent_off, budget, seq_lens, sel_idx, sel_cnt, pl.sel_stride, nullptr);
-  p.dc = make_decode_params(g, pl, sm_scale, q, k_cache, v_cache, page_table, seq_lens, sel_idx, sel_cnt,
+  // the attention reads the workspace's list (any order); the caller's, if wanted, is ascending
+  int32_t* work_list = reinterpret_cast<int32_t*>(ws + pl.ws_sel_idx);
+  p.tk = make_topk_params(g, scores, cent_off, budget, seq_lens, sel_idx_out, sel_cnt, pl.sel_stride, nullptr);
+  p.tk.work_list = work_list;
+  p.tk.flags = reinterpret_cast<int32_t*>(ws + pl.ws_flags);
+  p.dc = make_decode_params(g, pl, sm_scale, q, k_cache, v_cache, page_table, seq_lens, work_list, sel_cnt,
                             pl.sel_stride, out, lse, ws);
   p.dc.budget = budget;
   p.dc.cent_off = cent_off;

@@ -37,6 +37,11 @@ struct TopkParams {
   int32_t* sel_idx;
   int32_t* sel_cnt;
   int32_t* tickets;  // [nseg] or null: split counters of the attention kernel that follows, cleared here
+  // Only for the selection that runs inside the pipelined one-launch step (EARLY): the list the
+  // attention work-groups read, the flag per segment that says it is complete; sel_idx is then
+  // the caller's copy in ascending order and may be null.
+  int32_t* work_list;  // [nseg, sel_stride]
+  int32_t* flags;      // [nseg], ABSB_TICKET_STRIDE apart
   int32_t sel_stride, Hkv, tight;
   int32_t Hsel, Rk;  // selection segments per request, selection segments per KV head
   HeadTable heads;
@@ -56,6 +61,8 @@ inline TopkParams make_topk_params(const Geometry& g, const int32_t* scores, con
   p.sel_idx = sel_idx;
   p.sel_cnt = sel_cnt;
   p.tickets = tickets;
+  p.work_list = nullptr;
+  p.flags = nullptr;
   p.sel_stride = sel_stride;
   p.Hkv = g.Hkv;
   p.Hsel = g.Hsel;
@@ -173,9 +180,17 @@ __device__ __forceinline__ void pick_bin(TopkShared& sh, int tid, int lane, int 
 // The selection of selection segment t by one work-group of NT threads.
 //   KPT > 0: keys of the segment live in registers (competing blocks <= KPT*NT); KPT == 0: re-read.
 //   COH: the scores were written, and the list will be read, by other work-groups of this launch.
+//   EARLY: attention work-groups of this launch are waiting for the segment's flag.  What they read is
+//     p.work_list, a permutation of the selection (attention does not care about the order of its
+//     blocks), raised as soon as the members are known: forced blocks, then the blocks above the
+//     threshold bin in the order (thread, tile), then the admitted candidates by rank; the order is
+//     a function of the scores alone.  The ascending list in p.sel_idx, if the caller wants one, is
+//     written after the flag, off the path the attention waits on.  On the rare paths (a long
+//     candidate list, ties, more blocks than a register tile holds) the work list is the ascending
+//     list and the flag goes up at the end.
 //   sh, bitmap: LDS as sized by topk_lds_bytes().
 // Every thread of the work-group must call it; all of them return together.
-template <int NT, int KPT, bool COH>
+template <int NT, int KPT, bool COH, bool EARLY = false>
 __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkShared& sh, uint32_t* s_bitmap) {
   constexpr int WAVES = NT / 64;
   const SegMap sm = seg_map(t, p.Hsel, p.Rk, p.Hkv);
@@ -195,7 +210,14 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
   const int N = hi - lo;  // competing blocks; the code below indexes them from 0
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t* sc = p.scores + score_base(sm, p.Rk, off, rows) + (N > 0 ? lo : 0);
-  int32_t* out = p.sel_idx + (size_t)t * p.sel_stride;
+  // `out`: the ascending list (null: not wanted; only possible with EARLY); `wl`: the work list
+  int32_t* out = (!EARLY || p.sel_idx) ? p.sel_idx + (size_t)t * p.sel_stride : nullptr;
+  int32_t* wl = EARLY ? p.work_list + (size_t)t * p.sel_stride : nullptr;
+  auto publish = [&]() __attribute__((always_inline)) {  // EARLY: the work list is complete
+    wait_stores_acknowledged();
+    __syncthreads();
+    if (tid == 0) st_i32<true>(p.flags + (size_t)t * ABSB_TICKET_STRIDE, 1);
+  };
   constexpr int R = KPT > 0 ? KPT : 1;
   const int ntiles = KPT > 0 ? KPT : (N + NT - 1) / NT;
   const int nwords = (N + 31) >> 5;
@@ -219,26 +241,37 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
     st_i32<COH>(p.sel_cnt + t, K);
     if (p.tickets) p.tickets[(size_t)t * ABSB_TICKET_STRIDE] = 0;
   }
+  // entry i of the ascending list (and of the work list, while that one is kept ascending)
+  bool wl_ascending = EARLY;
+  auto put = [&](int i, int v) __attribute__((always_inline)) {
+    if (!EARLY || out) st_i32<COH>(out + i, v);
+    if (EARLY && wl_ascending) st_i32<true>(wl + i, v);
+  };
+  if (!EARLY || out) {
 #pragma unroll 1
-  for (int i = K + tid; i < p.sel_stride; i += NT) st_i32<COH>(out + i, -1);
+    for (int i = K + tid; i < p.sel_stride; i += NT) st_i32<COH>(out + i, -1);
+  }
   if (K >= Nall) {  // everything is selected
 #pragma unroll 1
-    for (int i = tid; i < Nall; i += NT) st_i32<COH>(out + i, i);
+    for (int i = tid; i < Nall; i += NT) put(i, i);
+    if (EARLY && K > 0) publish();
     return;
   }
   if (nforced >= K) {  // the forced blocks alone fill the list: lowest indices first
 #pragma unroll 1
-    for (int i = tid; i < K; i += NT) st_i32<COH>(out + i, i < lo ? i : hi + (i - lo));
+    for (int i = tid; i < K; i += NT) put(i, i < lo ? i : hi + (i - lo));
+    if (EARLY && K > 0) publish();
     return;
   }
-  // list = forced prefix, then the chosen ones of [lo, hi) (written below, relative to `out`), then
-  // the forced suffix
+  // list = forced prefix, then the chosen ones of [lo, hi) (written below, at lo + their rank by
+  // index), then the forced suffix
   K -= nforced;
 #pragma unroll 1
-  for (int i = tid; i < lo; i += NT) st_i32<COH>(out + i, i);
+  for (int i = tid; i < lo; i += NT) put(i, i);
+  if (!EARLY || out) {
 #pragma unroll 1
-  for (int i = tid; i < Nall - hi; i += NT) st_i32<COH>(out + lo + K + i, hi + i);
-  out += lo;
+    for (int i = tid; i < Nall - hi; i += NT) st_i32<COH>(out + lo + K + i, hi + i);
+  }
 
 #pragma unroll
   for (int i = tid; i < TOPK_BINS; i += NT) sh.hist[i] = 0;
@@ -317,6 +350,19 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
   uint32_t need = (uint32_t)K - sh.bcast[1];
   uint32_t ncand = sh.bcast[2];
   uint32_t need_eq = 0;
+  // The common case (a short candidate list) with EARLY: members go to the work list as they are
+  // found, at places fixed by a count per thread and one scan, and the bitmaps are only needed if
+  // the caller wants the ascending list.  Layout: [0, lo) forced prefix, [lo, nforced) forced
+  // suffix, then the K - need blocks above the bin, then the `need` admitted candidates.
+  const bool direct = EARLY && KPT > 0 && ncand <= (uint32_t)TOPK_RANK_MAX;
+  const bool use_bm = !direct || out != nullptr;
+  const uint32_t wl_cand0 = (uint32_t)nforced + ((uint32_t)K - need);  // first candidate's place
+  if (EARLY) {
+    wl_ascending = !direct;
+    const int at = direct ? lo : lo + K;
+#pragma unroll 1
+    for (int i = tid; i < Nall - hi; i += NT) st_i32<true>(wl + at + i, hi + i);
+  }
 
   if (shift == 0 || ncand <= (uint32_t)TOPK_MAX_CAND) {
     // ---- 3. keys above the bin are selected; keys inside it become candidates
@@ -337,6 +383,13 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
         above[w] = (above[w] << 1) | (uint32_t)(dg > d1);
         inside[w] = (inside[w] << 1) | (uint32_t)(dg == d1);
       }
+      uint32_t wl_pos = 0;  // direct: this thread's next place in the work list
+      if (direct) {
+        uint32_t mine = 0, total;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) mine += (uint32_t)__popc(above[w] & (uint32_t)(valid >> (32 * w)));
+        wl_pos = (uint32_t)nforced + block_excl_scan<NT>(mine, sh.wave_b, lane, wave, &total);
+      }
 #pragma unroll
       for (int w = 0; w < NW; ++w) {
         const uint32_t ok = (uint32_t)(valid >> (32 * w));
@@ -345,7 +398,11 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
         while (left) {
           const int j = (__builtin_ctz(left) + 32 * w) * NT + tid;
           left &= left - 1;
-          atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
+          if (use_bm) atomicOr(&bm_gt[j >> 5], 1u << (j & 31));
+          if (direct) {
+            if (wl_pos < wl_cand0) st_i32<true>(wl + wl_pos, j + lo);  // always true for consistent counts
+            ++wl_pos;
+          }
         }
         left = inside[w] & ok;
 #pragma unroll 1
@@ -438,7 +495,10 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
             const uint32_t ok = sh.cand_key[u], oi = sh.cand_idx[u];
             rank += (ok > mk) || (ok == mk && oi < mi);
           }
-          if (rank < need) atomicOr(&bm_gt[mi >> 5], 1u << (mi & 31));
+          if (rank < need) {
+            if (use_bm) atomicOr(&bm_gt[mi >> 5], 1u << (mi & 31));
+            if (direct) st_i32<true>(wl + wl_cand0 + rank, (int)mi + lo);
+          }
         }
       } else {
         // every digit used up: the candidates share one key value and tie, lowest index first
@@ -485,6 +545,10 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
     }
     __syncthreads();
   }
+  if (direct) {
+    publish();
+    if (!out) return;
+  }
   // ---- 4. bitmaps -> ascending index list, in one round: every thread owns a run of consecutive
   // bitmap words, counts their bits, one scan over the work-group places the run, and the thread
   // writes its blocks out in order
@@ -512,17 +576,18 @@ __device__ __forceinline__ void topk_segment(const TopkParams& p, int t, TopkSha
       const int idx = (w << 5) + bpos;
       if ((g >> bpos) & 1u) {
         const uint32_t slot = G + min(E, need_eq);
-        if (slot < (uint32_t)K) st_i32<COH>(out + slot, idx + lo);  // always true for consistent counts; keeps stores in bounds
+        if (slot < (uint32_t)K) put(lo + (int)slot, idx + lo);  // always true for consistent counts; keeps stores in bounds
         ++G;
       } else {
         if (E < need_eq) {
           const uint32_t slot = G + E;
-          if (slot < (uint32_t)K) st_i32<COH>(out + slot, idx + lo);
+          if (slot < (uint32_t)K) put(lo + (int)slot, idx + lo);
         }
         ++E;
       }
     }
   }
+  if (EARLY && !direct) publish();
 }
 
 }  // namespace absb

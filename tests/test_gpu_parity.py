@@ -138,8 +138,8 @@ def run_all_stages(wl, name, block_repr=O.MEAN, per_query_head=False, group_max=
     assert np.array_equal(first, second), "fused output depends on workspace contents or is not deterministic"
     # every way of enqueueing the step, forced (the default picks one by shape): two one-launch forms
     # and one launch per stage (which needs no cleared counters).  Same selection from all; outputs
-    # within tolerance of the oracle; the pipelined and the per-stage form cut the lists alike and give
-    # the same bits, the unit form sums in another order
+    # within tolerance of the oracle.  Each form is deterministic; they sum in different orders (the
+    # pipelined form's attention reads the selection in the order its members were found)
     from paper_2605_12110_amd import absb
     outs = {}
     for mode in (1, 2, 3):
@@ -162,7 +162,6 @@ def run_all_stages(wl, name, block_repr=O.MEAN, per_query_head=False, group_max=
                 dw.decode_fused(want_sel=False); _sync()
             again = dw.out.cpu().numpy() if dw.out.dtype == torch.float16 else dw.out.float().cpu().numpy()
             assert np.array_equal(outs[mode], again), f"{FORMS[mode]}: not deterministic, or the list request changes the output"
-    assert np.array_equal(outs[1], outs[3]), "pipelined and per-stage forms disagree"
     assert np.array_equal(first, outs[absb.absb_step_form_used(dw.layer, dw.batch)]), "default form"
     dw.check_device_contents(lists=True)      # the holder's host-side bounds checks agree with all of that
     dw.scribble(0x99)     # the stand-alone stages do not keep the other counters: clear them again
@@ -804,9 +803,10 @@ def test_group_maximum_selection_needs_the_offsets_and_mean_pooling():
 @pytest.mark.parametrize("context,sizes", [(131072, (8, 16)), (163840, (8, 8))])
 def test_one_launch_step_on_segments_longer_than_the_default_allows(context, sizes):
     """By default a batch with a segment of more than 8192 blocks does not run as the pipelined
-    one-launch step.  Forced into it, it must give the bits of the per-stage form: 16384 blocks (the
-    longest register tile of the 256-thread selection) and 20480 blocks (keys re-read, no register
-    tile).  The unit form, the default beyond 16384 blocks, selects the same blocks."""
+    one-launch step.  Forced into it, it must select the same blocks and give the same bits on every
+    call: 16384 blocks (the longest register tile of the 256-thread selection) and 20480 blocks (keys
+    re-read, no register tile: there the work list is the ascending list, and the bits are those of
+    the per-stage form).  The unit form, the default beyond 16384 blocks, selects the same blocks."""
     import torch
     from paper_2605_12110_amd import absb
     wl = synth.make_workload(3, context=context, budget=4096, block_sizes=sizes)
@@ -819,7 +819,7 @@ def test_one_launch_step_on_segments_longer_than_the_default_allows(context, siz
         dw.decode_fused()
         _check_out(dw, ref["out"], ref["lse"], f"per stage, context {context}")
     assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
-    first = dw.out.clone()
+    first = dw.out.clone() if context > 131072 else None
     for form in (1, 2, 0):
         with _opts(dw, step_form=form):
             for rep in range(2):                                     # twice: the counters must come back to zero
@@ -827,6 +827,8 @@ def test_one_launch_step_on_segments_longer_than_the_default_allows(context, siz
                 dw.decode_fused()
                 _check_out(dw, ref["out"], ref["lse"], f"form {form}, call {rep}, context {context}")
                 if form == 1:
+                    if first is None:
+                        first = dw.out.clone()
                     assert torch.equal(dw.out, first), f"pipelined, call {rep}"
                 assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
                 assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
