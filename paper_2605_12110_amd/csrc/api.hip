@@ -127,8 +127,8 @@ int make_plan(const absb_layer* layer, const absb_batch* batch, bool need_budget
 
   // How absb_decode_fused is enqueued.  Measured on MI355X with cold caches (every step on a copy
   // of the layer that the last-level cache has forgotten): the pipelined one-launch step wins by
-  // 3-7 % (config 1: 16.9 against 17.9 us, config 2: 31.1 / 32.7, config 3: 23.7 / 24.7, config 4:
-  // 53.2 / 56.8) wherever no segment is longer than 16384 blocks, the longest register tile of its
+  // 6-12 % (config 1: 16.6 against 18.9 us, config 2: 30.5 / 32.6, config 3: 22.2 / 24.3, config 4:
+  // 52.5 / 56.5) wherever no segment is longer than 16384 blocks, the longest register tile of its
   // 256-thread selection; beyond (keys re-read) that selection takes several times longer (69 against
   // 36 us at 256K context).  Very long lists (budgets near the context) go to the per-stage path: its
   // attention kernel reads the lists through the L2.
