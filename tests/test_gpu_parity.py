@@ -964,6 +964,38 @@ def test_one_launch_step_with_constant_keys_takes_the_tie_paths():
         assert dw.status() == 0
 
 
+@pytest.mark.parametrize("distinct", [3, 40, 700])
+def test_one_launch_step_on_long_segments_whose_scores_take_few_values(distinct):
+    """Segments of 8192 and 16384 blocks (register tiles of 32 and 64 keys per thread in the pipelined
+    form's selection) whose pages each hold one key out of a palette of 3, 40 or 700: the threshold bin holds
+    from a few to thousands of equal scores, so the selection leaves its common path (members handed
+    to the attention as they are found) for the ones that cut a long candidate list down, admit ties by
+    index, or re-read a crowded bin, while other segments of the same launch stay on the common path.
+    Every enqueue form must select the oracle's blocks, with and without the caller asking for the list."""
+    wl = synth.make_workload(3, context=131072, budget=4096, block_sizes=(8, 16, 64))
+    rng = np.random.default_rng(77 + distinct)
+    k = wl.k_cache.reshape(-1, wl.num_kv_heads, wl.page_size, wl.head_dim)
+    pal = synth.f32_to_bits(rng.standard_normal((distinct, wl.head_dim)).astype(np.float32), wl.dtype)
+    for h in range(0, wl.num_kv_heads, 2):                        # every other KV head; the rest keep their keys
+        k[:, h] = pal[rng.integers(0, distinct, size=k.shape[0])][:, None, :]   # one key per page: its blocks tie
+    st = O.build_centroids(wl)
+    ref = O.decode_step(wl, st)
+    for mode in (1, 3):
+        dw = _dev(wl, opts=dict(step_form=mode))
+        dw.build()
+        dw.sel_idx.fill_(-7); dw.sel_cnt.fill_(-7)
+        dw.decode_fused()
+        _check_out(dw, ref["out"], ref["lse"], f"{distinct} distinct keys, {FORMS[mode]}")
+        assert np.array_equal(dw.sel_cnt.cpu().numpy(), ref["sel_cnt"])
+        assert np.array_equal(dw.sel_idx.cpu().numpy(), ref["sel_idx"][:, :dw.sel_stride])
+        first = dw.out.clone()
+        dw.decode_fused(want_sel=False); _sync()
+        import torch
+        assert torch.equal(dw.out, first), "the list request changes the output"
+        if mode == 1:
+            assert dw.status() == 0
+
+
 @pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
 def test_log_sum_exp_does_not_carry_the_rounding_of_the_weights(dtype):
     """Few distinct keys per head: every softmax weight of a kind rounds the same way when it is
